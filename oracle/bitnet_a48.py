@@ -1,0 +1,239 @@
+"""CPU oracle for the quantized linear layers of BitNet a4.8 (arXiv 2411.04965).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the HIP
+kernels are checked against.  It must never be imported by the product package;
+only tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+It shares no code with the HIP path.
+
+Every function writes out one equation of the paper, in the paper's notation:
+
+    X  activations [M, K] (one token per row),  W latent weights [N, K],
+    Y = Q(X) . Q_w(W)^T  [M, N]                               (eq. 1 and eq. 6)
+
+Arithmetic conventions (the paper fixes none of them; these are the readings
+this build takes, each one listed in the design notes):
+
+  * statistics (mean |.|, max |.|) are per token for activations and per matrix
+    for weights;
+  * a mean is the float64 sum divided in float64, rounded once to float32;
+  * every other floating-point step is one IEEE float32 operation, never fused;
+  * round() is round-half-to-even;
+  * activations are multiplied by a precomputed scale c/(stat+eps), weights are
+    divided by (alpha+eps), as the equations are printed;
+  * Top_k keeps exactly k entries per token, ties go to the lower index.
+
+Parity pins: every function here is pinned by tests/test_oracle_*.py against
+hand-worked vectors, closed forms, brute force and invariants.  Nothing in
+this file is "parity unpinned".
+"""
+import numpy as np
+
+F32 = np.float32
+SQRT7 = F32(np.sqrt(7.0))  # 0x402953FD
+C127 = F32(127.0)
+DEFAULT_EPS = 1e-5
+
+
+# --------------------------------------------------------------------------
+# small helpers
+# --------------------------------------------------------------------------
+def round_clip(x, a, b):
+    """RoundClip(X, a, b) = min(max(round(X), a), b)   (eq. 4)."""
+    return np.minimum(np.maximum(np.rint(x), a), b)
+
+
+def bf16_round(x):
+    """Round float32 values to the nearest bfloat16 (ties to even); float32 out."""
+    u = np.ascontiguousarray(x, dtype=F32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    return r.view(F32)
+
+
+def _mean_abs_f32(x, axis=None):
+    """mean(|x|): float64 sum, float64 divide, one rounding to float32."""
+    a = np.abs(np.asarray(x, dtype=F32)).astype(np.float64)
+    n = a.size if axis is None else a.shape[axis]
+    return (a.sum(axis=axis) / np.float64(n)).astype(F32)
+
+
+# --------------------------------------------------------------------------
+# weights (eq. 2)
+# --------------------------------------------------------------------------
+def ternarize(W, eps=DEFAULT_EPS):
+    """Q_w(W) = alpha * RoundClip(W / (alpha + eps), -1, 1), alpha = mean|W|  (eq. 2).
+
+    Returns (T int8 [N, K] in {-1, 0, 1}, alpha float32 scalar)."""
+    W = np.asarray(W, dtype=F32)
+    alpha = _mean_abs_f32(W)
+    t = F32(alpha + F32(eps))
+    T = round_clip(W / t, -1, 1).astype(np.int8)
+    return T, F32(alpha)
+
+
+# --------------------------------------------------------------------------
+# activations
+# --------------------------------------------------------------------------
+def quant_int4(X, eps=DEFAULT_EPS):
+    """Q_INT4(X) = beta/sqrt7 * RoundClip(sqrt7/(beta+eps) * X, -8, 7), beta = mean|X|  (eq. 7).
+
+    Per token.  Returns (q int8 [M, K] in [-8, 7], d float32 [M] = beta/sqrt7)."""
+    X = np.asarray(X, dtype=F32)
+    beta = _mean_abs_f32(X, axis=1)                       # [M]
+    s = (SQRT7 / (beta + F32(eps)).astype(F32)).astype(F32)
+    q = round_clip((X * s[:, None]).astype(F32), -8, 7).astype(np.int8)
+    d = (beta / SQRT7).astype(F32)
+    return q, d
+
+
+def topk_mask(X, k_sel):
+    """M = Top_k(|X|) per token  (eq. 1): exactly k_sel ones per row.
+
+    Magnitudes are compared as float32 values (so -0 equals +0); among equal
+    magnitudes the lower channel index wins."""
+    X = np.asarray(X, dtype=F32)
+    M_, K = X.shape
+    assert 1 <= k_sel <= K
+    key = np.abs(X).view(np.uint32).astype(np.int64)      # order-preserving for finite |x|
+    order = np.argsort(-key, axis=1, kind="stable")       # descending, stable -> lower index first
+    mask = np.zeros((M_, K), dtype=bool)
+    np.put_along_axis(mask, order[:, :k_sel], True, axis=1)
+    return mask
+
+
+def quant_int8(X, eps=DEFAULT_EPS):
+    """Q_INT8(X) = gamma/127 * RoundClip(127/(gamma+eps) * X, -128, 127), gamma = max|X|  (eq. 3).
+
+    Per token.  Returns (q int8 [M, K], d float32 [M] = gamma/127)."""
+    X = np.asarray(X, dtype=F32)
+    gamma = np.abs(X).max(axis=1).astype(F32)
+    s = (C127 / (gamma + F32(eps)).astype(F32)).astype(F32)
+    q = round_clip((X * s[:, None]).astype(F32), -128, 127).astype(np.int8)
+    d = (gamma / C127).astype(F32)
+    return q, d
+
+
+def quant_topk_int8(X, k_sel, eps=DEFAULT_EPS):
+    """Q_INT8(X) (.) M with M = Top_k(|X|)  (eq. 1, eq. 3).
+
+    Returns (q int8 [M, K] with zeros outside the mask, d float32 [M], mask bool [M, K])."""
+    q, d = quant_int8(X, eps)
+    mask = topk_mask(X, k_sel)
+    return np.where(mask, q, np.int8(0)).astype(np.int8), d, mask
+
+
+# E2M1 magnitudes by 3-bit code (1 sign, 2 exponent, 1 mantissa bit).
+E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float64)
+FP4_BLOCK = 32
+
+
+def quant_fp4(X):
+    """FP4 (E2M1) MinMax quantizer (eq. 8-9) with one power-of-two scale per
+    block of 32 consecutive channels of a token.
+
+    Reading of eq. 8-9 for power-of-two scales: the bias b is an integer per
+    block, chosen as the largest one for which the block maximum does not clip,
+    i.e. the scale 2^e is the smallest power of two with max|x| / 2^e <= 6.
+    Within a block every value is rounded to the nearest E2M1 value (ties to
+    the even code).  A value that rounds to zero is stored as +0.
+
+    Returns (codes uint8 [M, K] = sign<<3 | code3,  e int16 [M, K/32] block exponents;
+    the E8M0 scale byte is e + 127)."""
+    X = np.asarray(X, dtype=F32)
+    M_, K = X.shape
+    assert K % FP4_BLOCK == 0
+    xb = X.reshape(M_, K // FP4_BLOCK, FP4_BLOCK).astype(np.float64)
+    a = np.abs(xb).max(axis=2)                             # [M, K/32]
+    mant, ex = np.frexp(a)                                 # a = mant * 2^ex, mant in [0.5, 1)
+    # a = (2 mant) * 2^(ex-1);  smallest e with a / 2^e <= 6 = 1.5 * 2^2
+    e = np.where(2.0 * mant <= 1.5, ex - 1 - 2, ex - 1 - 1)
+    e = np.where(a == 0.0, 0, e)
+    e = np.clip(e, -127, 127).astype(np.int64)
+    v = np.ldexp(xb, -e[:, :, None])                       # exact
+    av = np.abs(v)
+    step = np.where(av < 2.0, 0.5, np.where(av < 4.0, 1.0, 2.0))
+    r = np.minimum(np.rint(av / step) * step, 6.0)         # RNE on the local step == ties to even code
+    code3 = np.searchsorted(E2M1_GRID, r).astype(np.uint8)
+    assert np.all(E2M1_GRID[code3] == r)
+    sign = ((v < 0) & (code3 != 0)).astype(np.uint8)
+    codes = (sign << 3 | code3).reshape(M_, K)
+    return codes, e.astype(np.int16)
+
+
+def fp4_dequant(codes, e):
+    """float64 values encoded by quant_fp4's output."""
+    M_, K = codes.shape
+    mag = E2M1_GRID[codes & 7]
+    val = np.where(codes & 8, -mag, mag).reshape(M_, K // FP4_BLOCK, FP4_BLOCK)
+    return np.ldexp(val, e.astype(np.int64)[:, :, None]).reshape(M_, K)
+
+
+# --------------------------------------------------------------------------
+# matmul and rescale
+# --------------------------------------------------------------------------
+def matmul_int(q, T):
+    """acc[m, n] = sum_k q[m, k] * T[n, k], exact integers (int32).
+
+    Evaluated as a float64 matrix product: every partial sum is an integer far
+    below 2^53, so the result is exact whatever the summation order."""
+    acc = q.astype(np.float64) @ T.astype(np.float64).T
+    out = acc.astype(np.int64)
+    assert np.all(out == acc) and np.abs(out).max(initial=0) < 2 ** 31
+    return out.astype(np.int32)
+
+
+def rescale(acc, d, alpha, out_dtype="f32"):
+    """y = (float(acc) * d_m) * alpha, two float32 multiplies in this order;
+    then an optional rounding to bfloat16 (returned as float32 values)."""
+    y = (acc.astype(F32) * np.asarray(d, dtype=F32)[:, None]).astype(F32)
+    y = (y * F32(alpha)).astype(F32)
+    if out_dtype == "bf16":
+        y = bf16_round(y)
+    return y
+
+
+def relu2_glu(g, u):
+    """ReLU^2 GLU combine  h = u (.) ReLU(g)^2  (eq. 5), float32 steps, bf16 result."""
+    g = np.asarray(g, dtype=F32)
+    u = np.asarray(u, dtype=F32)
+    r = np.maximum(g, F32(0))
+    rr = (r * r).astype(F32)
+    return bf16_round((u * rr).astype(F32))
+
+
+# --------------------------------------------------------------------------
+# the linear layers
+# --------------------------------------------------------------------------
+def bitlinear_a4(X, W, eps=DEFAULT_EPS, out_dtype="f32"):
+    """Y = Q_INT4(X) . Q_w(W)^T  (eq. 6).  Returns a dict of every intermediate."""
+    T, alpha = ternarize(W, eps)
+    q, d = quant_int4(X, eps)
+    acc = matmul_int(q, T)
+    return dict(T=T, alpha=alpha, q=q, d=d, acc=acc, y=rescale(acc, d, alpha, out_dtype))
+
+
+def bitlinear_a8_sparse(X, W, k_sel, eps=DEFAULT_EPS, out_dtype="f32"):
+    """Y = (Q_INT8(X) (.) Top_k(|X|)) . Q_w(W)^T  (eq. 1)."""
+    T, alpha = ternarize(W, eps)
+    q, d, mask = quant_topk_int8(X, k_sel, eps)
+    acc = matmul_int(q, T)
+    return dict(T=T, alpha=alpha, q=q, d=d, mask=mask, acc=acc,
+                y=rescale(acc, d, alpha, out_dtype))
+
+
+def bitlinear_fp4(X, W, eps=DEFAULT_EPS):
+    """Y = Q_FP4(X) . Q_w(W)^T, float64 accumulation (the FP4 variant of eq. 6)."""
+    T, alpha = ternarize(W, eps)
+    codes, e = quant_fp4(X)
+    xhat = fp4_dequant(codes, e)
+    y = np.float64(alpha) * (xhat @ T.astype(np.float64).T)
+    return dict(T=T, alpha=alpha, codes=codes, e=e, y=y)
+
+
+def ffn_block(X, W_gate, W_up, W_down, k_sel, eps=DEFAULT_EPS):
+    """One FFN block: INT4 -> gate/up, ReLU^2 GLU, top-k + INT8 -> down."""
+    g = bitlinear_a4(X, W_gate, eps, "f32")
+    u = bitlinear_a4(X, W_up, eps, "f32")
+    h = relu2_glu(g["y"], u["y"])
+    dn = bitlinear_a8_sparse(h, W_down, k_sel, eps, "bf16")
+    return dict(gate=g, up=u, h=h, down=dn)

@@ -1,0 +1,385 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something
+that is not the oracle — hand-worked vectors, closed forms, brute force written
+from the definitions in pure Python / float64, library routines, invariants.
+No GPU needed."""
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+from scipy.stats import norm
+
+from oracle import bitnet_a48 as O
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+GOLD = json.load(open(os.path.join(HERE, "golden", "worked_vectors.json")))
+EPS = 1e-5
+F32 = np.float32
+
+
+def f32(x):
+    return np.float32(x)
+
+
+# ------------------------------------------------------------------ eq. 4
+def test_round_clip_half_even_and_clip():
+    x = np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 7.5, 8.4, -8.5, -9.0, 6.5], dtype=F32)
+    got = O.round_clip(x, -8, 7)
+    assert got.tolist() == [0, 2, 2, -0.0, -2, -2, 7, 7, -8, -8, 6]
+
+
+# ------------------------------------------------------------------ eq. 7
+@pytest.mark.parametrize("case", GOLD["int4"])
+def test_int4_worked_vectors(case):
+    x = np.array([case["x"]], dtype=F32)
+    q, d = O.quant_int4(x, EPS)
+    assert q[0].tolist() == case["q"]
+    assert d[0] == f32(case["d"])
+
+
+def test_int4_range_and_gaussian_closed_form():
+    # Closed form for a Gaussian token: beta = sigma*sqrt(2/pi); code c covers
+    # |x| in [(c-.5), (c+.5)) * beta/sqrt7.  Table 2 of the paper prints
+    # 12.0-12.1 % zeros for the QKV / gate inputs.
+    rng = np.random.default_rng(7)
+    X = rng.standard_normal((256, 8192)).astype(F32) * f32(3.0)
+    q, d = O.quant_int4(X, EPS)
+    assert q.min() == -8 and q.max() == 7
+    unit = math.sqrt(2 / math.pi) / math.sqrt(7)
+    p0 = 2 * norm.cdf(0.5 * unit) - 1
+    p7 = 1 - norm.cdf(6.5 * unit)
+    pm8 = norm.cdf(-7.5 * unit)
+    n = q.size
+    for val, p in ((0, p0), (7, p7), (-8, pm8)):
+        frac = np.mean(q == val)
+        assert abs(frac - p) < 5 * math.sqrt(p * (1 - p) / n) + 2e-4, (val, frac, p)
+    lo, hi = GOLD["table2"]["int4_zero_fraction_percent"]
+    assert lo - 0.1 <= 100 * np.mean(q == 0) <= hi + 0.1
+    # asymmetric clip: +7.6 units -> 7, -7.6 units -> -8
+    assert abs(np.mean(q == -7) - (norm.cdf(-6.5 * unit) - norm.cdf(-7.5 * unit))) < 1e-3
+
+
+def _int4_bruteforce(row):
+    """eq. 7 in exact rationals except for the float32 roundings the reading fixes."""
+    K = len(row)
+    S = sum(abs(Fraction(float(v))) for v in row)
+    beta = f32(float(S / K))
+    s = f32(O.SQRT7 / f32(beta + f32(EPS)))
+    out = []
+    for v in row:
+        p = f32(f32(v) * s)
+        r = round(Fraction(float(p)))          # Python round(): half to even on exact rationals
+        out.append(int(min(max(r, -8), 7)))
+    return out, f32(beta / O.SQRT7)
+
+
+def test_int4_bruteforce_rows():
+    rng = np.random.default_rng(11)
+    X = rng.standard_normal((12, 37)).astype(F32)
+    X[3] *= 50
+    X[5] = 0
+    X[6, :] = 0.25
+    q, d = O.quant_int4(X, EPS)
+    for m in range(X.shape[0]):
+        qb, db = _int4_bruteforce(X[m])
+        assert q[m].tolist() == qb
+        assert d[m] == db
+
+
+def test_int4_is_per_token_and_uniform_step():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((6, 64)).astype(F32)
+    q, d = O.quant_int4(X, EPS)
+    X2 = X.copy()
+    X2[0] *= 100                      # changing one token must not change the others
+    q2, d2 = O.quant_int4(X2, EPS)
+    assert np.array_equal(q[1:], q2[1:]) and np.array_equal(d[1:], d2[1:])
+    # textbook uniform quantizer with step d: unclipped values land within half a step
+    deq = q.astype(np.float64) * d[:, None].astype(np.float64)
+    unclipped = (q > -8) & (q < 7)
+    assert np.all(np.abs(deq - X)[unclipped] <= 0.5 * d[:, None].repeat(64, 1)[unclipped] * (1 + 1e-4))
+    # all-zero token: beta = 0 -> codes 0, scale 0
+    qz, dz = O.quant_int4(np.zeros((1, 16), F32), EPS)
+    assert not qz.any() and dz[0] == 0
+
+
+# ------------------------------------------------------------------ eq. 2
+@pytest.mark.parametrize("case", GOLD["ternary"])
+def test_ternary_worked_vector(case):
+    T, alpha = O.ternarize(np.array(case["W"], dtype=F32), EPS)
+    assert T.tolist() == case["T"]
+    assert alpha == f32(case["alpha"])
+
+
+def test_ternary_closed_form_and_bruteforce():
+    rng = np.random.default_rng(3)
+    W = (0.02 * rng.standard_normal((512, 1024))).astype(F32)
+    T, alpha = O.ternarize(W, EPS)
+    assert set(np.unique(T).tolist()) == {-1, 0, 1}
+    assert abs(float(alpha) - 0.02 * math.sqrt(2 / math.pi)) < 2e-5
+    # zero iff |w| < (alpha+eps)/2 ; Gaussian: P = 2*Phi(0.5*sqrt(2/pi)) - 1 = 31.0 %
+    p0 = 2 * norm.cdf(0.5 * math.sqrt(2 / math.pi)) - 1
+    assert abs(np.mean(T == 0) - p0) < 3e-3
+    assert abs(np.mean(T == 1) - np.mean(T == -1)) < 5e-3
+    # brute force on a small block, exact rationals + the fixed float32 roundings
+    Ws = W[:5, :9]
+    Ts, a = O.ternarize(Ws, EPS)
+    S = sum(abs(Fraction(float(v))) for v in Ws.ravel())
+    a_ref = f32(float(S / Ws.size))
+    assert a == a_ref                                  # the scale is alpha, not alpha + eps
+    t = f32(a_ref + f32(EPS))
+    for i in range(5):
+        for j in range(9):
+            r = round(Fraction(float(f32(Ws[i, j] / t))))
+            assert Ts[i, j] == min(max(r, -1), 1)
+    # sign symmetry
+    Tn, an = O.ternarize(-W, EPS)
+    assert an == alpha and np.array_equal(Tn, -T)
+
+
+# ------------------------------------------------------------------ eq. 1 (Top_k)
+def _topk_bruteforce(row, k):
+    """Rank definition: element i is kept iff fewer than k elements beat it, where j
+    beats i if |x_j| > |x_i|, or |x_j| == |x_i| and j < i."""
+    a = [abs(float(v)) for v in row]
+    keep = []
+    for i in range(len(a)):
+        rank = sum(1 for j in range(len(a)) if a[j] > a[i] or (a[j] == a[i] and j < i))
+        keep.append(rank < k)
+    return keep
+
+
+def test_topk_bruteforce_ties_zeros():
+    rng = np.random.default_rng(9)
+    X = np.round(rng.standard_normal((10, 48)) * 2).astype(F32) / 2      # many ties
+    X[2, ::3] = -0.0
+    X[4] = 1.0                                                            # all equal
+    X[5] = 0.0
+    X[6] = np.eye(1, 48, 17, dtype=F32)[0] * -3                           # one-hot
+    for k in (1, 7, 24, 47, 48):
+        m = O.topk_mask(X, k)
+        assert np.all(m.sum(1) == k)
+        for r in range(X.shape[0]):
+            assert m[r].tolist() == _topk_bruteforce(X[r], k), (r, k)
+    # all-equal row keeps the first k channels; k = K keeps everything
+    assert O.topk_mask(X, 5)[4].tolist() == [True] * 5 + [False] * 43
+    assert O.topk_mask(X, 48).all()
+
+
+def test_topk_half_matches_table2_out_sparsity():
+    X = np.random.default_rng(1).standard_normal((32, 512)).astype(F32)
+    m = O.topk_mask(X, 256)
+    assert 100.0 * (1 - m.mean()) == GOLD["table2"]["out_sparsity_percent"]
+    kept_min = np.where(m, np.abs(X), np.inf).min(1)
+    drop_max = np.where(~m, np.abs(X), -np.inf).max(1)
+    assert np.all(kept_min >= drop_max)
+
+
+# ------------------------------------------------------------------ eq. 3
+@pytest.mark.parametrize("case", GOLD["topk_int8"])
+def test_topk_int8_worked_vectors(case):
+    x = np.array([case["x"]], dtype=F32)
+    q, d, m = O.quant_topk_int8(x, case["k"], EPS)
+    assert m[0].astype(int).tolist() == case["mask"]
+    assert q[0].tolist() == case["q"]
+    assert d[0] == f32(case["d"])
+
+
+def test_int8_properties():
+    rng = np.random.default_rng(2)
+    X = (rng.standard_normal((40, 96)) * rng.uniform(0.01, 30, (40, 1))).astype(F32)
+    q, d = O.quant_int8(X, EPS)
+    assert q.min() >= -127 and q.max() <= 127              # symmetric scale never reaches -128
+    am = np.abs(X).argmax(1)
+    assert np.all(np.abs(q[np.arange(40), am]) == 127)
+    qn, dn = O.quant_int8(-X, EPS)
+    assert np.array_equal(qn, -q) and np.array_equal(dn, d)
+    # textbook per-token absmax INT8 (float64): codes agree except at half-way cases
+    s64 = 127.0 / (np.abs(X).max(1, keepdims=True).astype(np.float64) + EPS)
+    p64 = X.astype(np.float64) * s64
+    far = np.abs(p64 - np.floor(p64) - 0.5) > 1e-3
+    assert np.array_equal(np.rint(p64)[far], q.astype(np.float64)[far])
+    # top-k with k = K is the plain dense INT8 quantizer
+    qk, dk, mk = O.quant_topk_int8(X, 96, EPS)
+    assert mk.all() and np.array_equal(qk, q) and np.array_equal(dk, d)
+    # masked codes are zero, kept codes are unchanged
+    qs, ds, ms = O.quant_topk_int8(X, 48, EPS)
+    assert np.array_equal(qs[ms], q[ms]) and not qs[~ms].any() and np.array_equal(ds, d)
+    assert np.all(ms.sum(1) == 48)
+
+
+# ------------------------------------------------------------------ matmul + rescale
+def test_matmul_int_bruteforce_and_special_cases():
+    rng = np.random.default_rng(4)
+    q = rng.integers(-8, 8, (5, 13)).astype(np.int8)
+    T = rng.integers(-1, 2, (7, 13)).astype(np.int8)
+    acc = O.matmul_int(q, T)
+    assert acc.shape == (5, 7) and acc.dtype == np.int32
+    for m in range(5):
+        for n in range(7):
+            assert acc[m, n] == sum(int(q[m, k]) * int(T[n, k]) for k in range(13))
+    # W == +1 everywhere: every output is the token's code sum
+    ones = np.ones((3, 13), np.int8)
+    assert np.array_equal(O.matmul_int(q, ones), np.repeat(q.sum(1, dtype=np.int32)[:, None], 3, 1))
+    # one-hot token picks a column of T
+    oh = np.zeros((1, 13), np.int8)
+    oh[0, 4] = -5
+    assert np.array_equal(O.matmul_int(oh, T)[0], -5 * T[:, 4].astype(np.int32))
+    # worst-case magnitudes at the largest K stay exact
+    qq = np.full((2, 11008), -128, np.int8)
+    TT = np.full((3, 11008), -1, np.int8)
+    assert np.all(O.matmul_int(qq, TT) == 128 * 11008)
+
+
+def test_bf16_round_matches_torch():
+    rng = np.random.default_rng(6)
+    x = np.concatenate([
+        rng.standard_normal(5000).astype(F32) * 100,
+        np.array([1 + 2 ** -8, 1 + 3 * 2 ** -8, -(1 + 2 ** -8), 0.0, 3.0e38, 1e-40], dtype=F32),
+    ])
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(O.bf16_round(x), ref)
+
+
+def _dense_f64(X_deq, W_deq):
+    return X_deq.astype(np.float64) @ W_deq.astype(np.float64).T
+
+
+def test_bitlinear_a4_against_dense_f64_of_dequantized_operands():
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((9, 40)).astype(F32)
+    W = (0.02 * rng.standard_normal((11, 40))).astype(F32)
+    r = O.bitlinear_a4(X, W, EPS)
+    assert r["y"].shape == (9, 11)
+    Xd = r["q"].astype(np.float64) * r["d"].astype(np.float64)[:, None]
+    Wd = r["T"].astype(np.float64) * np.float64(r["alpha"])
+    ref = _dense_f64(Xd, Wd)
+    assert np.allclose(r["y"], ref, rtol=1e-6, atol=1e-9)
+    # and it approximates the product of the raw activations with the ternary weights
+    full = _dense_f64(X, Wd)
+    cos = (ref * full).sum() / np.linalg.norm(ref) / np.linalg.norm(full)
+    assert cos > 0.97
+    yb = O.bitlinear_a4(X, W, EPS, "bf16")["y"]
+    assert np.array_equal(yb, torch.from_numpy(r["y"]).to(torch.bfloat16).float().numpy())
+
+
+def test_bitlinear_a8_sparse_against_dense_f64():
+    rng = np.random.default_rng(10)
+    X = rng.standard_normal((6, 64)).astype(F32)
+    W = (0.02 * rng.standard_normal((10, 64))).astype(F32)
+    r = O.bitlinear_a8_sparse(X, W, 32, EPS)
+    Xd = np.where(r["mask"], X, 0)                    # sparsify-then-quantize view of eq. 1
+    q_dense, d = O.quant_int8(X, EPS)
+    assert np.array_equal(r["q"], np.where(r["mask"], q_dense, 0))
+    ref = _dense_f64(r["q"].astype(np.float64) * r["d"].astype(np.float64)[:, None],
+                     r["T"].astype(np.float64) * np.float64(r["alpha"]))
+    assert np.allclose(r["y"], ref, rtol=1e-6, atol=1e-9)
+    # INT8 is fine grained: close to the float product of the sparsified input with ternary weights
+    ref2 = _dense_f64(Xd, r["T"].astype(np.float64) * np.float64(r["alpha"]))
+    assert np.abs(ref - ref2).max() < 0.02 * np.abs(ref2).max() + 1e-3
+
+
+def test_relu2_glu():
+    rng = np.random.default_rng(12)
+    g = rng.standard_normal((5, 33)).astype(F32) * 3
+    u = rng.standard_normal((5, 33)).astype(F32) * 3
+    h = O.relu2_glu(g, u)
+    ref = u.astype(np.float64) * np.maximum(g.astype(np.float64), 0) ** 2
+    assert np.all(np.abs(h - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30)       # one bf16 ulp
+    assert np.all(h[g <= 0] == 0)
+    assert np.all((h >= 0) == ((u >= 0) | (g <= 0)) | (h == 0))
+    assert np.array_equal(h, O.bf16_round(h))
+
+
+def test_ffn_block_shapes_and_chain():
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal((4, 32)).astype(F32)
+    Wg = (0.02 * rng.standard_normal((48, 32))).astype(F32)
+    Wu = (0.02 * rng.standard_normal((48, 32))).astype(F32)
+    Wd = (0.02 * rng.standard_normal((32, 48))).astype(F32)
+    r = O.ffn_block(X, Wg, Wu, Wd, 24, EPS)
+    assert r["h"].shape == (4, 48) and r["down"]["y"].shape == (4, 32)
+    assert np.array_equal(r["h"], O.relu2_glu(r["gate"]["y"], r["up"]["y"]))
+    assert np.all(r["down"]["mask"].sum(1) == 24)
+
+
+# ------------------------------------------------------------------ eq. 8-9 (FP4)
+GRID15 = sorted(set([s * v for s in (-1, 1) for v in (0, .5, 1, 1.5, 2, 3, 4, 6)]))
+
+
+def _nearest_e2m1(v):
+    """Nearest E2M1 magnitude, ties to the even code, by distance to all 8 grid points."""
+    grid = [0, .5, 1, 1.5, 2, 3, 4, 6]
+    a = abs(v)
+    best = min(range(8), key=lambda c: (abs(Fraction(a) - Fraction(grid[c])), c % 2))
+    return best
+
+
+def test_fp4_exhaustive_binades_against_nearest_grid_point():
+    # every bf16 magnitude in [2^-4, 8): put 6.0 in the block so the scale is 2^0
+    mags = []
+    for e in range(-4, 3):
+        for m in range(128):
+            mags.append((1 + m / 128.0) * 2.0 ** e)
+    mags = [v for v in mags if v <= 6.0]
+    vals = np.array(mags + [-v for v in mags], dtype=F32)
+    pad = (-len(vals)) % 31
+    vals = np.concatenate([vals, np.zeros(pad, F32)])
+    blocks = vals.reshape(-1, 31)
+    X = np.concatenate([np.full((blocks.shape[0], 1), 6.0, F32), blocks], axis=1)  # [B, 32]
+    codes, e = O.quant_fp4(X)
+    assert np.all(e == 0)
+    for b in range(X.shape[0]):
+        for j in range(32):
+            c = int(codes[b, j])
+            want = _nearest_e2m1(float(X[b, j]))
+            assert (c & 7) == want, (X[b, j], c, want)
+            assert bool(c & 8) == (X[b, j] < 0 and want != 0)
+
+
+def test_fp4_scale_choice_and_invariants():
+    rng = np.random.default_rng(14)
+    X = (rng.standard_normal((16, 128)) * np.exp(rng.uniform(-12, 12, (16, 1)))).astype(F32)
+    X[3, 32:64] = 0
+    codes, e = O.quant_fp4(X)
+    assert codes.max() <= 15
+    deq = O.fp4_dequant(codes, e)
+    a = np.abs(X.astype(np.float64)).reshape(16, 4, 32).max(2)
+    scaled = a / np.exp2(e.astype(np.float64))
+    nz = a > 0
+    assert np.all((scaled[nz] > 3.0) & (scaled[nz] <= 6.0))       # never clips, never wastes a binade
+    assert np.all(e[~nz] == 0) and not codes[3, 32:64].any()
+    # half-a-step accuracy (step = 2 * 2^e at most) and idempotence
+    err = np.abs(deq - X).reshape(16, 4, 32)
+    assert np.all(err <= np.exp2(e.astype(np.float64))[:, :, None] * 1.0 + 1e-300)
+    c2, e2 = O.quant_fp4(deq.astype(F32))                # values already on the grid are kept
+    assert np.array_equal(O.fp4_dequant(c2, e2), deq)
+    # the paper's formula with an integer bias b = floor(log2(12 / max)), E = 2, M = 1
+    Mb = 1
+    for (r, blk) in ((0, 0), (5, 2), (9, 3)):
+        x = X[r, blk * 32:(blk + 1) * 32].astype(np.float64)
+        b = math.floor(math.log2((2 - 2.0 ** -Mb) / np.abs(x).max()) + 2 ** 2 - 1)
+        assert e[r, blk] == 1 - b
+        with np.errstate(divide="ignore"):
+            p = np.maximum(np.floor(np.log2(np.abs(x))) + b, 1)
+        step = np.exp2(p - Mb - b)
+        ref = step * np.rint(x / step)
+        assert np.array_equal(ref, deq[r, blk * 32:(blk + 1) * 32])
+
+
+def test_bitlinear_fp4_against_dense():
+    rng = np.random.default_rng(15)
+    X = rng.standard_normal((5, 64)).astype(F32)
+    W = (0.02 * rng.standard_normal((7, 64))).astype(F32)
+    r = O.bitlinear_fp4(X, W, EPS)
+    # brute-force triple loop in Python floats
+    deq = O.fp4_dequant(r["codes"], r["e"])
+    for m in range(5):
+        for n in range(7):
+            s = math.fsum(float(deq[m, k]) * int(r["T"][n, k]) for k in range(64))
+            assert abs(r["y"][m, n] - float(r["alpha"]) * s) <= 1e-12 * (1 + abs(s))
+    for v in np.unique(deq / np.exp2(r["e"].astype(np.float64)).repeat(32, 1)):
+        assert v in GRID15
