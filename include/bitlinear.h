@@ -1,0 +1,184 @@
+/*
+ * bitlinear.h — C ABI of the MI355X (gfx950) quantized linear layers of BitNet a4.8
+ * (arXiv 2411.04965).
+ *
+ * Notation follows the paper: X activations [M, K] row-major (one token per row),
+ * W latent weights [N, K] row-major (out x in), Y = Q(X) . Q_w(W)^T [M, N] row-major.
+ *
+ * General rules for every entry point
+ *   - All data pointers are DEVICE pointers unless a comment says "host".
+ *   - The caller owns every buffer.  The library never allocates, frees or
+ *     synchronises; every kernel is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns at once.
+ *   - Data pointers must be 16-byte aligned; rows are dense (no strides).
+ *   - Inputs must be finite.  NaN/Inf give unspecified codes, never a trap.
+ *   - Return value: BL_OK (0) or a negative bl_status.  Arguments are validated
+ *     before anything is launched; on error nothing has been enqueued.
+ *   - eps is the epsilon of eq. 2, 3 and 7 (the paper gives no value; 1e-5 is used
+ *     by the tests and the benchmark).
+ *
+ * Packed formats (all little-endian; Kp = bl_padded_k(K) = K rounded up to 256,
+ * Np = N rounded up to 16; padding codes are zero):
+ *
+ *   Ternary code (2 bits, two's complement): 00 = 0, 01 = +1, 11 = -1, 10 unused.
+ *
+ *   BL_W_GEMM   tiles of 16 output channels x 256 input channels, 1024 bytes each,
+ *               stored tile-row major: tile (nt, kt) at byte ((nt * Kp/256) + kt) * 1024.
+ *               Inside a tile, the 16 bytes at offset ((g*16 + i) * 16) hold output
+ *               channel n = 16*nt + i, input channels k0 = 256*kt + 64*g ... k0+63 as four
+ *               32-bit words; word t covers k0 + 16*t ... + 15, and inside a word the
+ *               2-bit field f (bits 2f, 2f+1) holds channel k0 + 16*t + 4*(f%4) + f/4.
+ *   BL_W_KMAJOR input-channel major inside column blocks of 512 outputs (N rounded up to 512):
+ *               the 128 bytes at byte (cb * K + k) * 128 hold outputs 512*cb ... 512*cb+511 of
+ *               input channel k; inside, 32-bit word d holds outputs 512*cb + 16*d ... + 15,
+ *               field f = n % 16.  (K rows only, no K padding.)  Used by the row-skipping
+ *               decode path: one weight row segment is one 128-byte line.
+ *
+ *   INT4 activations  [M][Kp/2] bytes.  Channels are taken 8 at a time into one
+ *               32-bit word; byte b (0..3) of the word is (q[k0+b] & 15) | (q[k0+4+b] << 4).
+ *   INT8 activations  [M][Kp] bytes, plain int8, zeros where the Top_k mask is 0.
+ *   FP4 activations   [M][Kp/2] bytes of E2M1 nibbles (bit 3 sign, bits 2..0 code of
+ *               {0, .5, 1, 1.5, 2, 3, 4, 6}).  Channels are taken 16 at a time into two
+ *               32-bit words; nibble j (bits 4j..4j+3) of word 0 holds channel
+ *               k0 + 8*(j%2) + j/2, nibble j of word 1 holds channel k0 + 4 + 8*(j%2) + j/2.
+ *               Block scales: one E8M0 byte (value 2^(byte-127)) per 32 channels,
+ *               [M][Kp/32] bytes.
+ */
+#ifndef BITLINEAR_H_
+#define BITLINEAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { BL_F32 = 0, BL_BF16 = 1 } bl_dtype;
+
+typedef enum {
+  BL_ACT_INT4_ABSMEAN = 0,     /* eq. 7 */
+  BL_ACT_TOPK_INT8_ABSMAX = 1, /* eq. 1 + eq. 3 */
+  BL_ACT_FP4_E2M1_B32 = 2      /* eq. 8-9 with one power-of-two scale per 32 channels */
+} bl_act_mode;
+
+typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1 } bl_w_layout;
+
+typedef enum {
+  BL_OK = 0,
+  BL_EINVAL = -1,       /* null pointer, bad enum, non-positive size */
+  BL_ESHAPE = -2,       /* size outside what the kernels support */
+  BL_EALIGN = -3,       /* a pointer is not 16-byte aligned */
+  BL_EWORKSPACE = -4,   /* workspace missing or too small */
+  BL_EHIP = -5,         /* a HIP call failed (launch error) */
+  BL_EUNSUPPORTED = -6  /* valid request that this build does not implement */
+} bl_status;
+
+/* Largest sizes accepted: M, N, K >= 1, K <= BL_MAX_K, M*N and N*K below 2^40. */
+#define BL_MAX_K 32768
+
+/* K rounded up to the padding unit of the packed formats (256). */
+int64_t bl_padded_k(int64_t K);
+
+/* ---------------------------------------------------------------- weights (eq. 2)
+ * pack_ternary: alpha = mean|W| over the whole matrix (float64 sum, one rounding to
+ * float32); T = RoundClip(W / (alpha + eps), -1, 1); T is written 2-bit packed in
+ * `layout`; alpha (not alpha + eps) goes to alpha_out[0] (device, float32).
+ *   W          device, [N, K] of w_dtype (BL_F32 or BL_BF16)
+ *   packed_out device, pack_ternary_bytes(N, K, layout) bytes, fully overwritten
+ *   workspace  device, >= pack_ternary_workspace_bytes(N, K) bytes (partial sums)
+ * Offline step (done once per weight matrix). */
+size_t pack_ternary_bytes(int64_t N, int64_t K, bl_w_layout layout);
+size_t pack_ternary_workspace_bytes(int64_t N, int64_t K);
+int pack_ternary(const void* W, bl_dtype w_dtype, int64_t N, int64_t K, float eps,
+                 bl_w_layout layout, void* packed_out, float* alpha_out,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------- activations
+ * quantize_act: one token per row, statistics per token.
+ *   BL_ACT_INT4_ABSMEAN (eq. 7):  beta = mean|x| (float64 sum, rounded once);
+ *       q = RoundClip(x * (sqrt7 / (beta + eps)), -8, 7);  scale_out[m] = beta / sqrt7.
+ *   BL_ACT_TOPK_INT8_ABSMAX (eq. 1, 3): mask = the `topk` largest |x| of the token
+ *       (exactly topk entries; equal magnitudes: lower channel first; 1 <= topk <= K,
+ *       topk = K is the dense INT8 quantizer); gamma = max|x|;
+ *       q = mask ? RoundClip(x * (127 / (gamma + eps)), -128, 127) : 0;
+ *       scale_out[m] = gamma / 127.
+ *   BL_ACT_FP4_E2M1_B32 (eq. 8-9): per block of 32 channels the smallest power of two
+ *       2^e with max|x| / 2^e <= 6 (e = 0 for an all-zero block, clamped to [-127, 127]);
+ *       codes = x / 2^e rounded to the nearest E2M1 value, ties to the even code, zero
+ *       always stored as +0; scale_out = E8M0 bytes (e + 127), [M][Kp/32]; eps unused.
+ *   X           device, [M, K] of x_dtype
+ *   q_out       device, quantize_act_bytes(mode, M, K) bytes, fully overwritten
+ *   scale_out   device, float32[M] (INT modes) or uint8[M * Kp/32] (FP4)
+ *   rowsum_out  nullable; int32[M] = sum of the token's codes (INT modes only)
+ *   sel_idx_out nullable; TOPK mode only: int32[M, topk], the masked channel indices of
+ *               each token in ascending order
+ * Multiplications are single float32 operations (never fused), round() is
+ * round-half-to-even. */
+size_t quantize_act_bytes(bl_act_mode mode, int64_t M, int64_t K);
+int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, bl_act_mode mode,
+                 int64_t topk, float eps, void* q_out, void* scale_out,
+                 int32_t* rowsum_out, int32_t* sel_idx_out, void* stream);
+
+/* ---------------------------------------------------------------- linear layers
+ * bitlinear_a4 (eq. 6): Y = Q_INT4(X) . Q_w(W)^T, or the FP4 variant (act_fp4 = 1).
+ *   acc[m, n] = sum_k q[m, k] * T[n, k]          exact int32 (INT4 path)
+ *   Y[m, n]   = (float(acc) * scale[m]) * alpha  two float32 multiplies, then a
+ *               round-to-nearest-even conversion if y_dtype is BL_BF16.
+ *   FP4 path: Y = alpha * sum over blocks 2^e * sum_k v_k * T[n, k], accumulated in
+ *   float32 by the scaled FP4 matrix instruction (not bit-exact; acc_out must be NULL).
+ *   X          device, [M, K] of x_dtype
+ *   W_packed   device, output of pack_ternary for [N, K]; layout must be BL_W_GEMM
+ *   alpha      device, float32[1]
+ *   Y          device, [M, N] of y_dtype
+ *   acc_out    nullable; device int32[M, N], receives the integer accumulators
+ *   workspace  device, >= bitlinear_workspace_bytes(mode, M, N, K) bytes; holds the
+ *              packed activations and their scales between the two kernels
+ * Kernel choice is by M: up to BL_DECODE_MAX_M tokens the weights are streamed once
+ * by the skinny (decode) kernel, above that the tiled MFMA GEMM runs.
+ *
+ * bitlinear_a8_sparse (eq. 1): Y = (Q_INT8(X) (.) Top_k(|X|)) . Q_w(W)^T, same
+ * accumulation and rescale.  With layout BL_W_KMAJOR (decode, M <= BL_DECODE_MAX_M)
+ * only the weight rows of channels with a non-zero code in at least one token are read.
+ */
+#define BL_DECODE_MAX_M 64
+size_t bitlinear_workspace_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K);
+int bitlinear_a4(const void* X, bl_dtype x_dtype, int64_t M, int64_t K,
+                 const void* W_packed, bl_w_layout layout, const float* alpha, int64_t N,
+                 float eps, int act_fp4, void* Y, bl_dtype y_dtype, int32_t* acc_out,
+                 void* workspace, size_t workspace_bytes, void* stream);
+int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, int64_t topk,
+                        const void* W_packed, bl_w_layout layout, const float* alpha,
+                        int64_t N, float eps, void* Y, bl_dtype y_dtype, int32_t* acc_out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* The matmul + rescale stage alone, on activations already quantized by quantize_act
+ * (what the two calls above run after their quantize kernel).  q and scale are the
+ * outputs of quantize_act in `mode`; for BL_W_KMAJOR, `workspace` must hold
+ * bitlinear_workspace_bytes(mode, M, N, K) bytes, otherwise it may be NULL. */
+int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M, int64_t K,
+                   const void* W_packed, bl_w_layout layout, const float* alpha, int64_t N,
+                   void* Y, bl_dtype y_dtype, int32_t* acc_out,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* ReLU^2 GLU combine (eq. 5): H = bf16(U * max(G, 0)^2), float32 steps in that order.
+ * G, U device [M, N] of in_dtype; H device [M, N] bfloat16. */
+int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,
+              void* H, void* stream);
+
+/* ---------------------------------------------------------------- format helpers
+ * Expand packed data back to one int8 per element so that tests can compare codes
+ * without knowing the byte order: T_out int8[N, K]; codes_out int8[M, K] (INT modes)
+ * or uint8[M, K] E2M1 nibbles (FP4). */
+int unpack_ternary(const void* packed, int64_t N, int64_t K, bl_w_layout layout,
+                   int8_t* T_out, void* stream);
+int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K, int8_t* codes_out,
+               void* stream);
+
+/* Human-readable name of a status code (host pointer to a static string). */
+const char* bl_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITLINEAR_H_ */

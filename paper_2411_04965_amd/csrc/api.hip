@@ -1,0 +1,250 @@
+// C ABI of the library: argument validation and kernel dispatch.  See include/bitlinear.h for
+// the contract of every entry point.
+#include "common.h"
+
+static inline size_t ws_align(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static bool valid_dtype(int d) { return d == BL_F32 || d == BL_BF16; }
+static bool valid_layout(int l) { return l == BL_W_GEMM || l == BL_W_KMAJOR; }
+static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_FP4_E2M1_B32; }
+
+static int check_sizes(int64_t M, int64_t N, int64_t K) {
+  if (M < 1 || N < 1 || K < 1) return BL_EINVAL;
+  if (K > BL_MAX_K) return BL_ESHAPE;
+  const int64_t lim = (int64_t)1 << 40;
+  if (M > lim / N || N > lim / K || M > ((int64_t)1 << 31) - 1 || N > ((int64_t)1 << 31) - 1) return BL_ESHAPE;
+  return BL_OK;
+}
+
+extern "C" int64_t bl_padded_k(int64_t K) { return bl_round_up(K, BL_KPAD); }
+
+extern "C" const char* bl_status_string(int status) {
+  switch (status) {
+    case BL_OK: return "ok";
+    case BL_EINVAL: return "invalid argument";
+    case BL_ESHAPE: return "unsupported size";
+    case BL_EALIGN: return "pointer not 16-byte aligned";
+    case BL_EWORKSPACE: return "workspace missing or too small";
+    case BL_EHIP: return "HIP launch failed";
+    case BL_EUNSUPPORTED: return "not implemented for these arguments";
+    default: return "unknown status";
+  }
+}
+
+// ---------------------------------------------------------------- weights
+extern "C" size_t pack_ternary_bytes(int64_t N, int64_t K, bl_w_layout layout) {
+  if (N < 1 || K < 1) return 0;
+  if (layout == BL_W_GEMM) return (size_t)(bl_round_up(N, 16) * bl_round_up(K, BL_KPAD) / 4);
+  if (layout == BL_W_KMAJOR) return (size_t)(bl_round_up(N, 512) / 4 * K);
+  return 0;
+}
+
+extern "C" int pack_ternary(const void* W, bl_dtype w_dtype, int64_t N, int64_t K, float eps,
+                            bl_w_layout layout, void* packed_out, float* alpha_out,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  if (!W || !packed_out || !alpha_out) return BL_EINVAL;
+  if (!valid_dtype(w_dtype) || !valid_layout(layout) || !(eps >= 0.0f)) return BL_EINVAL;
+  int rc = check_sizes(1, N, K);
+  if (rc) return rc;
+  if (!bl_aligned16(W) || !bl_aligned16(packed_out)) return BL_EALIGN;
+  if (!workspace || workspace_bytes < pack_ternary_workspace_bytes(N, K)) return BL_EWORKSPACE;
+  if (!bl_aligned16(workspace)) return BL_EALIGN;
+  return bl_launch_pack_ternary(W, w_dtype, N, K, eps, layout, packed_out, alpha_out, workspace,
+                                (hipStream_t)stream);
+}
+
+extern "C" int unpack_ternary(const void* packed, int64_t N, int64_t K, bl_w_layout layout,
+                              int8_t* T_out, void* stream) {
+  if (!packed || !T_out || !valid_layout(layout)) return BL_EINVAL;
+  int rc = check_sizes(1, N, K);
+  if (rc) return rc;
+  return bl_launch_unpack_ternary(packed, N, K, layout, T_out, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- activations
+extern "C" size_t quantize_act_bytes(bl_act_mode mode, int64_t M, int64_t K) {
+  if (M < 1 || K < 1) return 0;
+  const int64_t Kp = bl_round_up(K, BL_KPAD);
+  switch (mode) {
+    case BL_ACT_INT4_ABSMEAN: return (size_t)(M * Kp / 2);
+    case BL_ACT_TOPK_INT8_ABSMAX: return (size_t)(M * Kp);
+    case BL_ACT_FP4_E2M1_B32: return (size_t)(M * Kp / 2);
+    default: return 0;
+  }
+}
+
+static size_t act_scale_bytes(bl_act_mode mode, int64_t M, int64_t K) {
+  if (mode == BL_ACT_FP4_E2M1_B32) return (size_t)(M * (bl_round_up(K, BL_KPAD) / 32));
+  return (size_t)M * sizeof(float);
+}
+
+extern "C" int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t K,
+                            bl_act_mode mode, int64_t topk, float eps, void* q_out,
+                            void* scale_out, int32_t* rowsum_out, int32_t* sel_idx_out,
+                            void* stream) {
+  if (!X || !q_out || !scale_out) return BL_EINVAL;
+  if (!valid_dtype(x_dtype) || !valid_mode(mode) || !(eps >= 0.0f)) return BL_EINVAL;
+  int rc = check_sizes(M, 1, K);
+  if (rc) return rc;
+  if (mode == BL_ACT_TOPK_INT8_ABSMAX && (topk < 1 || topk > K)) return BL_EINVAL;
+  if (mode != BL_ACT_TOPK_INT8_ABSMAX && sel_idx_out) return BL_EINVAL;
+  if (mode == BL_ACT_FP4_E2M1_B32 && rowsum_out) return BL_EINVAL;
+  if (!bl_aligned16(X) || !bl_aligned16(q_out)) return BL_EALIGN;
+  return bl_launch_quantize(X, x_dtype, M, K, mode, topk, eps, q_out, scale_out, rowsum_out,
+                            sel_idx_out, (hipStream_t)stream);
+}
+
+extern "C" int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K,
+                          int8_t* codes_out, void* stream) {
+  if (!q || !codes_out || !valid_mode(mode)) return BL_EINVAL;
+  int rc = check_sizes(M, 1, K);
+  if (rc) return rc;
+  return bl_launch_unpack_act(q, mode, M, K, codes_out, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- linear layers
+// Workspace layout: [codes | scales | stage-2 scratch], each part 256-byte aligned.
+static size_t stage2_ws_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K) {
+  if (mode == BL_ACT_FP4_E2M1_B32 || M > BL_DECODE_MAX_M) return 0;
+  size_t a = bl_gemm_decode_ws_bytes(M, N, K);
+  if (mode == BL_ACT_TOPK_INT8_ABSMAX && M <= 8) {
+    const size_t b = bl_gemv_sparse_ws_bytes(M, N, K);
+    if (b > a) a = b;
+  }
+  return a;
+}
+
+extern "C" size_t bitlinear_workspace_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K) {
+  if (!valid_mode(mode) || M < 1 || N < 1 || K < 1) return 0;
+  return ws_align(quantize_act_bytes(mode, M, K)) + ws_align(act_scale_bytes(mode, M, K)) +
+         ws_align(stage2_ws_bytes(mode, M, N, K));
+}
+
+static int gemm_dispatch(const void* q, const void* scale, bl_act_mode mode, int64_t M, int64_t K,
+                         const void* W_packed, bl_w_layout layout, const float* alpha, int64_t N,
+                         void* Y, bl_dtype y_dtype, int32_t* acc_out, void* ws, size_t ws_bytes,
+                         hipStream_t s) {
+  if (mode == BL_ACT_FP4_E2M1_B32) {
+    if (layout != BL_W_GEMM || acc_out) return BL_EINVAL;
+    return bl_launch_gemm_fp4(q, (const uint8_t*)scale, M, K, W_packed, alpha, N, Y, y_dtype, s);
+  }
+  if (layout == BL_W_KMAJOR) {
+    if (mode != BL_ACT_TOPK_INT8_ABSMAX) return BL_EUNSUPPORTED;
+    if (M > 8) return BL_EUNSUPPORTED;
+    if (!ws || ws_bytes < bl_gemv_sparse_ws_bytes(M, N, K)) return BL_EWORKSPACE;
+    return bl_launch_gemv_sparse(q, (const float*)scale, M, K, W_packed, alpha, N, Y, y_dtype,
+                                 acc_out, ws, s);
+  }
+  if (M <= BL_DECODE_MAX_M) {
+    const size_t need = bl_gemm_decode_ws_bytes(M, N, K);
+    if (need && (!ws || ws_bytes < need)) return BL_EWORKSPACE;
+    return bl_launch_gemm_decode(q, (const float*)scale, mode, M, K, W_packed, alpha, N, Y,
+                                 y_dtype, acc_out, ws, s);
+  }
+  return bl_launch_gemm_prefill(q, (const float*)scale, mode, M, K, W_packed, alpha, N, Y,
+                                y_dtype, acc_out, s);
+}
+
+extern "C" int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M,
+                              int64_t K, const void* W_packed, bl_w_layout layout,
+                              const float* alpha, int64_t N, void* Y, bl_dtype y_dtype,
+                              int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  if (!q || !scale || !W_packed || !alpha || !Y) return BL_EINVAL;
+  if (!valid_mode(mode) || !valid_layout(layout) || !valid_dtype(y_dtype)) return BL_EINVAL;
+  int rc = check_sizes(M, N, K);
+  if (rc) return rc;
+  if (!bl_aligned16(q) || !bl_aligned16(W_packed) || !bl_aligned16(Y) ||
+      (acc_out && !bl_aligned16(acc_out)) || (workspace && !bl_aligned16(workspace)))
+    return BL_EALIGN;
+  return gemm_dispatch(q, scale, mode, M, K, W_packed, layout, alpha, N, Y, y_dtype, acc_out,
+                       workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, bl_act_mode mode,
+                         int64_t topk, const void* W_packed, bl_w_layout layout,
+                         const float* alpha, int64_t N, float eps, void* Y, bl_dtype y_dtype,
+                         int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!X || !W_packed || !alpha || !Y) return BL_EINVAL;
+  if (!valid_dtype(x_dtype) || !valid_dtype(y_dtype) || !valid_layout(layout) || !(eps >= 0.0f))
+    return BL_EINVAL;
+  int rc = check_sizes(M, N, K);
+  if (rc) return rc;
+  if (mode == BL_ACT_TOPK_INT8_ABSMAX && (topk < 1 || topk > K)) return BL_EINVAL;
+  if (!bl_aligned16(X) || !bl_aligned16(W_packed) || !bl_aligned16(Y) ||
+      (acc_out && !bl_aligned16(acc_out)))
+    return BL_EALIGN;
+  if (!workspace || workspace_bytes < bitlinear_workspace_bytes(mode, M, N, K)) return BL_EWORKSPACE;
+  if (!bl_aligned16(workspace)) return BL_EALIGN;
+  // reject what the second stage would reject, before the first kernel is enqueued
+  if (mode == BL_ACT_FP4_E2M1_B32 && (layout != BL_W_GEMM || acc_out)) return BL_EINVAL;
+  if (layout == BL_W_KMAJOR && (mode != BL_ACT_TOPK_INT8_ABSMAX || M > 8)) return BL_EUNSUPPORTED;
+
+  unsigned char* p = (unsigned char*)workspace;
+  void* codes = p;
+  p += ws_align(quantize_act_bytes(mode, M, K));
+  void* scales = p;
+  p += ws_align(act_scale_bytes(mode, M, K));
+  void* ws2 = p;
+  const size_t ws2_bytes = workspace_bytes - (size_t)(p - (unsigned char*)workspace);
+  rc = bl_launch_quantize(X, x_dtype, M, K, mode, topk, eps, codes, scales, nullptr, nullptr,
+                          (hipStream_t)stream);
+  if (rc) return rc;
+  return gemm_dispatch(codes, scales, mode, M, K, W_packed, layout, alpha, N, Y, y_dtype, acc_out,
+                       ws2, ws2_bytes, (hipStream_t)stream);
+}
+
+extern "C" int bitlinear_a4(const void* X, bl_dtype x_dtype, int64_t M, int64_t K,
+                            const void* W_packed, bl_w_layout layout, const float* alpha,
+                            int64_t N, float eps, int act_fp4, void* Y, bl_dtype y_dtype,
+                            int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  if (act_fp4 != 0 && act_fp4 != 1) return BL_EINVAL;
+  if (layout != BL_W_GEMM) return valid_layout(layout) ? BL_EUNSUPPORTED : BL_EINVAL;
+  return linear_common(X, x_dtype, M, K, act_fp4 ? BL_ACT_FP4_E2M1_B32 : BL_ACT_INT4_ABSMEAN, 0,
+                       W_packed, layout, alpha, N, eps, Y, y_dtype, acc_out, workspace,
+                       workspace_bytes, stream);
+}
+
+extern "C" int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, int64_t K,
+                                   int64_t topk, const void* W_packed, bl_w_layout layout,
+                                   const float* alpha, int64_t N, float eps, void* Y,
+                                   bl_dtype y_dtype, int32_t* acc_out, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  return linear_common(X, x_dtype, M, K, BL_ACT_TOPK_INT8_ABSMAX, topk, W_packed, layout, alpha,
+                       N, eps, Y, y_dtype, acc_out, workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------- ReLU^2 GLU (eq. 5)
+template <typename RawT>
+__global__ __launch_bounds__(256) void relu2_glu_kernel(const RawT* __restrict__ G,
+                                                        const RawT* __restrict__ U, int64_t n,
+                                                        uint16_t* __restrict__ H) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float g, u;
+  if (sizeof(RawT) == 2) {
+    g = bl_bf16_to_f32((uint16_t)G[i]);
+    u = bl_bf16_to_f32((uint16_t)U[i]);
+  } else {
+    g = __uint_as_float((u32)G[i]);
+    u = __uint_as_float((u32)U[i]);
+  }
+  const float r = fmaxf(g, 0.0f);
+  const float rr = r * r;
+  H[i] = bl_f32_to_bf16_rne(u * rr);
+}
+
+extern "C" int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,
+                         void* H, void* stream) {
+  if (!G || !U || !H || !valid_dtype(in_dtype)) return BL_EINVAL;
+  if (M < 1 || N < 1 || M > ((int64_t)1 << 40) / N) return BL_ESHAPE;
+  const int64_t n = M * N;
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (in_dtype == BL_BF16)
+    relu2_glu_kernel<uint16_t><<<blocks, 256, 0, (hipStream_t)stream>>>((const uint16_t*)G, (const uint16_t*)U, n, (uint16_t*)H);
+  else
+    relu2_glu_kernel<u32><<<blocks, 256, 0, (hipStream_t)stream>>>((const u32*)G, (const u32*)U, n, (uint16_t*)H);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}

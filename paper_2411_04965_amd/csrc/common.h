@@ -1,0 +1,76 @@
+// Shared device/host helpers of the gfx950 BitNet a4.8 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/bitlinear.h"
+
+#define BL_KPAD 256   // K padding unit of every packed format
+#define BL_WAVE 64
+
+#define BL_HIP_CHECK_LAUNCH()                         \
+  do {                                                \
+    if (hipGetLastError() != hipSuccess) return BL_EHIP; \
+  } while (0)
+
+static inline int64_t bl_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+static inline bool bl_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int u32;
+
+// bfloat16 <-> float32 on raw bits.
+__device__ __forceinline__ float bl_bf16_to_f32(uint16_t b) { return __uint_as_float(((u32)b) << 16); }
+__device__ __forceinline__ uint16_t bl_f32_to_bf16_rne(float f) {
+  u32 u = __float_as_uint(f);
+  u32 lsb = (u >> 16) & 1u;
+  return (uint16_t)((u + 0x7FFFu + lsb) >> 16);   // finite inputs only
+}
+
+// Sum over a 64-lane wave (all lanes get the result).
+__device__ __forceinline__ double bl_wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ int bl_wave_sum_i32(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ u32 bl_wave_max_u32(u32 v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    u32 t = (u32)__shfl_xor((int)v, o, 64);
+    v = t > v ? t : v;
+  }
+  return v;
+}
+
+// Internal launchers (one per source file); all return a bl_status.
+int bl_launch_pack_ternary(const void* W, bl_dtype dt, int64_t N, int64_t K, float eps,
+                           bl_w_layout layout, void* out, float* alpha, void* ws, hipStream_t s);
+int bl_launch_unpack_ternary(const void* packed, int64_t N, int64_t K, bl_w_layout layout,
+                             int8_t* T, hipStream_t s);
+int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K, bl_act_mode mode,
+                       int64_t topk, float eps, void* q, void* scale, int32_t* rowsum,
+                       int32_t* sel_idx, hipStream_t s);
+int bl_launch_unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K, int8_t* codes,
+                         hipStream_t s);
+int bl_launch_gemm_prefill(const void* q, const float* scale, bl_act_mode mode, int64_t M,
+                           int64_t K, const void* Wp, const float* alpha, int64_t N, void* Y,
+                           bl_dtype ydt, int32_t* acc_out, hipStream_t s);
+int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, int64_t M,
+                          int64_t K, const void* Wp, const float* alpha, int64_t N, void* Y,
+                          bl_dtype ydt, int32_t* acc_out, void* ws, hipStream_t s);
+size_t bl_gemm_decode_ws_bytes(int64_t M, int64_t N, int64_t K);
+int bl_launch_gemv_sparse(const void* q, const float* scale, int64_t M, int64_t K,
+                          const void* Wk, const float* alpha, int64_t N, void* Y, bl_dtype ydt,
+                          int32_t* acc_out, void* ws, hipStream_t s);
+size_t bl_gemv_sparse_ws_bytes(int64_t M, int64_t N, int64_t K);
+int bl_launch_gemm_fp4(const void* q, const uint8_t* scale, int64_t M, int64_t K, const void* Wp,
+                       const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);
+int bl_launch_relu2_glu(const void* G, const void* U, bl_dtype dt, int64_t n, void* H,
+                        hipStream_t s);

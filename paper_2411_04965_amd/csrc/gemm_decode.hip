@@ -1,0 +1,424 @@
+// Decode-shaped (1..64 tokens) linears: the packed ternary weights are streamed from HBM once.
+//   Dense path  (BL_W_GEMM tiles):   skinny int8-MFMA GEMM, K split over waves and blocks.
+//   Sparse path (BL_W_KMAJOR rows):  eq. 1's sparsity used for I/O — only the weight rows of
+//                                    channels whose INT8 code is non-zero in some token are read.
+// Integer partial sums are exact, so any split of K gives the same accumulators.
+#include "common.h"
+
+#define GD_THREADS 256
+#define GD_BN 64           // outputs per block (4 MFMA tiles of 16)
+
+// ---------------------------------------------------------------- shared epilogue
+__device__ __forceinline__ void gd_store4(void* Y, int y_bf16, int32_t* acc_out, size_t o, int n,
+                                          int N, const int (&iv)[4], float d, float alpha) {
+  float fv[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) fv[r] = ((float)iv[r] * d) * alpha;
+  if ((N & 3) == 0) {
+    if (y_bf16) {
+      uint2 p;
+      p.x = (u32)bl_f32_to_bf16_rne(fv[0]) | ((u32)bl_f32_to_bf16_rne(fv[1]) << 16);
+      p.y = (u32)bl_f32_to_bf16_rne(fv[2]) | ((u32)bl_f32_to_bf16_rne(fv[3]) << 16);
+      *reinterpret_cast<uint2*>((uint16_t*)Y + o) = p;
+    } else {
+      *reinterpret_cast<float4*>((float*)Y + o) = make_float4(fv[0], fv[1], fv[2], fv[3]);
+    }
+    if (acc_out) *reinterpret_cast<int4*>(acc_out + o) = make_int4(iv[0], iv[1], iv[2], iv[3]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if (n + r < N) {
+        if (y_bf16) ((uint16_t*)Y)[o + r] = bl_f32_to_bf16_rne(fv[r]);
+        else ((float*)Y)[o + r] = fv[r];
+        if (acc_out) acc_out[o + r] = iv[r];
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- dense skinny GEMM
+// Block = 4 waves, 64 outputs.  The block's K range is dealt tile by tile (256 channels) to
+// the waves; every wave keeps 4 x MT accumulator tiles, reduced through LDS at the end.
+template <int MT, bool A4>
+__global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
+    const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
+    const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
+    void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out, int32_t* __restrict__ partial,
+    int NB, int S) {
+  extern __shared__ __align__(16) unsigned char gd_smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lg = lane >> 4;
+  const int nb = blockIdx.x % NB, split = blockIdx.x / NB;
+  const int KT = Kp >> 8;
+  const int t_begin = (int)((int64_t)split * KT / S), t_end = (int)((int64_t)(split + 1) * KT / S);
+  const int NT16 = (N + 15) >> 4;
+  constexpr int XV = A4 ? 2 : 4;                 // 16-byte loads per token row per tile
+  const int a_row_bytes = A4 ? (Kp >> 1) : Kp;
+
+  const unsigned char* w_src[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const int nt = min(nb * 4 + a, NT16 - 1);
+    w_src[a] = Wp + (size_t)nt * KT * 1024 + lane * 16;
+  }
+  const unsigned char* x_src[MT];
+#pragma unroll
+  for (int b = 0; b < MT; ++b) {
+    const int row = min(b * 16 + li, M - 1);
+    x_src[b] = A + (size_t)row * a_row_bytes + lg * (A4 ? 32 : 64);
+  }
+
+  v4i acc[4][MT];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < MT; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
+
+  uint4 wr[4], xr[MT][XV];
+  auto load_tile = [&](int t) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) wr[a] = *reinterpret_cast<const uint4*>(w_src[a] + (size_t)t * 1024);
+#pragma unroll
+    for (int b = 0; b < MT; ++b)
+#pragma unroll
+      for (int c = 0; c < XV; ++c)
+        xr[b][c] = *reinterpret_cast<const uint4*>(x_src[b] + (size_t)t * (A4 ? 128 : 256) + c * 16);
+  };
+
+  int t = t_begin + wave;
+  if (t < t_end) load_tile(t);
+  while (t < t_end) {
+    uint4 wc[4], xc[MT][XV];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) wc[a] = wr[a];
+#pragma unroll
+    for (int b = 0; b < MT; ++b)
+#pragma unroll
+      for (int c = 0; c < XV; ++c) xc[b][c] = xr[b][c];
+    const int tn = t + 4;
+    if (tn < t_end) load_tile(tn);                 // prefetch while computing
+#pragma unroll
+    for (int t4 = 0; t4 < 4; ++t4) {
+      v4i xo[MT];
+#pragma unroll
+      for (int b = 0; b < MT; ++b) {
+        if (A4) {
+          // 64 channels = 8 words; MFMA step t4 takes words 2*t4 and 2*t4+1
+          const uint4 v = xc[b][t4 >> 1];
+          const u32 x0 = (t4 & 1) ? v.z : v.x, x1 = (t4 & 1) ? v.w : v.y;
+          xo[b] = (v4i){(int)((x0 << 4) & 0xF0F0F0F0u), (int)(x0 & 0xF0F0F0F0u),
+                        (int)((x1 << 4) & 0xF0F0F0F0u), (int)(x1 & 0xF0F0F0F0u)};
+        } else {
+          const uint4 v = xc[b][t4];
+          xo[b] = (v4i){(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+        }
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const u32 w = t4 == 0 ? wc[a].x : t4 == 1 ? wc[a].y : t4 == 2 ? wc[a].z : wc[a].w;
+        const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
+                             (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo[b], acc[a][b], 0, 0, 0);
+      }
+    }
+    t = tn;
+  }
+
+  // cross-wave reduction: wave w ends up owning output tile a = w
+  v4i* red = reinterpret_cast<v4i*>(gd_smem);     // [wave][a][b][lane]
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < MT; ++b) red[((wave * 4 + a) * MT + b) * 64 + lane] = acc[a][b];
+  __syncthreads();
+  const float alpha = alpha_p[0];
+  constexpr int SHIFT = A4 ? 10 : 6;
+  const int n = nb * GD_BN + wave * 16 + 4 * lg;
+#pragma unroll
+  for (int b = 0; b < MT; ++b) {
+    v4i sum = (v4i){0, 0, 0, 0};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) sum += red[((w * 4 + wave) * MT + b) * 64 + lane];
+    const int m = b * 16 + li;
+    if (m >= M || n >= N) continue;
+    const size_t o = (size_t)m * N + n;
+    if (S == 1) {
+      const int iv[4] = {sum[0] >> SHIFT, sum[1] >> SHIFT, sum[2] >> SHIFT, sum[3] >> SHIFT};
+      gd_store4(Y, y_bf16, acc_out, o, n, N, iv, scale[m], alpha);
+    } else {
+      int32_t* p = partial + (size_t)split * M * N + o;
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (n + r < N) p[r] = sum[r];
+    }
+  }
+}
+
+// Sum S integer partials, shift back, rescale.  One thread per 4 consecutive outputs.
+__global__ __launch_bounds__(GD_THREADS) void decode_reduce_kernel(
+    const int32_t* __restrict__ partial, int S, int M, int N, int shift,
+    const float* __restrict__ scale, const float* __restrict__ alpha_p, void* __restrict__ Y,
+    int y_bf16, int32_t* __restrict__ acc_out) {
+  const int nq = (N + 3) >> 2;
+  const int64_t id = (int64_t)blockIdx.x * GD_THREADS + threadIdx.x;
+  if (id >= (int64_t)M * nq) return;
+  const int m = (int)(id / nq), n = (int)(id % nq) * 4;
+  int iv[4] = {0, 0, 0, 0};
+  for (int s = 0; s < S; ++s) {
+    const int32_t* p = partial + ((size_t)s * M + m) * N + n;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (n + r < N) iv[r] += p[r];
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) iv[r] >>= shift;
+  gd_store4(Y, y_bf16, acc_out, (size_t)m * N + n, n, N, iv, scale[m], alpha_p[0]);
+}
+
+static int gd_pick_split(int NB, int KT) {
+  int S = 1;
+  while (NB * S < 512 && S * 2 <= KT && S < 32) S *= 2;
+  return S;
+}
+
+size_t bl_gemm_decode_ws_bytes(int64_t M, int64_t N, int64_t K) {
+  const int NB = (int)((N + GD_BN - 1) / GD_BN);
+  const int KT = (int)(bl_round_up(K, BL_KPAD) >> 8);
+  const int S = gd_pick_split(NB, KT);
+  return S > 1 ? (size_t)S * M * N * sizeof(int32_t) : 0;
+}
+
+template <int MT, bool A4>
+static int gd_run(const void* q, const float* scale, int M, int Kp, const void* Wp,
+                  const float* alpha, int N, void* Y, bl_dtype ydt, int32_t* acc_out, void* ws,
+                  hipStream_t s) {
+  const int NB = (N + GD_BN - 1) / GD_BN, KT = Kp >> 8;
+  const int S = gd_pick_split(NB, KT);
+  if (S > 1 && !ws) return BL_EWORKSPACE;
+  const size_t smem = (size_t)4 * 4 * MT * 64 * sizeof(v4i);
+  auto kern = gemm_decode_kernel<MT, A4>;
+  if (smem > 48 * 1024 &&
+      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+    return BL_EHIP;
+  const int ybf = ydt == BL_BF16 ? 1 : 0;
+  kern<<<(unsigned)(NB * S), GD_THREADS, smem, s>>>((const unsigned char*)q, scale, M, Kp,
+                                                    (const unsigned char*)Wp, alpha, N, Y, ybf,
+                                                    acc_out, (int32_t*)ws, NB, S);
+  BL_HIP_CHECK_LAUNCH();
+  if (S > 1) {
+    const int64_t n_thr = (int64_t)M * ((N + 3) >> 2);
+    decode_reduce_kernel<<<(unsigned)((n_thr + GD_THREADS - 1) / GD_THREADS), GD_THREADS, 0, s>>>(
+        (const int32_t*)ws, S, M, N, A4 ? 10 : 6, scale, alpha, Y, ybf, acc_out);
+    BL_HIP_CHECK_LAUNCH();
+  }
+  return BL_OK;
+}
+
+int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, int64_t M,
+                          int64_t K, const void* Wp, const float* alpha, int64_t N, void* Y,
+                          bl_dtype ydt, int32_t* acc_out, void* ws, hipStream_t s) {
+  const int Kp = (int)bl_round_up(K, BL_KPAD);
+  const bool a4 = mode == BL_ACT_INT4_ABSMEAN;
+  const int MT = (int)((M + 15) / 16);
+#define GD_CASE(mt)                                                                              \
+  return a4 ? gd_run<mt, true>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)  \
+            : gd_run<mt, false>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)
+  if (MT <= 1) { GD_CASE(1); }
+  if (MT == 2) { GD_CASE(2); }
+  GD_CASE(4);
+#undef GD_CASE
+}
+
+// ---------------------------------------------------------------- sparse row-skipping GEMV
+// Step 1: ascending list of the channels with a non-zero code in at least one token, padded
+// to a multiple of 4 entries (padding repeats a valid channel with code 0), plus, per token,
+// the codes of the listed channels packed 4 to a word.
+#define GS_LIST_THREADS 1024
+__global__ __launch_bounds__(GS_LIST_THREADS) void nz_union_kernel(
+    const int8_t* __restrict__ q, int M, int K, int Kp, int Lmax, int32_t* __restrict__ count_out,
+    int32_t* __restrict__ list, u32* __restrict__ qpack) {
+  __shared__ int wave_cnt[GS_LIST_THREADS / 64];
+  __shared__ int base_sh;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) base_sh = 0;
+  __syncthreads();
+  for (int k0 = 0; k0 < K; k0 += GS_LIST_THREADS) {
+    const int k = k0 + threadIdx.x;
+    bool nz = false;
+    if (k < K)
+      for (int m = 0; m < M; ++m) nz |= q[(size_t)m * Kp + k] != 0;
+    const uint64_t b = __ballot(nz);
+    if (lane == 0) wave_cnt[wave] = __popcll(b);
+    __syncthreads();
+    int before = base_sh;
+    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+    if (nz) list[before + __popcll(b & ((1ull << lane) - 1ull))] = k;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = 0;
+      for (int w = 0; w < GS_LIST_THREADS / 64; ++w) t += wave_cnt[w];
+      base_sh += t;
+    }
+    __syncthreads();
+  }
+  const int L = base_sh;
+  const int Lp = (L + 3) & ~3;
+  if (threadIdx.x == 0) count_out[0] = L;
+  // padding entries: channel 0 with code 0
+  if (threadIdx.x < Lp - L) list[L + threadIdx.x] = -1;
+  __syncthreads();
+  __threadfence_block();
+  for (int i = threadIdx.x; i < M * (Lp >> 2); i += GS_LIST_THREADS) {
+    const int m = i / (Lp >> 2), g = i % (Lp >> 2);
+    u32 word = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = list[4 * g + j];
+      const u32 c = k >= 0 ? (u32)(uint8_t)q[(size_t)m * Kp + k] : 0u;
+      word |= c << (8 * j);
+    }
+    qpack[(size_t)m * (Lmax >> 2) + g] = word;
+  }
+  __syncthreads();
+  if (threadIdx.x < Lp - L) list[L + threadIdx.x] = 0;
+}
+
+// Step 2: block = 4 waves, one 512-output column block and one slice of the channel list.
+// A half wave reads one 128-byte weight row segment per load (32 lanes x 4 bytes); each lane
+// gathers 4 listed rows, byte-transposes the four raw words so that a byte lane holds the
+// four rows of one group of outputs, expands the 2-bit fields, and feeds v_dot4 with the
+// four matching codes.
+template <int MV>
+__global__ __launch_bounds__(GD_THREADS) void gemv_sparse_kernel(
+    const u32* __restrict__ Wk, int Np, int K, const int32_t* __restrict__ count_p,
+    const int32_t* __restrict__ list, const u32* __restrict__ qpack, int Lmax, int M, int S,
+    int32_t* __restrict__ partial) {
+  __shared__ int red[MV][16][32];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, hl = lane & 31;
+  const int CB = Np >> 9;
+  const int cb = blockIdx.x % CB, split = blockIdx.x / CB;
+  const int groups = (count_p[0] + 3) >> 2;               // groups of 4 listed channels
+  const int g_begin = (int)((int64_t)split * groups / S), g_end = (int)((int64_t)(split + 1) * groups / S);
+  const u32* wbase = Wk + (size_t)cb * K * 32 + hl;     // 128-byte row segments of this column block
+
+  int acc[MV][16];
+#pragma unroll
+  for (int m = 0; m < MV; ++m)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[m][j] = 0;
+
+  for (int g = g_begin + wave * 2 + half; g < g_end; g += 8) {
+    u32 w[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) w[r] = wbase[(size_t)list[4 * g + r] * 32];
+    // 4x4 byte transpose: x[b] = byte b of (w0, w1, w2, w3)
+    const u32 t01l = __builtin_amdgcn_perm(w[1], w[0], 0x05010400u);  // w0.b0 w1.b0 w0.b1 w1.b1
+    const u32 t01h = __builtin_amdgcn_perm(w[1], w[0], 0x07030602u);  // w0.b2 w1.b2 w0.b3 w1.b3
+    const u32 t23l = __builtin_amdgcn_perm(w[3], w[2], 0x05010400u);
+    const u32 t23h = __builtin_amdgcn_perm(w[3], w[2], 0x07030602u);
+    u32 x[4];
+    x[0] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
+    x[1] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
+    x[2] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
+    x[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
+    u32 qv[MV];
+#pragma unroll
+    for (int m = 0; m < MV; ++m) qv[m] = m < M ? qpack[(size_t)m * (Lmax >> 2) + g] : 0u;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const u32 tw = (x[b] << (6 - 2 * j)) & 0xC0C0C0C0u;   // rows 0..3 of output 4b+j, times 64
+#pragma unroll
+        for (int m = 0; m < MV; ++m)
+          acc[m][4 * b + j] = __builtin_amdgcn_sdot4((int)tw, (int)qv[m], acc[m][4 * b + j], false);
+      }
+    }
+  }
+  // the two half waves hold different channels of the same outputs
+#pragma unroll
+  for (int m = 0; m < MV; ++m)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[m][j] += __shfl_xor(acc[m][j], 32, 64);
+  // waves 1..3 add into LDS (integer adds: any order gives the same sum), wave 0 finishes
+  for (int i = tid; i < MV * 16 * 32; i += GD_THREADS) (&red[0][0][0])[i] = 0;
+  __syncthreads();
+  if (wave > 0 && half == 0) {
+#pragma unroll
+    for (int m = 0; m < MV; ++m)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) atomicAdd(&red[m][j][hl], acc[m][j]);
+  }
+  __syncthreads();
+  if (wave == 0 && half == 0) {
+#pragma unroll
+    for (int m = 0; m < MV; ++m) {
+      if (m >= M) break;
+      int32_t* p = partial + ((size_t)split * M + m) * Np + cb * 512 + hl * 16;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) p[j] = acc[m][j] + red[m][j][hl];
+    }
+  }
+}
+
+// Partials of the sparse path are [S][M][Np]; reduce + rescale into Y[M][N].
+__global__ __launch_bounds__(GD_THREADS) void sparse_reduce_kernel(
+    const int32_t* __restrict__ partial, int S, int M, int N, int Np,
+    const float* __restrict__ scale, const float* __restrict__ alpha_p, void* __restrict__ Y,
+    int y_bf16, int32_t* __restrict__ acc_out) {
+  const int nq = (N + 3) >> 2;
+  const int64_t id = (int64_t)blockIdx.x * GD_THREADS + threadIdx.x;
+  if (id >= (int64_t)M * nq) return;
+  const int m = (int)(id / nq), n = (int)(id % nq) * 4;
+  int iv[4] = {0, 0, 0, 0};
+  for (int s = 0; s < S; ++s) {
+    const int32_t* p = partial + ((size_t)s * M + m) * Np + n;   // Np is a multiple of 512
+#pragma unroll
+    for (int r = 0; r < 4; ++r) iv[r] += p[r];
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) iv[r] >>= 6;
+  gd_store4(Y, y_bf16, acc_out, (size_t)m * N + n, n, N, iv, scale[m], alpha_p[0]);
+}
+
+#define GS_SPLIT 32
+static inline size_t gs_align(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t bl_gemv_sparse_ws_bytes(int64_t M, int64_t N, int64_t K) {
+  const size_t Np = (size_t)bl_round_up(N, 512), Lmax = (size_t)bl_round_up(K, 4);
+  return gs_align(16) + gs_align(Lmax * 4) + gs_align((size_t)M * Lmax) +
+         gs_align((size_t)GS_SPLIT * M * Np * 4);
+}
+
+int bl_launch_gemv_sparse(const void* q, const float* scale, int64_t M, int64_t K,
+                          const void* Wk, const float* alpha, int64_t N, void* Y, bl_dtype ydt,
+                          int32_t* acc_out, void* ws, hipStream_t s) {
+  if (!ws) return BL_EWORKSPACE;
+  if (M > 8) return BL_EUNSUPPORTED;
+  const int Kp = (int)bl_round_up(K, BL_KPAD), Np = (int)bl_round_up(N, 512);
+  const int Lmax = (int)bl_round_up(K, 4);
+  unsigned char* p = (unsigned char*)ws;
+  int32_t* count = (int32_t*)p;            p += gs_align(16);
+  int32_t* list = (int32_t*)p;             p += gs_align((size_t)Lmax * 4);
+  u32* qpack = (u32*)p;                    p += gs_align((size_t)M * Lmax);
+  int32_t* partial = (int32_t*)p;
+  nz_union_kernel<<<1, GS_LIST_THREADS, 0, s>>>((const int8_t*)q, (int)M, (int)K, Kp, Lmax, count, list, qpack);
+  BL_HIP_CHECK_LAUNCH();
+  const int CB = Np >> 9;
+  const unsigned grid = (unsigned)(CB * GS_SPLIT);
+  if (M <= 1)
+    gemv_sparse_kernel<1><<<grid, GD_THREADS, 0, s>>>((const u32*)Wk, Np, (int)K, count, list, qpack, Lmax, (int)M, GS_SPLIT, partial);
+  else if (M <= 4)
+    gemv_sparse_kernel<4><<<grid, GD_THREADS, 0, s>>>((const u32*)Wk, Np, (int)K, count, list, qpack, Lmax, (int)M, GS_SPLIT, partial);
+  else
+    gemv_sparse_kernel<8><<<grid, GD_THREADS, 0, s>>>((const u32*)Wk, Np, (int)K, count, list, qpack, Lmax, (int)M, GS_SPLIT, partial);
+  BL_HIP_CHECK_LAUNCH();
+  const int64_t n_thr = M * ((N + 3) >> 2);
+  sparse_reduce_kernel<<<(unsigned)((n_thr + GD_THREADS - 1) / GD_THREADS), GD_THREADS, 0, s>>>(
+      partial, GS_SPLIT, (int)M, (int)N, Np, scale, alpha, Y, ydt == BL_BF16 ? 1 : 0, acc_out);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}

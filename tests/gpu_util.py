@@ -1,0 +1,103 @@
+"""Helpers shared by the GPU parity tests (host <-> device plumbing, format decoders).
+
+The decoders below are written from the format description in include/bitlinear.h, in
+numpy, so that packed bytes coming back from the GPU are checked against the documented
+layout and not only against the library's own unpack kernels."""
+import numpy as np
+import torch
+
+from paper_2411_04965_amd import binding as B
+
+EPS = 1e-5
+REL_TOL = 1e-3          # spec tolerance on rescaled outputs
+
+
+def dev(x, dtype=torch.float32):
+    """numpy float32 array -> device tensor (bf16 conversion is exact for bf16-valued data)."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+    return t.to(dtype).contiguous()
+
+
+def host(t):
+    if t.dtype == torch.bfloat16:
+        t = t.float()
+    return t.cpu().numpy()
+
+
+def decode_w_gemm(packed, N, K):
+    """BL_W_GEMM bytes -> int8 [N, K]."""
+    Kp = (K + 255) // 256 * 256
+    Np = (N + 15) // 16 * 16
+    words = np.frombuffer(packed.tobytes(), dtype="<u4").reshape(Np // 16, Kp // 256, 4, 16, 4)
+    # [nt, kt, g, i, t] ; field f of a word holds channel 16 t + 4 (f % 4) + f // 4
+    f = np.arange(16)
+    fields = (words[..., None] >> (2 * f)) & 3                      # [nt, kt, g, i, t, f]
+    T = np.where(fields == 3, -1, fields).astype(np.int8)
+    assert not (fields == 2).any()
+    kk = 4 * (f % 4) + f // 4
+    out = np.zeros((Np // 16, 16, Kp // 256, 4, 4, 16), dtype=np.int8)   # [nt, i, kt, g, t, kk]
+    out[..., kk] = np.transpose(T, (0, 3, 1, 2, 4, 5))
+    full = out.reshape(Np, Kp)
+    assert not full[N:].any() and not full[:, K:].any()
+    return full[:N, :K]
+
+
+def decode_w_kmajor(packed, N, K):
+    """BL_W_KMAJOR bytes -> int8 [N, K]."""
+    Np = (N + 511) // 512 * 512
+    words = np.frombuffer(packed.tobytes(), dtype="<u4").reshape(Np // 512, K, 32)
+    f = np.arange(16)
+    fields = (words[..., None] >> (2 * f)) & 3                      # [cb, k, d, f]
+    assert not (fields == 2).any()
+    T = np.where(fields == 3, -1, fields).astype(np.int8)
+    full = np.transpose(T, (0, 2, 3, 1)).reshape(Np, K)             # n = 512 cb + 16 d + f
+    assert not full[N:].any()
+    return full[:N]
+
+
+def decode_int4(q, M, K):
+    Kp = (K + 255) // 256 * 256
+    b = np.frombuffer(q.tobytes(), dtype=np.uint8).reshape(M, Kp // 8, 4)
+    lo = (b & 15).astype(np.int8)
+    hi = (b >> 4).astype(np.int8)
+    lo = np.where(lo > 7, lo - 16, lo)
+    hi = np.where(hi > 7, hi - 16, hi)
+    full = np.concatenate([lo, hi], axis=2).reshape(M, Kp)         # k0+b then k0+4+b
+    assert not full[:, K:].any()
+    return full[:, :K].astype(np.int8)
+
+
+def decode_int8(q, M, K):
+    Kp = (K + 255) // 256 * 256
+    full = np.frombuffer(q.tobytes(), dtype=np.int8).reshape(M, Kp)
+    assert not full[:, K:].any()
+    return full[:, :K]
+
+
+def decode_fp4(q, M, K):
+    Kp = (K + 255) // 256 * 256
+    words = np.frombuffer(q.tobytes(), dtype="<u4").reshape(M, Kp // 16, 2)
+    j = np.arange(8)
+    nib = (words[..., None] >> (4 * j)) & 15                        # [M, grp, word, j]
+    out = np.zeros((M, Kp // 16, 16), dtype=np.uint8)
+    kk = 8 * (j % 2) + j // 2
+    out[:, :, kk] = nib[:, :, 0, :]
+    out[:, :, 4 + kk] = nib[:, :, 1, :]
+    full = out.reshape(M, Kp)
+    assert not full[:, K:].any()
+    return full[:, :K]
+
+
+def assert_close_rel(y_gpu, y_ref, tol=REL_TOL):
+    """|gpu - ref| <= tol * |ref| element-wise (plus a denormal-sized floor)."""
+    y_gpu = np.asarray(y_gpu, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    err = np.abs(y_gpu - y_ref)
+    bound = tol * np.abs(y_ref) + 1e-30
+    bad = err > bound
+    assert not bad.any(), "max rel err %g at %s" % ((err / (np.abs(y_ref) + 1e-30)).max(),
+                                                     np.argwhere(bad)[:5].tolist())
+
+
+def pack(W, layout=B.BL_W_GEMM, dtype=torch.float32):
+    return B.pack_ternary(dev(W, dtype), EPS, layout)

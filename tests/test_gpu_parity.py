@@ -1,0 +1,292 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer codes, masks, index lists and int32 accumulators must be bit-exact;
+rescaled outputs within 1e-3 relative (they are in fact bit-exact too, which is also checked
+where the rounding order is fixed)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import bitnet_a48 as O
+from paper_2411_04965_amd import binding as B
+from paper_2411_04965_amd import synth as S
+from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_int4, decode_int8,
+                            decode_w_gemm, decode_w_kmajor, dev, host, pack)
+
+pytestmark = pytest.mark.gpu
+BF16 = torch.bfloat16
+F32 = torch.float32
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+# ------------------------------------------------------------------ pack_ternary (eq. 2)
+@pytest.mark.parametrize("N,K,dtype", [(512, 256, F32), (256, 512, F32), (37, 100, F32),
+                                       (1030, 5460, BF16), (2048, 5460, F32)])
+@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_KMAJOR])
+def test_pack_ternary(N, K, dtype, layout):
+    say("pack_ternary N=%d K=%d %s layout=%d" % (N, K, dtype, layout))
+    W = S.latent_weights(N, K, seed=S.seed_for(0, N + K))
+    if dtype == BF16:
+        W = S.snap_bf16(W)
+    T_ref, alpha_ref = O.ternarize(W, EPS)
+    packed, alpha = pack(W, layout, dtype)
+    assert host(alpha)[0] == alpha_ref
+    T_lib = host(B.unpack_ternary(packed, N, K, layout))
+    assert np.array_equal(T_lib, T_ref)
+    dec = decode_w_gemm if layout == B.BL_W_GEMM else decode_w_kmajor
+    assert np.array_equal(dec(host(packed), N, K), T_ref)
+
+
+# ------------------------------------------------------------------ quantize_act
+def _x(kind, M, K, seed, dtype):
+    if kind == "gauss":
+        x = S.gauss_outlier(M, K, max(1, K // 64), 20.0, seed)
+    elif kind == "heavy":
+        x = S.heavy(M, K, seed)
+    elif kind == "glu":
+        x = S.glu_like(M, K, seed)
+    elif kind == "ties":
+        rng = np.random.default_rng(seed)
+        x = (np.round(rng.standard_normal((M, K)) * 2) / 2).astype(np.float32)
+        x[0] = 0
+        x[1 % M] = 1.0
+        x[2 % M, ::3] = -0.0
+    if dtype == BF16:
+        x = S.snap_bf16(x)
+    return x
+
+
+@pytest.mark.parametrize("kind,M,K,dtype", [("gauss", 16, 256, F32), ("heavy", 33, 4096, BF16),
+                                            ("gauss", 7, 5460, BF16), ("ties", 9, 1000, F32),
+                                            ("gauss", 5, 301, BF16), ("heavy", 3, 11008, BF16)])
+def test_quantize_int4(kind, M, K, dtype):
+    say("quantize_act INT4 %s M=%d K=%d %s" % (kind, M, K, dtype))
+    x = _x(kind, M, K, S.seed_for(0, 7 * M + K), dtype)
+    q_ref, d_ref = O.quant_int4(x, EPS)
+    r = B.quantize_act(dev(x, dtype), B.BL_ACT_INT4_ABSMEAN, 0, EPS, want_rowsum=True)
+    assert np.array_equal(host(r["scale"]), d_ref)
+    assert np.array_equal(host(B.unpack_act(r["q"], B.BL_ACT_INT4_ABSMEAN, M, K)), q_ref)
+    assert np.array_equal(decode_int4(host(r["q"]), M, K), q_ref)
+    assert np.array_equal(host(r["rowsum"]), q_ref.sum(1, dtype=np.int32))
+
+
+@pytest.mark.parametrize("kind,M,K,topk,dtype", [
+    ("gauss", 16, 512, 256, F32), ("heavy", 33, 4096, 2048, BF16), ("glu", 9, 5460, 2730, BF16),
+    ("ties", 9, 1000, 500, F32), ("ties", 9, 1000, 1, BF16), ("ties", 9, 1000, 1000, BF16),
+    ("gauss", 5, 301, 77, BF16), ("glu", 4, 11008, 5504, BF16), ("heavy", 2, 8640, 4320, BF16)])
+def test_quantize_topk_int8(kind, M, K, topk, dtype):
+    say("quantize_act TOPK %s M=%d K=%d topk=%d %s" % (kind, M, K, topk, dtype))
+    x = _x(kind, M, K, S.seed_for(0, 11 * M + K + topk), dtype)
+    q_ref, d_ref, mask_ref = O.quant_topk_int8(x, topk, EPS)
+    r = B.quantize_act(dev(x, dtype), B.BL_ACT_TOPK_INT8_ABSMAX, topk, EPS, want_rowsum=True,
+                       want_sel=True)
+    assert np.array_equal(host(r["scale"]), d_ref)
+    q_gpu = decode_int8(host(r["q"]), M, K)
+    assert np.array_equal(q_gpu, q_ref)
+    assert np.array_equal(host(B.unpack_act(r["q"], B.BL_ACT_TOPK_INT8_ABSMAX, M, K)), q_ref)
+    sel = host(r["sel"])
+    assert sel.shape == (M, topk)
+    for m in range(M):                                   # exactly topk channels, ascending
+        assert np.array_equal(sel[m], np.flatnonzero(mask_ref[m]))
+    assert np.array_equal(host(r["rowsum"]), q_ref.sum(1, dtype=np.int32))
+
+
+@pytest.mark.parametrize("kind,M,K,dtype", [("gauss", 16, 256, F32), ("heavy", 20, 3200, BF16),
+                                            ("glu", 6, 8640, BF16), ("ties", 9, 992, F32)])
+def test_quantize_fp4(kind, M, K, dtype):
+    say("quantize_act FP4 %s M=%d K=%d %s" % (kind, M, K, dtype))
+    x = _x(kind, M, K, S.seed_for(4, M + K), dtype)
+    x[M - 1, :32] *= 1e-30                                # tiny block
+    if dtype == BF16:
+        x = S.snap_bf16(x)
+    codes_ref, e_ref = O.quant_fp4(x)
+    r = B.quantize_act(dev(x, dtype), B.BL_ACT_FP4_E2M1_B32)
+    Kp = B.padded_k(K)
+    sc = host(r["scale"]).reshape(M, Kp // 32)
+    assert np.array_equal(sc[:, :K // 32].astype(np.int16) - 127, e_ref)
+    assert np.all(sc[:, K // 32:] == 127)
+    assert np.array_equal(decode_fp4(host(r["q"]), M, K), codes_ref)
+    lib_codes = host(B.unpack_act(r["q"], B.BL_ACT_FP4_E2M1_B32, M, K)).view(np.uint8)
+    assert np.array_equal(lib_codes, codes_ref)
+
+
+# ------------------------------------------------------------------ whole linears
+def _check_linear(res, ref, y_dtype):
+    Y, acc = res
+    assert np.array_equal(host(acc), ref["acc"]), "int32 accumulators differ"
+    assert_close_rel(host(Y), ref["y"])
+    assert np.array_equal(host(Y), ref["y"]), "rescaled output not bit-exact"
+
+
+def test_config0_pair():
+    """Single BitLinear pair: A4 256->512 on 16 tokens, then A8-sparse 512->256 (top-256)."""
+    say("config 0 pair")
+    X = S.gauss_outlier(16, 256, 4, 20.0, S.seed_for(0, 0))
+    W1 = S.latent_weights(512, 256, S.seed_for(0, 1))
+    W2 = S.latent_weights(256, 512, S.seed_for(0, 2))
+    ref1 = O.bitlinear_a4(X, W1, EPS, "f32")
+    p1, a1 = pack(W1)
+    Y1, acc1 = B.bitlinear_a4(dev(X), p1, a1, 512, EPS, y_dtype=F32, want_acc=True)
+    _check_linear((Y1, acc1), ref1, F32)
+    # chained: the sparse linear consumes Y1
+    ref2 = O.bitlinear_a8_sparse(ref1["y"], W2, 256, EPS, "f32")
+    for layout in (B.BL_W_GEMM, B.BL_W_KMAJOR):
+        p2, a2 = pack(W2, layout)
+        if layout == B.BL_W_KMAJOR:
+            res = B.bitlinear_a8_sparse(Y1[:8].contiguous(), 256, p2, a2, 256, EPS, layout, F32, True)
+            sub = dict(acc=ref2["acc"][:8], y=ref2["y"][:8])
+            _check_linear(res, sub, F32)
+        else:
+            res = B.bitlinear_a8_sparse(Y1, 256, p2, a2, 256, EPS, layout, F32, True)
+            _check_linear(res, ref2, F32)
+    # independent sparse input
+    X2 = S.gauss_outlier(16, 512, 8, 20.0, S.seed_for(0, 3))
+    ref3 = O.bitlinear_a8_sparse(X2, W2, 256, EPS, "bf16")
+    p2, a2 = pack(W2)
+    _check_linear(B.bitlinear_a8_sparse(dev(X2), 256, p2, a2, 256, EPS, B.BL_W_GEMM, BF16, True), ref3, BF16)
+    assert np.all((ref3["q"] != 0).sum(1) <= 256) and np.all(ref3["mask"].sum(1) == 256)
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 520, 1000), (130, 2048, 5460), (257, 5460, 2048),
+                                   (1100, 1100, 768)])
+def test_prefill_gemm_shapes(M, N, K):
+    """Several tiles, ragged M / N / K tails, both tile sizes, both activation formats."""
+    say("prefill M=%d N=%d K=%d" % (M, N, K))
+    X = S.heavy(M, K, S.seed_for(1, M + N))
+    W = S.latent_weights(N, K, S.seed_for(1, K + N + 1))
+    p, a = pack(W)
+    ref = O.bitlinear_a4(X, W, EPS, "bf16")
+    _check_linear(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=BF16, want_acc=True), ref, BF16)
+    Xs = S.glu_like(M, K, S.seed_for(1, M + N + 7))
+    ref = O.bitlinear_a8_sparse(Xs, W, K // 2, EPS, "bf16")
+    _check_linear(B.bitlinear_a8_sparse(dev(Xs, BF16), K // 2, p, a, N, EPS, B.BL_W_GEMM, BF16, True), ref, BF16)
+
+
+def test_config1_ffn_block():
+    """One FFN block at 1.3B width: 2048 tokens, 2048 -> 5460 (gate, up), ReLU^2 GLU, top-2730 + INT8 -> 2048."""
+    say("config 1 ffn block")
+    M, H, Fd = 2048, 2048, 5460
+    X = S.heavy(M, H, S.seed_for(1, 0))
+    Wg = S.latent_weights(Fd, H, S.seed_for(1, 1))
+    Wu = S.latent_weights(Fd, H, S.seed_for(1, 2))
+    Wd = S.latent_weights(H, Fd, S.seed_for(1, 3))
+    ref = O.ffn_block(X, Wg, Wu, Wd, Fd // 2, EPS)
+    pg, ag = pack(Wg)
+    pu, au = pack(Wu)
+    pd, ad = pack(Wd)
+    Xd = dev(X, BF16)
+    G, accg = B.bitlinear_a4(Xd, pg, ag, Fd, EPS, y_dtype=F32, want_acc=True)
+    U, accu = B.bitlinear_a4(Xd, pu, au, Fd, EPS, y_dtype=F32, want_acc=True)
+    _check_linear((G, accg), ref["gate"], F32)
+    _check_linear((U, accu), ref["up"], F32)
+    Hh = B.relu2_glu(G, U)
+    assert np.array_equal(host(Hh), ref["h"])
+    Yd, accd = B.bitlinear_a8_sparse(Hh, Fd // 2, pd, ad, H, EPS, B.BL_W_GEMM, BF16, True)
+    _check_linear((Yd, accd), ref["down"], BF16)
+
+
+# ------------------------------------------------------------------ decode shapes (config 2)
+DECODE = [("qkv", 12288, 4096, "a4"), ("o", 4096, 4096, "a8s"), ("gate", 11008, 4096, "a4"),
+          ("down", 4096, 11008, "a8s")]
+_wcache = {}
+
+
+def _decode_weights(name, N, K):
+    if name not in _wcache:
+        W = S.latent_weights(N, K, S.seed_for(2, len(name) + N))
+        T, alpha = O.ternarize(W, EPS)
+        packs = {B.BL_W_GEMM: pack(W)}
+        if name in ("o", "down"):
+            packs[B.BL_W_KMAJOR] = pack(W, B.BL_W_KMAJOR)
+        _wcache[name] = (T, alpha, packs)
+    return _wcache[name]
+
+
+@pytest.mark.parametrize("name,N,K,kind", DECODE)
+@pytest.mark.parametrize("M", [1, 8, 32, 64])
+def test_config2_decode(name, N, K, kind, M):
+    say("config 2 decode %s M=%d" % (name, M))
+    T, alpha, packs = _decode_weights(name, N, K)
+    if kind == "a4":
+        X = S.heavy(M, K, S.seed_for(2, 100 + M))
+        q, d = O.quant_int4(X, EPS)
+    else:
+        X = S.glu_like(M, K, S.seed_for(2, 200 + M)) if name == "down" else S.heavy(M, K, S.seed_for(2, 300 + M))
+        q, d, _ = O.quant_topk_int8(X, K // 2, EPS)
+    acc = O.matmul_int(q, T)
+    ref = dict(acc=acc, y=O.rescale(acc, d, alpha, "bf16"))
+    Xd = dev(X, BF16)
+    for layout, (p, a) in packs.items():
+        if layout == B.BL_W_KMAJOR and M > 8:
+            continue
+        assert host(a)[0] == alpha
+        if kind == "a4":
+            res = B.bitlinear_a4(Xd, p, a, N, EPS, y_dtype=BF16, want_acc=True)
+        else:
+            res = B.bitlinear_a8_sparse(Xd, K // 2, p, a, N, EPS, layout, BF16, True)
+        _check_linear(res, ref, BF16)
+
+
+@pytest.mark.parametrize("M", [3, 17, 48])
+def test_decode_odd_shapes(M):
+    say("decode odd shapes M=%d" % M)
+    N, K = 1000, 1500
+    X = S.heavy(M, K, S.seed_for(2, 400 + M))
+    W = S.latent_weights(N, K, S.seed_for(2, 401))
+    p, a = pack(W)
+    _check_linear(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=F32, want_acc=True),
+                  O.bitlinear_a4(X, W, EPS, "f32"), F32)
+    ref = O.bitlinear_a8_sparse(X, W, 700, EPS, "f32")
+    _check_linear(B.bitlinear_a8_sparse(dev(X, BF16), 700, p, a, N, EPS, B.BL_W_GEMM, F32, True), ref, F32)
+    if M <= 8:
+        pk, ak = pack(W, B.BL_W_KMAJOR)
+        _check_linear(B.bitlinear_a8_sparse(dev(X, BF16), 700, pk, ak, N, EPS, B.BL_W_KMAJOR, F32, True), ref, F32)
+
+
+# ------------------------------------------------------------------ full prefill size (config 3), sampled rows
+@pytest.mark.parametrize("name,N,K,kind", [("qkv", 12288, 4096, "a4"), ("down", 4096, 11008, "a8s")])
+def test_config3_prefill_sampled_rows(name, N, K, kind):
+    """M = 16384 in the launch configuration the benchmark times; the oracle checks 128 sampled
+    token rows in full (all N, full K) plus every activation code of those rows."""
+    say("config 3 prefill %s" % name)
+    M = 16384
+    T, alpha, packs = _decode_weights(name, N, K)
+    p, a = packs[B.BL_W_GEMM]
+    X = S.heavy(M, K, S.seed_for(3, 1)) if kind == "a4" else S.glu_like(M, K, S.seed_for(3, 2))
+    rows = np.random.default_rng(S.seed_for(3, 9)).choice(M, 128, replace=False)
+    rows[:2] = (0, M - 1)
+    Xd = dev(X, BF16)
+    if kind == "a4":
+        Y, acc = B.bitlinear_a4(Xd, p, a, N, EPS, y_dtype=BF16, want_acc=True)
+        q, d = O.quant_int4(X[rows], EPS)
+    else:
+        Y, acc = B.bitlinear_a8_sparse(Xd, K // 2, p, a, N, EPS, B.BL_W_GEMM, BF16, True)
+        q, d, _ = O.quant_topk_int8(X[rows], K // 2, EPS)
+    acc_ref = O.matmul_int(q, T)
+    idx = torch.from_numpy(rows).cuda()
+    assert np.array_equal(host(acc[idx]), acc_ref)
+    y_ref = O.rescale(acc_ref, d, alpha, "bf16")
+    assert_close_rel(host(Y[idx]), y_ref)
+    assert np.array_equal(host(Y[idx]), y_ref)
+
+
+# ------------------------------------------------------------------ error paths (no kernel runs)
+def test_argument_errors():
+    say("argument errors")
+    X = dev(np.zeros((4, 64), np.float32))
+    p, a = pack(S.latent_weights(32, 64, 1))
+    with pytest.raises(B.BitlinearError) as e:
+        B.bitlinear_a8_sparse(X, 0, p, a, 32)
+    assert e.value.status == -1
+    with pytest.raises(B.BitlinearError) as e:
+        B.bitlinear_a8_sparse(X, 65, p, a, 32)
+    assert e.value.status == -1
+    with pytest.raises(B.BitlinearError) as e:
+        B.bitlinear_a4(X, p, a, 32, ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -4
+    with pytest.raises(B.BitlinearError) as e:
+        Xu = torch.zeros(4 * 64 + 4, device="cuda")[1:257].view(4, 64)      # 4-byte offset
+        B.bitlinear_a4(Xu, p, a, 32)
+    assert e.value.status == -3
