@@ -5,8 +5,17 @@
 // Both are expanded to int8 while they are copied into LDS, without sign extension:
 //   an INT4 nibble is moved to the top of its byte  -> 16 * q,
 //   a 2-bit ternary field is moved to the top of its byte -> 64 * T,
-// so the MFMA accumulates 1024 * acc (64 * acc for INT8 activations), which is shifted back
-// exactly in the epilogue.  |1024 * acc| <= 8 * 11008 * 1024 < 2^31.
+// so the MFMA accumulates 1024 * acc (64 * acc for INT8 activations); the factor is a power of
+// two and is folded exactly into the per-token scale in the epilogue.
+// |1024 * acc| <= 8 * K * 1024 < 2^31 for K <= 32768.
+//
+// Block = 4 waves, tile BM x BN, each wave (BM/2) x (BN/2) as 16x16 MFMA tiles; the MFMA's
+// row operand is the weight fragment and its column operand the token fragment, so a lane
+// ends up with 4 consecutive outputs n of one token.  K advances 128 channels per step through
+// two LDS stages.  One step is one straight-line block: the first half multiplies k 0..63
+// while it expands the prefetched global data into the other stage and reads the fragments
+// of the second half; after the barrier the second half multiplies k 64..127 while it issues
+// the global loads two steps ahead and reads the first fragments of the next step.
 #include "common.h"
 
 #define GP_THREADS 256
@@ -24,7 +33,13 @@ __device__ __forceinline__ int gp_lds_off(int row, int chunk) {
   return row * GP_BK + ((chunk ^ (row & 7)) << 4);
 }
 
-template <int BM, int BN, bool A4>
+__device__ __forceinline__ u32 gp_pack_bf16(float lo, float hi) {
+  u32 r;
+  asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+  return r;
+}
+
+template <int BM, int BN, bool A4, bool VEC>
 __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N, void* __restrict__ Y,
@@ -34,6 +49,8 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   constexpr int PA = A4 ? 4 : 8;                 // 16-byte pieces per activation row per stage
   constexpr int LA = BM * PA / GP_THREADS;       // activation loads per thread per stage
   constexpr int LB = BN * 2 / GP_THREADS;        // weight loads per thread per stage
+  constexpr int STAGE = GpSmem<BM, BN>::stage;
+  constexpr int A_BYTES = GpSmem<BM, BN>::a_bytes;
   extern __shared__ __align__(16) unsigned char gp_smem[];
 
   // ---- block -> tile: spread consecutive tiles over one XCD (blocks are dealt round-robin to
@@ -61,145 +78,183 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   const int a_row_bytes = A4 ? (Kp >> 1) : Kp;
   const int nk = Kp / GP_BK;
 
-  // ---- per-thread global source pointers and LDS destinations
-  const unsigned char* a_src[LA];
-  int a_dst[LA];
-#pragma unroll
-  for (int j = 0; j < LA; ++j) {
-    const int idx = tid + GP_THREADS * j;
-    const int cq = idx % PA, row = idx / PA;
-    const int gr = min(m0 + row, M - 1);
-    a_src[j] = A + (size_t)gr * a_row_bytes + cq * 16;
-    a_dst[j] = A4 ? gp_lds_off(row, 2 * cq) : gp_lds_off(row, cq);
-  }
-  const unsigned char* b_src[LB];
-  int b_row[LB], b_gg[LB];
-#pragma unroll
-  for (int j = 0; j < LB; ++j) {
-    const int idx = tid + GP_THREADS * j;
-    const int i = idx & 15, gg = (idx >> 4) & 1, ntl = idx >> 5;
-    const int nt = min((n0 >> 4) + ntl, n_tiles16 - 1);
-    b_src[j] = Wp + ((size_t)nt * k_tiles) * 1024 + (gg * 16 + i) * 16;
-    b_row[j] = ntl * 16 + i;
-    b_gg[j] = gg;
-  }
+  // ---- global sources: one uniform base per operand plus a small per-lane offset that is
+  // rebuilt for every load (two VALU operations) instead of being kept in registers.
+  //   activations: load j of a thread covers row (tid / PA) + RPJ * j, 16-byte piece tid % PA
+  //   weights:     load j covers 16-row tile (tid / 32) + 8 * j, row tid % 16, k-group (tid / 16) % 2
+  constexpr int RPJ = GP_THREADS / PA;
+  constexpr int KSB = A4 ? 64 : 128;             // activation bytes per row per step
+  const unsigned char* a_base = A + (size_t)m0 * a_row_bytes;
+  const u32 a_row0 = tid / PA, a_piece = (tid % PA) * 16;
+  const u32 a_row_max = (u32)(M - 1 - m0);       // rows past the end of X re-read the last row
+  const unsigned char* b_base = Wp + (size_t)(n0 >> 4) * k_tiles * 1024;
+  const u32 b_tile0 = tid >> 5, b_piece = (((tid >> 4) & 1) * 16 + (tid & 15)) * 16;
+  const u32 b_tile_max = (u32)(n_tiles16 - 1 - (n0 >> 4));
+  const u32 b_tile_bytes = (u32)k_tiles * 1024;
+  const int a_dst0 = A4 ? gp_lds_off(a_row0, 2 * (tid % PA)) : gp_lds_off(a_row0, tid % PA);
+  const int b_dst0 = A_BYTES + gp_lds_off(b_tile0 * 16 + (tid & 15), 4 * ((tid >> 4) & 1));
 
   uint4 a_reg[LA], b_reg[LB];
-  auto load_global = [&](int ks) {
-#pragma unroll
-    for (int j = 0; j < LA; ++j)
-      a_reg[j] = *reinterpret_cast<const uint4*>(a_src[j] + (size_t)ks * (A4 ? 64 : 128));
-#pragma unroll
-    for (int j = 0; j < LB; ++j)
-      b_reg[j] = *reinterpret_cast<const uint4*>(b_src[j] + (size_t)(ks >> 1) * 1024 + (ks & 1) * 512);
+  auto load_a = [&](int j, int ks) {
+    const u32 off = min(a_row0 + RPJ * j, a_row_max) * (u32)a_row_bytes + a_piece;
+    a_reg[j] = *reinterpret_cast<const uint4*>(a_base + (size_t)ks * KSB + off);
   };
-  auto store_lds = [&](int stage) {
-    unsigned char* as = gp_smem + stage * GpSmem<BM, BN>::stage;
-    unsigned char* bs = as + GpSmem<BM, BN>::a_bytes;
-#pragma unroll
-    for (int j = 0; j < LA; ++j) {
-      if (A4) {
-        const u32 x[4] = {a_reg[j].x, a_reg[j].y, a_reg[j].z, a_reg[j].w};
-        const int idx = tid + GP_THREADS * j;
-        const int cq = idx % PA, row = idx / PA;
-        uint4 c0, c1;
-        c0.x = (x[0] << 4) & 0xF0F0F0F0u; c0.y = x[0] & 0xF0F0F0F0u;
-        c0.z = (x[1] << 4) & 0xF0F0F0F0u; c0.w = x[1] & 0xF0F0F0F0u;
-        c1.x = (x[2] << 4) & 0xF0F0F0F0u; c1.y = x[2] & 0xF0F0F0F0u;
-        c1.z = (x[3] << 4) & 0xF0F0F0F0u; c1.w = x[3] & 0xF0F0F0F0u;
-        *reinterpret_cast<uint4*>(as + a_dst[j]) = c0;
-        *reinterpret_cast<uint4*>(as + gp_lds_off(row, 2 * cq + 1)) = c1;
-      } else {
-        *reinterpret_cast<uint4*>(as + a_dst[j]) = a_reg[j];
-      }
+  auto load_b = [&](int j, int ks) {
+    const u32 off = min(b_tile0 + 8 * j, b_tile_max) * b_tile_bytes + b_piece;
+    b_reg[j] = *reinterpret_cast<const uint4*>(b_base + (size_t)ks * 512 + off);
+  };
+  // The expansion of one stage is cut into NWR_A + NWR_B single 16-byte LDS writes so that it
+  // can be spread over the MFMA stream.  Rows of load j sit RPJ (resp. 128) rows below those of
+  // load 0, a multiple of 8, so the swizzle is the same and the offset is an immediate.
+  constexpr int NWR_A = A4 ? 2 * LA : LA;
+  constexpr int NWR_B = 4 * LB;
+  auto write_a = [&](unsigned char* st, int i) {
+    if (A4) {
+      const int j = i >> 1;
+      const u32 x0 = (i & 1) ? a_reg[j].z : a_reg[j].x, x1 = (i & 1) ? a_reg[j].w : a_reg[j].y;
+      uint4 c;
+      c.x = (x0 << 4) & 0xF0F0F0F0u; c.y = x0 & 0xF0F0F0F0u;
+      c.z = (x1 << 4) & 0xF0F0F0F0u; c.w = x1 & 0xF0F0F0F0u;
+      *reinterpret_cast<uint4*>(st + j * (RPJ * GP_BK) + (a_dst0 ^ ((i & 1) << 4))) = c;
+    } else {
+      *reinterpret_cast<uint4*>(st + i * (RPJ * GP_BK) + a_dst0) =
+          make_uint4(a_reg[i].x, a_reg[i].y, a_reg[i].z, a_reg[i].w);
     }
-#pragma unroll
-    for (int j = 0; j < LB; ++j) {
-      const u32 w[4] = {b_reg[j].x, b_reg[j].y, b_reg[j].z, b_reg[j].w};
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        uint4 c;
-        c.x = (w[t] << 6) & 0xC0C0C0C0u;
-        c.y = (w[t] << 4) & 0xC0C0C0C0u;
-        c.z = (w[t] << 2) & 0xC0C0C0C0u;
-        c.w = w[t] & 0xC0C0C0C0u;
-        *reinterpret_cast<uint4*>(bs + gp_lds_off(b_row[j], 4 * b_gg[j] + t)) = c;
-      }
-    }
+  };
+  auto write_b = [&](unsigned char* st, int i) {
+    const int j = i >> 2, t = i & 3;
+    const u32 w = t == 0 ? b_reg[j].x : t == 1 ? b_reg[j].y : t == 2 ? b_reg[j].z : b_reg[j].w;
+    uint4 c;
+    c.x = (w << 6) & 0xC0C0C0C0u;
+    c.y = (w << 4) & 0xC0C0C0C0u;
+    c.z = (w << 2) & 0xC0C0C0C0u;
+    c.w = w & 0xC0C0C0C0u;
+    *reinterpret_cast<uint4*>(st + j * (128 * GP_BK) + (b_dst0 ^ (t << 4))) = c;
   };
 
+  // fragment addresses: row = wave base + tile * 16 + li, chunk = 4 * sub + lg
+  const int swz0 = ((lg) ^ (li & 7)) << 4, swz1 = ((4 + lg) ^ (li & 7)) << 4;
+  const int xf_base = (wm * WM + li) * GP_BK;
+  const int wf_base = A_BYTES + (wn * WN + li) * GP_BK;
+  auto read_x = [&](int stage, int sub, int b) -> v4i {
+    return *reinterpret_cast<const v4i*>(gp_smem + stage * STAGE + xf_base + b * (16 * GP_BK) + (sub ? swz1 : swz0));
+  };
+  auto read_w = [&](int stage, int sub, int a) -> v4i {
+    return *reinterpret_cast<const v4i*>(gp_smem + stage * STAGE + wf_base + a * (16 * GP_BK) + (sub ? swz1 : swz0));
+  };
+
+  // Accumulators are pinned to AGPRs and updated in place: the tied "+a" operand keeps the
+  // register allocator from rotating 256 accumulator registers through copies.
   v4i acc[TN][TM];
 #pragma unroll
   for (int a = 0; a < TN; ++a)
 #pragma unroll
     for (int b = 0; b < TM; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
+#define GP_MFMA(C, WF, XF) \
+  asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(C) : "v"(WF), "v"(XF))
 
-  load_global(0);
-  store_lds(0);
+  // ---- prologue: stage 0 <- step 0, registers <- step 1, fragments <- (step 0, first half)
+#pragma unroll
+  for (int j = 0; j < LA; ++j) load_a(j, 0);
+#pragma unroll
+  for (int j = 0; j < LB; ++j) load_b(j, 0);
+#pragma unroll
+  for (int i = 0; i < NWR_A; ++i) write_a(gp_smem, i);
+#pragma unroll
+  for (int i = 0; i < NWR_B; ++i) write_b(gp_smem, i);
+  {
+    const int k1 = min(1, nk - 1);
+#pragma unroll
+    for (int j = 0; j < LA; ++j) load_a(j, k1);
+#pragma unroll
+    for (int j = 0; j < LB; ++j) load_b(j, k1);
+  }
   __syncthreads();
+  // Token fragments are needed by every MFMA row of a half step: two full sets (xf, xg).
+  // Weight fragments are needed by one row only: a ring of 4, read two rows ahead.
+  v4i xf[TM], xg[TM], wr[4];
+#pragma unroll
+  for (int b = 0; b < TM; ++b) xf[b] = read_x(0, 0, b);
+  wr[0] = read_w(0, 0, 0);
+  wr[1] = read_w(0, 0, 1);
 
+  static_assert(TM == TN && (TN == 4 || TN == 8), "the interleaving below assumes a square wave tile");
+  static_assert(NWR_A == TN && NWR_B == TN, "one A write and one B write per MFMA row");
+  constexpr int A_EVERY = TN / LA, B_EVERY = TN / LB;
   for (int ks = 0; ks < nk; ++ks) {
     const int stage = ks & 1;
-    if (ks + 1 < nk) load_global(ks + 1);
-    const unsigned char* as = gp_smem + stage * GpSmem<BM, BN>::stage;
-    const unsigned char* bs = as + GpSmem<BM, BN>::a_bytes;
+    unsigned char* st_other = gp_smem + (stage ^ 1) * STAGE;
+    const int ks2 = min(ks + 2, nk - 1);
+    // first half: k 0..63 of this step.  Per MFMA row: one token fragment of the second half,
+    // the weight fragment two rows ahead, and one activation piece and one weight piece
+    // expanded into the other stage (written in the order in which they were loaded).
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      v4i wf[TN], xf[TM];
+    for (int a = 0; a < TN; ++a) {
+      xg[a] = read_x(stage, 1, a);
+      wr[(a + 2) & 3] = (a + 2 < TN) ? read_w(stage, 0, a + 2) : read_w(stage, 1, a + 2 - TN);
+      write_a(st_other, a);
+      write_b(st_other, a);
 #pragma unroll
-      for (int a = 0; a < TN; ++a)
-        wf[a] = *reinterpret_cast<const v4i*>(bs + gp_lds_off(wn * WN + a * 16 + li, 4 * sub + lg));
-#pragma unroll
-      for (int b = 0; b < TM; ++b)
-        xf[b] = *reinterpret_cast<const v4i*>(as + gp_lds_off(wm * WM + b * 16 + li, 4 * sub + lg));
-#pragma unroll
-      for (int a = 0; a < TN; ++a)
-#pragma unroll
-        for (int b = 0; b < TM; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[a], xf[b], acc[a][b], 0, 0, 0);
+      for (int b = 0; b < TM; ++b) GP_MFMA(acc[a][b], wr[a & 3], xf[b]);
     }
-    if (ks + 1 < nk) store_lds(stage ^ 1);
     __syncthreads();
+    // second half: k 64..127.  Per MFMA row: the global loads whose data the same row of the
+    // next first half will write, one token fragment of the next step, and the weight
+    // fragment two rows ahead (the last two belong to the next step, whose stage is complete
+    // now that the barrier has passed).
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+      if (a % A_EVERY == 0) load_a(a / A_EVERY, ks2);
+      if (a % B_EVERY == 0) load_b(a / B_EVERY, ks2);
+      xf[a] = read_x(stage ^ 1, 0, a);
+      wr[(a + 2) & 3] = (a + 2 < TN) ? read_w(stage, 1, a + 2) : read_w(stage ^ 1, 0, a + 2 - TN);
+#pragma unroll
+      for (int b = 0; b < TM; ++b) GP_MFMA(acc[a][b], wr[a & 3], xg[b]);
+    }
+    // The MFMAs are issued from inline assembly, so the compiler does not know that their
+    // results need wait states before a VALU may read them; the register allocator reads
+    // accumulators right at the loop exit.  16 wait states here cover the last MFMA.
+    asm volatile("s_nop 15" ::: "memory");
   }
+#undef GP_MFMA
 
-  // ---- epilogue: lane holds token m = ... + li and 4 consecutive outputs n = ... + 4*lg + r
+  // ---- epilogue: lane holds token m = ... + li and 4 consecutive outputs n = ... + 4*lg + r.
+  // float(1024 acc) * (d / 1024) rounds exactly like float(acc) * d.
   const float alpha = alpha_p[0];
+  const float unscale = A4 ? (1.0f / 1024.0f) : (1.0f / 64.0f);
   constexpr int SHIFT = A4 ? 10 : 6;
-  const bool vec_ok = (N & 3) == 0;
 #pragma unroll
   for (int b = 0; b < TM; ++b) {
     const int m = m0 + wm * WM + b * 16 + li;
-    if (m >= M) continue;
-    const float d = scale[m];
+    const float d = (m < M ? scale[m] : 0.0f) * unscale;
 #pragma unroll
     for (int a = 0; a < TN; ++a) {
       const int n = n0 + wn * WN + a * 16 + 4 * lg;
-      if (n >= N) continue;
-      int iv[4];
       float fv[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        iv[r] = acc[a][b][r] >> SHIFT;                 // exact: the low bits are zero
-        fv[r] = ((float)iv[r] * d) * alpha;
-      }
+      for (int r = 0; r < 4; ++r) fv[r] = ((float)acc[a][b][r] * d) * alpha;
       const size_t o = (size_t)m * N + n;
-      if (vec_ok) {
-        if (y_bf16) {
-          uint2 p;
-          p.x = (u32)bl_f32_to_bf16_rne(fv[0]) | ((u32)bl_f32_to_bf16_rne(fv[1]) << 16);
-          p.y = (u32)bl_f32_to_bf16_rne(fv[2]) | ((u32)bl_f32_to_bf16_rne(fv[3]) << 16);
-          *reinterpret_cast<uint2*>((uint16_t*)Y + o) = p;
-        } else {
-          *reinterpret_cast<float4*>((float*)Y + o) = make_float4(fv[0], fv[1], fv[2], fv[3]);
+      if (VEC) {
+        if (m < M && n < N) {
+          if (y_bf16) {
+            uint2 p;
+            p.x = gp_pack_bf16(fv[0], fv[1]);
+            p.y = gp_pack_bf16(fv[2], fv[3]);
+            *reinterpret_cast<uint2*>((uint16_t*)Y + o) = p;
+          } else {
+            *reinterpret_cast<float4*>((float*)Y + o) = make_float4(fv[0], fv[1], fv[2], fv[3]);
+          }
+          if (acc_out)
+            *reinterpret_cast<int4*>(acc_out + o) =
+                make_int4(acc[a][b][0] >> SHIFT, acc[a][b][1] >> SHIFT, acc[a][b][2] >> SHIFT, acc[a][b][3] >> SHIFT);
         }
-        if (acc_out) *reinterpret_cast<int4*>(acc_out + o) = make_int4(iv[0], iv[1], iv[2], iv[3]);
       } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          if (n + r < N) {
+          if (m < M && n + r < N) {
             if (y_bf16) ((uint16_t*)Y)[o + r] = bl_f32_to_bf16_rne(fv[r]);
             else ((float*)Y)[o + r] = fv[r];
-            if (acc_out) acc_out[o + r] = iv[r];
+            if (acc_out) acc_out[o + r] = acc[a][b][r] >> SHIFT;
           }
         }
       }
@@ -211,11 +266,12 @@ template <int BM, int BN, bool A4>
 static int gp_launch(const void* q, const float* scale, int M, int Kp, const void* Wp,
                      const float* alpha, int N, void* Y, bl_dtype ydt, int32_t* acc_out,
                      hipStream_t s) {
-  auto kern = gemm_prefill_kernel<BM, BN, A4>;
   constexpr int smem = GpSmem<BM, BN>::total;
+  const int MT = (M + BM - 1) / BM, NTB = (N + BN - 1) / BN;
+  const bool vec = (N & 3) == 0;
+  auto kern = vec ? gemm_prefill_kernel<BM, BN, A4, true> : gemm_prefill_kernel<BM, BN, A4, false>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
     return BL_EHIP;
-  const int MT = (M + BM - 1) / BM, NTB = (N + BN - 1) / BN;
   kern<<<(unsigned)(MT * NTB), GP_THREADS, smem, s>>>(
       (const unsigned char*)q, scale, M, Kp, (const unsigned char*)Wp, alpha, N, Y,
       ydt == BL_BF16 ? 1 : 0, acc_out, MT, NTB);
