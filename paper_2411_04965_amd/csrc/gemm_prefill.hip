@@ -9,16 +9,24 @@
 // two and is folded exactly into the per-token scale in the epilogue.
 // |1024 * acc| <= 8 * K * 1024 < 2^31 for K <= 32768.
 //
-// Block = 4 waves, tile BM x BN, each wave (BM/2) x (BN/2) as 16x16 MFMA tiles; the MFMA's
-// row operand is the weight fragment and its column operand the token fragment, so a lane
-// ends up with 4 consecutive outputs n of one token.  K advances 128 channels per step through
-// two LDS stages.  One step is one straight-line block: the first half multiplies k 0..63
-// while it expands the prefetched global data into the other stage and reads the fragments
-// of the second half; after the barrier the second half multiplies k 64..127 while it issues
-// the global loads two steps ahead and reads the first fragments of the next step.
+// Persistent blocks (one per CU) walk the tile list.  Block = 4 waves, tile BM x BN, each wave
+// (BM/2) x (BN/2) as 16x16 MFMA tiles; the MFMA's row operand is the weight fragment and its
+// column operand the token fragment, so a lane ends up with 4 consecutive outputs n of one
+// token.  K advances 128 channels per step through two LDS stages.  One step is one
+// straight-line block: the first half multiplies k 0..63 while it expands the prefetched
+// global data into the other stage, refills the staging registers from global memory and
+// reads the fragments of the second half; after the barrier the second half multiplies
+// k 64..127 while it reads the first fragments of the next step.  The K stream of a block runs
+// on across its tiles (no per-tile prologue); bf16 outputs leave through a small LDS transpose
+// so that every store instruction writes whole 128-byte lines.
 #include "common.h"
 
 #define GP_THREADS 256
+#ifdef GP_DEBUG_NOSTORE   // experiment: keep the arithmetic, drop (almost) all stores
+#define GP_STORE_COND(c) ((c) && alpha == 12345.0f)
+#else
+#define GP_STORE_COND(c) (c)
+#endif
 #define GP_BK 128     // bytes (= int8 channels) per LDS row per stage
 
 template <int BM, int BN>
@@ -26,7 +34,8 @@ struct GpSmem {
   static constexpr int a_bytes = BM * GP_BK;
   static constexpr int b_bytes = BN * GP_BK;
   static constexpr int stage = a_bytes + b_bytes;
-  static constexpr int total = 2 * stage;
+  static constexpr int tbuf = 4 * 16 * ((BN / 2) * 2 + 32);   // epilogue transpose buffers (4 waves)
+  static constexpr int total = 2 * stage + tbuf;
 };
 
 __device__ __forceinline__ int gp_lds_off(int row, int chunk) {
@@ -39,7 +48,26 @@ __device__ __forceinline__ u32 gp_pack_bf16(float lo, float hi) {
   return r;
 }
 
-template <int BM, int BN, bool A4, bool VEC>
+// Tile index -> tile origin.  Blocks are dealt round-robin to the 8 XCDs, so tiles whose index
+// is congruent mod 8 run on one XCD: give each XCD a contiguous range of the tile order, and
+// walk that order in groups of 4 token tiles, so that the tiles an XCD works on at one time
+// share activations and weights in its L2.
+__device__ __forceinline__ void gp_tile_origin(int t, int n_tiles, int MT, int NTB, int BM, int BN,
+                                               int& m0, int& n0) {
+  const int q = n_tiles >> 3, rmd = n_tiles & 7, xcd = t & 7, loc = t >> 3;
+  const int pid = xcd * q + min(xcd, rmd) + loc;
+  constexpr int GM = 4;
+  const int per_group = GM * NTB;
+  const int group = pid / per_group, in_group = pid % per_group;
+  const int first_m = group * GM;
+  const int gsz = min(MT - first_m, GM);
+  m0 = (first_m + in_group % gsz) * BM;
+  n0 = (in_group / gsz) * BN;
+}
+
+// OUT: 0 = bf16 rows through the LDS transpose (N % 8 == 0), 1 = 4 outputs per store (N % 4 == 0),
+// 2 = one output per store (any N).
+template <int BM, int BN, bool A4, int OUT>
 __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N, void* __restrict__ Y,
@@ -53,23 +81,6 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   constexpr int A_BYTES = GpSmem<BM, BN>::a_bytes;
   extern __shared__ __align__(16) unsigned char gp_smem[];
 
-  // ---- block -> tile: spread consecutive tiles over one XCD (blocks are dealt round-robin to
-  // the 8 XCDs), then walk the tile grid in groups of 4 token tiles so that an XCD's 32
-  // concurrent tiles share activations and weights in its L2.
-  int pid = blockIdx.x;
-  {
-    const int nb = gridDim.x, q = nb >> 3, rmd = nb & 7, xcd = pid & 7, loc = pid >> 3;
-    pid = xcd * q + min(xcd, rmd) + loc;
-  }
-  constexpr int GM = 4;
-  const int per_group = GM * NTB;
-  const int group = pid / per_group, in_group = pid % per_group;
-  const int first_m = group * GM;
-  const int gsz = min(MT - first_m, GM);
-  const int mt = first_m + in_group % gsz;
-  const int ntb = in_group / gsz;
-  const int m0 = mt * BM, n0 = ntb * BN;
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int li = lane & 15, lg = lane >> 4;
@@ -77,59 +88,79 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   const int k_tiles = Kp >> 8;
   const int a_row_bytes = A4 ? (Kp >> 1) : Kp;
   const int nk = Kp / GP_BK;
+  const int n_tiles = MT * NTB;
 
-  // ---- global sources: one uniform base per operand plus a small per-lane offset that is
-  // rebuilt for every load (two VALU operations) instead of being kept in registers.
+  // ---- global sources: one uniform base per operand and tile plus a small per-lane offset.
   //   activations: load j of a thread covers row (tid / PA) + RPJ * j, 16-byte piece tid % PA
   //   weights:     load j covers 16-row tile (tid / 32) + 8 * j, row tid % 16, k-group (tid / 16) % 2
   constexpr int RPJ = GP_THREADS / PA;
   constexpr int KSB = A4 ? 64 : 128;             // activation bytes per row per step
-  const unsigned char* a_base = A + (size_t)m0 * a_row_bytes;
   const u32 a_row0 = tid / PA, a_piece = (tid % PA) * 16;
-  const u32 a_row_max = (u32)(M - 1 - m0);       // rows past the end of X re-read the last row
-  const unsigned char* b_base = Wp + (size_t)(n0 >> 4) * k_tiles * 1024;
   const u32 b_tile0 = tid >> 5, b_piece = (((tid >> 4) & 1) * 16 + (tid & 15)) * 16;
-  const u32 b_tile_max = (u32)(n_tiles16 - 1 - (n0 >> 4));
   const u32 b_tile_bytes = (u32)k_tiles * 1024;
   const int a_dst0 = A4 ? gp_lds_off(a_row0, 2 * (tid % PA)) : gp_lds_off(a_row0, tid % PA);
   const int b_dst0 = A_BYTES + gp_lds_off(b_tile0 * 16 + (tid & 15), 4 * ((tid >> 4) & 1));
+  // Uniform parameters of the tile whose data a global load fetches (the loads run two steps
+  // ahead of the MFMAs and cross into the next tile near the end of a tile):
+  struct TileSrc {
+    const unsigned char* a_base;
+    const unsigned char* b_base;
+    u32 a_row_max, b_tile_max;                   // rows / weight tiles past the end re-read the last one
+  };
+  auto tile_src = [&](int m0, int n0) -> TileSrc {
+    TileSrc t;
+    t.a_base = A + (size_t)m0 * a_row_bytes;
+    t.a_row_max = (u32)(M - 1 - m0);
+    t.b_base = Wp + (size_t)(n0 >> 4) * k_tiles * 1024;
+    t.b_tile_max = (u32)(n_tiles16 - 1 - (n0 >> 4));
+    return t;
+  };
 
   uint4 a_reg[LA], b_reg[LB];
-  auto load_a = [&](int j, int ks) {
-    const u32 off = min(a_row0 + RPJ * j, a_row_max) * (u32)a_row_bytes + a_piece;
-    a_reg[j] = *reinterpret_cast<const uint4*>(a_base + (size_t)ks * KSB + off);
+  auto load_a = [&](const TileSrc& t, int j, int ks) {
+    const u32 off = min(a_row0 + RPJ * j, t.a_row_max) * (u32)a_row_bytes + a_piece;
+    a_reg[j] = *reinterpret_cast<const uint4*>(t.a_base + (size_t)ks * KSB + off);
   };
-  auto load_b = [&](int j, int ks) {
-    const u32 off = min(b_tile0 + 8 * j, b_tile_max) * b_tile_bytes + b_piece;
-    b_reg[j] = *reinterpret_cast<const uint4*>(b_base + (size_t)ks * 512 + off);
+  auto load_b = [&](const TileSrc& t, int j, int ks) {
+    const u32 off = min(b_tile0 + 8 * j, t.b_tile_max) * b_tile_bytes + b_piece;
+    b_reg[j] = *reinterpret_cast<const uint4*>(t.b_base + (size_t)ks * 512 + off);
   };
   // The expansion of one stage is cut into NWR_A + NWR_B single 16-byte LDS writes so that it
   // can be spread over the MFMA stream.  Rows of load j sit RPJ (resp. 128) rows below those of
   // load 0, a multiple of 8, so the swizzle is the same and the offset is an immediate.
   constexpr int NWR_A = A4 ? 2 * LA : LA;
   constexpr int NWR_B = 4 * LB;
+  constexpr u32 MA = 0xF0F0F0F0u, MB = 0xC0C0C0C0u;
+  auto store_a = [&](unsigned char* st, int i, const uint4& c) {
+    if (A4) *reinterpret_cast<uint4*>(st + (i >> 1) * (RPJ * GP_BK) + (a_dst0 ^ ((i & 1) << 4))) = c;
+    else *reinterpret_cast<uint4*>(st + i * (RPJ * GP_BK) + a_dst0) = c;
+  };
+  auto store_b = [&](unsigned char* st, int i, const uint4& c) {
+    *reinterpret_cast<uint4*>(st + (i >> 2) * (128 * GP_BK) + (b_dst0 ^ ((i & 3) << 4))) = c;
+  };
+  auto a_word = [&](int i, int h) -> u32 {      // word h (0, 1) of activation piece i (INT4)
+    const int j = i >> 1;
+    return (i & 1) ? (h ? a_reg[j].w : a_reg[j].z) : (h ? a_reg[j].y : a_reg[j].x);
+  };
+  auto b_word = [&](int i) -> u32 {
+    const int j = i >> 2, t = i & 3;
+    return t == 0 ? b_reg[j].x : t == 1 ? b_reg[j].y : t == 2 ? b_reg[j].z : b_reg[j].w;
+  };
   auto write_a = [&](unsigned char* st, int i) {
+    uint4 c;
     if (A4) {
-      const int j = i >> 1;
-      const u32 x0 = (i & 1) ? a_reg[j].z : a_reg[j].x, x1 = (i & 1) ? a_reg[j].w : a_reg[j].y;
-      uint4 c;
-      c.x = (x0 << 4) & 0xF0F0F0F0u; c.y = x0 & 0xF0F0F0F0u;
-      c.z = (x1 << 4) & 0xF0F0F0F0u; c.w = x1 & 0xF0F0F0F0u;
-      *reinterpret_cast<uint4*>(st + j * (RPJ * GP_BK) + (a_dst0 ^ ((i & 1) << 4))) = c;
+      const u32 x0 = a_word(i, 0), x1 = a_word(i, 1);
+      c.x = (x0 << 4) & MA; c.y = x0 & MA; c.z = (x1 << 4) & MA; c.w = x1 & MA;
     } else {
-      *reinterpret_cast<uint4*>(st + i * (RPJ * GP_BK) + a_dst0) =
-          make_uint4(a_reg[i].x, a_reg[i].y, a_reg[i].z, a_reg[i].w);
+      c = make_uint4(a_reg[i].x, a_reg[i].y, a_reg[i].z, a_reg[i].w);
     }
+    store_a(st, i, c);
   };
   auto write_b = [&](unsigned char* st, int i) {
-    const int j = i >> 2, t = i & 3;
-    const u32 w = t == 0 ? b_reg[j].x : t == 1 ? b_reg[j].y : t == 2 ? b_reg[j].z : b_reg[j].w;
+    const u32 w = b_word(i);
     uint4 c;
-    c.x = (w << 6) & 0xC0C0C0C0u;
-    c.y = (w << 4) & 0xC0C0C0C0u;
-    c.z = (w << 2) & 0xC0C0C0C0u;
-    c.w = w & 0xC0C0C0C0u;
-    *reinterpret_cast<uint4*>(st + j * (128 * GP_BK) + (b_dst0 ^ (t << 4))) = c;
+    c.x = (w << 6) & MB; c.y = (w << 4) & MB; c.z = (w << 2) & MB; c.w = w & MB;
+    store_b(st, i, c);
   };
 
   // fragment addresses: row = wave base + tile * 16 + li, chunk = 4 * sub + lg
@@ -145,30 +176,47 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
 
   // Accumulators are pinned to AGPRs and updated in place: the tied "+a" operand keeps the
   // register allocator from rotating 256 accumulator registers through copies.
-  v4i acc[TN][TM];
-#pragma unroll
-  for (int a = 0; a < TN; ++a)
-#pragma unroll
-    for (int b = 0; b < TM; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
 #define GP_MFMA(C, WF, XF) \
   asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(C) : "v"(WF), "v"(XF))
+  // A wave issues in order, and an MFMA keeps the matrix pipe busy for 16 cycles: up to three
+  // other instructions fit behind each MFMA for free, more than that stalls the pipe.  The
+  // per-row work (fragment reads, expansion, LDS writes, global loads) is therefore cut into
+  // small slots placed between the individual MFMAs of a row.  The empty asm statements pin
+  // a slot's VALU work between two MFMAs: GP_PIN_IN makes an input "change" at that point
+  // (nothing that depends on it can be scheduled earlier), GP_PIN_OUT uses the results
+  // (they cannot be computed later).
+#define GP_PIN_IN(x) asm volatile("" : "+v"(x))
+#define GP_PIN_OUT(x, y) asm volatile("" ::"v"(x), "v"(y))
+  static_assert(TM == TN && (TN == 4 || TN == 8), "the interleaving below assumes a square wave tile");
+  static_assert(NWR_A == TN && NWR_B == TN, "one A write and one B write per MFMA row");
+  constexpr int A_EVERY = TN / LA, B_EVERY = TN / LB;
 
-  // ---- prologue: stage 0 <- step 0, registers <- step 1, fragments <- (step 0, first half)
+  const float alpha = alpha_p[0];
+  const float unscale = A4 ? (1.0f / 1024.0f) : (1.0f / 64.0f);
+  constexpr int SHIFT = A4 ? 10 : 6;
+
+  // LDS after the two stages: one transpose buffer per wave for the epilogue (16 token rows of
+  // the wave's WN outputs as bf16, rows padded by 32 bytes against bank conflicts).
+  constexpr int TB_ROW = WN * 2 + 32;
+  unsigned char* tbuf = gp_smem + 2 * STAGE + wave * (16 * TB_ROW);
+
+  // ---- first tile of this block: stage 0 <- step 0, registers <- step 1, fragments <- step 0
+  int tile = blockIdx.x;
+  int m0, n0;
+  gp_tile_origin(tile, n_tiles, MT, NTB, BM, BN, m0, n0);
+  TileSrc cur = tile_src(m0, n0);
 #pragma unroll
-  for (int j = 0; j < LA; ++j) load_a(j, 0);
+  for (int j = 0; j < LA; ++j) load_a(cur, j, 0);
 #pragma unroll
-  for (int j = 0; j < LB; ++j) load_b(j, 0);
+  for (int j = 0; j < LB; ++j) load_b(cur, j, 0);
 #pragma unroll
   for (int i = 0; i < NWR_A; ++i) write_a(gp_smem, i);
 #pragma unroll
   for (int i = 0; i < NWR_B; ++i) write_b(gp_smem, i);
-  {
-    const int k1 = min(1, nk - 1);
 #pragma unroll
-    for (int j = 0; j < LA; ++j) load_a(j, k1);
+  for (int j = 0; j < LA; ++j) load_a(cur, j, 1);
 #pragma unroll
-    for (int j = 0; j < LB; ++j) load_b(j, k1);
-  }
+  for (int j = 0; j < LB; ++j) load_b(cur, j, 1);
   __syncthreads();
   // Token fragments are needed by every MFMA row of a half step: two full sets (xf, xg).
   // Weight fragments are needed by one row only: a ring of 4, read two rows ahead.
@@ -178,88 +226,253 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   wr[0] = read_w(0, 0, 0);
   wr[1] = read_w(0, 0, 1);
 
-  static_assert(TM == TN && (TN == 4 || TN == 8), "the interleaving below assumes a square wave tile");
-  static_assert(NWR_A == TN && NWR_B == TN, "one A write and one B write per MFMA row");
-  constexpr int A_EVERY = TN / LA, B_EVERY = TN / LB;
-  for (int ks = 0; ks < nk; ++ks) {
-    const int stage = ks & 1;
-    unsigned char* st_other = gp_smem + (stage ^ 1) * STAGE;
-    const int ks2 = min(ks + 2, nk - 1);
-    // first half: k 0..63 of this step.  Per MFMA row: one token fragment of the second half,
-    // the weight fragment two rows ahead, and one activation piece and one weight piece
-    // expanded into the other stage (written in the order in which they were loaded).
-#pragma unroll
-    for (int a = 0; a < TN; ++a) {
-      xg[a] = read_x(stage, 1, a);
-      wr[(a + 2) & 3] = (a + 2 < TN) ? read_w(stage, 0, a + 2) : read_w(stage, 1, a + 2 - TN);
-      write_a(st_other, a);
-      write_b(st_other, a);
-#pragma unroll
-      for (int b = 0; b < TM; ++b) GP_MFMA(acc[a][b], wr[a & 3], xf[b]);
-    }
-    __syncthreads();
-    // second half: k 64..127.  Per MFMA row: the global loads whose data the same row of the
-    // next first half will write, one token fragment of the next step, and the weight
-    // fragment two rows ahead (the last two belong to the next step, whose stage is complete
-    // now that the barrier has passed).
-#pragma unroll
-    for (int a = 0; a < TN; ++a) {
-      if (a % A_EVERY == 0) load_a(a / A_EVERY, ks2);
-      if (a % B_EVERY == 0) load_b(a / B_EVERY, ks2);
-      xf[a] = read_x(stage ^ 1, 0, a);
-      wr[(a + 2) & 3] = (a + 2 < TN) ? read_w(stage, 1, a + 2) : read_w(stage ^ 1, 0, a + 2 - TN);
-#pragma unroll
-      for (int b = 0; b < TM; ++b) GP_MFMA(acc[a][b], wr[a & 3], xg[b]);
-    }
-    // The MFMAs are issued from inline assembly, so the compiler does not know that their
-    // results need wait states before a VALU may read them; the register allocator reads
-    // accumulators right at the loop exit.  16 wait states here cover the last MFMA.
-    asm volatile("s_nop 15" ::: "memory");
-  }
-#undef GP_MFMA
+#ifdef GP_DEBUG_TIMING
+  long long* tlog = (long long*)acc_out + (size_t)blockIdx.x * 64; int tcount = 0; acc_out = nullptr;
+  if (tid == 0) tlog[tcount++] = wall_clock64();
+  unsigned long long bar_sum = 0;
+#endif
+  while (true) {
+    // The K stream runs on across tile boundaries: the loads of the last two steps of a tile
+    // fetch steps 0 and 1 of the block's next tile, so that tile starts with its first stage,
+    // staging registers and fragments already in place (nk is even: stage parity carries over).
+    const int next = tile + (int)gridDim.x;
+    const bool has_next = next < n_tiles;
+    int nm0 = m0, nn0 = n0;
+    if (has_next) gp_tile_origin(next, n_tiles, MT, NTB, BM, BN, nm0, nn0);
+    const TileSrc nxt = tile_src(nm0, nn0);
 
-  // ---- epilogue: lane holds token m = ... + li and 4 consecutive outputs n = ... + 4*lg + r.
-  // float(1024 acc) * (d / 1024) rounds exactly like float(acc) * d.
-  const float alpha = alpha_p[0];
-  const float unscale = A4 ? (1.0f / 1024.0f) : (1.0f / 64.0f);
-  constexpr int SHIFT = A4 ? 10 : 6;
+    v4i acc[TN][TM];
 #pragma unroll
-  for (int b = 0; b < TM; ++b) {
-    const int m = m0 + wm * WM + b * 16 + li;
-    const float d = (m < M ? scale[m] : 0.0f) * unscale;
+    for (int a = 0; a < TN; ++a)
 #pragma unroll
-    for (int a = 0; a < TN; ++a) {
-      const int n = n0 + wn * WN + a * 16 + 4 * lg;
-      float fv[4];
+      for (int b = 0; b < TM; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
+    // Per-token scales of this tile, fetched now: a global load inside the epilogue would have
+    // to wait for the stores issued before it (loads and stores share one counter).
+    float dsc[TM];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) fv[r] = ((float)acc[a][b][r] * d) * alpha;
-      const size_t o = (size_t)m * N + n;
-      if (VEC) {
-        if (m < M && n < N) {
-          if (y_bf16) {
-            uint2 p;
-            p.x = gp_pack_bf16(fv[0], fv[1]);
-            p.y = gp_pack_bf16(fv[2], fv[3]);
-            *reinterpret_cast<uint2*>((uint16_t*)Y + o) = p;
-          } else {
-            *reinterpret_cast<float4*>((float*)Y + o) = make_float4(fv[0], fv[1], fv[2], fv[3]);
-          }
-          if (acc_out)
-            *reinterpret_cast<int4*>(acc_out + o) =
-                make_int4(acc[a][b][0] >> SHIFT, acc[a][b][1] >> SHIFT, acc[a][b][2] >> SHIFT, acc[a][b][3] >> SHIFT);
+    for (int b = 0; b < TM; ++b) {
+      const int m = m0 + wm * WM + b * 16 + li;
+      dsc[b] = (m < M ? scale[m] : 0.0f) * unscale;
+    }
+
+    for (int ks = 0; ks < nk; ++ks) {
+      const int stage = ks & 1;
+      unsigned char* st_other = gp_smem + (stage ^ 1) * STAGE;
+      // target of this step's global loads: two steps ahead
+      const bool wrap = ks + 2 >= nk;
+      const int ks2 = wrap ? (has_next ? ks + 2 - nk : nk - 1) : ks + 2;
+      TileSrc ld;
+      ld.a_base = (wrap && has_next) ? nxt.a_base : cur.a_base;
+      ld.b_base = (wrap && has_next) ? nxt.b_base : cur.b_base;
+      ld.a_row_max = (wrap && has_next) ? nxt.a_row_max : cur.a_row_max;
+      ld.b_tile_max = (wrap && has_next) ? nxt.b_tile_max : cur.b_tile_max;
+      // first half: k 0..63 of this step.  Per MFMA row: one token fragment of the second
+      // half, the weight fragment two rows ahead, one activation piece and one weight piece
+      // expanded into the other stage, and the global loads that refill the registers just
+      // consumed (a full step, 2048 MFMA cycles, before their data is expanded).
+#pragma unroll
+      for (int a = 0; a < TN; ++a) {
+        uint4 ca, cb;
+        u32 x0 = 0, x1 = 0, w = b_word(a);
+        if (A4) {
+          x0 = a_word(a, 0);
+          x1 = a_word(a, 1);
         }
-      } else {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (m < M && n + r < N) {
-            if (y_bf16) ((uint16_t*)Y)[o + r] = bl_f32_to_bf16_rne(fv[r]);
-            else ((float*)Y)[o + r] = fv[r];
-            if (acc_out) acc_out[o + r] = acc[a][b][r] >> SHIFT;
+        for (int b = 0; b < TM; ++b) {
+          GP_MFMA(acc[a][b], wr[a & 3], xf[b]);
+          const int slot = (TM == 8) ? b : 2 * b;    // 8 slots per row; a 4-MFMA row takes two at a time
+          if (slot == 0) {
+            xg[a] = read_x(stage, 1, a);
+            wr[(a + 2) & 3] = (a + 2 < TN) ? read_w(stage, 0, a + 2) : read_w(stage, 1, a + 2 - TN);
+          }
+          if (A4) {
+            if (slot == 1 || (TM == 4 && slot == 2)) {
+              GP_PIN_IN(x0);
+              ca.x = (x0 << 4) & MA; ca.y = x0 & MA;
+              GP_PIN_OUT(ca.x, ca.y);
+            }
+            if (slot == 2) {
+              GP_PIN_IN(x1);
+              ca.z = (x1 << 4) & MA; ca.w = x1 & MA;
+              GP_PIN_OUT(ca.z, ca.w);
+            }
+          } else if (slot == 2) {
+            ca = make_uint4(a_reg[a].x, a_reg[a].y, a_reg[a].z, a_reg[a].w);
+          }
+          if (slot == 3 || (TM == 4 && slot == 2)) store_a(st_other, a, ca);
+          if (slot == 4) {
+            GP_PIN_IN(w);
+            cb.x = (w << 6) & MB; cb.y = (w << 4) & MB;
+            GP_PIN_OUT(cb.x, cb.y);
+          }
+          if (slot == 5 || (TM == 4 && slot == 4)) {
+            GP_PIN_IN(w);
+            cb.z = (w << 2) & MB; cb.w = w & MB;
+            GP_PIN_OUT(cb.z, cb.w);
+          }
+          if (slot == 6) store_b(st_other, a, cb);
+          if (slot == 7 || (TM == 4 && slot == 6)) {
+            if (a % A_EVERY == A_EVERY - 1) load_a(ld, a / A_EVERY, ks2);
+            if (a % B_EVERY == B_EVERY - 1) load_b(ld, a / B_EVERY, ks2);
+          }
+        }
+      }
+#ifdef GP_DEBUG_TIMING
+      const unsigned long long tb0 = __builtin_amdgcn_s_memtime();
+#endif
+      __syncthreads();
+#ifdef GP_DEBUG_TIMING
+      const unsigned long long tb1 = __builtin_amdgcn_s_memtime();
+#endif
+      // second half: k 64..127.  Per MFMA row: one token fragment of the next step and the
+      // weight fragment two rows ahead (the last two belong to the next step, whose stage is
+      // complete now that the barrier has passed).
+#pragma unroll
+      for (int a = 0; a < TN; ++a) {
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+          GP_MFMA(acc[a][b], wr[a & 3], xg[b]);
+          if (b == 0) {
+            xf[a] = read_x(stage ^ 1, 0, a);
+            wr[(a + 2) & 3] = (a + 2 < TN) ? read_w(stage, 1, a + 2) : read_w(stage ^ 1, 0, a + 2 - TN);
+          }
+        }
+      }
+      // The MFMAs are issued from inline assembly, so the compiler does not know that their
+      // results need wait states before a VALU may read them; the register allocator reads
+      // accumulators right at the loop exit.  16 wait states here cover the last MFMA.
+      asm volatile("s_nop 15" ::: "memory");
+#ifdef GP_DEBUG_TIMING
+      bar_sum += tb1 - tb0;
+#endif
+    }
+#ifdef GP_DEBUG_TIMING
+    if (tid == 0 && tcount < 60) tlog[tcount++] = (long long)bar_sum;
+    if (tid == 0 && tcount < 60) tlog[tcount++] = (long long)__builtin_amdgcn_s_memtime();
+#endif
+
+#ifdef GP_DEBUG_TIMING
+    if (tid == 0 && tcount < 60) tlog[tcount++] = wall_clock64();
+#endif
+    // The staging registers already hold the next tile's step 1: make their loads complete
+    // here, before the epilogue's stores join the same counter.
+#pragma unroll
+    for (int j = 0; j < LA; ++j) asm volatile("" ::"v"(a_reg[j].x), "v"(a_reg[j].y), "v"(a_reg[j].z), "v"(a_reg[j].w));
+#pragma unroll
+    for (int j = 0; j < LB; ++j) asm volatile("" ::"v"(b_reg[j].x), "v"(b_reg[j].y), "v"(b_reg[j].z), "v"(b_reg[j].w));
+    // ---- epilogue: lane holds token m = ... + li and 4 consecutive outputs n = ... + 4*lg + r.
+    // float(1024 acc) * (d / 1024) rounds exactly like float(acc) * d.  The output path is
+    // chosen once, outside the unrolled tile loops, to keep the code small.
+    if (OUT == 0) {
+      // bf16 through the wave's transpose buffer, 16 tokens x WN outputs at a time; read back
+      // row-wise, 16 lanes cover one token's WN * 2 contiguous bytes, so every store
+      // instruction writes whole 128-byte lines
+      constexpr int LANES_PER_ROW = WN * 2 / 16;           // 16 (WN = 128) or 8 (WN = 64)
+      constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+      const int rr = lane / LANES_PER_ROW, cc = lane % LANES_PER_ROW;
+      const int gn = n0 + wn * WN + cc * 8;
+#pragma unroll
+      for (int b = 0; b < TM; ++b) {
+        const float d = dsc[b];
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+          float fv[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) fv[r] = ((float)acc[a][b][r] * d) * alpha;
+          uint2 p;
+          p.x = gp_pack_bf16(fv[0], fv[1]);
+          p.y = gp_pack_bf16(fv[2], fv[3]);
+          *reinterpret_cast<uint2*>(tbuf + li * TB_ROW + (a * 16 + 4 * lg) * 2) = p;
+        }
+        const int mrow0 = m0 + wm * WM + b * 16;
+#pragma unroll
+        for (int i = 0; i < 16 / ROWS_PER_PASS; ++i) {
+          const int row = rr + i * ROWS_PER_PASS;
+          const uint4 v = *reinterpret_cast<const uint4*>(tbuf + row * TB_ROW + cc * 16);
+          const int gm = mrow0 + row;
+          if (GP_STORE_COND(gm < M && gn < N))
+            *reinterpret_cast<uint4*>((uint16_t*)Y + (size_t)gm * N + gn) = v;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int b = 0; b < TM; ++b) {
+        const int m = m0 + wm * WM + b * 16 + li;
+        const float d = dsc[b];
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+          const int n = n0 + wn * WN + a * 16 + 4 * lg;
+          const size_t o = (size_t)m * N + n;
+          float fv[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) fv[r] = ((float)acc[a][b][r] * d) * alpha;
+          if (OUT == 1) {
+            if (m < M && n < N) {
+              if (y_bf16) {
+                uint2 p;
+                p.x = gp_pack_bf16(fv[0], fv[1]);
+                p.y = gp_pack_bf16(fv[2], fv[3]);
+                *reinterpret_cast<uint2*>((uint16_t*)Y + o) = p;
+              } else {
+                *reinterpret_cast<float4*>((float*)Y + o) = make_float4(fv[0], fv[1], fv[2], fv[3]);
+              }
+            }
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              if (m < M && n + r < N) {
+                if (y_bf16) ((uint16_t*)Y)[o + r] = bl_f32_to_bf16_rne(fv[r]);
+                else ((float*)Y)[o + r] = fv[r];
+              }
+            }
           }
         }
       }
     }
+    if (acc_out) {
+#pragma unroll
+      for (int b = 0; b < TM; ++b) {
+        const int m = m0 + wm * WM + b * 16 + li;
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+          const int n = n0 + wn * WN + a * 16 + 4 * lg;
+          const size_t o = (size_t)m * N + n;
+          if (OUT != 2) {
+            if (m < M && n < N)
+              *reinterpret_cast<int4*>(acc_out + o) =
+                  make_int4(acc[a][b][0] >> SHIFT, acc[a][b][1] >> SHIFT, acc[a][b][2] >> SHIFT, acc[a][b][3] >> SHIFT);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (m < M && n + r < N) acc_out[o + r] = acc[a][b][r] >> SHIFT;
+          }
+        }
+      }
+    }
+#ifdef GP_DEBUG_TIMING
+    if (tid == 0 && tcount < 60) tlog[tcount++] = wall_clock64();
+#endif
+    if (!has_next) break;
+    tile = next;
+    m0 = nm0;
+    n0 = nn0;
+    cur = nxt;
   }
+#undef GP_PIN_IN
+#undef GP_PIN_OUT
+#undef GP_MFMA
+}
+
+static int gp_num_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  return cus;
 }
 
 template <int BM, int BN, bool A4>
@@ -268,11 +481,15 @@ static int gp_launch(const void* q, const float* scale, int M, int Kp, const voi
                      hipStream_t s) {
   constexpr int smem = GpSmem<BM, BN>::total;
   const int MT = (M + BM - 1) / BM, NTB = (N + BN - 1) / BN;
-  const bool vec = (N & 3) == 0;
-  auto kern = vec ? gemm_prefill_kernel<BM, BN, A4, true> : gemm_prefill_kernel<BM, BN, A4, false>;
+  const int out = (ydt == BL_BF16 && (N & 7) == 0) ? 0 : ((N & 3) == 0 ? 1 : 2);
+  auto kern = out == 0 ? gemm_prefill_kernel<BM, BN, A4, 0>
+            : out == 1 ? gemm_prefill_kernel<BM, BN, A4, 1> : gemm_prefill_kernel<BM, BN, A4, 2>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
     return BL_EHIP;
-  kern<<<(unsigned)(MT * NTB), GP_THREADS, smem, s>>>(
+  // one persistent block per CU (a block owns 128 KB of LDS and 512 registers per lane)
+  const int per_cu = (BM == 256) ? 1 : 2;
+  const int grid = min(MT * NTB, gp_num_cus() * per_cu);
+  kern<<<(unsigned)grid, GP_THREADS, smem, s>>>(
       (const unsigned char*)q, scale, M, Kp, (const unsigned char*)Wp, alpha, N, Y,
       ydt == BL_BF16 ? 1 : 0, acc_out, MT, NTB);
   BL_HIP_CHECK_LAUNCH();
