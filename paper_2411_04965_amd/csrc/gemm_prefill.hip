@@ -1,5 +1,5 @@
 // Prefill GEMM of the W1.58A4 and sparse W1.58A8 linears (eq. 6 and eq. 1 of the paper):
-//   acc[m, n] = sum_k q[m, k] * T[n, k]   (exact int32 on v_mfma_i32_16x16x64_i8)
+//   acc[m, n] = sum_k q[m, k] * T[n, k]   (exact int32 on v_mfma_i32_32x32x32_i8)
 //   Y[m, n]   = (float(acc) * d[m]) * alpha
 // Activations arrive packed (INT4 nibbles or INT8), weights 2-bit packed in 16 x 256 tiles.
 // Both are expanded to int8 while they are copied into LDS, without sign extension:
@@ -9,33 +9,35 @@
 // two and is folded exactly into the per-token scale in the epilogue.
 // |1024 * acc| <= 8 * K * 1024 < 2^31 for K <= 32768.
 //
-// Persistent blocks (one per CU) walk the tile list.  Block = 4 waves, tile BM x BN, each wave
-// (BM/2) x (BN/2) as 16x16 MFMA tiles; the MFMA's row operand is the weight fragment and its
-// column operand the token fragment, so a lane ends up with 4 consecutive outputs n of one
-// token.  K advances 128 channels per step through two LDS stages.  One step is one
-// straight-line block: the first half multiplies k 0..63 while it expands the prefetched
-// global data into the other stage, refills the staging registers from global memory and
-// reads the fragments of the second half; after the barrier the second half multiplies
-// k 64..127 while it reads the first fragments of the next step.  The K stream of a block runs
-// on across its tiles (no per-tile prologue); bf16 outputs leave through a small LDS transpose
+// Structure.  Persistent blocks (one per CU) walk the tile list.  Block = 4 waves, tile
+// BM x BN, each wave (BM/2) x (BN/2) as 32x32 MFMA tiles; the MFMA's row operand is the weight
+// fragment and its column operand the token fragment, so a lane ends up with groups of 4
+// consecutive outputs n of one token.  K advances 128 channels per step through two LDS stages,
+// four MFMA sub-steps of 32 channels each.  One step is one straight-line block: its first
+// half (sub-steps 0, 1) also expands the prefetched global data into the other stage and
+// refills the staging registers from global memory; after the barrier the second half
+// (sub-steps 2, 3) also reads the first fragments of the next step.  The K stream of a block
+// runs on across its tiles (no per-tile prologue).  bf16 outputs leave through an LDS transpose
 // so that every store instruction writes whole 128-byte lines.
+//
+// Issue budget.  A wave issues in order and one SIMD issues one instruction at a time; an
+// MFMA costs 8 issue cycles and runs 32, a VALU operation costs 4, a 16-byte LDS access more.
+// Everything that is not an MFMA must fit into the 24 free cycles behind each MFMA, so the
+// per-step work is cut into small slots placed between individual MFMAs, and the 32x32x32
+// MFMA is used instead of 16x16x64 (same rate, half as many instructions to issue).
 #include "common.h"
 
 #define GP_THREADS 256
-#ifdef GP_DEBUG_NOSTORE   // experiment: keep the arithmetic, drop (almost) all stores
-#define GP_STORE_COND(c) ((c) && alpha == 12345.0f)
-#else
-#define GP_STORE_COND(c) (c)
-#endif
 #define GP_BK 128     // bytes (= int8 channels) per LDS row per stage
+
+typedef int v16i __attribute__((ext_vector_type(16)));
 
 template <int BM, int BN>
 struct GpSmem {
   static constexpr int a_bytes = BM * GP_BK;
   static constexpr int b_bytes = BN * GP_BK;
   static constexpr int stage = a_bytes + b_bytes;
-  static constexpr int tbuf = 4 * 16 * ((BN / 2) * 2 + 32);   // epilogue transpose buffers (4 waves)
-  static constexpr int total = 2 * stage + tbuf;
+  static constexpr int total = 2 * stage;
 };
 
 __device__ __forceinline__ int gp_lds_off(int row, int chunk) {
@@ -66,14 +68,14 @@ __device__ __forceinline__ void gp_tile_origin(int t, int n_tiles, int MT, int N
 }
 
 // OUT: 0 = bf16 rows through the LDS transpose (N % 8 == 0), 1 = 4 outputs per store (N % 4 == 0),
-// 2 = one output per store (any N).
-template <int BM, int BN, bool A4, int OUT>
+// 2 = one output per store (any N).  ACC: also write the int32 accumulators (tests).
+template <int BM, int BN, bool A4, int OUT, bool ACC>
 __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N, void* __restrict__ Y,
     int y_bf16, int32_t* __restrict__ acc_out, int MT, int NTB) {
   constexpr int WM = BM / 2, WN = BN / 2;        // wave tile
-  constexpr int TM = WM / 16, TN = WN / 16;      // 16x16 MFMA tiles per wave
+  constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA tiles per wave
   constexpr int PA = A4 ? 4 : 8;                 // 16-byte pieces per activation row per stage
   constexpr int LA = BM * PA / GP_THREADS;       // activation loads per thread per stage
   constexpr int LB = BN * 2 / GP_THREADS;        // weight loads per thread per stage
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int li = lane & 15, lg = lane >> 4;
+  const int l32 = lane & 31, lh = lane >> 5;     // MFMA operand row / k-group of this lane
   const int n_tiles16 = (N + 15) >> 4;
   const int k_tiles = Kp >> 8;
   const int a_row_bytes = A4 ? (Kp >> 1) : Kp;
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     const u32 off = min(b_tile0 + 8 * j, t.b_tile_max) * b_tile_bytes + b_piece;
     b_reg[j] = *reinterpret_cast<const uint4*>(t.b_base + (size_t)ks * 512 + off);
   };
-  // The expansion of one stage is cut into NWR_A + NWR_B single 16-byte LDS writes so that it
+  // The expansion of one stage is cut into NWR single 16-byte LDS writes per operand so that it
   // can be spread over the MFMA stream.  Rows of load j sit RPJ (resp. 128) rows below those of
   // load 0, a multiple of 8, so the swizzle is the same and the offset is an immediate.
   constexpr int NWR_A = A4 ? 2 * LA : LA;
@@ -163,42 +165,36 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     store_b(st, i, c);
   };
 
-  // fragment addresses: row = wave base + tile * 16 + li, chunk = 4 * sub + lg
-  const int swz0 = ((lg) ^ (li & 7)) << 4, swz1 = ((4 + lg) ^ (li & 7)) << 4;
-  const int xf_base = (wm * WM + li) * GP_BK;
-  const int wf_base = A_BYTES + (wn * WN + li) * GP_BK;
+  // fragment addresses: row = wave base + tile * 32 + l32, 16-byte chunk = 2 * sub + lh
+  const int xf_base = (wm * WM + l32) * GP_BK;
+  const int wf_base = A_BYTES + (wn * WN + l32) * GP_BK;
+  int swz[4];
+#pragma unroll
+  for (int sub = 0; sub < 4; ++sub) swz[sub] = ((2 * sub + lh) ^ (l32 & 7)) << 4;
   auto read_x = [&](int stage, int sub, int b) -> v4i {
-    return *reinterpret_cast<const v4i*>(gp_smem + stage * STAGE + xf_base + b * (16 * GP_BK) + (sub ? swz1 : swz0));
+    return *reinterpret_cast<const v4i*>(gp_smem + stage * STAGE + xf_base + b * (32 * GP_BK) + swz[sub]);
   };
   auto read_w = [&](int stage, int sub, int a) -> v4i {
-    return *reinterpret_cast<const v4i*>(gp_smem + stage * STAGE + wf_base + a * (16 * GP_BK) + (sub ? swz1 : swz0));
+    return *reinterpret_cast<const v4i*>(gp_smem + stage * STAGE + wf_base + a * (32 * GP_BK) + swz[sub]);
   };
 
   // Accumulators are pinned to AGPRs and updated in place: the tied "+a" operand keeps the
   // register allocator from rotating 256 accumulator registers through copies.
 #define GP_MFMA(C, WF, XF) \
-  asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(C) : "v"(WF), "v"(XF))
-  // A wave issues in order, and an MFMA keeps the matrix pipe busy for 16 cycles: up to three
-  // other instructions fit behind each MFMA for free, more than that stalls the pipe.  The
-  // per-row work (fragment reads, expansion, LDS writes, global loads) is therefore cut into
-  // small slots placed between the individual MFMAs of a row.  The empty asm statements pin
-  // a slot's VALU work between two MFMAs: GP_PIN_IN makes an input "change" at that point
-  // (nothing that depends on it can be scheduled earlier), GP_PIN_OUT uses the results
-  // (they cannot be computed later).
+  asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+a"(C) : "v"(WF), "v"(XF))
+  // The empty asm statements pin a slot's VALU work between two MFMAs: GP_PIN_IN makes an
+  // input "change" at that point (nothing that depends on it can be scheduled earlier),
+  // GP_PIN_OUT uses the results (they cannot be computed later).
 #define GP_PIN_IN(x) asm volatile("" : "+v"(x))
 #define GP_PIN_OUT(x, y) asm volatile("" ::"v"(x), "v"(y))
-  static_assert(TM == TN && (TN == 4 || TN == 8), "the interleaving below assumes a square wave tile");
-  static_assert(NWR_A == TN && NWR_B == TN, "one A write and one B write per MFMA row");
-  constexpr int A_EVERY = TN / LA, B_EVERY = TN / LB;
+  static_assert(TM == TN && (TN == 2 || TN == 4), "the interleaving below assumes a square wave tile");
+  constexpr int ROWS = 2 * TN;                   // MFMA rows (one weight fragment each) per half step
+  static_assert(NWR_A == ROWS && NWR_B == ROWS, "one A write and one B write per MFMA row");
+  constexpr int A_EVERY = ROWS / LA, B_EVERY = ROWS / LB;
 
   const float alpha = alpha_p[0];
   const float unscale = A4 ? (1.0f / 1024.0f) : (1.0f / 64.0f);
   constexpr int SHIFT = A4 ? 10 : 6;
-
-  // LDS after the two stages: one transpose buffer per wave for the epilogue (16 token rows of
-  // the wave's WN outputs as bf16, rows padded by 32 bytes against bank conflicts).
-  constexpr int TB_ROW = WN * 2 + 32;
-  unsigned char* tbuf = gp_smem + 2 * STAGE + wave * (16 * TB_ROW);
 
   // ---- first tile of this block: stage 0 <- step 0, registers <- step 1, fragments <- step 0
   int tile = blockIdx.x;
@@ -218,19 +214,19 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
 #pragma unroll
   for (int j = 0; j < LB; ++j) load_b(cur, j, 1);
   __syncthreads();
-  // Token fragments are needed by every MFMA row of a half step: two full sets (xf, xg).
-  // Weight fragments are needed by one row only: a ring of 4, read two rows ahead.
-  v4i xf[TM], xg[TM], wr[4];
+  // Two full fragment sets, one per half step.  Each half reads the other half's set, so a
+  // stage is read only before the barrier of its own step and, for the next step, only after
+  // the barrier of the step that filled it: one barrier per step orders everything.
+  v4i xF[2][TM], wF[2][TN];                      // sub-steps 0, 1
+  v4i xS[2][TM], wS[2][TN];                      // sub-steps 2, 3
 #pragma unroll
-  for (int b = 0; b < TM; ++b) xf[b] = read_x(0, 0, b);
-  wr[0] = read_w(0, 0, 0);
-  wr[1] = read_w(0, 0, 1);
+  for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+      xF[sub][a] = read_x(0, sub, a);
+      wF[sub][a] = read_w(0, sub, a);
+    }
 
-#ifdef GP_DEBUG_TIMING
-  long long* tlog = (long long*)acc_out + (size_t)blockIdx.x * 64; int tcount = 0; acc_out = nullptr;
-  if (tid == 0) tlog[tcount++] = wall_clock64();
-  unsigned long long bar_sum = 0;
-#endif
   while (true) {
     // The K stream runs on across tile boundaries: the loads of the last two steps of a tile
     // fetch steps 0 and 1 of the block's next tile, so that tile starts with its first stage,
@@ -241,17 +237,19 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     if (has_next) gp_tile_origin(next, n_tiles, MT, NTB, BM, BN, nm0, nn0);
     const TileSrc nxt = tile_src(nm0, nn0);
 
-    v4i acc[TN][TM];
+    v16i acc[TN][TM];
 #pragma unroll
     for (int a = 0; a < TN; ++a)
 #pragma unroll
-      for (int b = 0; b < TM; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
+      for (int b = 0; b < TM; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
     // Per-token scales of this tile, fetched now: a global load inside the epilogue would have
     // to wait for the stores issued before it (loads and stores share one counter).
     float dsc[TM];
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
-      const int m = m0 + wm * WM + b * 16 + li;
+      const int m = m0 + wm * WM + b * 32 + l32;
       dsc[b] = (m < M ? scale[m] : 0.0f) * unscale;
     }
 
@@ -266,76 +264,80 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
       ld.b_base = (wrap && has_next) ? nxt.b_base : cur.b_base;
       ld.a_row_max = (wrap && has_next) ? nxt.a_row_max : cur.a_row_max;
       ld.b_tile_max = (wrap && has_next) ? nxt.b_tile_max : cur.b_tile_max;
-      // first half: k 0..63 of this step.  Per MFMA row: one token fragment of the second
-      // half, the weight fragment two rows ahead, one activation piece and one weight piece
-      // expanded into the other stage, and the global loads that refill the registers just
-      // consumed (a full step, 2048 MFMA cycles, before their data is expanded).
+
+      // first half: sub-steps 0, 1 (k 0..63) on this step's stage.  Per MFMA row: one token
+      // and one weight fragment of the second half, one activation piece and one weight
+      // piece expanded into the other stage, and the global loads that refill the staging
+      // registers just consumed (a full step before their data is expanded).
 #pragma unroll
-      for (int a = 0; a < TN; ++a) {
-        uint4 ca, cb;
-        u32 x0 = 0, x1 = 0, w = b_word(a);
-        if (A4) {
-          x0 = a_word(a, 0);
-          x1 = a_word(a, 1);
-        }
+      for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-        for (int b = 0; b < TM; ++b) {
-          GP_MFMA(acc[a][b], wr[a & 3], xf[b]);
-          const int slot = (TM == 8) ? b : 2 * b;    // 8 slots per row; a 4-MFMA row takes two at a time
-          if (slot == 0) {
-            xg[a] = read_x(stage, 1, a);
-            wr[(a + 2) & 3] = (a + 2 < TN) ? read_w(stage, 0, a + 2) : read_w(stage, 1, a + 2 - TN);
-          }
+        for (int a = 0; a < TN; ++a) {
+          const int hrow = sub * TN + a;         // row within the half step
+          uint4 ca, cb;
+          u32 x0 = 0, x1 = 0, w = b_word(hrow);
           if (A4) {
-            if (slot == 1 || (TM == 4 && slot == 2)) {
-              GP_PIN_IN(x0);
-              ca.x = (x0 << 4) & MA; ca.y = x0 & MA;
-              GP_PIN_OUT(ca.x, ca.y);
+            x0 = a_word(hrow, 0);
+            x1 = a_word(hrow, 1);
+          }
+#pragma unroll
+          for (int b = 0; b < TM; ++b) {
+            GP_MFMA(acc[a][b], wF[sub][a], xF[sub][b]);
+            // slots behind MFMA b of this row (4 per row; a 2-MFMA row takes two at a time)
+            const int s0 = (TM == 4) ? b : 2 * b, s1 = (TM == 4) ? b : 2 * b + 1;
+            if (s0 == 0) {
+              xS[sub][a] = read_x(stage, 2 + sub, a);
+              wS[sub][a] = read_w(stage, 2 + sub, a);
+              if (A4) {
+                GP_PIN_IN(x0);
+                ca.x = (x0 << 4) & MA;
+                GP_PIN_OUT(ca.x, ca.x);
+              }
             }
-            if (slot == 2) {
-              GP_PIN_IN(x1);
-              ca.z = (x1 << 4) & MA; ca.w = x1 & MA;
-              GP_PIN_OUT(ca.z, ca.w);
+            if (s0 <= 1 && 1 <= s1) {
+              if (A4) {
+                GP_PIN_IN(x0);
+                ca.y = x0 & MA;
+                GP_PIN_IN(x1);
+                ca.z = (x1 << 4) & MA; ca.w = x1 & MA;
+                GP_PIN_OUT(ca.y, ca.z);
+                GP_PIN_OUT(ca.w, ca.w);
+              } else {
+                ca = make_uint4(a_reg[hrow].x, a_reg[hrow].y, a_reg[hrow].z, a_reg[hrow].w);
+              }
+              store_a(st_other, hrow, ca);
             }
-          } else if (slot == 2) {
-            ca = make_uint4(a_reg[a].x, a_reg[a].y, a_reg[a].z, a_reg[a].w);
-          }
-          if (slot == 3 || (TM == 4 && slot == 2)) store_a(st_other, a, ca);
-          if (slot == 4) {
-            GP_PIN_IN(w);
-            cb.x = (w << 6) & MB; cb.y = (w << 4) & MB;
-            GP_PIN_OUT(cb.x, cb.y);
-          }
-          if (slot == 5 || (TM == 4 && slot == 4)) {
-            GP_PIN_IN(w);
-            cb.z = (w << 2) & MB; cb.w = w & MB;
-            GP_PIN_OUT(cb.z, cb.w);
-          }
-          if (slot == 6) store_b(st_other, a, cb);
-          if (slot == 7 || (TM == 4 && slot == 6)) {
-            if (a % A_EVERY == A_EVERY - 1) load_a(ld, a / A_EVERY, ks2);
-            if (a % B_EVERY == B_EVERY - 1) load_b(ld, a / B_EVERY, ks2);
+            if (s0 <= 2 && 2 <= s1) {
+              GP_PIN_IN(w);
+              cb.x = (w << 6) & MB; cb.y = (w << 4) & MB;
+              cb.z = (w << 2) & MB;
+              GP_PIN_OUT(cb.x, cb.y);
+              GP_PIN_OUT(cb.z, cb.z);
+            }
+            if (s0 <= 3 && 3 <= s1) {
+              GP_PIN_IN(w);
+              cb.w = w & MB;
+              store_b(st_other, hrow, cb);
+              if (hrow % A_EVERY == A_EVERY - 1) load_a(ld, hrow / A_EVERY, ks2);
+              if (hrow % B_EVERY == B_EVERY - 1) load_b(ld, hrow / B_EVERY, ks2);
+            }
           }
         }
       }
-#ifdef GP_DEBUG_TIMING
-      const unsigned long long tb0 = __builtin_amdgcn_s_memtime();
-#endif
       __syncthreads();
-#ifdef GP_DEBUG_TIMING
-      const unsigned long long tb1 = __builtin_amdgcn_s_memtime();
-#endif
-      // second half: k 64..127.  Per MFMA row: one token fragment of the next step and the
-      // weight fragment two rows ahead (the last two belong to the next step, whose stage is
-      // complete now that the barrier has passed).
+      // second half: sub-steps 2, 3 (k 64..127).  Per MFMA row: one token and one weight
+      // fragment of the next step's first half, from the stage all waves have just filled.
 #pragma unroll
-      for (int a = 0; a < TN; ++a) {
+      for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-        for (int b = 0; b < TM; ++b) {
-          GP_MFMA(acc[a][b], wr[a & 3], xg[b]);
-          if (b == 0) {
-            xf[a] = read_x(stage ^ 1, 0, a);
-            wr[(a + 2) & 3] = (a + 2 < TN) ? read_w(stage, 1, a + 2) : read_w(stage ^ 1, 0, a + 2 - TN);
+        for (int a = 0; a < TN; ++a) {
+#pragma unroll
+          for (int b = 0; b < TM; ++b) {
+            GP_MFMA(acc[a][b], wS[sub][a], xS[sub][b]);
+            if (b == 0) {
+              xF[sub][a] = read_x(stage ^ 1, sub, a);
+              wF[sub][a] = read_w(stage ^ 1, sub, a);
+            }
           }
         }
       }
@@ -343,121 +345,137 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
       // results need wait states before a VALU may read them; the register allocator reads
       // accumulators right at the loop exit.  16 wait states here cover the last MFMA.
       asm volatile("s_nop 15" ::: "memory");
-#ifdef GP_DEBUG_TIMING
-      bar_sum += tb1 - tb0;
-#endif
     }
-#ifdef GP_DEBUG_TIMING
-    if (tid == 0 && tcount < 60) tlog[tcount++] = (long long)bar_sum;
-    if (tid == 0 && tcount < 60) tlog[tcount++] = (long long)__builtin_amdgcn_s_memtime();
-#endif
 
-#ifdef GP_DEBUG_TIMING
-    if (tid == 0 && tcount < 60) tlog[tcount++] = wall_clock64();
-#endif
     // The staging registers already hold the next tile's step 1: make their loads complete
     // here, before the epilogue's stores join the same counter.
 #pragma unroll
     for (int j = 0; j < LA; ++j) asm volatile("" ::"v"(a_reg[j].x), "v"(a_reg[j].y), "v"(a_reg[j].z), "v"(a_reg[j].w));
 #pragma unroll
     for (int j = 0; j < LB; ++j) asm volatile("" ::"v"(b_reg[j].x), "v"(b_reg[j].y), "v"(b_reg[j].z), "v"(b_reg[j].w));
-    // ---- epilogue: lane holds token m = ... + li and 4 consecutive outputs n = ... + 4*lg + r.
-    // float(1024 acc) * (d / 1024) rounds exactly like float(acc) * d.  The output path is
-    // chosen once, outside the unrolled tile loops, to keep the code small.
+
+    // ---- epilogue.  acc[a][b][r] is output n = 32 a + 8 (r / 4) + 4 lh + r % 4 of token
+    // m = 32 b + l32 (relative to the wave tile).  float(1024 acc) * (d / 1024) rounds exactly
+    // like float(acc) * d.
     if (OUT == 0) {
-      // bf16 through the wave's transpose buffer, 16 tokens x WN outputs at a time; read back
-      // row-wise, 16 lanes cover one token's WN * 2 contiguous bytes, so every store
-      // instruction writes whole 128-byte lines
+      // bf16 through an LDS transpose, 32 tokens x WN outputs at a time.  The last step ran
+      // on stage 1 (nk is even) and read it only before its barrier; stage 0 already holds
+      // the next tile's first step.  So stage 1 is free until the barrier at the end of the
+      // epilogue.  Rows are padded by 32 bytes against bank
+      // conflicts; read back row-wise, 16 lanes cover one token's WN * 2 contiguous bytes, so
+      // every store instruction writes whole 128-byte lines.
+      constexpr int TB_ROW = WN * 2 + 32;
+      unsigned char* tbuf = gp_smem + STAGE + wave * (32 * TB_ROW);
+      static_assert(4 * 32 * TB_ROW <= STAGE, "transpose buffers must fit into one stage");
       constexpr int LANES_PER_ROW = WN * 2 / 16;           // 16 (WN = 128) or 8 (WN = 64)
       constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
       const int rr = lane / LANES_PER_ROW, cc = lane % LANES_PER_ROW;
-      const int gn = n0 + wn * WN + cc * 8;
+      // uniform base of the wave's output block plus one per-lane offset: the stores need no
+      // per-store address registers
+      uint16_t* ywave = (uint16_t*)Y + (size_t)(m0 + wm * WM) * N + (n0 + wn * WN);
+      const u32 lane_off = (u32)rr * (u32)N + cc * 8;
+      const bool interior = (m0 + BM <= M) && (n0 + BN <= N);
+      const int m_left = M - (m0 + wm * WM) - rr, n_left = N - (n0 + wn * WN) - cc * 8;
 #pragma unroll
       for (int b = 0; b < TM; ++b) {
         const float d = dsc[b];
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
-          float fv[4];
+          asm volatile("" : "+a"(acc[a][b]));    // the tile stays in its AGPRs until this point
 #pragma unroll
-          for (int r = 0; r < 4; ++r) fv[r] = ((float)acc[a][b][r] * d) * alpha;
-          uint2 p;
-          p.x = gp_pack_bf16(fv[0], fv[1]);
-          p.y = gp_pack_bf16(fv[2], fv[3]);
-          *reinterpret_cast<uint2*>(tbuf + li * TB_ROW + (a * 16 + 4 * lg) * 2) = p;
-        }
-        const int mrow0 = m0 + wm * WM + b * 16;
+          for (int g = 0; g < 4; ++g) {
+            float fv[4];
 #pragma unroll
-        for (int i = 0; i < 16 / ROWS_PER_PASS; ++i) {
-          const int row = rr + i * ROWS_PER_PASS;
-          const uint4 v = *reinterpret_cast<const uint4*>(tbuf + row * TB_ROW + cc * 16);
-          const int gm = mrow0 + row;
-          if (GP_STORE_COND(gm < M && gn < N))
-            *reinterpret_cast<uint4*>((uint16_t*)Y + (size_t)gm * N + gn) = v;
+            for (int r = 0; r < 4; ++r) fv[r] = ((float)acc[a][b][4 * g + r] * d) * alpha;
+            uint2 p;
+            p.x = gp_pack_bf16(fv[0], fv[1]);
+            p.y = gp_pack_bf16(fv[2], fv[3]);
+            *reinterpret_cast<uint2*>(tbuf + l32 * TB_ROW + (a * 32 + 8 * g + 4 * lh) * 2) = p;
+          }
+          // keep the scheduler from reading many accumulators ahead of their use: the next
+          // tile's fragments and staging registers are live here, and a spill in this section
+          // would wait on the stores in flight
+          __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int i = 0; i < 32 / ROWS_PER_PASS; ++i) {
+          const int row = b * 32 + i * ROWS_PER_PASS;      // + rr: token row within the wave tile
+          const uint4 v = *reinterpret_cast<const uint4*>(tbuf + (rr + i * ROWS_PER_PASS) * TB_ROW + cc * 16);
+          uint16_t* yrow = ywave + (size_t)row * N;
+          if (interior || (row < m_left && 0 < n_left)) *reinterpret_cast<uint4*>(yrow + lane_off) = v;
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
 #pragma unroll
       for (int b = 0; b < TM; ++b) {
-        const int m = m0 + wm * WM + b * 16 + li;
+        const int m = m0 + wm * WM + b * 32 + l32;
         const float d = dsc[b];
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
-          const int n = n0 + wn * WN + a * 16 + 4 * lg;
-          const size_t o = (size_t)m * N + n;
-          float fv[4];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) fv[r] = ((float)acc[a][b][r] * d) * alpha;
-          if (OUT == 1) {
-            if (m < M && n < N) {
-              if (y_bf16) {
-                uint2 p;
-                p.x = gp_pack_bf16(fv[0], fv[1]);
-                p.y = gp_pack_bf16(fv[2], fv[3]);
-                *reinterpret_cast<uint2*>((uint16_t*)Y + o) = p;
-              } else {
-                *reinterpret_cast<float4*>((float*)Y + o) = make_float4(fv[0], fv[1], fv[2], fv[3]);
+          for (int g = 0; g < 4; ++g) {
+            const int n = n0 + wn * WN + a * 32 + 8 * g + 4 * lh;
+            const size_t o = (size_t)m * N + n;
+            float fv[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) fv[r] = ((float)acc[a][b][4 * g + r] * d) * alpha;
+            if (OUT == 1) {
+              if (m < M && n < N) {
+                if (y_bf16) {
+                  uint2 p;
+                  p.x = gp_pack_bf16(fv[0], fv[1]);
+                  p.y = gp_pack_bf16(fv[2], fv[3]);
+                  *reinterpret_cast<uint2*>((uint16_t*)Y + o) = p;
+                } else {
+                  *reinterpret_cast<float4*>((float*)Y + o) = make_float4(fv[0], fv[1], fv[2], fv[3]);
+                }
               }
-            }
-          } else {
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              if (m < M && n + r < N) {
-                if (y_bf16) ((uint16_t*)Y)[o + r] = bl_f32_to_bf16_rne(fv[r]);
-                else ((float*)Y)[o + r] = fv[r];
+              for (int r = 0; r < 4; ++r) {
+                if (m < M && n + r < N) {
+                  if (y_bf16) ((uint16_t*)Y)[o + r] = bl_f32_to_bf16_rne(fv[r]);
+                  else ((float*)Y)[o + r] = fv[r];
+                }
               }
             }
           }
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
-    if (acc_out) {
+    if (ACC) {
 #pragma unroll
       for (int b = 0; b < TM; ++b) {
-        const int m = m0 + wm * WM + b * 16 + li;
+        const int m = m0 + wm * WM + b * 32 + l32;
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
-          const int n = n0 + wn * WN + a * 16 + 4 * lg;
-          const size_t o = (size_t)m * N + n;
-          if (OUT != 2) {
-            if (m < M && n < N)
-              *reinterpret_cast<int4*>(acc_out + o) =
-                  make_int4(acc[a][b][0] >> SHIFT, acc[a][b][1] >> SHIFT, acc[a][b][2] >> SHIFT, acc[a][b][3] >> SHIFT);
-          } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (m < M && n + r < N) acc_out[o + r] = acc[a][b][r] >> SHIFT;
+          for (int g = 0; g < 4; ++g) {
+            const int n = n0 + wn * WN + a * 32 + 8 * g + 4 * lh;
+            const size_t o = (size_t)m * N + n;
+            if (OUT != 2) {
+              if (m < M && n < N)
+                *reinterpret_cast<int4*>(acc_out + o) =
+                    make_int4(acc[a][b][4 * g] >> SHIFT, acc[a][b][4 * g + 1] >> SHIFT,
+                              acc[a][b][4 * g + 2] >> SHIFT, acc[a][b][4 * g + 3] >> SHIFT);
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                if (m < M && n + r < N) acc_out[o + r] = acc[a][b][4 * g + r] >> SHIFT;
+            }
           }
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
-#ifdef GP_DEBUG_TIMING
-    if (tid == 0 && tcount < 60) tlog[tcount++] = wall_clock64();
-#endif
     if (!has_next) break;
     tile = next;
     m0 = nm0;
     n0 = nn0;
     cur = nxt;
+    if (OUT == 0) __syncthreads();     // transpose buffers are read out before stage 1 is refilled
   }
 #undef GP_PIN_IN
 #undef GP_PIN_OUT
@@ -482,11 +500,17 @@ static int gp_launch(const void* q, const float* scale, int M, int Kp, const voi
   constexpr int smem = GpSmem<BM, BN>::total;
   const int MT = (M + BM - 1) / BM, NTB = (N + BN - 1) / BN;
   const int out = (ydt == BL_BF16 && (N & 7) == 0) ? 0 : ((N & 3) == 0 ? 1 : 2);
-  auto kern = out == 0 ? gemm_prefill_kernel<BM, BN, A4, 0>
-            : out == 1 ? gemm_prefill_kernel<BM, BN, A4, 1> : gemm_prefill_kernel<BM, BN, A4, 2>;
+  void (*kern)(const unsigned char*, const float*, int, int, const unsigned char*, const float*, int,
+               void*, int, int32_t*, int, int);
+  if (acc_out)
+    kern = out == 0 ? gemm_prefill_kernel<BM, BN, A4, 0, true>
+         : out == 1 ? gemm_prefill_kernel<BM, BN, A4, 1, true> : gemm_prefill_kernel<BM, BN, A4, 2, true>;
+  else
+    kern = out == 0 ? gemm_prefill_kernel<BM, BN, A4, 0, false>
+         : out == 1 ? gemm_prefill_kernel<BM, BN, A4, 1, false> : gemm_prefill_kernel<BM, BN, A4, 2, false>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
     return BL_EHIP;
-  // one persistent block per CU (a block owns 128 KB of LDS and 512 registers per lane)
+  // persistent blocks: one per CU for the large tile (128 KB of LDS, 512 registers per lane)
   const int per_cu = (BM == 256) ? 1 : 2;
   const int grid = min(MT * NTB, gp_num_cus() * per_cu);
   kern<<<(unsigned)grid, GP_THREADS, smem, s>>>(
