@@ -290,3 +290,60 @@ def test_argument_errors():
         Xu = torch.zeros(4 * 64 + 4, device="cuda")[1:257].view(4, 64)      # 4-byte offset
         B.bitlinear_a4(Xu, p, a, 32)
     assert e.value.status == -3
+
+
+# ------------------------------------------------------------------ FP4 variant (config 4)
+def _check_fp4(Y, ref, rows=None):
+    """FP4 path: float32 accumulation inside the matrix instruction, so tolerance only:
+    1e-3 of the sum of |terms| of each output (plus bf16 rounding when the output is bf16)."""
+    y = host(Y).astype(np.float64)
+    deq = np.abs(O.fp4_dequant(ref["codes"], ref["e"]))
+    bound = 1e-3 * float(ref["alpha"]) * (deq @ np.abs(ref["T"]).astype(np.float64).T)
+    if Y.dtype == BF16:
+        bound = bound + np.abs(ref["y"]) * 2.0 ** -8
+    err = np.abs(y - ref["y"])
+    assert np.all(err <= bound + 1e-30), "max err/bound %g" % (err / (bound + 1e-30)).max()
+
+
+@pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (130, 200, 992, BF16), (300, 1100, 3200, BF16)])
+def test_fp4_linear(M, N, K, dtype):
+    say("fp4 linear M=%d N=%d K=%d" % (M, N, K))
+    X = S.heavy(M, K, S.seed_for(4, M + N)) if dtype == BF16 else S.gauss_outlier(M, K, 4, 20.0, S.seed_for(4, M))
+    W = S.latent_weights(N, K, S.seed_for(4, N + K))
+    ref = O.bitlinear_fp4(X, W, EPS)
+    p, a = pack(W)
+    for ydt in (F32, BF16):
+        Y = B.bitlinear_a4(dev(X, dtype), p, a, N, EPS, act_fp4=True, y_dtype=ydt)
+        _check_fp4(Y, ref)
+    # an exactly representable case must be exact: integers up to 6 times ternary weights
+    Xi = np.random.default_rng(5).integers(-6, 7, (M, K)).astype(np.float32)
+    Xi[np.abs(Xi) == 5] = 4
+    Xi[:, ::32] = 6                                         # every block has scale 2^0
+    refi = O.bitlinear_fp4(Xi, W, EPS)
+    Yi = B.bitlinear_a4(dev(Xi, dtype), p, a, N, EPS, act_fp4=True, y_dtype=F32)
+    acc_exact = refi["y"] / np.float64(refi["alpha"])       # integers
+    assert np.array_equal(host(Yi), (acc_exact.astype(np.float32) * refi["alpha"]).astype(np.float32))
+
+
+@pytest.mark.parametrize("name,N,K", [("qkv", 9600, 3200), ("gate", 8640, 3200)])
+def test_config4_fp4_sampled_rows(name, N, K):
+    """3B-like FP4 variant at M = 8192, 64 sampled token rows against the float64 oracle."""
+    say("config 4 fp4 %s" % name)
+    M = 8192
+    X = S.heavy(M, K, S.seed_for(4, 1))
+    W = S.latent_weights(N, K, S.seed_for(4, 2 + len(name)))
+    p, a = pack(W)
+    rows = np.random.default_rng(S.seed_for(4, 9)).choice(M, 64, replace=False)
+    rows[:2] = (0, M - 1)
+    Y = B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, act_fp4=True, y_dtype=F32)
+    ref = O.bitlinear_fp4(X[rows], W, EPS)
+    _check_fp4(Y[torch.from_numpy(rows).cuda()], ref)
+    # the INT4 path on identical inputs (the comparison the paper makes): both are reported
+    # against the product of the raw activations with the same ternary weights; with
+    # heavy-tailed outlier channels the FP4 grid, which never clips, must be the closer one
+    Yi = host(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=F32)[torch.from_numpy(rows).cuda()])
+    full = X[rows].astype(np.float64) @ (ref["T"].astype(np.float64) * np.float64(ref["alpha"])).T
+    rel_fp4 = np.linalg.norm(host(Y[torch.from_numpy(rows).cuda()]) - full) / np.linalg.norm(full)
+    rel_int4 = np.linalg.norm(Yi - full) / np.linalg.norm(full)
+    say("relative error vs unquantized activations: fp4 %.4f, int4 %.4f" % (rel_fp4, rel_int4))
+    assert rel_fp4 < rel_int4 and rel_fp4 < 0.2
