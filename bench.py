@@ -29,6 +29,10 @@ if ROOT not in sys.path:
 EPS = 1e-5
 INT8_PEAK_TOPS = 5033.0      # MI355X dense int8 MFMA
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the W1.58A4 prefill GEMM at the benchmark shapes, from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_prefill_7b_hbm_traffic.txt
+# (calibrated against a 1 GiB device copy): 386.5 MB fetched + 374.7 MB written.
+A4_GEMM_TRAFFIC_BYTES = 761.2e6
 HIDDEN, FFN = 4096, 11008
 
 
@@ -40,6 +44,8 @@ def parse():
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for the HBM traffic counters)")
     return ap.parse_args()
 
 
@@ -144,6 +150,14 @@ def main():
                 quant_events[name].append((e0, e1))
                 gemm_events[name].append((e1, e2))
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)              # 1 GiB read + 1 GiB written per launch
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -172,7 +186,9 @@ def main():
     achieved = a4_ops / (a4_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_prefill_kernel<256,256,INT4> (qkv, gate, up)",
                 "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": None,
+                "frac": round(achieved / INT8_PEAK_TOPS, 4),
+                "traffic": A4_GEMM_TRAFFIC_BYTES if M == 16384 else None,
+                "algorithmic_bytes": round(sum(M * K / 2 + N * K / 4 + 2 * M * N for _, N, K in a4) / len(a4)),
                 "avg_launch_ms": round(a4_ms / len(a4), 4)}
 
     out = {
@@ -199,9 +215,10 @@ def bl_code_bytes(kind, K):
     return Kp // 2 if kind == "a4" else Kp
 
 
-def decode_bench(B, S, torch, dev, layers=8, iters=20):
-    """Packed-weight bandwidth at decode shapes: `layers` distinct weight sets per projection are
-    cycled so that the 256 MB last-level cache cannot hold them; time per launch from events."""
+def decode_bench(B, S, torch, dev, layers=8, replays=20):
+    """Packed-weight bandwidth at decode shapes.  `layers` distinct weight sets per projection
+    (more than the 256 MB last-level cache holds in total) are run back to back from one HIP
+    graph per projection, so launch overhead of the Python binding is not in the timing."""
     res = {}
     bf16 = torch.bfloat16
     projs = S.projections(HIDDEN, FFN)
@@ -213,6 +230,7 @@ def decode_bench(B, S, torch, dev, layers=8, iters=20):
             sets.append(B.pack_ternary(w, EPS, B.BL_W_GEMM))
             del w
         packed[name] = sets
+    side = torch.cuda.Stream()
     for M in (1, 8, 32, 64):
         row = {}
         tot_bytes, tot_ms = 0.0, 0.0
@@ -232,18 +250,26 @@ def decode_bench(B, S, torch, dev, layers=8, iters=20):
             for l in range(layers):
                 run(l)
             torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    for l in range(layers):
+                        run(l)
+            g.replay()
+            torch.cuda.synchronize()
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
             e0.record()
-            for l in range(iters):
-                run(l)
+            for _ in range(replays):
+                g.replay()
             e1.record()
             torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / iters
+            ms = e0.elapsed_time(e1) / (replays * layers)
             wbytes = N * K / 4
             row[name] = {"us": round(ms * 1e3, 2), "weight_gbs": round(wbytes / ms / 1e6, 1)}
             tot_bytes += wbytes
             tot_ms += ms
+            del g
         row["layer_weight_gbs"] = round(tot_bytes / tot_ms / 1e6, 1)
         row["frac_hbm_peak"] = round(tot_bytes / tot_ms / 1e6 / HBM_PEAK_GBS, 4)
         res["M%d" % M] = row
