@@ -37,9 +37,11 @@ __device__ __forceinline__ void gd_store4(void* Y, int y_bf16, int32_t* acc_out,
 }
 
 // ---------------------------------------------------------------- dense skinny GEMM
-// Block = 4 waves, 64 outputs.  The block's K range is dealt tile by tile (256 channels) to
-// the waves; every wave keeps 4 x MT accumulator tiles, reduced through LDS at the end.
-template <int MT, bool A4>
+// Block = 4 waves, NTB tiles of 16 outputs.  The block's K range is dealt tile by tile (256
+// channels) to the waves; every wave keeps NTB x MT accumulator tiles, reduced through LDS at
+// the end.  NTB = 1 (very few tokens: every block streams its own slice of W over all of K, no
+// split, one launch) or 4 (the token fragments are reused by four weight tiles).
+template <int MT, bool A4, int NTB>
 __global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
@@ -55,10 +57,10 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
   constexpr int XV = A4 ? 2 : 4;                 // 16-byte loads per token row per tile
   const int a_row_bytes = A4 ? (Kp >> 1) : Kp;
 
-  const unsigned char* w_src[4];
+  const unsigned char* w_src[NTB];
 #pragma unroll
-  for (int a = 0; a < 4; ++a) {
-    const int nt = min(nb * 4 + a, NT16 - 1);
+  for (int a = 0; a < NTB; ++a) {
+    const int nt = min(nb * NTB + a, NT16 - 1);
     w_src[a] = Wp + (size_t)nt * KT * 1024 + lane * 16;
   }
   const unsigned char* x_src[MT];
@@ -68,90 +70,108 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
     x_src[b] = A + (size_t)row * a_row_bytes + lg * (A4 ? 32 : 64);
   }
 
-  v4i acc[4][MT];
+  v4i acc[NTB][MT];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < NTB; ++a)
 #pragma unroll
     for (int b = 0; b < MT; ++b) acc[a][b] = (v4i){0, 0, 0, 0};
 
-  uint4 wr[4], xr[MT][XV];
-  auto load_tile = [&](int t) {
+  // UNR tiles (256 channels each) are loaded together before they are multiplied, so that a
+  // wave keeps several KB of weights in flight; the next group is prefetched meanwhile.
+  constexpr int UNR = NTB == 1 ? 4 : 1;
+  uint4 wr[UNR][NTB], xr[UNR][MT][XV];
+  auto load_group = [&](int t) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a) wr[a] = *reinterpret_cast<const uint4*>(w_src[a] + (size_t)t * 1024);
+    for (int u = 0; u < UNR; ++u) {
+      const int tt = min(t + 4 * u, t_end - 1);     // tiles past the end re-read the last one (unused)
 #pragma unroll
-    for (int b = 0; b < MT; ++b)
+      for (int a = 0; a < NTB; ++a) wr[u][a] = *reinterpret_cast<const uint4*>(w_src[a] + (size_t)tt * 1024);
 #pragma unroll
-      for (int c = 0; c < XV; ++c)
-        xr[b][c] = *reinterpret_cast<const uint4*>(x_src[b] + (size_t)t * (A4 ? 128 : 256) + c * 16);
+      for (int b = 0; b < MT; ++b)
+#pragma unroll
+        for (int c = 0; c < XV; ++c)
+          xr[u][b][c] = *reinterpret_cast<const uint4*>(x_src[b] + (size_t)tt * (A4 ? 128 : 256) + c * 16);
+    }
   };
 
   int t = t_begin + wave;
-  if (t < t_end) load_tile(t);
+  if (t < t_end) load_group(t);
   while (t < t_end) {
-    uint4 wc[4], xc[MT][XV];
+    uint4 wc[UNR][NTB], xc[UNR][MT][XV];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) wc[a] = wr[a];
+    for (int u = 0; u < UNR; ++u) {
 #pragma unroll
-    for (int b = 0; b < MT; ++b)
+      for (int a = 0; a < NTB; ++a) wc[u][a] = wr[u][a];
 #pragma unroll
-      for (int c = 0; c < XV; ++c) xc[b][c] = xr[b][c];
-    const int tn = t + 4;
-    if (tn < t_end) load_tile(tn);                 // prefetch while computing
+      for (int b = 0; b < MT; ++b)
 #pragma unroll
-    for (int t4 = 0; t4 < 4; ++t4) {
-      v4i xo[MT];
+        for (int c = 0; c < XV; ++c) xc[u][b][c] = xr[u][b][c];
+    }
+    const int tn = t + 4 * UNR;
+    if (tn < t_end) load_group(tn);                // prefetch while computing
 #pragma unroll
-      for (int b = 0; b < MT; ++b) {
-        if (A4) {
-          // 64 channels = 8 words; MFMA step t4 takes words 2*t4 and 2*t4+1
-          const uint4 v = xc[b][t4 >> 1];
-          const u32 x0 = (t4 & 1) ? v.z : v.x, x1 = (t4 & 1) ? v.w : v.y;
-          xo[b] = (v4i){(int)((x0 << 4) & 0xF0F0F0F0u), (int)(x0 & 0xF0F0F0F0u),
-                        (int)((x1 << 4) & 0xF0F0F0F0u), (int)(x1 & 0xF0F0F0F0u)};
-        } else {
-          const uint4 v = xc[b][t4];
-          xo[b] = (v4i){(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+    for (int u = 0; u < UNR; ++u) {
+      if (t + 4 * u >= t_end) break;
+#pragma unroll
+      for (int t4 = 0; t4 < 4; ++t4) {
+        v4i xo[MT];
+#pragma unroll
+        for (int b = 0; b < MT; ++b) {
+          if (A4) {
+            // 64 channels = 8 words; MFMA step t4 takes words 2*t4 and 2*t4+1
+            const uint4 v = xc[u][b][t4 >> 1];
+            const u32 x0 = (t4 & 1) ? v.z : v.x, x1 = (t4 & 1) ? v.w : v.y;
+            xo[b] = (v4i){(int)((x0 << 4) & 0xF0F0F0F0u), (int)(x0 & 0xF0F0F0F0u),
+                          (int)((x1 << 4) & 0xF0F0F0F0u), (int)(x1 & 0xF0F0F0F0u)};
+          } else {
+            const uint4 v = xc[u][b][t4];
+            xo[b] = (v4i){(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+          }
         }
-      }
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const u32 w = t4 == 0 ? wc[a].x : t4 == 1 ? wc[a].y : t4 == 2 ? wc[a].z : wc[a].w;
-        const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
-                             (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+        for (int a = 0; a < NTB; ++a) {
+          const u32 w = t4 == 0 ? wc[u][a].x : t4 == 1 ? wc[u][a].y : t4 == 2 ? wc[u][a].z : wc[u][a].w;
+          const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
+                               (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
 #pragma unroll
-        for (int b = 0; b < MT; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo[b], acc[a][b], 0, 0, 0);
+          for (int b = 0; b < MT; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo[b], acc[a][b], 0, 0, 0);
+        }
       }
     }
     t = tn;
   }
 
-  // cross-wave reduction: wave w ends up owning output tile a = w
+  // cross-wave reduction: the NTB x MT accumulator tiles are dealt round-robin to the waves
   v4i* red = reinterpret_cast<v4i*>(gd_smem);     // [wave][a][b][lane]
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < NTB; ++a)
 #pragma unroll
-    for (int b = 0; b < MT; ++b) red[((wave * 4 + a) * MT + b) * 64 + lane] = acc[a][b];
+    for (int b = 0; b < MT; ++b) red[((wave * NTB + a) * MT + b) * 64 + lane] = acc[a][b];
   __syncthreads();
   const float alpha = alpha_p[0];
   constexpr int SHIFT = A4 ? 10 : 6;
-  const int n = nb * GD_BN + wave * 16 + 4 * lg;
 #pragma unroll
-  for (int b = 0; b < MT; ++b) {
-    v4i sum = (v4i){0, 0, 0, 0};
+  for (int a = 0; a < NTB; ++a) {
 #pragma unroll
-    for (int w = 0; w < 4; ++w) sum += red[((w * 4 + wave) * MT + b) * 64 + lane];
-    const int m = b * 16 + li;
-    if (m >= M || n >= N) continue;
-    const size_t o = (size_t)m * N + n;
-    if (S == 1) {
-      const int iv[4] = {sum[0] >> SHIFT, sum[1] >> SHIFT, sum[2] >> SHIFT, sum[3] >> SHIFT};
-      gd_store4(Y, y_bf16, acc_out, o, n, N, iv, scale[m], alpha);
-    } else {
-      int32_t* p = partial + (size_t)split * M * N + o;
+    for (int b = 0; b < MT; ++b) {
+      if (((a * MT + b) & 3) != wave) continue;
+      v4i sum = (v4i){0, 0, 0, 0};
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (n + r < N) p[r] = sum[r];
+      for (int w = 0; w < 4; ++w) sum += red[((w * NTB + a) * MT + b) * 64 + lane];
+      const int m = b * 16 + li;
+      const int n = (nb * NTB + a) * 16 + 4 * lg;
+      if (m >= M || n >= N) continue;
+      const size_t o = (size_t)m * N + n;
+      if (S == 1) {
+        const int iv[4] = {sum[0] >> SHIFT, sum[1] >> SHIFT, sum[2] >> SHIFT, sum[3] >> SHIFT};
+        gd_store4(Y, y_bf16, acc_out, o, n, N, iv, scale[m], alpha);
+      } else {
+        int32_t* p = partial + (size_t)split * M * N + o;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (n + r < N) p[r] = sum[r];
+      }
     }
   }
 }
@@ -166,39 +186,50 @@ __global__ __launch_bounds__(GD_THREADS) void decode_reduce_kernel(
   if (id >= (int64_t)M * nq) return;
   const int m = (int)(id / nq), n = (int)(id % nq) * 4;
   int iv[4] = {0, 0, 0, 0};
-  for (int s = 0; s < S; ++s) {
-    const int32_t* p = partial + ((size_t)s * M + m) * N + n;
+  const bool vec = (N & 3) == 0;
+  for (int s0 = 0; s0 < S; s0 += 8) {               // 8 independent loads in flight
+    int4 v[8];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      if (n + r < N) iv[r] += p[r];
+    for (int j = 0; j < 8; ++j) {
+      const int32_t* p = partial + ((size_t)min(s0 + j, S - 1) * M + m) * N + n;
+      if (vec) v[j] = *reinterpret_cast<const int4*>(p);
+      else v[j] = make_int4(p[0], n + 1 < N ? p[1] : 0, n + 2 < N ? p[2] : 0, n + 3 < N ? p[3] : 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < S) { iv[0] += v[j].x; iv[1] += v[j].y; iv[2] += v[j].z; iv[3] += v[j].w; }
   }
 #pragma unroll
   for (int r = 0; r < 4; ++r) iv[r] >>= shift;
   gd_store4(Y, y_bf16, acc_out, (size_t)m * N + n, n, N, iv, scale[m], alpha_p[0]);
 }
 
-static int gd_pick_split(int NB, int KT) {
+// Up to 4 tokens with enough output tiles to fill the chip: one 16-output tile per block, no
+// split of K, one launch.  Otherwise 64 outputs per block and K split until the grid is large.
+static bool gd_single_tile(int M, int N) { return M <= 4 && (N + 15) / 16 >= 128; }
+static int gd_pick_split(int M, int N, int KT) {
+  if (gd_single_tile(M, N)) return 1;
+  const int NB = (N + GD_BN - 1) / GD_BN;
   int S = 1;
   while (NB * S < 512 && S * 2 <= KT && S < 32) S *= 2;
   return S;
 }
 
 size_t bl_gemm_decode_ws_bytes(int64_t M, int64_t N, int64_t K) {
-  const int NB = (int)((N + GD_BN - 1) / GD_BN);
   const int KT = (int)(bl_round_up(K, BL_KPAD) >> 8);
-  const int S = gd_pick_split(NB, KT);
+  const int S = gd_pick_split((int)M, (int)N, KT);
   return S > 1 ? (size_t)S * M * N * sizeof(int32_t) : 0;
 }
 
-template <int MT, bool A4>
+template <int MT, bool A4, int NTB>
 static int gd_run(const void* q, const float* scale, int M, int Kp, const void* Wp,
                   const float* alpha, int N, void* Y, bl_dtype ydt, int32_t* acc_out, void* ws,
                   hipStream_t s) {
-  const int NB = (N + GD_BN - 1) / GD_BN, KT = Kp >> 8;
-  const int S = gd_pick_split(NB, KT);
+  const int NB = (N + 16 * NTB - 1) / (16 * NTB), KT = Kp >> 8;
+  const int S = gd_pick_split(M, N, KT);
   if (S > 1 && !ws) return BL_EWORKSPACE;
-  const size_t smem = (size_t)4 * 4 * MT * 64 * sizeof(v4i);
-  auto kern = gemm_decode_kernel<MT, A4>;
+  const size_t smem = (size_t)4 * NTB * MT * 64 * sizeof(v4i);
+  auto kern = gemm_decode_kernel<MT, A4, NTB>;
   if (smem > 48 * 1024 &&
       hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
     return BL_EHIP;
@@ -222,9 +253,12 @@ int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, i
   const int Kp = (int)bl_round_up(K, BL_KPAD);
   const bool a4 = mode == BL_ACT_INT4_ABSMEAN;
   const int MT = (int)((M + 15) / 16);
-#define GD_CASE(mt)                                                                              \
-  return a4 ? gd_run<mt, true>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)  \
-            : gd_run<mt, false>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)
+#define GD_CASE(mt)                                                                                 \
+  return a4 ? gd_run<mt, true, 4>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)  \
+            : gd_run<mt, false, 4>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)
+  if (gd_single_tile((int)M, (int)N))
+    return a4 ? gd_run<1, true, 1>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)
+              : gd_run<1, false, 1>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s);
   if (MT <= 1) { GD_CASE(1); }
   if (MT == 2) { GD_CASE(2); }
   GD_CASE(4);
@@ -374,10 +408,14 @@ __global__ __launch_bounds__(GD_THREADS) void sparse_reduce_kernel(
   if (id >= (int64_t)M * nq) return;
   const int m = (int)(id / nq), n = (int)(id % nq) * 4;
   int iv[4] = {0, 0, 0, 0};
-  for (int s = 0; s < S; ++s) {
-    const int32_t* p = partial + ((size_t)s * M + m) * Np + n;   // Np is a multiple of 512
+  for (int s0 = 0; s0 < S; s0 += 8) {               // 8 independent loads in flight
+    int4 v[8];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) iv[r] += p[r];
+    for (int j = 0; j < 8; ++j)                     // Np is a multiple of 512: always aligned
+      v[j] = *reinterpret_cast<const int4*>(partial + ((size_t)min(s0 + j, S - 1) * M + m) * Np + n);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < S) { iv[0] += v[j].x; iv[1] += v[j].y; iv[2] += v[j].z; iv[3] += v[j].w; }
   }
 #pragma unroll
   for (int r = 0; r < 4; ++r) iv[r] >>= 6;

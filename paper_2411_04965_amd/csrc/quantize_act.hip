@@ -23,15 +23,15 @@ template <> struct QaVec<u32, 1> { typedef u32 type; };
 
 // Copy one row of K raw elements from global memory into LDS (zero padded to Kp), VEC
 // elements per load.  The row start must be aligned to VEC elements.
-template <typename RawT, int VEC>
+template <typename RawT, int VEC, int NT = QA_THREADS>
 __device__ __forceinline__ void qa_stage_row(const RawT* __restrict__ x, int K, int Kp,
                                              RawT* __restrict__ row) {
   typedef typename QaVec<RawT, VEC>::type V;
   const V* xv = reinterpret_cast<const V*>(x);
   V* rv = reinterpret_cast<V*>(row);
   const int nv = K / VEC;                  // K % VEC == 0 by dispatch
-  for (int i = threadIdx.x; i < nv; i += QA_THREADS) rv[i] = xv[i];
-  for (int i = K + threadIdx.x; i < Kp; i += QA_THREADS) row[i] = (RawT)0;
+  for (int i = threadIdx.x; i < nv; i += NT) rv[i] = xv[i];
+  for (int i = K + threadIdx.x; i < Kp; i += NT) row[i] = (RawT)0;
 }
 
 // ---------------------------------------------------------------- INT4 absmean (eq. 7)
@@ -112,24 +112,27 @@ template <> __device__ __forceinline__ void qa_load4<u32>(const u32* row, int id
   raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
 }
 
-template <typename RawT, int VEC>
-__global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_kernel(
+// NT threads per token: 256 when there are many tokens (several workgroups per CU), 1024 for
+// decode-sized inputs, where the latency of one token's passes is what counts.
+template <typename RawT, int VEC, int NT>
+__global__ __launch_bounds__(NT) void quant_topk_int8_kernel(
     const RawT* __restrict__ X, int K, int Kp, int topk, float eps, u32* __restrict__ q_out,
     float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out,
     int32_t* __restrict__ sel_idx_out) {
+  constexpr int NW = NT / 64;
   extern __shared__ __align__(16) unsigned char qa_smem[];
   RawT* row = reinterpret_cast<RawT*>(qa_smem);
-  __shared__ u32 sh_a[2][QA_WAVES];
-  __shared__ u32 sh_b[QA_WAVES];
-  __shared__ u32 sh_c[QA_WAVES];
+  __shared__ u32 sh_a[2][NW];
+  __shared__ u32 sh_b[NW];
+  __shared__ u32 sh_c[NW];
   constexpr u32 KMASK = QaKey<RawT>::mask;
   const int64_t m = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  qa_stage_row<RawT, VEC>(X + m * (int64_t)K, K, Kp, row);
+  qa_stage_row<RawT, VEC, NT>(X + m * (int64_t)K, K, Kp, row);
   __syncthreads();
 
   const int n_chunks = Kp / 256;
-  const int per_wave = (n_chunks + QA_WAVES - 1) / QA_WAVES;
+  const int per_wave = (n_chunks + NW - 1) / NW;
   const int c_begin = min(wave * per_wave, n_chunks), c_end = min(c_begin + per_wave, n_chunks);
 
   // gamma = max|x| (as a key)
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_kernel(
   __syncthreads();
   kmax = 0;
 #pragma unroll
-  for (int w = 0; w < QA_WAVES; ++w) kmax = max(kmax, sh_b[w]);
+  for (int w = 0; w < NW; ++w) kmax = max(kmax, sh_b[w]);
   const float gamma = sizeof(RawT) == 2 ? __uint_as_float(kmax << 16) : __uint_as_float(kmax);
   const float s = 127.0f / (gamma + eps);
   if (threadIdx.x == 0) scale_out[m] = gamma / 127.0f;
@@ -155,44 +158,41 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_kernel(
   int pass = 0;
   for (int bit = 31 - __clz((int)(kmax | 1u)); bit >= 0; --bit, ++pass) {
     const u32 cand = tau | (1u << bit);
-    int cnt = 0;
+    int cnt = 0;                          // wave-uniform: ballots, no cross-lane reduction
     for (int c = c_begin; c < c_end; ++c) {
       u32 raw[4];
       qa_load4<RawT>(row, c * 256 + lane * 4, raw);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) cnt += ((raw[j] & KMASK) >= cand) ? 1 : 0;
+      for (int j = 0; j < 4; ++j) cnt += __popcll(__ballot((raw[j] & KMASK) >= cand));
     }
-    cnt = bl_wave_sum_i32(cnt);
     if (lane == 0) sh_a[pass & 1][wave] = (u32)cnt;
     __syncthreads();                      // one barrier per pass: slots alternate
     u32 total = 0;
 #pragma unroll
-    for (int w = 0; w < QA_WAVES; ++w) total += sh_a[pass & 1][w];
+    for (int w = 0; w < NW; ++w) total += sh_a[pass & 1][w];
     if (total >= (u32)topk) tau = cand;
   }
 
   // per-wave counts of keys above and equal to tau
   {
-    int gt = 0, eq = 0;
+    int gt = 0, eq = 0;                   // wave-uniform
     for (int c = c_begin; c < c_end; ++c) {
       u32 raw[4];
       qa_load4<RawT>(row, c * 256 + lane * 4, raw);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const u32 key = raw[j] & KMASK;
-        gt += key > tau ? 1 : 0;
-        eq += key == tau ? 1 : 0;
+        gt += __popcll(__ballot(key > tau));
+        eq += __popcll(__ballot(key == tau));
       }
     }
-    gt = bl_wave_sum_i32(gt);
-    eq = bl_wave_sum_i32(eq);
     __syncthreads();                      // sh_b was read above by every thread
     if (lane == 0) { sh_b[wave] = (u32)gt; sh_c[wave] = (u32)eq; }
     __syncthreads();
   }
   int total_gt = 0;
 #pragma unroll
-  for (int w = 0; w < QA_WAVES; ++w) total_gt += (int)sh_b[w];
+  for (int w = 0; w < NW; ++w) total_gt += (int)sh_b[w];
   const int r = topk - total_gt;          // >= 1: how many keys equal to tau are kept
   int eq_base = 0, idx_base = 0;          // equal keys / kept channels before this wave
   for (int w = 0; w < wave; ++w) {
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_kernel(
     __syncthreads();
     if (threadIdx.x == 0) {
       int t = 0;
-      for (int w = 0; w < QA_WAVES; ++w) t += (int)sh_a[0][w];
+      for (int w = 0; w < NW; ++w) t += (int)sh_a[0][w];
       rowsum_out[m] = t;
     }
   }
@@ -374,8 +374,14 @@ static int qa_run_row_kernels(const RawT* X, int64_t M, int K, int Kp, bl_act_mo
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return BL_EHIP;
     kern<<<(unsigned)M, QA_THREADS, smem, s>>>(X, K, Kp, eps, (u32*)q, (float*)scale, rowsum);
+  } else if (M <= 64) {
+    auto kern = quant_topk_int8_kernel<RawT, VEC, 1024>;
+    if (smem > 48 * 1024 &&
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+      return BL_EHIP;
+    kern<<<(unsigned)M, 1024, smem, s>>>(X, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum, sel);
   } else {
-    auto kern = quant_topk_int8_kernel<RawT, VEC>;
+    auto kern = quant_topk_int8_kernel<RawT, VEC, QA_THREADS>;
     if (smem > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return BL_EHIP;
