@@ -273,6 +273,182 @@ __global__ __launch_bounds__(NT) void quant_topk_int8_kernel(
   }
 }
 
+// ---------------------------------------------------------------- Top_k + INT8, keys in registers
+// Same selection as above for bfloat16 rows of up to 4 * CPW * 256 channels, with the token held
+// in registers instead of LDS and counted on the vector ALU instead of through ballots (the
+// scalar unit is shared by the four SIMDs of a compute unit and limits the ballot version).
+// A lane keeps its 4 * CPW channels as 2 * CPW words of two 15-bit keys, each with bit 15 set
+// as a guard: (word - cand * 0x10001) then has bit 15 / bit 31 set exactly where key >= cand,
+// with no borrow between the halves, and v_bcnt accumulates the two flags in one instruction:
+// 1.5 vector instructions per key and pass.  Lane counts are summed inside the wave with DPP
+// adds, across the 4 waves through LDS with one barrier per pass.
+__device__ __forceinline__ int qa_wave_sum_dpp(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x124, 0xF, 0xF, false);   // row_ror:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, false);   // row_ror:8
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+         __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+}
+
+#define QA_GUARD 0x80008000u
+
+// keys >= cand among this lane's, cand in 1 .. 0x8000
+template <int CPW>
+__device__ __forceinline__ int qa_count_ge(const u32 (&pg)[CPW][2], u32 cand) {
+  const u32 c2 = cand * 0x10001u;
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < CPW; ++i)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) cnt += __popc((pg[i][h] - c2) & QA_GUARD);
+  return cnt;
+}
+
+template <int CPW>
+__global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
+    const uint16_t* __restrict__ X, int K, int Kp, int topk, float eps, u32* __restrict__ q_out,
+    float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out) {
+  constexpr int NW = QA_WAVES;
+  static_assert(NW == 4, "one 16-byte LDS read fetches the four wave counts");
+  __shared__ __align__(16) u32 sh_a[2][NW];
+  __shared__ __align__(16) u32 sh_b[NW];
+  __shared__ __align__(16) u32 sh_c[NW];
+  const int64_t m = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_chunks = Kp / 256;
+  const int per_wave = (n_chunks + NW - 1) / NW;          // <= CPW by dispatch
+  const int c_begin = min(wave * per_wave, n_chunks), c_end = min(c_begin + per_wave, n_chunks);
+  const int nc = c_end - c_begin;                         // chunks of this wave; the rest hold key 0
+
+  // one pass over the row: 4 consecutive channels (8 bytes) per lane and chunk, zero beyond K
+  u32 raw[CPW][2], pg[CPW][2];
+  const uint16_t* x = X + m * (int64_t)K;
+  u32 km2 = QA_GUARD;
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) {
+    uint2 v = make_uint2(0u, 0u);
+    const int ch = (c_begin + i) * 256 + lane * 4;
+    if (i < nc && ch < K) v = *reinterpret_cast<const uint2*>(x + ch);   // K % 4 == 0 by dispatch
+    raw[i][0] = v.x; raw[i][1] = v.y;
+    pg[i][0] = v.x | QA_GUARD; pg[i][1] = v.y | QA_GUARD;
+  }
+#pragma unroll
+  for (int i = 0; i < CPW; ++i)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const u32 w = pg[i][h];
+      km2 = max(km2 & 0xFFFFu, w & 0xFFFFu) | (max(km2 >> 16, w >> 16) << 16);
+    }
+  u32 kmax = max(km2 & 0x7FFFu, (km2 >> 16) & 0x7FFFu);
+  kmax = bl_wave_max_u32(kmax);
+  if (lane == 0) sh_b[wave] = kmax;
+  __syncthreads();
+  {
+    const uint4 t = *reinterpret_cast<const uint4*>(sh_b);
+    kmax = (u32)__builtin_amdgcn_readfirstlane((int)max(max(t.x, t.y), max(t.z, t.w)));
+  }
+  const float gamma = __uint_as_float(kmax << 16);
+  const float s = 127.0f / (gamma + eps);
+  if (threadIdx.x == 0) scale_out[m] = gamma / 127.0f;
+
+  // tau = topk-th largest key, bit by bit
+  u32 tau = 0;
+  int pass = 0;
+  for (int bit = 31 - __clz((int)(kmax | 1u)); bit >= 0; --bit, ++pass) {
+    const u32 cand = tau | (1u << bit);
+    const int cnt = qa_wave_sum_dpp(qa_count_ge<CPW>(pg, cand));
+    if (lane == 0) sh_a[pass & 1][wave] = (u32)cnt;
+    __syncthreads();                                      // one barrier per pass: slots alternate
+    const uint4 t = *reinterpret_cast<const uint4*>(sh_a[pass & 1]);
+    const u32 total = (u32)__builtin_amdgcn_readfirstlane((int)(t.x + t.y + t.z + t.w));
+    if (total >= (u32)topk) tau = cand;
+  }
+
+  // per-wave counts of keys above and equal to tau (for tau = 0 every key of the wave's real
+  // chunks is "equal", padding inside the last chunk included, as in the LDS kernel)
+  {
+    const int gt = qa_wave_sum_dpp(qa_count_ge<CPW>(pg, tau + 1u));
+    const int ge = tau ? qa_wave_sum_dpp(qa_count_ge<CPW>(pg, tau)) : nc * 256;
+    __syncthreads();                                      // sh_b was read above by every thread
+    if (lane == 0) { sh_b[wave] = (u32)gt; sh_c[wave] = (u32)(ge - gt); }
+    __syncthreads();
+  }
+  const uint4 gtw = *reinterpret_cast<const uint4*>(sh_b);
+  const uint4 eqw4 = *reinterpret_cast<const uint4*>(sh_c);
+  const int r = topk - (int)__builtin_amdgcn_readfirstlane((int)(gtw.x + gtw.y + gtw.z + gtw.w));
+  const u32 eqs[4] = {eqw4.x, eqw4.y, eqw4.z, eqw4.w};
+  int eq_base = 0;                                        // keys equal to tau in earlier waves
+#pragma unroll
+  for (int w = 0; w < NW - 1; ++w)
+    if (w < wave) eq_base += (int)eqs[w];
+  eq_base = __builtin_amdgcn_readfirstlane(eq_base);
+  const int eq_here = __builtin_amdgcn_readfirstlane((int)sh_c[wave]);
+  // Of the keys equal to tau the first r in channel order are kept.  For a whole wave that is
+  // all of them, none of them, or (for one wave of the token) a prefix found with ballots.
+  const bool eq_all = eq_base + eq_here <= r;
+  const bool eq_none = eq_base >= r;
+  const u32 eq_mode = eq_all ? QA_GUARD : 0u;
+
+  const u32 t1 = (tau + 1u) * 0x10001u, t0 = tau * 0x10001u;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  int sum = 0;
+  u32* out = q_out + m * (int64_t)(Kp / 4);
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) {
+    if (i < nc) {                                         // wave-uniform
+      const int c = c_begin + i;
+      const u32 g0 = (pg[i][0] - t1) & QA_GUARD, g1 = (pg[i][1] - t1) & QA_GUARD;   // key > tau
+      const u32 e0 = ((pg[i][0] - t0) & QA_GUARD) ^ g0, e1 = ((pg[i][1] - t0) & QA_GUARD) ^ g1;
+      u32 k0 = g0 | (e0 & eq_mode), k1 = g1 | (e1 & eq_mode);                       // kept
+      if (!eq_all && !eq_none) {                          // the wave that holds the r-th equal key
+        const bool eqf[4] = {(e0 & 0x8000u) != 0, (e0 >> 31) != 0, (e1 & 0x8000u) != 0, (e1 >> 31) != 0};
+        uint64_t beq[4], any_eq = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { beq[j] = __ballot(eqf[j]); any_eq |= beq[j]; }
+        if (any_eq) {
+          int rank = eq_base, in_chunk = 0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            rank += __popcll(beq[j] & lt_mask);
+            in_chunk += __popcll(beq[j]);
+          }
+          if (eqf[0]) { if (rank < r) k0 |= 0x8000u; ++rank; }
+          if (eqf[1]) { if (rank < r) k0 |= 0x80000000u; ++rank; }
+          if (eqf[2]) { if (rank < r) k1 |= 0x8000u; ++rank; }
+          if (eqf[3]) { if (rank < r) k1 |= 0x80000000u; ++rank; }
+          eq_base += in_chunk;
+        }
+      }
+      // codes: |x * s| <= 127 for every finite row, so RoundClip is the rounding alone, taken
+      // from the low byte of (x * s) + 1.5 * 2^23 (round to nearest even at integer spacing)
+      const float xs[4] = {
+          __uint_as_float((raw[i][0] << 16) & (u32)((int)(k0 << 16) >> 31)),
+          __uint_as_float((raw[i][0] & 0xFFFF0000u) & (u32)((int)k0 >> 31)),
+          __uint_as_float((raw[i][1] << 16) & (u32)((int)(k1 << 16) >> 31)),
+          __uint_as_float((raw[i][1] & 0xFFFF0000u) & (u32)((int)k1 >> 31))};
+      u32 rb[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) rb[j] = __float_as_uint(xs[j] * s + 12582912.0f);
+      const u32 w01 = __builtin_amdgcn_perm(rb[1], rb[0], 0x0c0c0400u);   // bytes: rb0.b0, rb1.b0, 0, 0
+      const u32 w23 = __builtin_amdgcn_perm(rb[3], rb[2], 0x04000c0cu);   // bytes: 0, 0, rb2.b0, rb3.b0
+      const u32 word = w01 | w23;
+      sum = __builtin_amdgcn_sdot4((int)word, 0x01010101, sum, false);
+      out[c * 64 + lane] = word;
+    }
+  }
+  if (rowsum_out) {
+    sum = qa_wave_sum_dpp(sum);
+    __syncthreads();
+    if (lane == 0) sh_a[0][wave] = (u32)sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const uint4 t = *reinterpret_cast<const uint4*>(sh_a[0]);
+      rowsum_out[m] = (int32_t)(t.x + t.y + t.z + t.w);
+    }
+  }
+}
+
 // ---------------------------------------------------------------- FP4 E2M1, block of 32 (eq. 8-9)
 // One thread per block of 32 channels.
 template <typename RawT>
@@ -402,6 +578,20 @@ int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K64, bl_ac
       quant_fp4_kernel<uint16_t><<<(unsigned)blocks, QA_THREADS, 0, s>>>((const uint16_t*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
     else
       quant_fp4_kernel<u32><<<(unsigned)blocks, QA_THREADS, 0, s>>>((const u32*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
+    BL_HIP_CHECK_LAUNCH();
+    return BL_OK;
+  }
+  if (dt == BL_BF16 && mode == BL_ACT_TOPK_INT8_ABSMAX && M > 64 && K % 4 == 0 && Kp <= 12288 &&
+      sel_idx == nullptr) {
+    // many tokens: keys in registers, one memory pass
+    const uint16_t* x = (const uint16_t*)X;
+    const int cpw = (Kp / 256 + QA_WAVES - 1) / QA_WAVES;
+    if (cpw <= 4)
+      quant_topk_int8_regs_kernel<4><<<(unsigned)M, QA_THREADS, 0, s>>>(x, K, Kp, (int)topk, eps, (u32*)q, (float*)scale, rowsum);
+    else if (cpw <= 8)
+      quant_topk_int8_regs_kernel<8><<<(unsigned)M, QA_THREADS, 0, s>>>(x, K, Kp, (int)topk, eps, (u32*)q, (float*)scale, rowsum);
+    else
+      quant_topk_int8_regs_kernel<12><<<(unsigned)M, QA_THREADS, 0, s>>>(x, K, Kp, (int)topk, eps, (u32*)q, (float*)scale, rowsum);
     BL_HIP_CHECK_LAUNCH();
     return BL_OK;
   }
