@@ -13,12 +13,14 @@
 // BM x BN, each wave (BM/2) x (BN/2) as 32x32 MFMA tiles; the MFMA's row operand is the weight
 // fragment and its column operand the token fragment, so a lane ends up with groups of 4
 // consecutive outputs n of one token.  K advances 128 channels per step through two LDS stages,
-// four MFMA sub-steps of 32 channels each.  One step is one straight-line block: its first
-// half (sub-steps 0, 1) also expands the prefetched global data into the other stage and
-// refills the staging registers from global memory; after the barrier the second half
-// (sub-steps 2, 3) also reads the first fragments of the next step.  The K stream of a block
-// runs on across its tiles (no per-tile prologue).  bf16 outputs leave through an LDS transpose
-// so that every store instruction writes whole 128-byte lines.
+// four MFMA sub-steps of 32 channels each.  One step is one straight-line block with one
+// barrier in the middle, and the copy work is split evenly over its halves: the first half
+// (sub-steps 0, 1) expands the prefetched weights of the next step into the other stage, the
+// second half (sub-steps 2, 3) expands the prefetched activations of the step after next into
+// the activation area of the step's own stage, which nobody reads any more once the barrier
+// has been passed; each half reads the MFMA fragments of the other half.  The K stream of a
+// block runs on across its tiles (no per-tile prologue).  bf16 outputs leave through an LDS
+// transpose so that every store instruction writes whole 128-byte lines.
 //
 // Issue budget.  A wave issues in order and one SIMD issues one instruction at a time; an
 // MFMA costs 8 issue cycles and runs 32, a VALU operation costs 4, a 16-byte LDS access more.
@@ -37,7 +39,10 @@ struct GpSmem {
   static constexpr int a_bytes = BM * GP_BK;
   static constexpr int b_bytes = BN * GP_BK;
   static constexpr int stage = a_bytes + b_bytes;
-  static constexpr int total = 2 * stage;
+  // the bf16 transpose buffers of the epilogue (4 waves x 32 rows x (BN + 32) bytes) lie over
+  // the weight area of stage 1 and run on into `extra` bytes behind it
+  static constexpr int extra = 4096;
+  static constexpr int total = 2 * stage + extra;
 };
 
 __device__ __forceinline__ int gp_lds_off(int row, int chunk) {
@@ -102,30 +107,45 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   const u32 b_tile_bytes = (u32)k_tiles * 1024;
   const int a_dst0 = A4 ? gp_lds_off(a_row0, 2 * (tid % PA)) : gp_lds_off(a_row0, tid % PA);
   const int b_dst0 = A_BYTES + gp_lds_off(b_tile0 * 16 + (tid & 15), 4 * ((tid >> 4) & 1));
-  // Uniform parameters of the tile whose data a global load fetches (the loads run two steps
-  // ahead of the MFMAs and cross into the next tile near the end of a tile):
-  struct TileSrc {
-    const unsigned char* a_base;
-    const unsigned char* b_base;
-    u32 a_row_max, b_tile_max;                   // rows / weight tiles past the end re-read the last one
+  // The global loads run ahead of the MFMAs along the block's stream of (tile, K step) pairs,
+  // weights by two steps and activations by three, and cross into the block's following tiles
+  // on their own: each operand has a cursor with the uniform parameters of the tile it reads.
+  struct Cursor {
+    const unsigned char* base;                   // first row (activations) / weight tile of the tile
+    u32 lim;                                     // rows / weight tiles past this one re-read it
+    int ks, tile;
   };
-  auto tile_src = [&](int m0, int n0) -> TileSrc {
-    TileSrc t;
-    t.a_base = A + (size_t)m0 * a_row_bytes;
-    t.a_row_max = (u32)(M - 1 - m0);
-    t.b_base = Wp + (size_t)(n0 >> 4) * k_tiles * 1024;
-    t.b_tile_max = (u32)(n_tiles16 - 1 - (n0 >> 4));
-    return t;
+  auto point_a = [&](Cursor& c, int m0) {
+    c.base = A + (size_t)m0 * a_row_bytes;
+    c.lim = (u32)(M - 1 - m0);
+  };
+  auto point_b = [&](Cursor& c, int n0) {
+    c.base = Wp + (size_t)(n0 >> 4) * k_tiles * 1024;
+    c.lim = (u32)(n_tiles16 - 1 - (n0 >> 4));
+  };
+  // one step on; behind the block's last tile the cursor stays on that tile (loads that nobody uses)
+  auto advance = [&](Cursor& c, bool is_a) {
+    if (++c.ks == nk) {
+      c.ks = 0;
+      const int nt = c.tile + (int)gridDim.x;
+      if (nt < n_tiles) {
+        int tm0, tn0;
+        gp_tile_origin(nt, n_tiles, MT, NTB, BM, BN, tm0, tn0);
+        c.tile = nt;
+        if (is_a) point_a(c, tm0);
+        else point_b(c, tn0);
+      }
+    }
   };
 
   uint4 a_reg[LA], b_reg[LB];
-  auto load_a = [&](const TileSrc& t, int j, int ks) {
-    const u32 off = min(a_row0 + RPJ * j, t.a_row_max) * (u32)a_row_bytes + a_piece;
-    a_reg[j] = *reinterpret_cast<const uint4*>(t.a_base + (size_t)ks * KSB + off);
+  auto load_a = [&](const Cursor& c, int j) {
+    const u32 off = min(a_row0 + RPJ * j, c.lim) * (u32)a_row_bytes + a_piece;
+    a_reg[j] = *reinterpret_cast<const uint4*>(c.base + (size_t)c.ks * KSB + off);
   };
-  auto load_b = [&](const TileSrc& t, int j, int ks) {
-    const u32 off = min(b_tile0 + 8 * j, t.b_tile_max) * b_tile_bytes + b_piece;
-    b_reg[j] = *reinterpret_cast<const uint4*>(t.b_base + (size_t)ks * 512 + off);
+  auto load_b = [&](const Cursor& c, int j) {
+    const u32 off = min(b_tile0 + 8 * j, c.lim) * b_tile_bytes + b_piece;
+    b_reg[j] = *reinterpret_cast<const uint4*>(c.base + (size_t)c.ks * 512 + off);
   };
   // The expansion of one stage is cut into NWR single 16-byte LDS writes per operand so that it
   // can be spread over the MFMA stream.  Rows of load j sit RPJ (resp. 128) rows below those of
@@ -196,27 +216,46 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   const float unscale = A4 ? (1.0f / 1024.0f) : (1.0f / 64.0f);
   constexpr int SHIFT = A4 ? 10 : 6;
 
-  // ---- first tile of this block: stage 0 <- step 0, registers <- step 1, fragments <- step 0
+  // ---- first tile of this block: stage 0 <- step 0, activation area of stage 1 <- step 1,
+  // registers <- activations of step 2 and weights of step 1, fragments <- step 0
   int tile = blockIdx.x;
   int m0, n0;
   gp_tile_origin(tile, n_tiles, MT, NTB, BM, BN, m0, n0);
-  TileSrc cur = tile_src(m0, n0);
+  Cursor ca, cb;
+  ca.ks = cb.ks = 0;
+  ca.tile = cb.tile = tile;
+  point_a(ca, m0);
+  point_b(cb, n0);
 #pragma unroll
-  for (int j = 0; j < LA; ++j) load_a(cur, j, 0);
+  for (int j = 0; j < LA; ++j) load_a(ca, j);
 #pragma unroll
-  for (int j = 0; j < LB; ++j) load_b(cur, j, 0);
+  for (int j = 0; j < LB; ++j) load_b(cb, j);
+  advance(ca, true);
+  advance(cb, false);
 #pragma unroll
   for (int i = 0; i < NWR_A; ++i) write_a(gp_smem, i);
 #pragma unroll
   for (int i = 0; i < NWR_B; ++i) write_b(gp_smem, i);
 #pragma unroll
-  for (int j = 0; j < LA; ++j) load_a(cur, j, 1);
+  for (int j = 0; j < LA; ++j) load_a(ca, j);
+  advance(ca, true);
 #pragma unroll
-  for (int j = 0; j < LB; ++j) load_b(cur, j, 1);
+  for (int i = 0; i < NWR_A; ++i) write_a(gp_smem + STAGE, i);
+  // (weights before activations, the order in which the loop refills them: the compiler derives
+  // the loop's wait counts from the oldest-first order of the loads in flight on every path)
+#pragma unroll
+  for (int j = 0; j < LB; ++j) load_b(cb, j);
+#pragma unroll
+  for (int j = 0; j < LA; ++j) load_a(ca, j);
+  advance(ca, true);
+  advance(cb, false);
   __syncthreads();
   // Two full fragment sets, one per half step.  Each half reads the other half's set, so a
-  // stage is read only before the barrier of its own step and, for the next step, only after
-  // the barrier of the step that filled it: one barrier per step orders everything.
+  // stage is read only before the barrier of its own step (second-half fragments) and after
+  // the barrier of the step before (first-half fragments).  Writes: weights of step k + 1 go
+  // to the other stage before the barrier of step k and are first read behind it; activations
+  // of step k + 2 go to step k's own stage behind its barrier and are first read behind the
+  // barrier of step k + 1.  One barrier per step orders everything.
   v4i xF[2][TM], wF[2][TN];                      // sub-steps 0, 1
   v4i xS[2][TM], wS[2][TN];                      // sub-steps 2, 3
 #pragma unroll
@@ -228,14 +267,11 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     }
 
   while (true) {
-    // The K stream runs on across tile boundaries: the loads of the last two steps of a tile
-    // fetch steps 0 and 1 of the block's next tile, so that tile starts with its first stage,
-    // staging registers and fragments already in place (nk is even: stage parity carries over).
+    // The K stream runs on across tile boundaries: the last steps of a tile already fetch and
+    // expand the first steps of the block's next tile, so that tile starts with its stages,
+    // staging registers and fragments in place (nk is even: stage parity carries over).
     const int next = tile + (int)gridDim.x;
     const bool has_next = next < n_tiles;
-    int nm0 = m0, nn0 = n0;
-    if (has_next) gp_tile_origin(next, n_tiles, MT, NTB, BM, BN, nm0, nn0);
-    const TileSrc nxt = tile_src(nm0, nn0);
 
     v16i acc[TN][TM];
 #pragma unroll
@@ -255,99 +291,118 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
 
     for (int ks = 0; ks < nk; ++ks) {
       const int stage = ks & 1;
+      unsigned char* st_own = gp_smem + stage * STAGE;
       unsigned char* st_other = gp_smem + (stage ^ 1) * STAGE;
-      // target of this step's global loads: two steps ahead
-      const bool wrap = ks + 2 >= nk;
-      const int ks2 = wrap ? (has_next ? ks + 2 - nk : nk - 1) : ks + 2;
-      TileSrc ld;
-      ld.a_base = (wrap && has_next) ? nxt.a_base : cur.a_base;
-      ld.b_base = (wrap && has_next) ? nxt.b_base : cur.b_base;
-      ld.a_row_max = (wrap && has_next) ? nxt.a_row_max : cur.a_row_max;
-      ld.b_tile_max = (wrap && has_next) ? nxt.b_tile_max : cur.b_tile_max;
 
       // first half: sub-steps 0, 1 (k 0..63) on this step's stage.  Per MFMA row: one token
-      // and one weight fragment of the second half, one activation piece and one weight
-      // piece expanded into the other stage, and the global loads that refill the staging
+      // and one weight fragment of the second half, one weight piece (the next step's)
+      // expanded into the other stage, and the global loads that refill the weight staging
       // registers just consumed (a full step before their data is expanded).
+      // Order inside a row, from measurement: a 16-byte LDS write costs about 30 issue cycles
+      // and stalls the MFMA stream least directly behind the fragment reads and not behind
+      // vector instructions, which in turn are free at up to 4 per MFMA gap.  So a row writes
+      // the piece expanded during the row before it and then expands its own.
+      {
+        uint4 cw_prev;
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
+        for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-        for (int a = 0; a < TN; ++a) {
-          const int hrow = sub * TN + a;         // row within the half step
-          uint4 ca, cb;
-          u32 x0 = 0, x1 = 0, w = b_word(hrow);
-          if (A4) {
-            x0 = a_word(hrow, 0);
-            x1 = a_word(hrow, 1);
-          }
+          for (int a = 0; a < TN; ++a) {
+            const int hrow = sub * TN + a;       // row within the half step
+            uint4 cw;
+            u32 w = b_word(hrow);
 #pragma unroll
-          for (int b = 0; b < TM; ++b) {
-            GP_MFMA(acc[a][b], wF[sub][a], xF[sub][b]);
-            // slots behind MFMA b of this row (4 per row; a 2-MFMA row takes two at a time)
-            const int s0 = (TM == 4) ? b : 2 * b, s1 = (TM == 4) ? b : 2 * b + 1;
-            if (s0 == 0) {
-              xS[sub][a] = read_x(stage, 2 + sub, a);
-              wS[sub][a] = read_w(stage, 2 + sub, a);
-              if (A4) {
-                GP_PIN_IN(x0);
-                ca.x = (x0 << 4) & MA;
-                GP_PIN_OUT(ca.x, ca.x);
+            for (int b = 0; b < TM; ++b) {
+              GP_MFMA(acc[a][b], wF[sub][a], xF[sub][b]);
+              // slots behind MFMA b of this row (4 per row; a 2-MFMA row takes two at a time)
+              const int s0 = (TM == 4) ? b : 2 * b, s1 = (TM == 4) ? b : 2 * b + 1;
+              if (s0 == 0) {
+                xS[sub][a] = read_x(stage, 2 + sub, a);
+                wS[sub][a] = read_w(stage, 2 + sub, a);
+              }
+              if (s0 <= 1 && 1 <= s1) {
+                if (hrow > 0) store_b(st_other, hrow - 1, cw_prev);
+              }
+              if (s0 <= 2 && 2 <= s1) {
+                GP_PIN_IN(w);
+                cw.x = (w << 6) & MB; cw.y = (w << 4) & MB;
+                GP_PIN_OUT(cw.x, cw.y);
+              }
+              if (s0 <= 3 && 3 <= s1) {
+                GP_PIN_IN(w);
+                cw.z = (w << 2) & MB; cw.w = w & MB;
+                GP_PIN_OUT(cw.z, cw.w);
+                if (hrow % B_EVERY == B_EVERY - 1) load_b(cb, hrow / B_EVERY);
               }
             }
-            if (s0 <= 1 && 1 <= s1) {
-              if (A4) {
-                GP_PIN_IN(x0);
-                ca.y = x0 & MA;
-                GP_PIN_IN(x1);
-                ca.z = (x1 << 4) & MA; ca.w = x1 & MA;
-                GP_PIN_OUT(ca.y, ca.z);
-                GP_PIN_OUT(ca.w, ca.w);
-              } else {
-                ca = make_uint4(a_reg[hrow].x, a_reg[hrow].y, a_reg[hrow].z, a_reg[hrow].w);
-              }
-              store_a(st_other, hrow, ca);
-            }
-            if (s0 <= 2 && 2 <= s1) {
-              GP_PIN_IN(w);
-              cb.x = (w << 6) & MB; cb.y = (w << 4) & MB;
-              cb.z = (w << 2) & MB;
-              GP_PIN_OUT(cb.x, cb.y);
-              GP_PIN_OUT(cb.z, cb.z);
-            }
-            if (s0 <= 3 && 3 <= s1) {
-              GP_PIN_IN(w);
-              cb.w = w & MB;
-              store_b(st_other, hrow, cb);
-              if (hrow % A_EVERY == A_EVERY - 1) load_a(ld, hrow / A_EVERY, ks2);
-              if (hrow % B_EVERY == B_EVERY - 1) load_b(ld, hrow / B_EVERY, ks2);
-            }
+            cw_prev = cw;
           }
         }
+        store_b(st_other, ROWS - 1, cw_prev);
       }
+      advance(cb, false);
       __syncthreads();
       // second half: sub-steps 2, 3 (k 64..127).  Per MFMA row: one token and one weight
-      // fragment of the next step's first half, from the stage all waves have just filled.
+      // fragment of the next step's first half from the other stage, one activation piece (of
+      // the step after next) expanded into this step's own stage, and the global loads that
+      // refill the activation staging registers.
+      {
+        uint4 cx_prev;
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
+        for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-        for (int a = 0; a < TN; ++a) {
-#pragma unroll
-          for (int b = 0; b < TM; ++b) {
-            GP_MFMA(acc[a][b], wS[sub][a], xS[sub][b]);
-            if (b == 0) {
-              xF[sub][a] = read_x(stage ^ 1, sub, a);
-              wF[sub][a] = read_w(stage ^ 1, sub, a);
+          for (int a = 0; a < TN; ++a) {
+            const int hrow = sub * TN + a;
+            uint4 cx;
+            u32 x0 = 0, x1 = 0;
+            if (A4) {
+              x0 = a_word(hrow, 0);
+              x1 = a_word(hrow, 1);
             }
+#pragma unroll
+            for (int b = 0; b < TM; ++b) {
+              GP_MFMA(acc[a][b], wS[sub][a], xS[sub][b]);
+              const int s0 = (TM == 4) ? b : 2 * b, s1 = (TM == 4) ? b : 2 * b + 1;
+              if (s0 == 0) {
+                xF[sub][a] = read_x(stage ^ 1, sub, a);
+                wF[sub][a] = read_w(stage ^ 1, sub, a);
+              }
+              if (s0 <= 1 && 1 <= s1) {
+                if (A4) {
+                  if (hrow > 0) store_a(st_own, hrow - 1, cx_prev);
+                } else {                          // INT8: a plain copy, nothing to wait for
+                  store_a(st_own, hrow, make_uint4(a_reg[hrow].x, a_reg[hrow].y, a_reg[hrow].z, a_reg[hrow].w));
+                }
+              }
+              if (s0 <= 2 && 2 <= s1) {
+                if (A4) {
+                  GP_PIN_IN(x0);
+                  cx.x = (x0 << 4) & MA; cx.y = x0 & MA;
+                  GP_PIN_OUT(cx.x, cx.y);
+                }
+              }
+              if (s0 <= 3 && 3 <= s1) {
+                if (A4) {
+                  GP_PIN_IN(x1);
+                  cx.z = (x1 << 4) & MA; cx.w = x1 & MA;
+                  GP_PIN_OUT(cx.z, cx.w);
+                }
+                if (hrow % A_EVERY == A_EVERY - 1) load_a(ca, hrow / A_EVERY);
+              }
+            }
+            if (A4) cx_prev = cx;
           }
         }
+        if (A4) store_a(st_own, ROWS - 1, cx_prev);
       }
+      advance(ca, true);
       // The MFMAs are issued from inline assembly, so the compiler does not know that their
       // results need wait states before a VALU may read them; the register allocator reads
       // accumulators right at the loop exit.  16 wait states here cover the last MFMA.
       asm volatile("s_nop 15" ::: "memory");
     }
 
-    // The staging registers already hold the next tile's step 1: make their loads complete
+    // The staging registers already hold data of the next tile: make their loads complete
     // here, before the epilogue's stores join the same counter.
 #pragma unroll
     for (int j = 0; j < LA; ++j) asm volatile("" ::"v"(a_reg[j].x), "v"(a_reg[j].y), "v"(a_reg[j].z), "v"(a_reg[j].w));
@@ -359,14 +414,16 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     // like float(acc) * d.
     if (OUT == 0) {
       // bf16 through an LDS transpose, 32 tokens x WN outputs at a time.  The last step ran
-      // on stage 1 (nk is even) and read it only before its barrier; stage 0 already holds
-      // the next tile's first step.  So stage 1 is free until the barrier at the end of the
-      // epilogue.  Rows are padded by 32 bytes against bank
+      // on stage 1 (nk is even); stage 0 and the activation area of stage 1 already hold the
+      // next tile's first two steps, but the weight area of stage 1 was last read before the
+      // last barrier and is written again only in the next tile's first step, behind the
+      // barrier at the end of the epilogue.  Rows are padded by 32 bytes against bank
       // conflicts; read back row-wise, 16 lanes cover one token's WN * 2 contiguous bytes, so
       // every store instruction writes whole 128-byte lines.
       constexpr int TB_ROW = WN * 2 + 32;
-      unsigned char* tbuf = gp_smem + STAGE + wave * (32 * TB_ROW);
-      static_assert(4 * 32 * TB_ROW <= STAGE, "transpose buffers must fit into one stage");
+      unsigned char* tbuf = gp_smem + STAGE + A_BYTES + wave * (32 * TB_ROW);
+      static_assert(4 * 32 * TB_ROW <= GpSmem<BM, BN>::b_bytes + GpSmem<BM, BN>::extra,
+                    "transpose buffers must fit into the weight area of stage 1 plus the tail");
       constexpr int LANES_PER_ROW = WN * 2 / 16;           // 16 (WN = 128) or 8 (WN = 64)
       constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
       const int rr = lane / LANES_PER_ROW, cc = lane % LANES_PER_ROW;
@@ -472,9 +529,7 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     }
     if (!has_next) break;
     tile = next;
-    m0 = nm0;
-    n0 = nn0;
-    cur = nxt;
+    gp_tile_origin(tile, n_tiles, MT, NTB, BM, BN, m0, n0);
     if (OUT == 0) __syncthreads();     // transpose buffers are read out before stage 1 is refilled
   }
 #undef GP_PIN_IN
