@@ -454,12 +454,24 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
           // would wait on the stores in flight
           __builtin_amdgcn_sched_barrier(0);
         }
+        // row b * 32 + i * ROWS_PER_PASS + rr of the wave tile per pass i
+        constexpr int NPASS = 32 / ROWS_PER_PASS;
+        if (interior) {                                    // uniform: all reads in flight, then all stores
+          v4i v[NPASS];
 #pragma unroll
-        for (int i = 0; i < 32 / ROWS_PER_PASS; ++i) {
-          const int row = b * 32 + i * ROWS_PER_PASS;      // + rr: token row within the wave tile
-          const uint4 v = *reinterpret_cast<const uint4*>(tbuf + (rr + i * ROWS_PER_PASS) * TB_ROW + cc * 16);
-          uint16_t* yrow = ywave + (size_t)row * N;
-          if (interior || (row < m_left && 0 < n_left)) *reinterpret_cast<uint4*>(yrow + lane_off) = v;
+          for (int i = 0; i < NPASS; ++i)
+            v[i] = *reinterpret_cast<const v4i*>(tbuf + (rr + i * ROWS_PER_PASS) * TB_ROW + cc * 16);
+          __builtin_amdgcn_sched_barrier(0);               // (keeps the reads from being paired off with the stores)
+#pragma unroll
+          for (int i = 0; i < NPASS; ++i)
+            *reinterpret_cast<v4i*>(ywave + (size_t)(b * 32 + i * ROWS_PER_PASS) * N + lane_off) = v[i];
+        } else {
+#pragma unroll
+          for (int i = 0; i < NPASS; ++i) {
+            const int row = b * 32 + i * ROWS_PER_PASS;
+            const uint4 v = *reinterpret_cast<const uint4*>(tbuf + (rr + i * ROWS_PER_PASS) * TB_ROW + cc * 16);
+            if (row < m_left && 0 < n_left) *reinterpret_cast<uint4*>(ywave + (size_t)row * N + lane_off) = v;
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
