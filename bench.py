@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 
 EPS = 1e-5
 INT8_PEAK_TOPS = 5033.0      # MI355X dense int8 MFMA
+FP6_FP4_PEAK_TOPS = 10066.0  # MI355X dense fp6 / fp4 MFMA (the INT4 GEMM runs on E3M2 x E2M1 operands)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the W1.58A4 prefill GEMM at the benchmark shapes, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_prefill_7b_hbm_traffic.txt
@@ -103,7 +104,8 @@ def main():
     W = {}
     for i, (name, N, K, kind) in enumerate(projs):
         w = torch.from_numpy(S.latent_weights(N, K, S.seed_for(3, 20 + i))).to(dev)
-        W[name] = B.pack_ternary(w, EPS, B.BL_W_GEMM)
+        # INT4 projections: block-float layout (E2M1 nibbles) for the 6-bit x 4-bit matrix instruction
+        W[name] = B.pack_ternary(w, EPS, B.BL_W_MX4 if kind == "a4" else B.BL_W_GEMM)
         del w
     x_hidden = to_dev(S.heavy(M, HIDDEN, S.seed_for(3, 1)))
     x_attn = to_dev(S.heavy(M, HIDDEN, S.seed_for(3, 3)))
@@ -113,10 +115,10 @@ def main():
     # preallocated outputs / code buffers (no allocation inside the timed region)
     bufs = {}
     for name, N, K, kind in projs:
-        mode = B.BL_ACT_INT4_ABSMEAN if kind == "a4" else B.BL_ACT_TOPK_INT8_ABSMAX
+        mode = B.BL_ACT_INT4_ABSMEAN_MX6 if kind == "a4" else B.BL_ACT_TOPK_INT8_ABSMAX
         L = B.lib()
         bufs[name] = dict(
-            mode=mode,
+            mode=mode, layout=B.BL_W_MX4 if kind == "a4" else B.BL_W_GEMM,
             q=torch.empty(L.quantize_act_bytes(mode, M, K), dtype=torch.uint8, device=dev),
             scale=torch.empty(M, dtype=torch.float32, device=dev),
             Y=torch.empty((M, N), dtype=bf16, device=dev),
@@ -141,7 +143,7 @@ def main():
             if record:
                 e1.record()
             rc = L.bitlinear_gemm(b["q"].data_ptr(), b["scale"].data_ptr(), b["mode"], M, K,
-                                  W[name][0].data_ptr(), B.BL_W_GEMM, W[name][1].data_ptr(), N,
+                                  W[name][0].data_ptr(), b["layout"], W[name][1].data_ptr(), N,
                                   b["Y"].data_ptr(), B.BL_BF16, None, b["ws"].data_ptr(),
                                   b["ws"].numel(), stream)
             assert rc == 0, rc
@@ -184,11 +186,12 @@ def main():
     a4_ops = sum(2.0 * M * N * K for _, N, K in a4)
     a4_ms = sum(per_kernel[n_]["gemm_ms"] for n_, _, _ in a4)
     achieved = a4_ops / (a4_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_prefill_kernel<256,256,INT4> (qkv, gate, up)",
-                "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                "frac": round(achieved / INT8_PEAK_TOPS, 4),
+    roofline = {"bound": "mfma", "kernel": "gemm_a4_mx_kernel (qkv, gate, up): E3M2 x E2M1 block-float MFMA",
+                "achieved": round(achieved, 1), "peak": FP6_FP4_PEAK_TOPS, "unit": "TOP/s",
+                "frac": round(achieved / FP6_FP4_PEAK_TOPS, 4),
+                "frac_of_int8_peak": round(achieved / INT8_PEAK_TOPS, 4),
                 "traffic": A4_GEMM_TRAFFIC_BYTES if M == 16384 else None,
-                "algorithmic_bytes": round(sum(M * K / 2 + N * K / 4 + 2 * M * N for _, N, K in a4) / len(a4)),
+                "algorithmic_bytes": round(sum(M * K * 3 / 4 + N * K / 2 + 2 * M * N for _, N, K in a4) / len(a4)),
                 "avg_launch_ms": round(a4_ms / len(a4), 4)}
 
     out = {
@@ -212,7 +215,7 @@ def main():
 
 def bl_code_bytes(kind, K):
     Kp = (K + 255) // 256 * 256
-    return Kp // 2 if kind == "a4" else Kp
+    return Kp * 3 // 4 if kind == "a4" else Kp      # 6-bit codes / int8
 
 
 def decode_bench(B, S, torch, dev, layers=8, replays=20):

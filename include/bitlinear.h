@@ -34,8 +34,25 @@
  *               field f = n % 16.  (K rows only, no K padding.)  Used by the row-skipping
  *               decode path: one weight row segment is one 128-byte line.
  *
+ *   BL_W_MX4    ternary weights as E2M1 nibbles (0000 = 0, 0010 = +1, 1010 = -1) in the order the
+ *               block-float matrix instruction reads them: blocks of 32 output channels x 256
+ *               input channels, 4096 bytes each, block (nb, kb) at byte (nb * Kp/256 + kb) * 4096
+ *               (N rounded up to 32).  Inside a block, row r = n % 32 takes 128 bytes; its 16-byte
+ *               piece p holds unit u = p ^ (r % 8), i.e. channels 256*kb + 32*u ... + 31, channel
+ *               i of the unit in nibble i (low nibble of a byte first).  Used by the prefill
+ *               GEMM of the INT4 path; twice the bytes of BL_W_GEMM.
+ *
  *   INT4 activations  [M][Kp/2] bytes.  Channels are taken 8 at a time into one
  *               32-bit word; byte b (0..3) of the word is (q[k0+b] & 15) | (q[k0+4+b] << 4).
+ *   INT4 activations, MX6 form: the same 16 levels, each stored as its 6-bit E3M2 code
+ *               (bit 5 sign, bits 4..2 exponent with bias 3, bits 1..0 mantissa; all INT4
+ *               levels are exact), in blocks of 32 tokens x 256 channels, 6144 bytes each,
+ *               block (mb, kb) at byte (mb * Kp/256 + kb) * 6144 (M rounded up to 32; rows past
+ *               M are not written).  The 32 channels of unit u (channels 256*kb + 32*u ... + 31)
+ *               form a 24-byte little-endian bit stream, channel i in bits 6i ... 6i+5.  Inside a
+ *               block, token row r = m % 32 keeps stream bytes 0..15 of unit u in the 16-byte
+ *               piece p = u ^ (r % 8) at byte r*128 + 16*p, and stream bytes 16..23 in the 8-byte
+ *               piece p' = u ^ ((r / 4) % 8) at byte 4096 + r*64 + 8*p'.
  *   INT8 activations  [M][Kp] bytes, plain int8, zeros where the Top_k mask is 0.
  *   FP4 activations   [M][Kp/2] bytes of E2M1 nibbles (bit 3 sign, bits 2..0 code of
  *               {0, .5, 1, 1.5, 2, 3, 4, 6}).  Channels are taken 16 at a time into two
@@ -59,10 +76,11 @@ typedef enum { BL_F32 = 0, BL_BF16 = 1 } bl_dtype;
 typedef enum {
   BL_ACT_INT4_ABSMEAN = 0,     /* eq. 7 */
   BL_ACT_TOPK_INT8_ABSMAX = 1, /* eq. 1 + eq. 3 */
-  BL_ACT_FP4_E2M1_B32 = 2      /* eq. 8-9 with one power-of-two scale per 32 channels */
+  BL_ACT_FP4_E2M1_B32 = 2,     /* eq. 8-9 with one power-of-two scale per 32 channels */
+  BL_ACT_INT4_ABSMEAN_MX6 = 3  /* eq. 7, levels stored as E3M2 codes for the block-float GEMM */
 } bl_act_mode;
 
-typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1 } bl_w_layout;
+typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1, BL_W_MX4 = 2 } bl_w_layout;
 
 typedef enum {
   BL_OK = 0,
@@ -98,6 +116,7 @@ int pack_ternary(const void* W, bl_dtype w_dtype, int64_t N, int64_t K, float ep
  * quantize_act: one token per row, statistics per token.
  *   BL_ACT_INT4_ABSMEAN (eq. 7):  beta = mean|x| (float64 sum, rounded once);
  *       q = RoundClip(x * (sqrt7 / (beta + eps)), -8, 7);  scale_out[m] = beta / sqrt7.
+ *   BL_ACT_INT4_ABSMEAN_MX6: the same quantizer, codes in the MX6 form (for BL_W_MX4 weights).
  *   BL_ACT_TOPK_INT8_ABSMAX (eq. 1, 3): mask = the `topk` largest |x| of the token
  *       (exactly topk entries; equal magnitudes: lower channel first; 1 <= topk <= K,
  *       topk = K is the dense INT8 quantizer); gamma = max|x|;
@@ -128,7 +147,12 @@ int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, bl_act_m
  *   FP4 path: Y = alpha * sum over blocks 2^e * sum_k v_k * T[n, k], accumulated in
  *   float32 by the scaled FP4 matrix instruction (not bit-exact; acc_out must be NULL).
  *   X          device, [M, K] of x_dtype
- *   W_packed   device, output of pack_ternary for [N, K]; layout must be BL_W_GEMM
+ *   W_packed   device, output of pack_ternary for [N, K]; layout BL_W_GEMM, or BL_W_MX4
+ *              (INT4 path only): then the activations are quantized to the MX6 form and the
+ *              product runs on the 6-bit x 4-bit block-float matrix instruction at twice the
+ *              INT8 rate; every product and every partial sum is an integer below 2^24, so the
+ *              float32 accumulator equals the int32 one bit for bit.  Size the workspace with
+ *              mode BL_ACT_INT4_ABSMEAN_MX6 in that case.
  *   alpha      device, float32[1]
  *   Y          device, [M, N] of y_dtype
  *   acc_out    nullable; device int32[M, N], receives the integer accumulators
@@ -154,8 +178,10 @@ int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, i
 
 /* The matmul + rescale stage alone, on activations already quantized by quantize_act
  * (what the two calls above run after their quantize kernel).  q and scale are the
- * outputs of quantize_act in `mode`; for BL_W_KMAJOR, `workspace` must hold
- * bitlinear_workspace_bytes(mode, M, N, K) bytes, otherwise it may be NULL. */
+ * outputs of quantize_act in `mode`; BL_ACT_INT4_ABSMEAN_MX6 goes with BL_W_MX4 and with
+ * nothing else.  `workspace` must hold bitlinear_workspace_bytes(mode, M, N, K) bytes when
+ * M <= BL_DECODE_MAX_M (partial sums of the split-K decode kernels) or the layout is
+ * BL_W_KMAJOR; otherwise it may be NULL. */
 int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M, int64_t K,
                    const void* W_packed, bl_w_layout layout, const float* alpha, int64_t N,
                    void* Y, bl_dtype y_dtype, int32_t* acc_out,

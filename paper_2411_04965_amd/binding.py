@@ -14,8 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libbitlinear.so")
 
 BL_F32, BL_BF16 = 0, 1
-BL_ACT_INT4_ABSMEAN, BL_ACT_TOPK_INT8_ABSMAX, BL_ACT_FP4_E2M1_B32 = 0, 1, 2
-BL_W_GEMM, BL_W_KMAJOR = 0, 1
+BL_ACT_INT4_ABSMEAN, BL_ACT_TOPK_INT8_ABSMAX, BL_ACT_FP4_E2M1_B32, BL_ACT_INT4_ABSMEAN_MX6 = 0, 1, 2, 3
+BL_W_GEMM, BL_W_KMAJOR, BL_W_MX4 = 0, 1, 2
 BL_DECODE_MAX_M = 64
 DEFAULT_EPS = 1e-5
 
@@ -154,15 +154,16 @@ def _out(M, N, y_dtype, device, want_acc):
 
 
 def bitlinear_a4(X, W_packed, alpha, N, eps=DEFAULT_EPS, act_fp4=False, y_dtype=torch.bfloat16,
-                 want_acc=False, ws=None, out=None):
+                 want_acc=False, ws=None, out=None, layout=BL_W_GEMM):
     _dev(X)
     M, K = X.shape
-    mode = BL_ACT_FP4_E2M1_B32 if act_fp4 else BL_ACT_INT4_ABSMEAN
+    mode = BL_ACT_FP4_E2M1_B32 if act_fp4 else (
+        BL_ACT_INT4_ABSMEAN_MX6 if layout == BL_W_MX4 else BL_ACT_INT4_ABSMEAN)
     if ws is None:
         ws = workspace(mode, M, N, K, X.device)
     Y, acc = _out(M, N, y_dtype, X.device, want_acc) if out is None else (out, None)
     _check("bitlinear_a4", lib().bitlinear_a4(
-        _ptr(X), _dt(X), M, K, _ptr(W_packed), BL_W_GEMM, _ptr(alpha), N, eps, int(act_fp4),
+        _ptr(X), _dt(X), M, K, _ptr(W_packed), layout, _ptr(alpha), N, eps, int(act_fp4),
         _ptr(Y), _dt(Y), _ptr(acc), _ptr(ws), ws.numel(), _stream()))
     return (Y, acc) if want_acc else Y
 

@@ -5,8 +5,8 @@
 static inline size_t ws_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static bool valid_dtype(int d) { return d == BL_F32 || d == BL_BF16; }
-static bool valid_layout(int l) { return l == BL_W_GEMM || l == BL_W_KMAJOR; }
-static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_FP4_E2M1_B32; }
+static bool valid_layout(int l) { return l == BL_W_GEMM || l == BL_W_KMAJOR || l == BL_W_MX4; }
+static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_INT4_ABSMEAN_MX6; }
 
 static int check_sizes(int64_t M, int64_t N, int64_t K) {
   if (M < 1 || N < 1 || K < 1) return BL_EINVAL;
@@ -36,6 +36,7 @@ extern "C" size_t pack_ternary_bytes(int64_t N, int64_t K, bl_w_layout layout) {
   if (N < 1 || K < 1) return 0;
   if (layout == BL_W_GEMM) return (size_t)(bl_round_up(N, 16) * bl_round_up(K, BL_KPAD) / 4);
   if (layout == BL_W_KMAJOR) return (size_t)(bl_round_up(N, 512) / 4 * K);
+  if (layout == BL_W_MX4) return (size_t)(bl_round_up(N, 32) * bl_round_up(K, BL_KPAD) / 2);
   return 0;
 }
 
@@ -69,6 +70,7 @@ extern "C" size_t quantize_act_bytes(bl_act_mode mode, int64_t M, int64_t K) {
     case BL_ACT_INT4_ABSMEAN: return (size_t)(M * Kp / 2);
     case BL_ACT_TOPK_INT8_ABSMAX: return (size_t)(M * Kp);
     case BL_ACT_FP4_E2M1_B32: return (size_t)(M * Kp / 2);
+    case BL_ACT_INT4_ABSMEAN_MX6: return (size_t)(bl_round_up(M, 32) * Kp / 4 * 3);
     default: return 0;
   }
 }
@@ -105,7 +107,7 @@ extern "C" int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K,
 // ---------------------------------------------------------------- linear layers
 // Workspace layout: [codes | scales | stage-2 scratch], each part 256-byte aligned.
 static size_t stage2_ws_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K) {
-  if (mode == BL_ACT_FP4_E2M1_B32 || M > BL_DECODE_MAX_M) return 0;
+  if (mode == BL_ACT_FP4_E2M1_B32 || mode == BL_ACT_INT4_ABSMEAN_MX6 || M > BL_DECODE_MAX_M) return 0;
   size_t a = bl_gemm_decode_ws_bytes(M, N, K);
   if (mode == BL_ACT_TOPK_INT8_ABSMAX && M <= 8) {
     const size_t b = bl_gemv_sparse_ws_bytes(M, N, K);
@@ -124,6 +126,10 @@ static int gemm_dispatch(const void* q, const void* scale, bl_act_mode mode, int
                          const void* W_packed, bl_w_layout layout, const float* alpha, int64_t N,
                          void* Y, bl_dtype y_dtype, int32_t* acc_out, void* ws, size_t ws_bytes,
                          hipStream_t s) {
+  // the block-float forms of activations and weights go together and with nothing else
+  if ((mode == BL_ACT_INT4_ABSMEAN_MX6) != (layout == BL_W_MX4)) return BL_EINVAL;
+  if (mode == BL_ACT_INT4_ABSMEAN_MX6)
+    return bl_launch_gemm_a4_mx(q, (const float*)scale, M, K, W_packed, alpha, N, Y, y_dtype, acc_out, s);
   if (mode == BL_ACT_FP4_E2M1_B32) {
     if (layout != BL_W_GEMM || acc_out) return BL_EINVAL;
     return bl_launch_gemm_fp4(q, (const uint8_t*)scale, M, K, W_packed, alpha, N, Y, y_dtype, s);
@@ -178,6 +184,7 @@ static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, 
   if (!bl_aligned16(workspace)) return BL_EALIGN;
   // reject what the second stage would reject, before the first kernel is enqueued
   if (mode == BL_ACT_FP4_E2M1_B32 && (layout != BL_W_GEMM || acc_out)) return BL_EINVAL;
+  if ((mode == BL_ACT_INT4_ABSMEAN_MX6) != (layout == BL_W_MX4)) return BL_EINVAL;
   if (layout == BL_W_KMAJOR && (mode != BL_ACT_TOPK_INT8_ABSMAX || M > 8)) return BL_EUNSUPPORTED;
 
   unsigned char* p = (unsigned char*)workspace;
@@ -200,8 +207,10 @@ extern "C" int bitlinear_a4(const void* X, bl_dtype x_dtype, int64_t M, int64_t 
                             int32_t* acc_out, void* workspace, size_t workspace_bytes,
                             void* stream) {
   if (act_fp4 != 0 && act_fp4 != 1) return BL_EINVAL;
-  if (layout != BL_W_GEMM) return valid_layout(layout) ? BL_EUNSUPPORTED : BL_EINVAL;
-  return linear_common(X, x_dtype, M, K, act_fp4 ? BL_ACT_FP4_E2M1_B32 : BL_ACT_INT4_ABSMEAN, 0,
+  if (layout != BL_W_GEMM && layout != BL_W_MX4) return valid_layout(layout) ? BL_EUNSUPPORTED : BL_EINVAL;
+  if (layout == BL_W_MX4 && act_fp4) return BL_EINVAL;
+  const bl_act_mode int4_mode = layout == BL_W_MX4 ? BL_ACT_INT4_ABSMEAN_MX6 : BL_ACT_INT4_ABSMEAN;
+  return linear_common(X, x_dtype, M, K, act_fp4 ? BL_ACT_FP4_E2M1_B32 : int4_mode, 0,
                        W_packed, layout, alpha, N, eps, Y, y_dtype, acc_out, workspace,
                        workspace_bytes, stream);
 }

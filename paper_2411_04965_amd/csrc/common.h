@@ -49,6 +49,23 @@ __device__ __forceinline__ u32 bl_wave_max_u32(u32 v) {
   return v;
 }
 
+// Tile index -> tile origin.  Blocks are dealt round-robin to the 8 XCDs, so tiles whose index
+// is congruent mod 8 run on one XCD: give each XCD a contiguous range of the tile order, and
+// walk that order in groups of 4 token tiles, so that the tiles an XCD works on at one time
+// share activations and weights in its L2.
+__device__ __forceinline__ void bl_tile_origin(int t, int n_tiles, int MT, int NTB, int BM, int BN,
+                                               int& m0, int& n0) {
+  const int q = n_tiles >> 3, rmd = n_tiles & 7, xcd = t & 7, loc = t >> 3;
+  const int pid = xcd * q + min(xcd, rmd) + loc;
+  constexpr int GM = 4;
+  const int per_group = GM * NTB;
+  const int group = pid / per_group, in_group = pid % per_group;
+  const int first_m = group * GM;
+  const int gsz = min(MT - first_m, GM);
+  m0 = (first_m + in_group % gsz) * BM;
+  n0 = (in_group / gsz) * BN;
+}
+
 // Internal launchers (one per source file); all return a bl_status.
 int bl_launch_pack_ternary(const void* W, bl_dtype dt, int64_t N, int64_t K, float eps,
                            bl_w_layout layout, void* out, float* alpha, void* ws, hipStream_t s);
@@ -70,6 +87,9 @@ int bl_launch_gemv_sparse(const void* q, const float* scale, int64_t M, int64_t 
                           const void* Wk, const float* alpha, int64_t N, void* Y, bl_dtype ydt,
                           int32_t* acc_out, void* ws, hipStream_t s);
 size_t bl_gemv_sparse_ws_bytes(int64_t M, int64_t N, int64_t K);
+int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K, const void* Wp,
+                         const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,
+                         hipStream_t s);
 int bl_launch_gemm_fp4(const void* q, const uint8_t* scale, int64_t M, int64_t K, const void* Wp,
                        const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);
 int bl_launch_relu2_glu(const void* G, const void* U, bl_dtype dt, int64_t n, void* H,

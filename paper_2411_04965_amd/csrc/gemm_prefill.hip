@@ -55,23 +55,6 @@ __device__ __forceinline__ u32 gp_pack_bf16(float lo, float hi) {
   return r;
 }
 
-// Tile index -> tile origin.  Blocks are dealt round-robin to the 8 XCDs, so tiles whose index
-// is congruent mod 8 run on one XCD: give each XCD a contiguous range of the tile order, and
-// walk that order in groups of 4 token tiles, so that the tiles an XCD works on at one time
-// share activations and weights in its L2.
-__device__ __forceinline__ void gp_tile_origin(int t, int n_tiles, int MT, int NTB, int BM, int BN,
-                                               int& m0, int& n0) {
-  const int q = n_tiles >> 3, rmd = n_tiles & 7, xcd = t & 7, loc = t >> 3;
-  const int pid = xcd * q + min(xcd, rmd) + loc;
-  constexpr int GM = 4;
-  const int per_group = GM * NTB;
-  const int group = pid / per_group, in_group = pid % per_group;
-  const int first_m = group * GM;
-  const int gsz = min(MT - first_m, GM);
-  m0 = (first_m + in_group % gsz) * BM;
-  n0 = (in_group / gsz) * BN;
-}
-
 // OUT: 0 = bf16 rows through the LDS transpose (N % 8 == 0), 1 = 4 outputs per store (N % 4 == 0),
 // 2 = one output per store (any N).  ACC: also write the int32 accumulators (tests).
 template <int BM, int BN, bool A4, int OUT, bool ACC>
@@ -130,7 +113,7 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
       const int nt = c.tile + (int)gridDim.x;
       if (nt < n_tiles) {
         int tm0, tn0;
-        gp_tile_origin(nt, n_tiles, MT, NTB, BM, BN, tm0, tn0);
+        bl_tile_origin(nt, n_tiles, MT, NTB, BM, BN, tm0, tn0);
         c.tile = nt;
         if (is_a) point_a(c, tm0);
         else point_b(c, tn0);
@@ -220,7 +203,7 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   // registers <- activations of step 2 and weights of step 1, fragments <- step 0
   int tile = blockIdx.x;
   int m0, n0;
-  gp_tile_origin(tile, n_tiles, MT, NTB, BM, BN, m0, n0);
+  bl_tile_origin(tile, n_tiles, MT, NTB, BM, BN, m0, n0);
   Cursor ca, cb;
   ca.ks = cb.ks = 0;
   ca.tile = cb.tile = tile;
@@ -541,7 +524,7 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
     }
     if (!has_next) break;
     tile = next;
-    gp_tile_origin(tile, n_tiles, MT, NTB, BM, BN, m0, n0);
+    bl_tile_origin(tile, n_tiles, MT, NTB, BM, BN, m0, n0);
     if (OUT == 0) __syncthreads();     // transpose buffers are read out before stage 1 is refilled
   }
 #undef GP_PIN_IN

@@ -109,6 +109,41 @@ __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_kmajor_kernel(
   out[((d >> 5) * K + k) * 32 + (d & 31)] = word;
 }
 
+// One thread per 32-bit word of the block-float GEMM layout: blocks of 32 outputs x 256 input
+// channels (4096 bytes); inside, row r = n % 32 takes 128 bytes, its 16-byte piece p holds the
+// 32 channels of unit u = p ^ (r & 7) as E2M1 nibbles (0 -> 0000, +1 -> 0010, -1 -> 1010), low
+// nibble first.  A word covers 8 consecutive channels.
+template <typename T>
+__global__ __launch_bounds__(PT_THREADS) void ternarize_pack_mx4_kernel(
+    const T* __restrict__ W, int64_t N, int64_t K, int64_t Kp, float eps,
+    const double* __restrict__ partial, int n_partial, u32* __restrict__ out,
+    float* __restrict__ alpha_out, int64_t n_words) {
+  __shared__ double red[PT_THREADS / BL_WAVE];
+  const float alpha = pt_alpha(partial, n_partial, N * K, red);
+  if (blockIdx.x == 0 && threadIdx.x == 0) alpha_out[0] = alpha;
+  const float t = alpha + eps;
+  const int64_t w = (int64_t)blockIdx.x * PT_THREADS + threadIdx.x;
+  if (w >= n_words) return;
+  const int64_t blk = w >> 10;              // 1024 words per block
+  const int in = (int)(w & 1023);
+  const int r = in >> 5, p = (in >> 2) & 7, j = in & 3;
+  const int64_t KB = Kp / 256;
+  const int64_t n = (blk / KB) * 32 + r;
+  const int64_t k0 = (blk % KB) * 256 + 32 * (p ^ (r & 7)) + 8 * j;
+  u32 word = 0;
+  if (n < N) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t k = k0 + i;
+      if (k < K) {
+        const u32 c = pt_code(pt_load<T>(W, n * K + k), t);        // 00, 01, 11
+        word |= (((c & 2u) << 2) | ((c & 1u) << 1)) << (4 * i);    // sign to bit 3, magnitude 1.0 = 010
+      }
+    }
+  }
+  out[w] = word;
+}
+
 __global__ __launch_bounds__(PT_THREADS) void unpack_ternary_kernel(const u32* __restrict__ packed,
                                                                     int64_t N, int64_t K,
                                                                     int64_t Kp, int64_t Np,
@@ -119,6 +154,13 @@ __global__ __launch_bounds__(PT_THREADS) void unpack_ternary_kernel(const u32* _
   const int64_t n = id / K, k = id % K;
   u32 word;
   int f;
+  if (layout == BL_W_MX4) {
+    const int r = (int)(n & 31), u = (int)((k >> 5) & 7), i = (int)(k & 31);
+    const u32 w4 = packed[((n >> 5) * (Kp / 256) + (k >> 8)) * 1024 + r * 32 + ((u ^ (r & 7)) << 2) + (i >> 3)];
+    const u32 c = (w4 >> (4 * (i & 7))) & 15u;
+    T[id] = (int8_t)(c == 0 ? 0 : ((c & 8u) ? -1 : 1));
+    return;
+  }
   if (layout == BL_W_GEMM) {
     const int64_t nt = n >> 4, kt = k >> 8;
     const int i = (int)(n & 15), g = (int)((k >> 6) & 3), t = (int)((k >> 4) & 3);
@@ -153,7 +195,13 @@ static int pt_run(const T* W, int64_t N, int64_t K, float eps, bl_w_layout layou
   double* partial = (double*)ws;
   abs_sum_partial_kernel<T><<<np, PT_THREADS, 0, s>>>(W, n, partial);
   BL_HIP_CHECK_LAUNCH();
-  if (layout == BL_W_GEMM) {
+  if (layout == BL_W_MX4) {
+    const int64_t Kp = bl_round_up(K, BL_KPAD), Np = bl_round_up(N, 32);
+    const int64_t n_words = Np * Kp / 8;
+    const int64_t blocks = (n_words + PT_THREADS - 1) / PT_THREADS;
+    ternarize_pack_mx4_kernel<T><<<(unsigned)blocks, PT_THREADS, 0, s>>>(
+        W, N, K, Kp, eps, partial, np, (u32*)out, alpha, n_words);
+  } else if (layout == BL_W_GEMM) {
     const int64_t Kp = bl_round_up(K, BL_KPAD), Np = bl_round_up(N, 16);
     const int64_t n_words = Np * Kp / 16;
     const int64_t blocks = (n_words + PT_THREADS - 1) / PT_THREADS;

@@ -35,7 +35,20 @@ __device__ __forceinline__ void qa_stage_row(const RawT* __restrict__ x, int K, 
 }
 
 // ---------------------------------------------------------------- INT4 absmean (eq. 7)
-template <typename RawT, int VEC>
+// E3M2 code (sign, 3 exponent bits with bias 3, 2 mantissa bits) of an INT4 level -8..7: every
+// level is exact in that format.  Magnitudes 0..8 -> 00, 0C, 10, 12, 14, 15, 16, 17, 18.
+__device__ __forceinline__ u32 qa_e3m2_of_level(int q) {
+  const unsigned long long lut = 0x00ull | (0x0Cull << 6) | (0x10ull << 12) | (0x12ull << 18) |
+                                 (0x14ull << 24) | (0x15ull << 30) | (0x16ull << 36) |
+                                 (0x17ull << 42) | (0x18ull << 48);
+  const int a = q < 0 ? -q : q;
+  return ((u32)(lut >> (6 * a)) & 63u) | (q < 0 ? 32u : 0u);
+}
+
+// MX6: the same levels, written as E3M2 codes in the tile order of the block-float GEMM (blocks of
+// 32 tokens x 256 channels, 6144 bytes; see the format notes of the public header) instead of
+// packed nibbles.
+template <typename RawT, int VEC, bool MX6>
 __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
     const RawT* __restrict__ X, int K, int Kp, float eps, u32* __restrict__ q_out,
     float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out) {
@@ -62,8 +75,37 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
   if (threadIdx.x == 0) scale_out[m] = beta / sqrt7;
 
   int sum = 0;
+  if (MX6) {
+    // one thread per half unit: 16 channels = 96 bits of the unit's 192-bit stream
+    unsigned char* blk = reinterpret_cast<unsigned char*>(q_out) + (m >> 5) * (int64_t)(Kp / 256) * 6144;
+    const int r = (int)(m & 31);
+    for (int h = threadIdx.x; h < Kp / 16; h += QA_THREADS) {
+      u32 w3[3] = {0u, 0u, 0u};
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        float p = qa_to_f32<RawT>(row[16 * h + j]) * s;     // one float32 multiply
+        p = fminf(fmaxf(rintf(p), -8.0f), 7.0f);
+        const int q = (int)p;
+        sum += q;
+        const u32 c = qa_e3m2_of_level(q);
+        const int bit = 6 * j;
+        w3[bit >> 5] |= c << (bit & 31);
+        if ((bit & 31) > 26) w3[(bit >> 5) + 1] |= c >> (32 - (bit & 31));
+      }
+      const int kb = h >> 4, u = (h >> 1) & 7;
+      unsigned char* b = blk + (int64_t)kb * 6144;
+      u32* pp = reinterpret_cast<u32*>(b + r * 128 + ((u ^ (r & 7)) << 4));
+      if ((h & 1) == 0) {                                   // stream bytes 0..11
+        pp[0] = w3[0]; pp[1] = w3[1]; pp[2] = w3[2];
+      } else {                                              // stream bytes 12..15 and 16..23
+        pp[3] = w3[0];
+        u32* qq = reinterpret_cast<u32*>(b + 4096 + r * 64 + ((u ^ ((r >> 2) & 7)) << 3));
+        qq[0] = w3[1]; qq[1] = w3[2];
+      }
+    }
+  }
   u32* out = q_out + m * (int64_t)(Kp / 8);
-  for (int w = threadIdx.x; w < Kp / 8; w += QA_THREADS) {
+  for (int w = threadIdx.x; !MX6 && w < Kp / 8; w += QA_THREADS) {
     int q[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -527,6 +569,25 @@ __global__ __launch_bounds__(QA_THREADS) void unpack_act_kernel(const u32* __res
   } else if (mode == BL_ACT_TOPK_INT8_ABSMAX) {
     const u32 word = q[m * (Kp / 4) + (k >> 2)];
     v = (int)(int8_t)((word >> (8 * (k & 3))) & 255u);
+  } else if (mode == BL_ACT_INT4_ABSMEAN_MX6) {
+    // value i of unit u: bits 6 i .. 6 i + 5 of the unit's stream, bytes 0..15 in the P piece and
+    // bytes 16..23 in the Q piece of the token's row inside its 32-token block
+    const unsigned char* blk = reinterpret_cast<const unsigned char*>(q) +
+                               ((m >> 5) * (int64_t)(Kp / 256) + (k >> 8)) * 6144;
+    const int r = (int)(m & 31), u = (k >> 5) & 7, bit = 6 * (k & 31);
+    const unsigned char* pp = blk + r * 128 + ((u ^ (r & 7)) << 4);
+    const unsigned char* qq = blk + 4096 + r * 64 + ((u ^ ((r >> 2) & 7)) << 3);
+    u32 two = 0;                                            // the two stream bytes that hold the code
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int byte = (bit >> 3) + j;
+      if (byte < 24) two |= (u32)(byte < 16 ? pp[byte] : qq[byte - 16]) << (8 * j);
+    }
+    const u32 c = (two >> (bit & 7)) & 63u;
+    const int e = (int)((c >> 2) & 7u), mant = (int)(c & 3u);
+    // levels are integers: 2^(e-3) * (1 + mant/4) for e >= 1, zero otherwise
+    const int mag = e == 0 ? 0 : (((4 + mant) << e) >> 5);
+    v = (c & 32u) ? -mag : mag;
   } else {
     const int kk = k & 15;
     const int wsel = (kk >> 2) & 1;
@@ -544,8 +605,8 @@ static int qa_run_row_kernels(const RawT* X, int64_t M, int K, int Kp, bl_act_mo
                               float eps, void* q, void* scale, int32_t* rowsum, int32_t* sel,
                               hipStream_t s) {
   const size_t smem = (size_t)Kp * sizeof(RawT);
-  if (mode == BL_ACT_INT4_ABSMEAN) {
-    auto kern = quant_int4_kernel<RawT, VEC>;
+  if (mode == BL_ACT_INT4_ABSMEAN || mode == BL_ACT_INT4_ABSMEAN_MX6) {
+    auto kern = mode == BL_ACT_INT4_ABSMEAN ? quant_int4_kernel<RawT, VEC, false> : quant_int4_kernel<RawT, VEC, true>;
     if (smem > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return BL_EHIP;

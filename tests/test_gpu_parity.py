@@ -9,8 +9,9 @@ import torch
 from oracle import bitnet_a48 as O
 from paper_2411_04965_amd import binding as B
 from paper_2411_04965_amd import synth as S
-from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_int4, decode_int8,
-                            decode_w_gemm, decode_w_kmajor, dev, host, pack)
+from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_int4, decode_int4_mx6,
+                            decode_int8, decode_w_gemm, decode_w_kmajor, decode_w_mx4, dev, host,
+                            pack)
 
 pytestmark = pytest.mark.gpu
 BF16 = torch.bfloat16
@@ -24,7 +25,7 @@ def say(msg):
 # ------------------------------------------------------------------ pack_ternary (eq. 2)
 @pytest.mark.parametrize("N,K,dtype", [(512, 256, F32), (256, 512, F32), (37, 100, F32),
                                        (1030, 5460, BF16), (2048, 5460, F32)])
-@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_KMAJOR])
+@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_KMAJOR, B.BL_W_MX4])
 def test_pack_ternary(N, K, dtype, layout):
     say("pack_ternary N=%d K=%d %s layout=%d" % (N, K, dtype, layout))
     W = S.latent_weights(N, K, seed=S.seed_for(0, N + K))
@@ -35,7 +36,7 @@ def test_pack_ternary(N, K, dtype, layout):
     assert host(alpha)[0] == alpha_ref
     T_lib = host(B.unpack_ternary(packed, N, K, layout))
     assert np.array_equal(T_lib, T_ref)
-    dec = decode_w_gemm if layout == B.BL_W_GEMM else decode_w_kmajor
+    dec = {B.BL_W_GEMM: decode_w_gemm, B.BL_W_KMAJOR: decode_w_kmajor, B.BL_W_MX4: decode_w_mx4}[layout]
     assert np.array_equal(dec(host(packed), N, K), T_ref)
 
 
@@ -69,6 +70,12 @@ def test_quantize_int4(kind, M, K, dtype):
     assert np.array_equal(host(r["scale"]), d_ref)
     assert np.array_equal(host(B.unpack_act(r["q"], B.BL_ACT_INT4_ABSMEAN, M, K)), q_ref)
     assert np.array_equal(decode_int4(host(r["q"]), M, K), q_ref)
+    assert np.array_equal(host(r["rowsum"]), q_ref.sum(1, dtype=np.int32))
+    # the same levels in the form the block-float GEMM reads (E3M2 codes, 32-token blocks)
+    r = B.quantize_act(dev(x, dtype), B.BL_ACT_INT4_ABSMEAN_MX6, 0, EPS, want_rowsum=True)
+    assert np.array_equal(host(r["scale"]), d_ref)
+    assert np.array_equal(host(B.unpack_act(r["q"], B.BL_ACT_INT4_ABSMEAN_MX6, M, K)), q_ref)
+    assert np.array_equal(decode_int4_mx6(host(r["q"]), M, K), q_ref)
     assert np.array_equal(host(r["rowsum"]), q_ref.sum(1, dtype=np.int32))
 
 
@@ -200,6 +207,8 @@ def _decode_weights(name, N, K):
         packs = {B.BL_W_GEMM: pack(W)}
         if name in ("o", "down"):
             packs[B.BL_W_KMAJOR] = pack(W, B.BL_W_KMAJOR)
+        else:
+            packs[B.BL_W_MX4] = pack(W, B.BL_W_MX4)
         _wcache[name] = (T, alpha, packs)
     return _wcache[name]
 
@@ -223,7 +232,7 @@ def test_config2_decode(name, N, K, kind, M):
             continue
         assert host(a)[0] == alpha
         if kind == "a4":
-            res = B.bitlinear_a4(Xd, p, a, N, EPS, y_dtype=BF16, want_acc=True)
+            res = B.bitlinear_a4(Xd, p, a, N, EPS, y_dtype=BF16, want_acc=True, layout=layout)
         else:
             res = B.bitlinear_a8_sparse(Xd, K // 2, p, a, N, EPS, layout, BF16, True)
         _check_linear(res, ref, BF16)
@@ -246,6 +255,25 @@ def test_decode_odd_shapes(M):
 
 
 # ------------------------------------------------------------------ full prefill size (config 3), sampled rows
+@pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (300, 520, 1000, BF16), (130, 2048, 5460, BF16),
+                                         (257, 5460, 2048, BF16), (1100, 1100, 768, BF16),
+                                         (70, 1030, 300, BF16), (33, 257, 4096, F32), (600, 1500, 256, BF16)])
+def test_a4_block_float_gemm(M, N, K, dtype):
+    """The INT4 linear on the 6-bit x 4-bit matrix instruction (BL_W_MX4 weights): accumulators
+    bit-exact against the integer oracle, for several tiles, ragged M / N / K, every store path
+    (N % 8 == 0, N % 4 == 0, odd N) and a single K block."""
+    say("a4 block-float M=%d N=%d K=%d %s" % (M, N, K, dtype))
+    X = S.heavy(M, K, S.seed_for(1, M + N))
+    W = S.latent_weights(N, K, S.seed_for(1, K + N + 1))
+    p, a = pack(W, B.BL_W_MX4)
+    ref = O.bitlinear_a4(X, W, EPS, "bf16" if dtype == BF16 else "f32")
+    _check_linear(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=dtype, want_acc=True, layout=B.BL_W_MX4),
+                  ref, dtype)
+    # the kernel variant without accumulator output (the one a caller normally runs)
+    Y = B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=dtype, layout=B.BL_W_MX4)
+    assert np.array_equal(host(Y), ref["y"])
+
+
 @pytest.mark.parametrize("name,N,K,kind", [("qkv", 12288, 4096, "a4"), ("down", 4096, 11008, "a8s")])
 def test_config3_prefill_sampled_rows(name, N, K, kind):
     """M = 16384 in the launch configuration the benchmark times; the oracle checks 128 sampled
@@ -261,6 +289,10 @@ def test_config3_prefill_sampled_rows(name, N, K, kind):
     if kind == "a4":
         Y, acc = B.bitlinear_a4(Xd, p, a, N, EPS, y_dtype=BF16, want_acc=True)
         q, d = O.quant_int4(X[rows], EPS)
+        # and on the block-float path, in the launch configuration the benchmark times
+        pm, am = packs[B.BL_W_MX4]
+        Ym = B.bitlinear_a4(Xd, pm, am, N, EPS, y_dtype=BF16, layout=B.BL_W_MX4)
+        assert torch.equal(Ym, Y)
     else:
         Y, acc = B.bitlinear_a8_sparse(Xd, K // 2, p, a, N, EPS, B.BL_W_GEMM, BF16, True)
         q, d, _ = O.quant_topk_int8(X[rows], K // 2, EPS)
