@@ -35,24 +35,24 @@
  *               decode path: one weight row segment is one 128-byte line.
  *
  *   BL_W_MX4    ternary weights as E2M1 nibbles (0000 = 0, 0010 = +1, 1010 = -1) in the order the
- *               block-float matrix instruction reads them: blocks of 32 output channels x 256
- *               input channels, 4096 bytes each, block (nb, kb) at byte (nb * Kp/256 + kb) * 4096
- *               (N rounded up to 32).  Inside a block, row r = n % 32 takes 128 bytes; its 16-byte
- *               piece p holds unit u = p ^ (r % 8), i.e. channels 256*kb + 32*u ... + 31, channel
- *               i of the unit in nibble i (low nibble of a byte first).  Used by the prefill
- *               GEMM of the INT4 path; twice the bytes of BL_W_GEMM.
+ *               block-float matrix instruction reads them: blocks of 32 output channels x 128
+ *               input channels, 2048 bytes each, block (nb, kb) at byte (nb * Kp/128 + kb) * 2048
+ *               (N rounded up to 32).  Inside a block, row r = n % 32 takes 64 bytes; its 16-byte
+ *               piece p holds unit u = p ^ ((r / 2) % 4), i.e. channels 128*kb + 32*u ... + 31,
+ *               channel i of the unit in nibble i (low nibble of a byte first).  Used by the
+ *               prefill GEMM of the INT4 path; twice the bytes of BL_W_GEMM.
  *
  *   INT4 activations  [M][Kp/2] bytes.  Channels are taken 8 at a time into one
  *               32-bit word; byte b (0..3) of the word is (q[k0+b] & 15) | (q[k0+4+b] << 4).
  *   INT4 activations, MX6 form: the same 16 levels, each stored as its 6-bit E3M2 code
  *               (bit 5 sign, bits 4..2 exponent with bias 3, bits 1..0 mantissa; all INT4
- *               levels are exact), in blocks of 32 tokens x 256 channels, 6144 bytes each,
- *               block (mb, kb) at byte (mb * Kp/256 + kb) * 6144 (M rounded up to 32; rows past
- *               M are not written).  The 32 channels of unit u (channels 256*kb + 32*u ... + 31)
+ *               levels are exact), in blocks of 32 tokens x 128 channels, 3072 bytes each,
+ *               block (mb, kb) at byte (mb * Kp/128 + kb) * 3072 (M rounded up to 32; rows past
+ *               M are not written).  The 32 channels of unit u (channels 128*kb + 32*u ... + 31)
  *               form a 24-byte little-endian bit stream, channel i in bits 6i ... 6i+5.  Inside a
  *               block, token row r = m % 32 keeps stream bytes 0..15 of unit u in the 16-byte
- *               piece p = u ^ (r % 8) at byte r*128 + 16*p, and stream bytes 16..23 in the 8-byte
- *               piece p' = u ^ ((r / 4) % 8) at byte 4096 + r*64 + 8*p'.
+ *               piece p = u ^ ((r / 2) % 4) at byte r*64 + 16*p, and stream bytes 16..23 in the
+ *               8-byte piece p' = u ^ ((r / 4) % 4) at byte 2048 + r*32 + 8*p'.
  *   INT8 activations  [M][Kp] bytes, plain int8, zeros where the Top_k mask is 0.
  *   FP4 activations   [M][Kp/2] bytes of E2M1 nibbles (bit 3 sign, bits 2..0 code of
  *               {0, .5, 1, 1.5, 2, 3, 4, 6}).  Channels are taken 16 at a time into two

@@ -8,7 +8,7 @@
 // for bit, whatever the order of the additions.
 //
 // Both operands arrive in HBM in the order in which LDS wants them (see the format notes in the
-// public header): blocks of 32 rows x 256 channels, rows XOR-swizzled by 16-byte (8-byte) piece so
+// public header): blocks of 32 rows x 128 channels, rows XOR-swizzled by 16-byte (8-byte) piece so
 // that the fragment reads are free of bank conflicts.  The copy from global memory to LDS is
 // therefore linear and is done by global_load_lds_dwordx4: no staging registers, no LDS write
 // instructions and no vector work in the main loop, which consists of MFMAs, fragment reads and
@@ -17,24 +17,31 @@
 // Structure.  Persistent blocks (one per CU) walk the tile list; block = 4 waves, tile
 // 256 x 256, each wave 128 x 128 as 4 x 4 MFMA tiles; the MFMA's row operand is the weight
 // fragment and its column operand the token fragment, so a lane ends up with groups of 4
-// consecutive outputs n of one token.  K advances 256 channels per step through two LDS stages
-// of 80 KB (the whole LDS), four MFMA sub-steps of 64 channels each, with two register sets of
-// fragments: sub-step s computes on one set while the other is filled for sub-step s + 1.
-// One barrier per step, at the end of sub-step 2: by then every wave has read its last
+// consecutive outputs n of one token.  K advances 128 channels per step through a ring of four
+// LDS stages of 40 KB (the whole LDS), two MFMA sub-steps of 64 channels each, with two register
+// sets of fragments: a sub-step computes on one set while the other is filled for the next.
+// One barrier per step, at the end of its first sub-step: by then every wave has read its last
 // fragments of the step's stage, and (after waiting for its own loads) the next step's stage is
-// complete.  Behind the barrier the loads of the step after next go into the stage just freed.
-// Each wave copies the row blocks 2w and 2w + 1 of both operands.
+// complete.  Behind the barrier the loads of step g + 4 go into the stage of step g.
+//
+// The asynchronous loads are limited by the 64 bytes per clock between L1 and the CU: a 1 KB
+// load occupies a wave's share of that path for 64 cycles, and a burst of loads stalls the MFMA
+// stream of the issuing wave.  The tile needs 40 KB per 1024 MFMA cycles, 62% of the path, so
+// the loads are issued evenly, five per sub-step, each behind its own MFMA, and run three steps
+// ahead of the MFMAs.  Each wave copies the row blocks 2w and 2w + 1 of both operands.
 #include "common.h"
 
 #define GX_THREADS 256
 #define GX_BM 256
 #define GX_BN 256
-#define GX_XQ 32768                  // stage layout: [XP 8 x 4096 | XQ 8 x 2048 | W 8 x 4096]
-#define GX_W 49152
-#define GX_STAGE 81920
-#define GX_LDS (2 * GX_STAGE)
-#define GX_A_BLOCK 6144              // bytes of 32 tokens x 256 channels of 6-bit codes
-#define GX_W_BLOCK 4096              // bytes of 32 outputs x 256 channels of 4-bit codes
+#define GX_XQ 16384                  // stage layout: [XP 8 x 2048 | XQ 8 x 1024 | W 8 x 2048]
+#define GX_W 24576
+#define GX_STAGE 40960
+#define GX_NSTAGE 4
+#define GX_LDS (GX_NSTAGE * GX_STAGE)
+#define GX_A_BLOCK 3072              // bytes of 32 tokens x 128 channels of 6-bit codes
+#define GX_W_BLOCK 2048              // bytes of 32 outputs x 128 channels of 4-bit codes
+#define GX_LOADS_PER_STEP 10         // asynchronous 1 KB loads per wave and step
 
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v6i __attribute__((ext_vector_type(6)));
@@ -47,27 +54,18 @@ __device__ __forceinline__ u32 gx_pack_bf16(float lo, float hi) {
   return r;
 }
 
-// Four (two) asynchronous 1 KB copies global -> LDS: lane l moves 16 bytes from base + voff + o to
-// LDS byte address lds + 16 l + o for o = 0, 1024, ...  (M0 holds the LDS address; the immediate
-// offset applies to both sides.)  The copies are counted by vmcnt like any other load.
-// (The host pass of the compiler parses kernel bodies too and knows no scalar-register
+// One asynchronous 1 KB copy global -> LDS: lane l moves 16 bytes from base + voff to LDS byte
+// address lds + 16 l (M0 holds the LDS address).  The copies are counted by vmcnt like any other
+// load.  (The host pass of the compiler parses kernel bodies too and knows no scalar-register
 // constraint, so it sees empty statements here.)
 #if defined(__HIP_DEVICE_COMPILE__)
-#define GX_DMA4(lds, base, voff)                                                        \
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"                                        \
-               "global_load_lds_dwordx4 %1, %2\n\t"                                     \
-               "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"                         \
-               "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"                         \
-               "global_load_lds_dwordx4 %1, %2 offset:3072"                             \
+#define GX_DMA(lds, base, voff)                                                         \
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"          \
                ::"s"(lds), "v"(voff), "s"(base) : "memory")
-#define GX_DMA2(lds, base, voff)                                                        \
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"                                        \
-               "global_load_lds_dwordx4 %1, %2\n\t"                                     \
-               "global_load_lds_dwordx4 %1, %2 offset:1024"                             \
-               ::"s"(lds), "v"(voff), "s"(base) : "memory")
+#define GX_WAIT_LOADS(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
 #else
-#define GX_DMA4(lds, base, voff) ((void)0)
-#define GX_DMA2(lds, base, voff) ((void)0)
+#define GX_DMA(lds, base, voff) ((void)0)
+#define GX_WAIT_LOADS(n) ((void)0)
 #endif
 
 // OUT: 0 = bf16 rows through the LDS transpose (N % 8 == 0), 1 = 4 outputs per store (N % 4 == 0),
@@ -87,13 +85,12 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   const int MB = (M + 31) >> 5, NB = (N + 31) >> 5;           // 32-row blocks of the operands
   constexpr int WM = 128, WN = 128, TM = 4, TN = 4;
 
-  // ---- asynchronous copies.  The cursor names the (tile, K block) that is copied next and
+  // ---- asynchronous copies.  The cursor names the (tile, K step) that is copied next and
   // moves on along the block's stream of tiles by itself.
   struct Cursor {
     const unsigned char* a[2];
     const unsigned char* w[2];
     int kb, tile;
-    bool live;                                   // false once the stream has run out
   };
   auto point = [&](Cursor& c, int tile) {
     int m0, n0;
@@ -108,12 +105,14 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       c.w[i] = Wp + (size_t)wb * KB * GX_W_BLOCK;
     }
   };
+  // one step on; behind the block's last step the cursor stays where it is (the loads go on, so
+  // that the number of loads in flight is the same at every barrier; their data is never used)
   auto advance = [&](Cursor& c) {
-    if (++c.kb == KB) {
+    if (c.kb + 1 == KB) {
       const int nt = c.tile + (int)gridDim.x;
       if (nt < n_tiles) point(c, nt);
-      else c.live = false;
     } else {
+      ++c.kb;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         c.a[i] += GX_A_BLOCK;
@@ -122,34 +121,35 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     }
   };
   const u32 dma_voff = lane * 16;
-  // copy part p (0..5) of the cursor's K block into the stage at LDS address st
+  // load p (0..9) of the cursor's K step into the stage at LDS address st: row block 2w + p / 5,
+  // there XP (2 KB), XQ (1 KB), W (2 KB)
   auto dma_part = [&](const Cursor& c, u32 st, int p) {
-    const int i = p / 3, rb = 2 * wave + i;
-    if (p % 3 == 0) GX_DMA4(st + rb * 4096, c.a[i], dma_voff);
-    else if (p % 3 == 1) GX_DMA2(st + GX_XQ + rb * 2048, c.a[i] + 4096, dma_voff);
-    else GX_DMA4(st + GX_W + rb * 4096, c.w[i], dma_voff);
+    const int i = p / 5, j = p % 5, rb = 2 * wave + i;
+    if (j < 2) GX_DMA(st + rb * 2048 + j * 1024, c.a[i] + j * 1024, dma_voff);
+    else if (j == 2) GX_DMA(st + GX_XQ + rb * 1024, c.a[i] + 2048, dma_voff);
+    else GX_DMA(st + GX_W + rb * 2048 + (j - 3) * 1024, c.w[i] + (j - 3) * 1024, dma_voff);
   };
 
   // ---- fragment addresses (within a stage): lane (l32, lh) reads unit u = 2 s + lh of its row
-  int xp_off[4], xq_off[4], w_off[4];
+  int xp_off[2], xq_off[2], w_off[2];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
+  for (int s = 0; s < 2; ++s) {
     const int u = 2 * s + lh;
-    xp_off[s] = (wm * WM + l32) * 128 + ((u ^ (l32 & 7)) << 4);
-    xq_off[s] = GX_XQ + (wm * WM + l32) * 64 + ((u ^ ((l32 >> 2) & 7)) << 3);
-    w_off[s] = GX_W + (wn * WN + l32) * 128 + ((u ^ (l32 & 7)) << 4);
+    xp_off[s] = (wm * WM + l32) * 64 + ((u ^ ((l32 >> 1) & 3)) << 4);
+    xq_off[s] = GX_XQ + (wm * WM + l32) * 32 + ((u ^ ((l32 >> 2) & 3)) << 3);
+    w_off[s] = GX_W + (wn * WN + l32) * 64 + ((u ^ ((l32 >> 1) & 3)) << 4);
   }
   struct Frags {
     v6i x[TM];
     v4i w[TN];
   };
   auto read_x = [&](const unsigned char* st, int s, int b) -> v6i {
-    const v4i p = *reinterpret_cast<const v4i*>(st + xp_off[s] + b * 4096);
-    const v2i q = *reinterpret_cast<const v2i*>(st + xq_off[s] + b * 2048);
+    const v4i p = *reinterpret_cast<const v4i*>(st + xp_off[s] + b * 2048);
+    const v2i q = *reinterpret_cast<const v2i*>(st + xq_off[s] + b * 1024);
     return (v6i){p[0], p[1], p[2], p[3], q[0], q[1]};
   };
   auto read_w = [&](const unsigned char* st, int s, int a) -> v4i {
-    return *reinterpret_cast<const v4i*>(st + w_off[s] + a * 4096);
+    return *reinterpret_cast<const v4i*>(st + w_off[s] + a * 2048);
   };
 
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -161,23 +161,24 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 
   const float alpha = alpha_p[0];
 
-  // ---- first tile of this block: stage 0 <- step 0, stage 1 <- step 1 (in flight), fragments
+  // ---- first tile of this block.  Loads of step g are issued in two halves of five: the
+  // first during sub-step 1 of step g - 4, the second during sub-step 0 of step g - 3.  So the
+  // loop starts with steps 0, 1, 2 and the first half of step 3 under way.
   int tile = blockIdx.x;
   int m0, n0;
   bl_tile_origin(tile, n_tiles, MT, NTB, GX_BM, GX_BN, m0, n0);
   Cursor cur;
-  cur.live = true;
   point(cur, tile);
 #pragma unroll
-  for (int p = 0; p < 6; ++p) dma_part(cur, lds0, p);
-  advance(cur);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  if (cur.live) {
+  for (int st = 0; st < 3; ++st) {
 #pragma unroll
-    for (int p = 0; p < 6; ++p) dma_part(cur, lds0 + GX_STAGE, p);
+    for (int p = 0; p < GX_LOADS_PER_STEP; ++p) dma_part(cur, lds0 + st * GX_STAGE, p);
     advance(cur);
   }
+#pragma unroll
+  for (int p = 0; p < GX_LOADS_PER_STEP / 2; ++p) dma_part(cur, lds0 + 3 * GX_STAGE, p);
+  GX_WAIT_LOADS(2 * GX_LOADS_PER_STEP + GX_LOADS_PER_STEP / 2);      // step 0 has landed
+  __syncthreads();
   Frags F[2];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -185,10 +186,19 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     F[0].w[i] = read_w(gx_smem, 0, i);
   }
 
-  int g = 0;                                     // steps done by this block (stage = g & 1)
+  int g = 0;                                     // steps done by this block (stage = g % 4)
+  // When step g reaches its barrier, the loads in flight that are younger than those of step
+  // g + 1 (which must have landed) are the 20 of steps g + 2 and g + 3 and, for the two steps
+  // behind the epilogue of an interior bf16 tile, also that epilogue's 32 stores.  (Any other
+  // epilogue waits for its stores itself.)  Vector memory operations complete in order, so
+  // "at most that many in flight" is the condition to wait for; operations this count does not
+  // know of (the scale loads of a tile) only make the wait longer.
+  constexpr int EPI_STORES = 32;
+  int steps_behind_stores = 0;
   while (true) {
     const int next = tile + (int)gridDim.x;
     const bool has_next = next < n_tiles;
+    const bool interior = (m0 + GX_BM <= M) && (n0 + GX_BN <= N);
     v16f acc[TN][TM];
 #pragma unroll
     for (int a = 0; a < TN; ++a)
@@ -204,35 +214,44 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     }
 
     for (int kb = 0; kb < KB; ++kb, ++g) {
-      const unsigned char* st_own = gx_smem + (g & 1) * GX_STAGE;
-      const unsigned char* st_other = gx_smem + ((g & 1) ^ 1) * GX_STAGE;
-      const u32 lds_own = lds0 + (g & 1) * GX_STAGE;
+      const unsigned char* st_own = gx_smem + (g & 3) * GX_STAGE;
+      const unsigned char* st_next = gx_smem + ((g + 1) & 3) * GX_STAGE;
+      const u32 lds_own = lds0 + (g & 3) * GX_STAGE, lds_prev = lds0 + ((g + 3) & 3) * GX_STAGE;
       const bool last = kb == KB - 1;
+      // ---- sub-step 0: computes on F[0], fills F[1] from the own stage, issues the second half
+      // of the loads of step g + 3 (into the stage that step g - 1 has left)
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        Frags& use = F[s & 1];
-        Frags& fill = F[(s & 1) ^ 1];
-        const unsigned char* src = s < 3 ? st_own : st_other;
-        const int ns = (s + 1) & 3;
-        // Behind the barrier (sub-step 3) the own stage is free: the step after next goes
-        // there.  At the end of a tile the stage first serves the epilogue as transpose space.
-        const bool dma_now = s == 3 && !last && cur.live;
+      for (int a = 0; a < TN; ++a) {
 #pragma unroll
-        for (int a = 0; a < TN; ++a) {
-#pragma unroll
-          for (int b = 0; b < TM; ++b) {
-            GX_MFMA(acc[a][b], use.w[a], use.x[b]);
-            const int i = a * TM + b;              // one slot behind each MFMA
-            if (i < 4) fill.x[i] = read_x(src, ns, i);
-            else if (i < 8) fill.w[i - 4] = read_w(src, ns, i - 4);
-            else if (i < 14 && dma_now) dma_part(cur, lds_own, i - 8);
-          }
+        for (int b = 0; b < TM; ++b) {
+          GX_MFMA(acc[a][b], F[0].w[a], F[0].x[b]);
+          const int i = a * TM + b;              // one slot behind each MFMA
+          if (i < 4) F[1].x[i] = read_x(st_own, 1, i);
+          else if (i < 8) F[1].w[i - 4] = read_w(st_own, 1, i - 4);
+          else if (i < 13) dma_part(cur, lds_prev, 5 + (i - 8));
         }
-        if (s == 3 && dma_now) advance(cur);
-        if (s == 2) {
-          // own loads of the next step have landed; every wave is done reading this stage
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-          __syncthreads();
+      }
+      advance(cur);
+      // own loads of the next step have landed; every wave is done reading this stage
+      if (steps_behind_stores > 0) {
+        GX_WAIT_LOADS(2 * GX_LOADS_PER_STEP + EPI_STORES);
+        --steps_behind_stores;
+      } else {
+        GX_WAIT_LOADS(2 * GX_LOADS_PER_STEP);
+      }
+      __syncthreads();
+      // ---- sub-step 1: computes on F[1], fills F[0] from the next step's stage, issues the
+      // first half of the loads of step g + 4 into the own stage, which is free now.  At the end
+      // of a tile the stage first serves the epilogue as transpose space: the loads follow it.
+#pragma unroll
+      for (int a = 0; a < TN; ++a) {
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+          GX_MFMA(acc[a][b], F[1].w[a], F[1].x[b]);
+          const int i = a * TM + b;
+          if (i < 4) F[0].x[i] = read_x(st_next, 0, i);
+          else if (i < 8) F[0].w[i - 4] = read_w(st_next, 0, i - 4);
+          else if (i < 13 && !last) dma_part(cur, lds_own, i - 8);
         }
       }
     }
@@ -243,17 +262,17 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     // ---- epilogue.  acc[a][b][r] is output n = 32 a + 8 (r / 4) + 4 lh + r % 4 of token
     // m = 32 b + l32 (relative to the wave tile).  The stage of the tile's last step is free
     // (its refill was held back) and serves as transpose space.
-    const int free_stage = (g - 1) & 1;
+    const int free_stage = (g - 1) & 3;
     if (OUT == 0) {
       constexpr int TB_ROW = WN * 2 + 32;
       unsigned char* tbuf = gx_smem + free_stage * GX_STAGE + wave * (32 * TB_ROW);
+      static_assert(4 * 32 * TB_ROW <= GX_STAGE, "transpose space must fit into one stage");
       constexpr int LANES_PER_ROW = WN * 2 / 16;           // 16 lanes cover one token's 256 bytes
       constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
       constexpr int NPASS = 32 / ROWS_PER_PASS;
       const int rr = lane / LANES_PER_ROW, cc = lane % LANES_PER_ROW;
       uint16_t* ywave = (uint16_t*)Y + (size_t)(m0 + wm * WM) * N + (n0 + wn * WN);
       const u32 lane_off = (u32)rr * (u32)N + cc * 8;
-      const bool interior = (m0 + GX_BM <= M) && (n0 + GX_BN <= N);
       const int m_left = M - (m0 + wm * WM) - rr, n_left = N - (n0 + wn * WN) - cc * 8;
 #pragma unroll
       for (int b = 0; b < TM; ++b) {
@@ -352,15 +371,18 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     if (!has_next) break;
     tile = next;
     bl_tile_origin(tile, n_tiles, MT, NTB, GX_BM, GX_BN, m0, n0);
-    __syncthreads();                   // transpose space has been read out by every wave
-    // the refill that was held back: the step after the next tile's first
-    if (cur.live) {
-#pragma unroll
-      for (int p = 0; p < 6; ++p) dma_part(cur, lds0 + free_stage * GX_STAGE, p);
-      advance(cur);
+    if (OUT == 0 && !ACC && interior) {
+      steps_behind_stores = 2;
+    } else {
+      GX_WAIT_LOADS(0);                // a store count that depends on the tile: wait for all of them
+      steps_behind_stores = 0;
     }
+    __syncthreads();                   // transpose space has been read out by every wave
+    // the loads that were held back: first half of the step after the next three
+#pragma unroll
+    for (int p = 0; p < GX_LOADS_PER_STEP / 2; ++p) dma_part(cur, lds0 + free_stage * GX_STAGE, p);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no copy may be in flight when the LDS is released
+  GX_WAIT_LOADS(0);                    // no copy may be in flight when the LDS is released
 #undef GX_MFMA
 }
 
@@ -391,7 +413,7 @@ static int gx_go(const void* q, const float* scale, int M, int KB, const void* W
 int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K, const void* Wp,
                          const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,
                          hipStream_t s) {
-  const int KB = (int)(bl_round_up(K, BL_KPAD) / 256);
+  const int KB = (int)(bl_round_up(K, BL_KPAD) / 128);
   const int MT = (int)((M + GX_BM - 1) / GX_BM), NTB = (int)((N + GX_BN - 1) / GX_BN);
   const int out = (ydt == BL_BF16 && (N & 7) == 0) ? 0 : ((N & 3) == 0 ? 1 : 2);
   const int yb = ydt == BL_BF16 ? 1 : 0;

@@ -109,10 +109,10 @@ __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_kmajor_kernel(
   out[((d >> 5) * K + k) * 32 + (d & 31)] = word;
 }
 
-// One thread per 32-bit word of the block-float GEMM layout: blocks of 32 outputs x 256 input
-// channels (4096 bytes); inside, row r = n % 32 takes 128 bytes, its 16-byte piece p holds the
-// 32 channels of unit u = p ^ (r & 7) as E2M1 nibbles (0 -> 0000, +1 -> 0010, -1 -> 1010), low
-// nibble first.  A word covers 8 consecutive channels.
+// One thread per 32-bit word of the block-float GEMM layout: blocks of 32 outputs x 128 input
+// channels (2048 bytes); inside, row r = n % 32 takes 64 bytes, its 16-byte piece p holds the
+// 32 channels of unit u = p ^ ((r / 2) % 4) as E2M1 nibbles (0 -> 0000, +1 -> 0010, -1 -> 1010),
+// low nibble first.  A word covers 8 consecutive channels.
 template <typename T>
 __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_mx4_kernel(
     const T* __restrict__ W, int64_t N, int64_t K, int64_t Kp, float eps,
@@ -124,12 +124,12 @@ __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_mx4_kernel(
   const float t = alpha + eps;
   const int64_t w = (int64_t)blockIdx.x * PT_THREADS + threadIdx.x;
   if (w >= n_words) return;
-  const int64_t blk = w >> 10;              // 1024 words per block
-  const int in = (int)(w & 1023);
-  const int r = in >> 5, p = (in >> 2) & 7, j = in & 3;
-  const int64_t KB = Kp / 256;
+  const int64_t blk = w >> 9;               // 512 words per block
+  const int in = (int)(w & 511);
+  const int r = in >> 4, p = (in >> 2) & 3, j = in & 3;
+  const int64_t KB = Kp / 128;
   const int64_t n = (blk / KB) * 32 + r;
-  const int64_t k0 = (blk % KB) * 256 + 32 * (p ^ (r & 7)) + 8 * j;
+  const int64_t k0 = (blk % KB) * 128 + 32 * (p ^ ((r >> 1) & 3)) + 8 * j;
   u32 word = 0;
   if (n < N) {
 #pragma unroll
@@ -155,8 +155,8 @@ __global__ __launch_bounds__(PT_THREADS) void unpack_ternary_kernel(const u32* _
   u32 word;
   int f;
   if (layout == BL_W_MX4) {
-    const int r = (int)(n & 31), u = (int)((k >> 5) & 7), i = (int)(k & 31);
-    const u32 w4 = packed[((n >> 5) * (Kp / 256) + (k >> 8)) * 1024 + r * 32 + ((u ^ (r & 7)) << 2) + (i >> 3)];
+    const int r = (int)(n & 31), u = (int)((k >> 5) & 3), i = (int)(k & 31);
+    const u32 w4 = packed[((n >> 5) * (Kp / 128) + (k >> 7)) * 512 + r * 16 + ((u ^ ((r >> 1) & 3)) << 2) + (i >> 3)];
     const u32 c = (w4 >> (4 * (i & 7))) & 15u;
     T[id] = (int8_t)(c == 0 ? 0 : ((c & 8u) ? -1 : 1));
     return;

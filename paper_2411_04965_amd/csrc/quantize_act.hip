@@ -46,7 +46,7 @@ __device__ __forceinline__ u32 qa_e3m2_of_level(int q) {
 }
 
 // MX6: the same levels, written as E3M2 codes in the tile order of the block-float GEMM (blocks of
-// 32 tokens x 256 channels, 6144 bytes; see the format notes of the public header) instead of
+// 32 tokens x 128 channels, 3072 bytes; see the format notes of the public header) instead of
 // packed nibbles.
 template <typename RawT, int VEC, bool MX6>
 __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
   int sum = 0;
   if (MX6) {
     // one thread per half unit: 16 channels = 96 bits of the unit's 192-bit stream
-    unsigned char* blk = reinterpret_cast<unsigned char*>(q_out) + (m >> 5) * (int64_t)(Kp / 256) * 6144;
+    unsigned char* blk = reinterpret_cast<unsigned char*>(q_out) + (m >> 5) * (int64_t)(Kp / 128) * 3072;
     const int r = (int)(m & 31);
     for (int h = threadIdx.x; h < Kp / 16; h += QA_THREADS) {
       u32 w3[3] = {0u, 0u, 0u};
@@ -92,14 +92,14 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
         w3[bit >> 5] |= c << (bit & 31);
         if ((bit & 31) > 26) w3[(bit >> 5) + 1] |= c >> (32 - (bit & 31));
       }
-      const int kb = h >> 4, u = (h >> 1) & 7;
-      unsigned char* b = blk + (int64_t)kb * 6144;
-      u32* pp = reinterpret_cast<u32*>(b + r * 128 + ((u ^ (r & 7)) << 4));
+      const int kb = h >> 3, u = (h >> 1) & 3;
+      unsigned char* b = blk + (int64_t)kb * 3072;
+      u32* pp = reinterpret_cast<u32*>(b + r * 64 + ((u ^ ((r >> 1) & 3)) << 4));
       if ((h & 1) == 0) {                                   // stream bytes 0..11
         pp[0] = w3[0]; pp[1] = w3[1]; pp[2] = w3[2];
       } else {                                              // stream bytes 12..15 and 16..23
         pp[3] = w3[0];
-        u32* qq = reinterpret_cast<u32*>(b + 4096 + r * 64 + ((u ^ ((r >> 2) & 7)) << 3));
+        u32* qq = reinterpret_cast<u32*>(b + 2048 + r * 32 + ((u ^ ((r >> 2) & 3)) << 3));
         qq[0] = w3[1]; qq[1] = w3[2];
       }
     }
@@ -573,10 +573,10 @@ __global__ __launch_bounds__(QA_THREADS) void unpack_act_kernel(const u32* __res
     // value i of unit u: bits 6 i .. 6 i + 5 of the unit's stream, bytes 0..15 in the P piece and
     // bytes 16..23 in the Q piece of the token's row inside its 32-token block
     const unsigned char* blk = reinterpret_cast<const unsigned char*>(q) +
-                               ((m >> 5) * (int64_t)(Kp / 256) + (k >> 8)) * 6144;
-    const int r = (int)(m & 31), u = (k >> 5) & 7, bit = 6 * (k & 31);
-    const unsigned char* pp = blk + r * 128 + ((u ^ (r & 7)) << 4);
-    const unsigned char* qq = blk + 4096 + r * 64 + ((u ^ ((r >> 2) & 7)) << 3);
+                               ((m >> 5) * (int64_t)(Kp / 128) + (k >> 7)) * 3072;
+    const int r = (int)(m & 31), u = (k >> 5) & 3, bit = 6 * (k & 31);
+    const unsigned char* pp = blk + r * 64 + ((u ^ ((r >> 1) & 3)) << 4);
+    const unsigned char* qq = blk + 2048 + r * 32 + ((u ^ ((r >> 2) & 3)) << 3);
     u32 two = 0;                                            // the two stream bytes that hold the code
 #pragma unroll
     for (int j = 0; j < 2; ++j) {

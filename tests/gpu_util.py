@@ -71,15 +71,15 @@ def decode_w_mx4(packed, N, K):
     """BL_W_MX4 bytes -> int8 [N, K]."""
     Kp = (K + 255) // 256 * 256
     Np = (N + 31) // 32 * 32
-    b = np.frombuffer(packed.tobytes(), dtype=np.uint8).reshape(Np // 32, Kp // 256, 32, 8, 16)
+    b = np.frombuffer(packed.tobytes(), dtype=np.uint8).reshape(Np // 32, Kp // 128, 32, 4, 16)
     r = np.arange(32)
-    u = np.arange(8)
-    piece = u[None, :] ^ (r[:, None] & 7)                           # [r, u] -> piece that holds unit u
+    u = np.arange(4)
+    piece = u[None, :] ^ ((r[:, None] >> 1) & 3)                    # [r, u] -> piece that holds unit u
     units = b[:, :, r[:, None], piece, :]                           # [nb, kb, r, u, 16]
-    nib = np.stack([units & 15, units >> 4], axis=-1).reshape(Np // 32, Kp // 256, 32, 8, 32)
+    nib = np.stack([units & 15, units >> 4], axis=-1).reshape(Np // 32, Kp // 128, 32, 4, 32)
     assert np.isin(nib, (0, 2, 10)).all()
     T = np.where(nib == 2, 1, np.where(nib == 10, -1, 0)).astype(np.int8)
-    full = np.transpose(T, (0, 2, 1, 3, 4)).reshape(Np, Kp)         # n = 32 nb + r, k = 256 kb + 32 u + i
+    full = np.transpose(T, (0, 2, 1, 3, 4)).reshape(Np, Kp)         # n = 32 nb + r, k = 128 kb + 32 u + i
     assert not full[N:].any() and not full[:, K:].any()
     return full[:N, :K]
 
@@ -88,23 +88,23 @@ def decode_int4_mx6(q, M, K):
     """INT4 levels in the MX6 form (E3M2 codes, 32-token blocks) -> int8 [M, K]."""
     Kp = (K + 255) // 256 * 256
     Mp = (M + 31) // 32 * 32
-    b = np.frombuffer(q.tobytes(), dtype=np.uint8).reshape(Mp // 32, Kp // 256, 6144)
-    P = b[:, :, :4096].reshape(Mp // 32, Kp // 256, 32, 8, 16)
-    Q = b[:, :, 4096:].reshape(Mp // 32, Kp // 256, 32, 8, 8)
+    b = np.frombuffer(q.tobytes(), dtype=np.uint8).reshape(Mp // 32, Kp // 128, 3072)
+    P = b[:, :, :2048].reshape(Mp // 32, Kp // 128, 32, 4, 16)
+    Q = b[:, :, 2048:].reshape(Mp // 32, Kp // 128, 32, 4, 8)
     r = np.arange(32)
-    u = np.arange(8)
-    pp = u[None, :] ^ (r[:, None] & 7)
-    qq = u[None, :] ^ ((r[:, None] >> 2) & 7)
+    u = np.arange(4)
+    pp = u[None, :] ^ ((r[:, None] >> 1) & 3)
+    qq = u[None, :] ^ ((r[:, None] >> 2) & 3)
     stream = np.concatenate([P[:, :, r[:, None], pp, :], Q[:, :, r[:, None], qq, :]], axis=-1)   # [mb, kb, r, u, 24]
-    bits = np.unpackbits(stream, axis=-1, bitorder="little").reshape(Mp // 32, Kp // 256, 32, 8, 32, 6)
+    bits = np.unpackbits(stream, axis=-1, bitorder="little").reshape(Mp // 32, Kp // 128, 32, 4, 32, 6)
     code = (bits * (1 << np.arange(6))).sum(-1)
+    code = np.transpose(code, (0, 2, 1, 3, 4)).reshape(Mp, Kp)[:M]  # rows past M are never written
     e, mant, sign = (code >> 2) & 7, code & 3, code >> 5
     mag = np.where(e == 0, 0.0, (1 + mant / 4.0) * 2.0 ** (e - 3.0))
-    assert np.array_equal(mag[: M // 32], np.round(mag[: M // 32]))
-    val = np.where(sign == 1, -mag, mag)
-    full = np.transpose(val, (0, 2, 1, 3, 4)).reshape(Mp, Kp)[:M]
-    assert np.array_equal(full, np.round(full)) and not full[:, K:].any()
-    assert not ((code == 32).reshape(Mp // 32, Kp // 256, 32, 8, 32).transpose(0, 2, 1, 3, 4).reshape(Mp, Kp)[:M]).any(), "-0 code"
+    assert np.array_equal(mag, np.round(mag)) and mag.max() <= 8
+    assert not (code == 32).any(), "-0 code"
+    full = np.where(sign == 1, -mag, mag)
+    assert not full[:, K:].any()
     return full[:, :K].astype(np.int8)
 
 
