@@ -155,8 +155,12 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 #if defined(__HIP_DEVICE_COMPILE__)
 #define GX_MFMA(C, WF, XF) \
   asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0 cbsz:4 blgp:3" : "+a"(C) : "v"(WF), "v"(XF))
+// first MFMA on an accumulator tile: C = 0 (saves clearing 256 registers per output tile)
+#define GX_MFMA0(C, WF, XF) \
+  asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0 cbsz:4 blgp:3" : "=a"(C) : "v"(WF), "v"(XF))
 #else
 #define GX_MFMA(C, WF, XF) ((void)0)
+#define GX_MFMA0(C, WF, XF) ((void)0)
 #endif
 
   const float alpha = alpha_p[0];
@@ -185,6 +189,20 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     F[0].x[i] = read_x(gx_smem, 0, i);
     F[0].w[i] = read_w(gx_smem, 0, i);
   }
+  // Per-token scales of a tile.  The compiler cannot count the asynchronous loads, so wherever
+  // it has to wait for a load of its own it waits for every load in flight.  The scales are
+  // therefore fetched where that is cheap: here, and for every later tile inside the epilogue of
+  // the tile before it (see there).
+  auto load_scales = [&](int tm0, float (&d)[TM]) {
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+      const int m = tm0 + wm * WM + b * 32 + l32;
+      d[b] = m < M ? scale[m] : 0.0f;
+    }
+  };
+  float dsc[TM];
+  load_scales(m0, dsc);
+  asm volatile("" : "+v"(dsc[0]), "+v"(dsc[1]), "+v"(dsc[2]), "+v"(dsc[3]));
 
   int g = 0;                                     // steps done by this block (stage = g % 4)
   // When step g reaches its barrier, the loads in flight that are younger than those of step
@@ -200,18 +218,9 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     const bool has_next = next < n_tiles;
     const bool interior = (m0 + GX_BM <= M) && (n0 + GX_BN <= N);
     v16f acc[TN][TM];
-#pragma unroll
-    for (int a = 0; a < TN; ++a)
-#pragma unroll
-      for (int b = 0; b < TM; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
-    float dsc[TM];                               // per-token scales of this tile
-#pragma unroll
-    for (int b = 0; b < TM; ++b) {
-      const int m = m0 + wm * WM + b * 32 + l32;
-      dsc[b] = m < M ? scale[m] : 0.0f;
-    }
+    int nm0 = m0, nn0 = n0;                      // origin of the block's next tile
+    if (has_next) bl_tile_origin(next, n_tiles, MT, NTB, GX_BM, GX_BN, nm0, nn0);
+    float dsc_next[TM];
 
     for (int kb = 0; kb < KB; ++kb, ++g) {
       const unsigned char* st_own = gx_smem + (g & 3) * GX_STAGE;
@@ -224,11 +233,12 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       for (int a = 0; a < TN; ++a) {
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
-          GX_MFMA(acc[a][b], F[0].w[a], F[0].x[b]);
+          if (kb == 0) GX_MFMA0(acc[a][b], F[0].w[a], F[0].x[b]);
+          else GX_MFMA(acc[a][b], F[0].w[a], F[0].x[b]);
           const int i = a * TM + b;              // one slot behind each MFMA
           if (i < 4) F[1].x[i] = read_x(st_own, 1, i);
           else if (i < 8) F[1].w[i - 4] = read_w(st_own, 1, i - 4);
-          else if (i < 13) dma_part(cur, lds_prev, 5 + (i - 8));
+          if (i % 3 == 2) dma_part(cur, lds_prev, 5 + i / 3);          // slots 2, 5, 8, 11, 14
         }
       }
       advance(cur);
@@ -251,7 +261,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
           const int i = a * TM + b;
           if (i < 4) F[0].x[i] = read_x(st_next, 0, i);
           else if (i < 8) F[0].w[i - 4] = read_w(st_next, 0, i - 4);
-          else if (i < 13 && !last) dma_part(cur, lds_own, i - 8);
+          if (i % 3 == 2 && !last) dma_part(cur, lds_own, i / 3);
         }
       }
     }
@@ -274,9 +284,13 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       uint16_t* ywave = (uint16_t*)Y + (size_t)(m0 + wm * WM) * N + (n0 + wn * WN);
       const u32 lane_off = (u32)rr * (u32)N + cc * 8;
       const int m_left = M - (m0 + wm * WM) - rr, n_left = N - (n0 + wn * WN) - cc * 8;
+      // scales of the next tile: requested now, waited for behind the first column's arithmetic,
+      // when the last asynchronous loads are a few thousand cycles old and nothing else is in flight
+      load_scales(nm0, dsc_next);
 #pragma unroll
       for (int b = 0; b < TM; ++b) {
         const float d = dsc[b];
+        if (b == 1) asm volatile("" : "+v"(dsc_next[0]), "+v"(dsc_next[1]), "+v"(dsc_next[2]), "+v"(dsc_next[3]));
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
           asm volatile("" : "+a"(acc[a][b]));
@@ -312,6 +326,8 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
+      load_scales(nm0, dsc_next);
+      asm volatile("" : "+v"(dsc_next[0]), "+v"(dsc_next[1]), "+v"(dsc_next[2]), "+v"(dsc_next[3]));
 #pragma unroll
       for (int b = 0; b < TM; ++b) {
         const int m = m0 + wm * WM + b * 32 + l32;
@@ -370,7 +386,10 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     }
     if (!has_next) break;
     tile = next;
-    bl_tile_origin(tile, n_tiles, MT, NTB, GX_BM, GX_BN, m0, n0);
+    m0 = nm0;
+    n0 = nn0;
+#pragma unroll
+    for (int b = 0; b < TM; ++b) dsc[b] = dsc_next[b];
     if (OUT == 0 && !ACC && interior) {
       steps_behind_stores = 2;
     } else {
