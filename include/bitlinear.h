@@ -38,7 +38,7 @@
  *               block-float matrix instruction reads them: blocks of 32 output channels x 128
  *               input channels, 2048 bytes each, block (nb, kb) at byte (nb * Kp/128 + kb) * 2048
  *               (N rounded up to 32).  Inside a block, row r = n % 32 takes 64 bytes; its 16-byte
- *               piece p holds unit u = p ^ ((r / 2) % 4), i.e. channels 128*kb + 32*u ... + 31,
+ *               piece p holds unit u = p ^ ((r / 4) % 4), i.e. channels 128*kb + 32*u ... + 31,
  *               channel i of the unit in nibble i (low nibble of a byte first).  Used by the
  *               prefill GEMM of the INT4 path; twice the bytes of BL_W_GEMM.
  *
@@ -51,8 +51,8 @@
  *               M are not written).  The 32 channels of unit u (channels 128*kb + 32*u ... + 31)
  *               form a 24-byte little-endian bit stream, channel i in bits 6i ... 6i+5.  Inside a
  *               block, token row r = m % 32 keeps stream bytes 0..15 of unit u in the 16-byte
- *               piece p = u ^ ((r / 2) % 4) at byte r*64 + 16*p, and stream bytes 16..23 in the
- *               8-byte piece p' = u ^ ((r / 4) % 4) at byte 2048 + r*32 + 8*p'.
+ *               piece p = u ^ ((r / 4) % 4) at byte r*64 + 16*p, and stream bytes 16..23 in the
+ *               8-byte piece p' = u ^ ((r / 8) % 4) at byte 2048 + r*32 + 8*p'.
  *   INT8 activations  [M][Kp] bytes, plain int8, zeros where the Top_k mask is 0.
  *   FP4 activations   [M][Kp/2] bytes of E2M1 nibbles (bit 3 sign, bits 2..0 code of
  *               {0, .5, 1, 1.5, 2, 3, 4, 6}).  Channels are taken 16 at a time into two

@@ -9,7 +9,9 @@
 //
 // Both operands arrive in HBM in the order in which LDS wants them (see the format notes in the
 // public header): blocks of 32 rows x 128 channels, rows XOR-swizzled by 16-byte (8-byte) piece so
-// that the fragment reads are free of bank conflicts.  The copy from global memory to LDS is
+// that the fragment reads are free of bank conflicts (the LDS serves 256 bytes per clock: 16 lanes
+// of a 16-byte read, 32 lanes of an 8-byte read, which must fall into distinct slots of a 256-byte
+// window).  The copy from global memory to LDS is
 // therefore linear and is done by global_load_lds_dwordx4: no staging registers, no LDS write
 // instructions and no vector work in the main loop, which consists of MFMAs, fragment reads and
 // the asynchronous loads.
@@ -135,9 +137,9 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
     const int u = 2 * s + lh;
-    xp_off[s] = (wm * WM + l32) * 64 + ((u ^ ((l32 >> 1) & 3)) << 4);
-    xq_off[s] = GX_XQ + (wm * WM + l32) * 32 + ((u ^ ((l32 >> 2) & 3)) << 3);
-    w_off[s] = GX_W + (wn * WN + l32) * 64 + ((u ^ ((l32 >> 1) & 3)) << 4);
+    xp_off[s] = (wm * WM + l32) * 64 + ((u ^ ((l32 >> 2) & 3)) << 4);
+    xq_off[s] = GX_XQ + (wm * WM + l32) * 32 + ((u ^ ((l32 >> 3) & 3)) << 3);
+    w_off[s] = GX_W + (wn * WN + l32) * 64 + ((u ^ ((l32 >> 2) & 3)) << 4);
   }
   struct Frags {
     v6i x[TM];

@@ -46,7 +46,9 @@ struct GpSmem {
 };
 
 __device__ __forceinline__ int gp_lds_off(int row, int chunk) {
-  return row * GP_BK + ((chunk ^ (row & 7)) << 4);
+  // 16 lanes of a 16-byte access must fall into distinct 16-byte slots of a 256-byte window:
+  // two rows per window, so the row's parity picks the half and (row / 2) % 8 permutes the chunks
+  return row * GP_BK + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
 __device__ __forceinline__ u32 gp_pack_bf16(float lo, float hi) {
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   };
   // The expansion of one stage is cut into NWR single 16-byte LDS writes per operand so that it
   // can be spread over the MFMA stream.  Rows of load j sit RPJ (resp. 128) rows below those of
-  // load 0, a multiple of 8, so the swizzle is the same and the offset is an immediate.
+  // load 0, a multiple of 16, so the swizzle is the same and the offset is an immediate.
   constexpr int NWR_A = A4 ? 2 * LA : LA;
   constexpr int NWR_B = 4 * LB;
   constexpr u32 MA = 0xF0F0F0F0u, MB = 0xC0C0C0C0u;
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
   const int wf_base = A_BYTES + (wn * WN + l32) * GP_BK;
   int swz[4];
 #pragma unroll
-  for (int sub = 0; sub < 4; ++sub) swz[sub] = ((2 * sub + lh) ^ (l32 & 7)) << 4;
+  for (int sub = 0; sub < 4; ++sub) swz[sub] = ((2 * sub + lh) ^ ((l32 >> 1) & 7)) << 4;
   auto read_x = [&](int stage, int sub, int b) -> v4i {
     return *reinterpret_cast<const v4i*>(gp_smem + stage * STAGE + xf_base + b * (32 * GP_BK) + swz[sub]);
   };

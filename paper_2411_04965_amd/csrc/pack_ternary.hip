@@ -111,7 +111,7 @@ __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_kmajor_kernel(
 
 // One thread per 32-bit word of the block-float GEMM layout: blocks of 32 outputs x 128 input
 // channels (2048 bytes); inside, row r = n % 32 takes 64 bytes, its 16-byte piece p holds the
-// 32 channels of unit u = p ^ ((r / 2) % 4) as E2M1 nibbles (0 -> 0000, +1 -> 0010, -1 -> 1010),
+// 32 channels of unit u = p ^ ((r / 4) % 4) as E2M1 nibbles (0 -> 0000, +1 -> 0010, -1 -> 1010),
 // low nibble first.  A word covers 8 consecutive channels.
 template <typename T>
 __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_mx4_kernel(
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_mx4_kernel(
   const int r = in >> 4, p = (in >> 2) & 3, j = in & 3;
   const int64_t KB = Kp / 128;
   const int64_t n = (blk / KB) * 32 + r;
-  const int64_t k0 = (blk % KB) * 128 + 32 * (p ^ ((r >> 1) & 3)) + 8 * j;
+  const int64_t k0 = (blk % KB) * 128 + 32 * (p ^ ((r >> 2) & 3)) + 8 * j;
   u32 word = 0;
   if (n < N) {
 #pragma unroll
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(PT_THREADS) void unpack_ternary_kernel(const u32* _
   int f;
   if (layout == BL_W_MX4) {
     const int r = (int)(n & 31), u = (int)((k >> 5) & 3), i = (int)(k & 31);
-    const u32 w4 = packed[((n >> 5) * (Kp / 128) + (k >> 7)) * 512 + r * 16 + ((u ^ ((r >> 1) & 3)) << 2) + (i >> 3)];
+    const u32 w4 = packed[((n >> 5) * (Kp / 128) + (k >> 7)) * 512 + r * 16 + ((u ^ ((r >> 2) & 3)) << 2) + (i >> 3)];
     const u32 c = (w4 >> (4 * (i & 7))) & 15u;
     T[id] = (int8_t)(c == 0 ? 0 : ((c & 8u) ? -1 : 1));
     return;

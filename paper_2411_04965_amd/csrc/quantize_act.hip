@@ -94,12 +94,12 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
       }
       const int kb = h >> 3, u = (h >> 1) & 3;
       unsigned char* b = blk + (int64_t)kb * 3072;
-      u32* pp = reinterpret_cast<u32*>(b + r * 64 + ((u ^ ((r >> 1) & 3)) << 4));
+      u32* pp = reinterpret_cast<u32*>(b + r * 64 + ((u ^ ((r >> 2) & 3)) << 4));
       if ((h & 1) == 0) {                                   // stream bytes 0..11
         pp[0] = w3[0]; pp[1] = w3[1]; pp[2] = w3[2];
       } else {                                              // stream bytes 12..15 and 16..23
         pp[3] = w3[0];
-        u32* qq = reinterpret_cast<u32*>(b + 2048 + r * 32 + ((u ^ ((r >> 2) & 3)) << 3));
+        u32* qq = reinterpret_cast<u32*>(b + 2048 + r * 32 + ((u ^ ((r >> 3) & 3)) << 3));
         qq[0] = w3[1]; qq[1] = w3[2];
       }
     }
@@ -575,8 +575,8 @@ __global__ __launch_bounds__(QA_THREADS) void unpack_act_kernel(const u32* __res
     const unsigned char* blk = reinterpret_cast<const unsigned char*>(q) +
                                ((m >> 5) * (int64_t)(Kp / 128) + (k >> 7)) * 3072;
     const int r = (int)(m & 31), u = (k >> 5) & 3, bit = 6 * (k & 31);
-    const unsigned char* pp = blk + r * 64 + ((u ^ ((r >> 1) & 3)) << 4);
-    const unsigned char* qq = blk + 2048 + r * 32 + ((u ^ ((r >> 2) & 3)) << 3);
+    const unsigned char* pp = blk + r * 64 + ((u ^ ((r >> 2) & 3)) << 4);
+    const unsigned char* qq = blk + 2048 + r * 32 + ((u ^ ((r >> 3) & 3)) << 3);
     u32 two = 0;                                            // the two stream bytes that hold the code
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -642,9 +642,9 @@ int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K64, bl_ac
     BL_HIP_CHECK_LAUNCH();
     return BL_OK;
   }
-  if (dt == BL_BF16 && mode == BL_ACT_TOPK_INT8_ABSMAX && M > 64 && K % 4 == 0 && Kp <= 12288 &&
+  if (dt == BL_BF16 && mode == BL_ACT_TOPK_INT8_ABSMAX && K % 4 == 0 && Kp <= 12288 &&
       sel_idx == nullptr) {
-    // many tokens: keys in registers, one memory pass
+    // keys in registers, one memory pass
     const uint16_t* x = (const uint16_t*)X;
     const int cpw = (Kp / 256 + QA_WAVES - 1) / QA_WAVES;
     if (cpw <= 4)

@@ -74,7 +74,7 @@ def decode_w_mx4(packed, N, K):
     b = np.frombuffer(packed.tobytes(), dtype=np.uint8).reshape(Np // 32, Kp // 128, 32, 4, 16)
     r = np.arange(32)
     u = np.arange(4)
-    piece = u[None, :] ^ ((r[:, None] >> 1) & 3)                    # [r, u] -> piece that holds unit u
+    piece = u[None, :] ^ ((r[:, None] >> 2) & 3)                    # [r, u] -> piece that holds unit u
     units = b[:, :, r[:, None], piece, :]                           # [nb, kb, r, u, 16]
     nib = np.stack([units & 15, units >> 4], axis=-1).reshape(Np // 32, Kp // 128, 32, 4, 32)
     assert np.isin(nib, (0, 2, 10)).all()
@@ -93,8 +93,8 @@ def decode_int4_mx6(q, M, K):
     Q = b[:, :, 2048:].reshape(Mp // 32, Kp // 128, 32, 4, 8)
     r = np.arange(32)
     u = np.arange(4)
-    pp = u[None, :] ^ ((r[:, None] >> 1) & 3)
-    qq = u[None, :] ^ ((r[:, None] >> 2) & 3)
+    pp = u[None, :] ^ ((r[:, None] >> 2) & 3)
+    qq = u[None, :] ^ ((r[:, None] >> 3) & 3)
     stream = np.concatenate([P[:, :, r[:, None], pp, :], Q[:, :, r[:, None], qq, :]], axis=-1)   # [mb, kb, r, u, 24]
     bits = np.unpackbits(stream, axis=-1, bitorder="little").reshape(Mp // 32, Kp // 128, 32, 4, 32, 6)
     code = (bits * (1 << np.arange(6))).sum(-1)
