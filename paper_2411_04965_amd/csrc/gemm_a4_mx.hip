@@ -11,26 +11,33 @@
 // public header): blocks of 32 rows x 128 channels, rows XOR-swizzled by 16-byte (8-byte) piece so
 // that the fragment reads are free of bank conflicts (the LDS serves 256 bytes per clock: 16 lanes
 // of a 16-byte read, 32 lanes of an 8-byte read, which must fall into distinct slots of a 256-byte
-// window).  The copy from global memory to LDS is
-// therefore linear and is done by global_load_lds_dwordx4: no staging registers, no LDS write
-// instructions and no vector work in the main loop, which consists of MFMAs, fragment reads and
-// the asynchronous loads.
+// window).  The copy from global memory to LDS is therefore linear: lane l of a wave moves bytes
+// 16 l .. 16 l + 15 of a 1 KB piece, no address arithmetic and no vector work on the way.
+// The copy goes through registers (global_load_dwordx4, one step later ds_write_b128).  The
+// direct global-to-LDS load was measured at 33 bytes per clock and CU for data that hits in L2,
+// plain loads at more than 50; the 256 x 256 tile needs 40 bytes per MFMA-bound clock.
 //
 // Structure.  Persistent blocks (one per CU) walk the tile list; block = 4 waves, tile
 // 256 x 256, each wave 128 x 128 as 4 x 4 MFMA tiles; the MFMA's row operand is the weight
 // fragment and its column operand the token fragment, so a lane ends up with groups of 4
-// consecutive outputs n of one token.  K advances 128 channels per step through a ring of four
-// LDS stages of 40 KB (the whole LDS), two MFMA sub-steps of 64 channels each, with two register
-// sets of fragments: a sub-step computes on one set while the other is filled for the next.
-// One barrier per step, at the end of its first sub-step: by then every wave has read its last
-// fragments of the step's stage, and (after waiting for its own loads) the next step's stage is
-// complete.  Behind the barrier the loads of step g + 4 go into the stage of step g.
-//
-// The asynchronous loads are limited by the 64 bytes per clock between L1 and the CU: a 1 KB
-// load occupies a wave's share of that path for 64 cycles, and a burst of loads stalls the MFMA
-// stream of the issuing wave.  The tile needs 40 KB per 1024 MFMA cycles, 62% of the path, so
-// the loads are issued evenly, five per sub-step, each behind its own MFMA, and run three steps
-// ahead of the MFMAs.  Each wave copies the row blocks 2w and 2w + 1 of both operands.
+// consecutive outputs n of one token.  K advances 128 channels per step through two LDS
+// stages, two MFMA sub-steps of 64 channels each, with two register sets of fragments: a
+// sub-step computes on one set while the other is filled for the next.  One step is one
+// straight-line block with one barrier in the middle:
+//   sub-step 0  computes on F[0], reads F[1] (sub-step 1 of this step) from the own stage, and
+//               writes the weights of step g + 1 into the other stage;
+//   barrier
+//   sub-step 1  computes on F[1], reads F[0] (sub-step 0 of step g + 1) from the other stage,
+//               and writes the activations of step g + 2 into the own stage, which nobody
+//               reads any more once the barrier has been passed.
+// So a stage is read only before the barrier of its own step (second fragments) and behind the
+// barrier of the step before (first fragments), and every write is separated from the reads of
+// the data it replaces and of the data it brings by a barrier.  Each staging register is
+// refilled from global memory right behind the write that consumed it, a full step before it is
+// written out again.  The K stream of a block runs on across its tiles.  Each wave copies the
+// row blocks 2w and 2w + 1 of both operands.
+#include <type_traits>
+
 #include "common.h"
 
 #define GX_THREADS 256
@@ -39,36 +46,21 @@
 #define GX_XQ 16384                  // stage layout: [XP 8 x 2048 | XQ 8 x 1024 | W 8 x 2048]
 #define GX_W 24576
 #define GX_STAGE 40960
-#define GX_NSTAGE 4
-#define GX_LDS (GX_NSTAGE * GX_STAGE)
+#define GX_TB (2 * GX_STAGE)         // transpose space of the epilogue, behind the two stages
+#define GX_TB_BYTES 36864
+#define GX_LDS (GX_TB + GX_TB_BYTES)
 #define GX_A_BLOCK 3072              // bytes of 32 tokens x 128 channels of 6-bit codes
 #define GX_W_BLOCK 2048              // bytes of 32 outputs x 128 channels of 4-bit codes
-#define GX_LOADS_PER_STEP 10         // asynchronous 1 KB loads per wave and step
 
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v6i __attribute__((ext_vector_type(6)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(3))) unsigned char lds_uchar;
 
 __device__ __forceinline__ u32 gx_pack_bf16(float lo, float hi) {
   u32 r;
   asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
   return r;
 }
-
-// One asynchronous 1 KB copy global -> LDS: lane l moves 16 bytes from base + voff to LDS byte
-// address lds + 16 l (M0 holds the LDS address).  The copies are counted by vmcnt like any other
-// load.  (The host pass of the compiler parses kernel bodies too and knows no scalar-register
-// constraint, so it sees empty statements here.)
-#if defined(__HIP_DEVICE_COMPILE__)
-#define GX_DMA(lds, base, voff)                                                         \
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"          \
-               ::"s"(lds), "v"(voff), "s"(base) : "memory")
-#define GX_WAIT_LOADS(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
-#else
-#define GX_DMA(lds, base, voff) ((void)0)
-#define GX_WAIT_LOADS(n) ((void)0)
-#endif
 
 // OUT: 0 = bf16 rows through the LDS transpose (N % 8 == 0), 1 = 4 outputs per store (N % 4 == 0),
 // 2 = one output per store (any N).  ACC: also write the integer accumulators (tests).
@@ -78,7 +70,6 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N, void* __restrict__ Y,
     int y_bf16, int32_t* __restrict__ acc_out, int MT, int NTB) {
   extern __shared__ __align__(16) unsigned char gx_smem[];
-  const u32 lds0 = (u32)(uintptr_t)(lds_uchar*)gx_smem;      // LDS byte address of the first stage
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
@@ -86,15 +77,16 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   const int n_tiles = MT * NTB;
   const int MB = (M + 31) >> 5, NB = (N + 31) >> 5;           // 32-row blocks of the operands
   constexpr int WM = 128, WN = 128, TM = 4, TN = 4;
+  constexpr int LA = 6, LB = 4;                  // 1 KB pieces per wave and step: activations, weights
 
-  // ---- asynchronous copies.  The cursor names the (tile, K step) that is copied next and
-  // moves on along the block's stream of tiles by itself.
+  // ---- global loads.  One cursor per operand names the (tile, K step) that is loaded next and
+  // moves on along the block's stream of tiles by itself; weights run two steps ahead of the
+  // MFMAs, activations three.
   struct Cursor {
-    const unsigned char* a[2];
-    const unsigned char* w[2];
+    const unsigned char* p[2];                   // row blocks 2w and 2w + 1 of the operand
     int kb, tile;
   };
-  auto point = [&](Cursor& c, int tile) {
+  auto point = [&](Cursor& c, int tile, bool is_a) {
     int m0, n0;
     bl_tile_origin(tile, n_tiles, MT, NTB, GX_BM, GX_BN, m0, n0);
     c.tile = tile;
@@ -102,34 +94,40 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       // row blocks past the end of an operand re-read its last block (their results are never stored)
-      const int ab = min((m0 >> 5) + 2 * wave + i, MB - 1), wb = min((n0 >> 5) + 2 * wave + i, NB - 1);
-      c.a[i] = A + (size_t)ab * KB * GX_A_BLOCK;
-      c.w[i] = Wp + (size_t)wb * KB * GX_W_BLOCK;
+      if (is_a) c.p[i] = A + (size_t)min((m0 >> 5) + 2 * wave + i, MB - 1) * KB * GX_A_BLOCK;
+      else c.p[i] = Wp + (size_t)min((n0 >> 5) + 2 * wave + i, NB - 1) * KB * GX_W_BLOCK;
     }
   };
-  // one step on; behind the block's last step the cursor stays where it is (the loads go on, so
-  // that the number of loads in flight is the same at every barrier; their data is never used)
-  auto advance = [&](Cursor& c) {
+  // one step on; behind the block's last step the cursor stays where it is (loads that nobody uses)
+  auto advance = [&](Cursor& c, bool is_a) {
     if (c.kb + 1 == KB) {
       const int nt = c.tile + (int)gridDim.x;
-      if (nt < n_tiles) point(c, nt);
+      if (nt < n_tiles) point(c, nt, is_a);
     } else {
       ++c.kb;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        c.a[i] += GX_A_BLOCK;
-        c.w[i] += GX_W_BLOCK;
-      }
+      for (int i = 0; i < 2; ++i) c.p[i] += is_a ? GX_A_BLOCK : GX_W_BLOCK;
     }
   };
-  const u32 dma_voff = lane * 16;
-  // load p (0..9) of the cursor's K step into the stage at LDS address st: row block 2w + p / 5,
-  // there XP (2 KB), XQ (1 KB), W (2 KB)
-  auto dma_part = [&](const Cursor& c, u32 st, int p) {
-    const int i = p / 5, j = p % 5, rb = 2 * wave + i;
-    if (j < 2) GX_DMA(st + rb * 2048 + j * 1024, c.a[i] + j * 1024, dma_voff);
-    else if (j == 2) GX_DMA(st + GX_XQ + rb * 1024, c.a[i] + 2048, dma_voff);
-    else GX_DMA(st + GX_W + rb * 2048 + (j - 3) * 1024, c.w[i] + (j - 3) * 1024, dma_voff);
+  // Two sets of staging registers, used by even and odd steps in turn: a register is refilled
+  // right behind the LDS write that consumed it and written out again two steps later, so a
+  // load has two steps (about 1.5 microseconds) to arrive.
+  v4i a_reg[2][LA], b_reg[2][LB];
+  const int lane16 = lane * 16;
+  // piece j of the activations: row block 2w + j / 3, there XP (2 KB) then XQ (1 KB)
+  auto load_a = [&](const Cursor& c, int set, int j) {
+    a_reg[set][j] = *reinterpret_cast<const v4i*>(c.p[j / 3] + (j % 3) * 1024 + lane16);
+  };
+  auto load_b = [&](const Cursor& c, int set, int j) {
+    b_reg[set][j] = *reinterpret_cast<const v4i*>(c.p[j / 2] + (j % 2) * 1024 + lane16);
+  };
+  auto store_a = [&](unsigned char* st, int set, int j) {
+    const int rb = 2 * wave + j / 3, i = j % 3;
+    unsigned char* dst = i < 2 ? st + rb * 2048 + i * 1024 : st + GX_XQ + rb * 1024;
+    *reinterpret_cast<v4i*>(dst + lane16) = a_reg[set][j];
+  };
+  auto store_b = [&](unsigned char* st, int set, int j) {
+    *reinterpret_cast<v4i*>(st + GX_W + (2 * wave + j / 2) * 2048 + (j % 2) * 1024 + lane16) = b_reg[set][j];
   };
 
   // ---- fragment addresses (within a stage): lane (l32, lh) reads unit u = 2 s + lh of its row
@@ -154,6 +152,9 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     return *reinterpret_cast<const v4i*>(st + w_off[s] + a * 2048);
   };
 
+  // The accumulators are pinned to AGPRs and updated in place.  (The host pass of the compiler
+  // parses kernel bodies too and knows neither these register classes nor 192-bit operands, so it
+  // sees empty statements here.)
 #if defined(__HIP_DEVICE_COMPILE__)
 #define GX_MFMA(C, WF, XF) \
   asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0 cbsz:4 blgp:3" : "+a"(C) : "v"(WF), "v"(XF))
@@ -167,23 +168,44 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 
   const float alpha = alpha_p[0];
 
-  // ---- first tile of this block.  Loads of step g are issued in two halves of five: the
-  // first during sub-step 1 of step g - 4, the second during sub-step 0 of step g - 3.  So the
-  // loop starts with steps 0, 1, 2 and the first half of step 3 under way.
+  // ---- first tile of this block: stage 0 <- step 0, activation areas of stage 1 <- step 1,
+  // registers <- weights of steps 1, 2 and activations of steps 2, 3; fragments <- step 0
   int tile = blockIdx.x;
   int m0, n0;
   bl_tile_origin(tile, n_tiles, MT, NTB, GX_BM, GX_BN, m0, n0);
-  Cursor cur;
-  point(cur, tile);
+  Cursor ca, cb;
+  point(ca, tile, true);
+  point(cb, tile, false);
 #pragma unroll
-  for (int st = 0; st < 3; ++st) {
+  for (int j = 0; j < LA; ++j) load_a(ca, 0, j);
 #pragma unroll
-    for (int p = 0; p < GX_LOADS_PER_STEP; ++p) dma_part(cur, lds0 + st * GX_STAGE, p);
-    advance(cur);
-  }
+  for (int j = 0; j < LB; ++j) load_b(cb, 0, j);
+  advance(ca, true);
+  advance(cb, false);
 #pragma unroll
-  for (int p = 0; p < GX_LOADS_PER_STEP / 2; ++p) dma_part(cur, lds0 + 3 * GX_STAGE, p);
-  GX_WAIT_LOADS(2 * GX_LOADS_PER_STEP + GX_LOADS_PER_STEP / 2);      // step 0 has landed
+  for (int j = 0; j < LA; ++j) load_a(ca, 1, j);
+  advance(ca, true);
+#pragma unroll
+  for (int j = 0; j < LA; ++j) store_a(gx_smem, 0, j);
+#pragma unroll
+  for (int j = 0; j < LB; ++j) store_b(gx_smem, 0, j);
+#pragma unroll
+  for (int j = 0; j < LA; ++j) store_a(gx_smem + GX_STAGE, 1, j);
+  // (in the order in which the loop refills them: weights of an even step, activations of an even
+  // step, weights of an odd step, activations of an odd step.  The compiler derives the loop's
+  // wait counts from the oldest-first order of the loads in flight on every path into the loop)
+#pragma unroll
+  for (int j = 0; j < LB; ++j) load_b(cb, 0, j);               // weights of step 1: written by step 0
+  advance(cb, false);
+#pragma unroll
+  for (int j = 0; j < LA; ++j) load_a(ca, 0, j);               // activations of step 2: written by step 0
+  advance(ca, true);
+#pragma unroll
+  for (int j = 0; j < LB; ++j) load_b(cb, 1, j);               // weights of step 2: written by step 1
+  advance(cb, false);
+#pragma unroll
+  for (int j = 0; j < LA; ++j) load_a(ca, 1, j);               // activations of step 3: written by step 1
+  advance(ca, true);
   __syncthreads();
   Frags F[2];
 #pragma unroll
@@ -191,94 +213,89 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     F[0].x[i] = read_x(gx_smem, 0, i);
     F[0].w[i] = read_w(gx_smem, 0, i);
   }
-  // Per-token scales of a tile.  The compiler cannot count the asynchronous loads, so wherever
-  // it has to wait for a load of its own it waits for every load in flight.  The scales are
-  // therefore fetched where that is cheap: here, and for every later tile inside the epilogue of
-  // the tile before it (see there).
-  auto load_scales = [&](int tm0, float (&d)[TM]) {
-#pragma unroll
-    for (int b = 0; b < TM; ++b) {
-      const int m = tm0 + wm * WM + b * 32 + l32;
-      d[b] = m < M ? scale[m] : 0.0f;
-    }
-  };
-  float dsc[TM];
-  load_scales(m0, dsc);
-  asm volatile("" : "+v"(dsc[0]), "+v"(dsc[1]), "+v"(dsc[2]), "+v"(dsc[3]));
 
-  int g = 0;                                     // steps done by this block (stage = g % 4)
-  // When step g reaches its barrier, the loads in flight that are younger than those of step
-  // g + 1 (which must have landed) are the 20 of steps g + 2 and g + 3 and, for the two steps
-  // behind the epilogue of an interior bf16 tile, also that epilogue's 32 stores.  (Any other
-  // epilogue waits for its stores itself.)  Vector memory operations complete in order, so
-  // "at most that many in flight" is the condition to wait for; operations this count does not
-  // know of (the scale loads of a tile) only make the wait longer.
-  constexpr int EPI_STORES = 32;
-  int steps_behind_stores = 0;
   while (true) {
     const int next = tile + (int)gridDim.x;
     const bool has_next = next < n_tiles;
     const bool interior = (m0 + GX_BM <= M) && (n0 + GX_BN <= N);
     v16f acc[TN][TM];
-    int nm0 = m0, nn0 = n0;                      // origin of the block's next tile
-    if (has_next) bl_tile_origin(next, n_tiles, MT, NTB, GX_BM, GX_BN, nm0, nn0);
-    float dsc_next[TM];
+    // Per-token scales of this tile, fetched now: a global load inside the epilogue would have
+    // to wait for the stores issued before it (loads and stores share one counter).
+    float dsc[TM];
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+      const int m = m0 + wm * WM + b * 32 + l32;
+      dsc[b] = m < M ? scale[m] : 0.0f;
+    }
 
-    for (int kb = 0; kb < KB; ++kb, ++g) {
-      const unsigned char* st_own = gx_smem + (g & 3) * GX_STAGE;
-      const unsigned char* st_next = gx_smem + ((g + 1) & 3) * GX_STAGE;
-      const u32 lds_own = lds0 + (g & 3) * GX_STAGE, lds_prev = lds0 + ((g + 3) & 3) * GX_STAGE;
-      const bool last = kb == KB - 1;
-      // ---- sub-step 0: computes on F[0], fills F[1] from the own stage, issues the second half
-      // of the loads of step g + 3 (into the stage that step g - 1 has left)
+    // One step; PAR = parity of the step = its stage and its set of staging registers (KB is
+    // even, so the parity carries over from tile to tile).
+    auto step = [&](auto par, bool first) {
+      constexpr int PAR = decltype(par)::value;
+      unsigned char* st_own = gx_smem + PAR * GX_STAGE;
+      unsigned char* st_other = gx_smem + (PAR ^ 1) * GX_STAGE;
+      // ---- sub-step 0.  Slots behind the MFMAs: fragment reads first, then one LDS write and
+      // the global load that refills its register (a 16-byte LDS write costs the MFMA stream
+      // least directly behind the reads, and nothing here is vector arithmetic).
 #pragma unroll
       for (int a = 0; a < TN; ++a) {
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
-          if (kb == 0) GX_MFMA0(acc[a][b], F[0].w[a], F[0].x[b]);
+          if (first) GX_MFMA0(acc[a][b], F[0].w[a], F[0].x[b]);
           else GX_MFMA(acc[a][b], F[0].w[a], F[0].x[b]);
           const int i = a * TM + b;              // one slot behind each MFMA
           if (i < 4) F[1].x[i] = read_x(st_own, 1, i);
           else if (i < 8) F[1].w[i - 4] = read_w(st_own, 1, i - 4);
-          if (i % 3 == 2) dma_part(cur, lds_prev, 5 + i / 3);          // slots 2, 5, 8, 11, 14
+          else if (i % 2 == 0) {                 // slots 8, 10, 12, 14: weights of the next step
+            store_b(st_other, PAR, (i - 8) / 2);
+            load_b(cb, PAR, (i - 8) / 2);
+          }
         }
       }
-      advance(cur);
-      // own loads of the next step have landed; every wave is done reading this stage
-      if (steps_behind_stores > 0) {
-        GX_WAIT_LOADS(2 * GX_LOADS_PER_STEP + EPI_STORES);
-        --steps_behind_stores;
-      } else {
-        GX_WAIT_LOADS(2 * GX_LOADS_PER_STEP);
-      }
+      advance(cb, false);
       __syncthreads();
-      // ---- sub-step 1: computes on F[1], fills F[0] from the next step's stage, issues the
-      // first half of the loads of step g + 4 into the own stage, which is free now.  At the end
-      // of a tile the stage first serves the epilogue as transpose space: the loads follow it.
+      // ---- sub-step 1
 #pragma unroll
       for (int a = 0; a < TN; ++a) {
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
           GX_MFMA(acc[a][b], F[1].w[a], F[1].x[b]);
           const int i = a * TM + b;
-          if (i < 4) F[0].x[i] = read_x(st_next, 0, i);
-          else if (i < 8) F[0].w[i - 4] = read_w(st_next, 0, i - 4);
-          if (i % 3 == 2 && !last) dma_part(cur, lds_own, i / 3);
+          if (i < 4) F[0].x[i] = read_x(st_other, 0, i);
+          else if (i < 8) F[0].w[i - 4] = read_w(st_other, 0, i - 4);
+          else if (i < 14) {                     // slots 8 .. 13: activations of the step after next
+            store_a(st_own, PAR, i - 8);
+            load_a(ca, PAR, i - 8);
+          }
         }
       }
+      advance(ca, true);
+    };
+    for (int kb = 0; kb < KB; kb += 2) {
+      step(std::integral_constant<int, 0>{}, kb == 0);
+      step(std::integral_constant<int, 1>{}, false);
     }
     // The MFMAs are issued from inline assembly: the compiler does not know that their results
     // need wait states before a vector instruction may read them.
     asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
 
+    // The staging registers already hold data of the next tile: make their loads complete
+    // here, before the epilogue's stores join the same counter.
+#pragma unroll
+    for (int set = 0; set < 2; ++set) {
+#pragma unroll
+      for (int j = 0; j < LA; ++j) asm volatile("" ::"v"(a_reg[set][j]));
+#pragma unroll
+      for (int j = 0; j < LB; ++j) asm volatile("" ::"v"(b_reg[set][j]));
+    }
+
     // ---- epilogue.  acc[a][b][r] is output n = 32 a + 8 (r / 4) + 4 lh + r % 4 of token
-    // m = 32 b + l32 (relative to the wave tile).  The stage of the tile's last step is free
-    // (its refill was held back) and serves as transpose space.
-    const int free_stage = (g - 1) & 3;
+    // m = 32 b + l32 (relative to the wave tile).  bf16 rows leave through an LDS transpose
+    // (its own space behind the stages) so that every store instruction writes whole lines.
     if (OUT == 0) {
       constexpr int TB_ROW = WN * 2 + 32;
-      unsigned char* tbuf = gx_smem + free_stage * GX_STAGE + wave * (32 * TB_ROW);
-      static_assert(4 * 32 * TB_ROW <= GX_STAGE, "transpose space must fit into one stage");
+      unsigned char* tbuf = gx_smem + GX_TB + wave * (32 * TB_ROW);
+      static_assert(4 * 32 * TB_ROW <= GX_TB_BYTES, "transpose space");
       constexpr int LANES_PER_ROW = WN * 2 / 16;           // 16 lanes cover one token's 256 bytes
       constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
       constexpr int NPASS = 32 / ROWS_PER_PASS;
@@ -286,13 +303,9 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       uint16_t* ywave = (uint16_t*)Y + (size_t)(m0 + wm * WM) * N + (n0 + wn * WN);
       const u32 lane_off = (u32)rr * (u32)N + cc * 8;
       const int m_left = M - (m0 + wm * WM) - rr, n_left = N - (n0 + wn * WN) - cc * 8;
-      // scales of the next tile: requested now, waited for behind the first column's arithmetic,
-      // when the last asynchronous loads are a few thousand cycles old and nothing else is in flight
-      load_scales(nm0, dsc_next);
 #pragma unroll
       for (int b = 0; b < TM; ++b) {
         const float d = dsc[b];
-        if (b == 1) asm volatile("" : "+v"(dsc_next[0]), "+v"(dsc_next[1]), "+v"(dsc_next[2]), "+v"(dsc_next[3]));
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
           asm volatile("" : "+a"(acc[a][b]));
@@ -328,8 +341,6 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
-      load_scales(nm0, dsc_next);
-      asm volatile("" : "+v"(dsc_next[0]), "+v"(dsc_next[1]), "+v"(dsc_next[2]), "+v"(dsc_next[3]));
 #pragma unroll
       for (int b = 0; b < TM; ++b) {
         const int m = m0 + wm * WM + b * 32 + l32;
@@ -388,23 +399,11 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     }
     if (!has_next) break;
     tile = next;
-    m0 = nm0;
-    n0 = nn0;
-#pragma unroll
-    for (int b = 0; b < TM; ++b) dsc[b] = dsc_next[b];
-    if (OUT == 0 && !ACC && interior) {
-      steps_behind_stores = 2;
-    } else {
-      GX_WAIT_LOADS(0);                // a store count that depends on the tile: wait for all of them
-      steps_behind_stores = 0;
-    }
-    __syncthreads();                   // transpose space has been read out by every wave
-    // the loads that were held back: first half of the step after the next three
-#pragma unroll
-    for (int p = 0; p < GX_LOADS_PER_STEP / 2; ++p) dma_part(cur, lds0 + free_stage * GX_STAGE, p);
+    bl_tile_origin(tile, n_tiles, MT, NTB, GX_BM, GX_BN, m0, n0);
+    // (no barrier: the epilogue touches neither stage, and each wave has its own transpose space)
   }
-  GX_WAIT_LOADS(0);                    // no copy may be in flight when the LDS is released
 #undef GX_MFMA
+#undef GX_MFMA0
 }
 
 static int gx_num_cus() {
