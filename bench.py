@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the W1.58A4 prefill GEMM at the benchmark shapes, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_prefill_7b_hbm_traffic.txt
 # (calibrated against a 1 GiB device copy): 386.5 MB fetched + 374.7 MB written.
-A4_GEMM_TRAFFIC_BYTES = 761.2e6
+A4_GEMM_TRAFFIC_BYTES = 1052.4e6
 HIDDEN, FFN = 4096, 11008
 
 
