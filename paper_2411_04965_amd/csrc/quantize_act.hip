@@ -347,6 +347,37 @@ __device__ __forceinline__ int qa_count_ge(const u32 (&pg)[CPW][2], u32 cand) {
   return cnt;
 }
 
+// Bit planes.  The search for tau looks at one bit of every key per pass, so the keys of a lane are
+// turned into bit planes once: 16 keys (8 words of two 16-bit rows) -> 16 planes of 16 bits (word
+// p / 2, half p % 2 holds bit p of the 16 keys, key r in bit r).  The usual recursive block swap, on
+// packed halves: byte blocks with v_perm, 4-, 2- and 1-bit blocks with shift / xor / mask.
+__device__ __forceinline__ void qa_bit_transpose16(u32 (&w)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const u32 a = w[i], b = w[i + 4];
+    w[i] = __builtin_amdgcn_perm(b, a, 0x06020400u);        // a.b0 b.b0 a.b2 b.b2
+    w[i + 4] = __builtin_amdgcn_perm(b, a, 0x07030501u);    // a.b1 b.b1 a.b3 b.b3
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = (k & 1) + 4 * (k >> 1);                   // 0, 1, 4, 5
+    const u32 t = ((w[i] >> 4) ^ w[i + 2]) & 0x0F0F0F0Fu;
+    w[i + 2] ^= t;
+    w[i] ^= t << 4;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; i += 2) {
+    const u32 t = ((w[i] >> 2) ^ w[i + 1]) & 0x33333333u;
+    w[i + 1] ^= t;
+    w[i] ^= t << 2;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const u32 t = ((w[i] >> 1) ^ (w[i] >> 16)) & 0x5555u;
+    w[i] ^= (t << 16) | (t << 1);
+  }
+}
+
 template <int CPW>
 __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
     const uint16_t* __restrict__ X, int K, int Kp, int topk, float eps, u32* __restrict__ q_out,
@@ -394,31 +425,63 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
   const float s = 127.0f / (gamma + eps);
   if (threadIdx.x == 0) scale_out[m] = gamma / 127.0f;
 
-  // tau = topk-th largest key, bit by bit
+  // tau = topk-th largest key, bit by bit from the top, on bit planes.  `act` marks the keys whose
+  // bits above the current one equal tau's; `above` counts the keys already known to be larger.
+  // A bit of tau is 1 iff at least topk keys are >= the candidate, i.e. above + #(active keys with
+  // the bit set) >= topk; then those keys stay active, otherwise they join `above`.  Cost per pass:
+  // a handful of instructions per lane instead of 1.5 per key.
+  constexpr int NBK = CPW / 4;                            // blocks of 16 keys per lane
+  static_assert(CPW % 4 == 0 && NBK >= 1 && NBK <= 3, "16 keys per block, at most 48 keys per lane");
+  u32 pl[NBK][8];
+#pragma unroll
+  for (int B = 0; B < NBK; ++B) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pl[B][i] = raw[4 * B + (i >> 1)][i & 1] & 0x7FFF7FFFu;
+    qa_bit_transpose16(pl[B]);
+  }
+  // keys of chunks this wave does not have (key 0) stay out: they would count as equal to tau = 0
+  const unsigned long long real = nc >= 16 ? ~0ull : ((1ull << (4 * nc)) - 1ull);
+  u32 act_lo = (u32)real, act_hi = (u32)(real >> 32) & 0xFFFFu;
+  if (NBK == 1) act_lo &= 0xFFFFu;
   u32 tau = 0;
+  int above = 0;
   int pass = 0;
-  for (int bit = 31 - __clz((int)(kmax | 1u)); bit >= 0; --bit, ++pass) {
-    const u32 cand = tau | (1u << bit);
-    const int cnt = qa_wave_sum_dpp(qa_count_ge<CPW>(pg, cand));
-    if (lane == 0) sh_a[pass & 1][wave] = (u32)cnt;
-    __syncthreads();                                      // one barrier per pass: slots alternate
-    const uint4 t = *reinterpret_cast<const uint4*>(sh_a[pass & 1]);
-    const u32 total = (u32)__builtin_amdgcn_readfirstlane((int)(t.x + t.y + t.z + t.w));
-    if (total >= (u32)topk) tau = cand;
+  const int top_bit = 31 - __clz((int)(kmax | 1u));
+#pragma unroll
+  for (int bit = 14; bit >= 0; --bit) {
+    if (bit <= top_bit) {                                 // wave-uniform
+      u32 p_lo, p_hi = 0;
+      if (NBK == 1) p_lo = (bit & 1) ? pl[0][bit >> 1] >> 16 : pl[0][bit >> 1] & 0xFFFFu;
+      else p_lo = __builtin_amdgcn_perm(pl[1][bit >> 1], pl[0][bit >> 1], (bit & 1) ? 0x07060302u : 0x05040100u);
+      if (NBK == 3) p_hi = (bit & 1) ? pl[2][bit >> 1] >> 16 : pl[2][bit >> 1] & 0xFFFFu;
+      const u32 x_lo = act_lo & p_lo, x_hi = act_hi & p_hi;
+      const int cnt = qa_wave_sum_dpp(__popc(x_lo) + __popc(x_hi));
+      if (lane == 0) sh_a[pass & 1][wave] = (u32)cnt;
+      __syncthreads();                                    // one barrier per pass: slots alternate
+      const uint4 t = *reinterpret_cast<const uint4*>(sh_a[pass & 1]);
+      const int total = __builtin_amdgcn_readfirstlane((int)(t.x + t.y + t.z + t.w));
+      if (above + total >= topk) {
+        tau |= 1u << bit;
+        act_lo = x_lo;
+        act_hi = x_hi;
+      } else {
+        above += total;
+        act_lo ^= x_lo;
+        act_hi ^= x_hi;
+      }
+      ++pass;
+    }
   }
 
-  // per-wave counts of keys above and equal to tau (for tau = 0 every key of the wave's real
-  // chunks is "equal", padding inside the last chunk included, as in the LDS kernel)
+  // keys equal to tau per wave (the active ones); `above` is the number of keys larger than tau
   {
-    const int gt = qa_wave_sum_dpp(qa_count_ge<CPW>(pg, tau + 1u));
-    const int ge = tau ? qa_wave_sum_dpp(qa_count_ge<CPW>(pg, tau)) : nc * 256;
+    const int eq = qa_wave_sum_dpp(__popc(act_lo) + __popc(act_hi));
     __syncthreads();                                      // sh_b was read above by every thread
-    if (lane == 0) { sh_b[wave] = (u32)gt; sh_c[wave] = (u32)(ge - gt); }
+    if (lane == 0) sh_c[wave] = (u32)eq;
     __syncthreads();
   }
-  const uint4 gtw = *reinterpret_cast<const uint4*>(sh_b);
   const uint4 eqw4 = *reinterpret_cast<const uint4*>(sh_c);
-  const int r = topk - (int)__builtin_amdgcn_readfirstlane((int)(gtw.x + gtw.y + gtw.z + gtw.w));
+  const int r = topk - above;
   const u32 eqs[4] = {eqw4.x, eqw4.y, eqw4.z, eqw4.w};
   int eq_base = 0;                                        // keys equal to tau in earlier waves
 #pragma unroll
