@@ -335,18 +335,6 @@ __device__ __forceinline__ int qa_wave_sum_dpp(int v) {
 
 #define QA_GUARD 0x80008000u
 
-// keys >= cand among this lane's, cand in 1 .. 0x8000
-template <int CPW>
-__device__ __forceinline__ int qa_count_ge(const u32 (&pg)[CPW][2], u32 cand) {
-  const u32 c2 = cand * 0x10001u;
-  int cnt = 0;
-#pragma unroll
-  for (int i = 0; i < CPW; ++i)
-#pragma unroll
-    for (int h = 0; h < 2; ++h) cnt += __popc((pg[i][h] - c2) & QA_GUARD);
-  return cnt;
-}
-
 // Bit planes.  The search for tau looks at one bit of every key per pass, so the keys of a lane are
 // turned into bit planes once: 16 keys (8 words of two 16-bit rows) -> 16 planes of 16 bits (word
 // p / 2, half p % 2 holds bit p of the 16 keys, key r in bit r).  The usual recursive block swap, on
@@ -406,13 +394,15 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
     raw[i][0] = v.x; raw[i][1] = v.y;
     pg[i][0] = v.x | QA_GUARD; pg[i][1] = v.y | QA_GUARD;
   }
+  {
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    us2 km = __builtin_bit_cast(us2, km2);
 #pragma unroll
-  for (int i = 0; i < CPW; ++i)
+    for (int i = 0; i < CPW; ++i)
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const u32 w = pg[i][h];
-      km2 = max(km2 & 0xFFFFu, w & 0xFFFFu) | (max(km2 >> 16, w >> 16) << 16);
-    }
+      for (int h = 0; h < 2; ++h) km = __builtin_elementwise_max(km, __builtin_bit_cast(us2, pg[i][h]));   // v_pk_max_u16
+    km2 = __builtin_bit_cast(u32, km);
+  }
   u32 kmax = max(km2 & 0x7FFFu, (km2 >> 16) & 0x7FFFu);
   kmax = bl_wave_max_u32(kmax);
   if (lane == 0) sh_b[wave] = kmax;
@@ -493,9 +483,8 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
   // all of them, none of them, or (for one wave of the token) a prefix found with ballots.
   const bool eq_all = eq_base + eq_here <= r;
   const bool eq_none = eq_base >= r;
-  const u32 eq_mode = eq_all ? QA_GUARD : 0u;
-
   const u32 t1 = (tau + 1u) * 0x10001u, t0 = tau * 0x10001u;
+  const u32 tk = eq_all ? t0 : t1;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   int sum = 0;
   u32* out = q_out + m * (int64_t)(Kp / 4);
@@ -503,10 +492,11 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
   for (int i = 0; i < CPW; ++i) {
     if (i < nc) {                                         // wave-uniform
       const int c = c_begin + i;
-      const u32 g0 = (pg[i][0] - t1) & QA_GUARD, g1 = (pg[i][1] - t1) & QA_GUARD;   // key > tau
-      const u32 e0 = ((pg[i][0] - t0) & QA_GUARD) ^ g0, e1 = ((pg[i][1] - t0) & QA_GUARD) ^ g1;
-      u32 k0 = g0 | (e0 & eq_mode), k1 = g1 | (e1 & eq_mode);                       // kept
+      // kept keys as guard-bit flags: key >= tau where the wave keeps all its keys equal to tau,
+      // key > tau where it keeps none of them
+      u32 k0 = (pg[i][0] - tk) & QA_GUARD, k1 = (pg[i][1] - tk) & QA_GUARD;
       if (!eq_all && !eq_none) {                          // the wave that holds the r-th equal key
+        const u32 e0 = ((pg[i][0] - t0) & QA_GUARD) ^ k0, e1 = ((pg[i][1] - t0) & QA_GUARD) ^ k1;
         const bool eqf[4] = {(e0 & 0x8000u) != 0, (e0 >> 31) != 0, (e1 & 0x8000u) != 0, (e1 >> 31) != 0};
         uint64_t beq[4], any_eq = 0;
 #pragma unroll
@@ -527,17 +517,17 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
       }
       // codes: |x * s| <= 127 for every finite row, so RoundClip is the rounding alone, taken
       // from the low byte of (x * s) + 1.5 * 2^23 (round to nearest even at integer spacing)
-      const float xs[4] = {
-          __uint_as_float((raw[i][0] << 16) & (u32)((int)(k0 << 16) >> 31)),
-          __uint_as_float((raw[i][0] & 0xFFFF0000u) & (u32)((int)k0 >> 31)),
-          __uint_as_float((raw[i][1] << 16) & (u32)((int)(k1 << 16) >> 31)),
-          __uint_as_float((raw[i][1] & 0xFFFF0000u) & (u32)((int)k1 >> 31))};
+      const float xs[4] = {__uint_as_float(raw[i][0] << 16), __uint_as_float(raw[i][0] & 0xFFFF0000u),
+                           __uint_as_float(raw[i][1] << 16), __uint_as_float(raw[i][1] & 0xFFFF0000u)};
       u32 rb[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) rb[j] = __float_as_uint(xs[j] * s + 12582912.0f);
       const u32 w01 = __builtin_amdgcn_perm(rb[1], rb[0], 0x0c0c0400u);   // bytes: rb0.b0, rb1.b0, 0, 0
       const u32 w23 = __builtin_amdgcn_perm(rb[3], rb[2], 0x04000c0cu);   // bytes: 0, 0, rb2.b0, rb3.b0
-      const u32 word = w01 | w23;
+      // the four flags (bits 15 and 31 of k0, k1) as a byte mask: bytes 1 and 3 of each word hold
+      // 0x80 or 0; shifted down that is 1 or 0 per byte, times 255 it is the mask
+      const u32 keep4 = (__builtin_amdgcn_perm(k1, k0, 0x07050301u) >> 7) * 255u;
+      const u32 word = (w01 | w23) & keep4;
       sum = __builtin_amdgcn_sdot4((int)word, 0x01010101, sum, false);
       out[c * 64 + lane] = word;
     }
