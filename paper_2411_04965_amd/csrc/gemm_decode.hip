@@ -204,9 +204,10 @@ __global__ __launch_bounds__(GD_THREADS) void decode_reduce_kernel(
   gd_store4(Y, y_bf16, acc_out, (size_t)m * N + n, n, N, iv, scale[m], alpha_p[0]);
 }
 
-// Up to 4 tokens with enough output tiles to fill the chip: one 16-output tile per block, no
-// split of K, one launch.  Otherwise 64 outputs per block and K split until the grid is large.
-static bool gd_single_tile(int M, int N) { return M <= 4 && (N + 15) / 16 >= 128; }
+// Up to 16 tokens (one MFMA tile of tokens) with enough output tiles to fill the chip: one
+// 16-output tile per block, no split of K, one launch.  Otherwise 64 outputs per block and K split
+// until the grid is large.
+static bool gd_single_tile(int M, int N) { return M <= 16 && (N + 15) / 16 >= 128; }
 static int gd_pick_split(int M, int N, int KT) {
   if (gd_single_tile(M, N)) return 1;
   const int NB = (N + GD_BN - 1) / GD_BN;
