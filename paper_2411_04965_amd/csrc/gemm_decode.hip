@@ -1,5 +1,5 @@
 // Decode-shaped (1..64 tokens) linears: the packed ternary weights are streamed from HBM once.
-//   Dense path  (BL_W_GEMM tiles):   skinny int8-MFMA GEMM, K split over waves and blocks.
+//   Dense path  (BL_W_GEMM tiles):   skinny int8-MFMA GEMM; three kernels by token count.
 //   Sparse path (BL_W_KMAJOR rows):  eq. 1's sparsity used for I/O — only the weight rows of
 //                                    channels whose INT8 code is non-zero in some token are read.
 // Integer partial sums are exact, so any split of K gives the same accumulators.
@@ -37,16 +37,16 @@ __device__ __forceinline__ void gd_store4(void* Y, int y_bf16, int32_t* acc_out,
 }
 
 // ---------------------------------------------------------------- dense skinny GEMM
-// Block = 4 waves, NTB tiles of 16 outputs.  The block's K range is dealt tile by tile (256
-// channels) to the waves; every wave keeps NTB x MT accumulator tiles, reduced through LDS at
-// the end.  NTB = 1 (very few tokens: every block streams its own slice of W over all of K, no
-// split, one launch) or 4 (the token fragments are reused by four weight tiles).
-template <int MT, bool A4, int NTB>
+// Up to 16 tokens.  Block = 4 waves, one tile of 16 outputs.  The K tiles (256 channels) are dealt
+// to the waves; every wave keeps MT accumulator tiles, added through LDS at the end: every block
+// streams its own slice of W over all of K, no split across blocks, one launch.
+template <int MT, bool A4>
 __global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
     void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out, int32_t* __restrict__ partial,
     int NB, int S) {
+  constexpr int NTB = 1;
   extern __shared__ __align__(16) unsigned char gd_smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
@@ -176,6 +176,273 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
   }
 }
 
+// More than one MFMA tile of tokens, or too few output tiles for the kernel above: block = 4 waves
+// = 64 outputs, every wave owns one tile of 16 outputs and walks the block's whole K range (a
+// slice of K when the grid would otherwise be small), so there is no reduction inside the block.
+// The tokens' codes of one K tile (M rows of 128 or 256 bytes, far apart in memory) are fetched
+// once per block with whole-line loads and passed through LDS (rows padded by 16 bytes, so the
+// 16-byte fragment reads of 16 token rows fall into 16 different slots of a 256-byte window); a
+// wave reading them straight from memory asks for 16 to 32 lines per load and uses a quarter of
+// each.  Weights are fetched four K tiles ahead (HBM latency), tokens one tile ahead.
+template <int MT, bool A4>
+__global__ __launch_bounds__(GD_THREADS) void gemm_decode_rows_kernel(
+    const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
+    const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
+    void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out, int32_t* __restrict__ partial,
+    int NB, int S) {
+  constexpr int TB = A4 ? 128 : 256;             // bytes of one token row per K tile
+  constexpr int ROW = TB + 16;                   // LDS row pitch
+  constexpr int PER_ROW = TB / 16;               // 16-byte pieces per row
+  constexpr int XL = MT * 16 * PER_ROW / GD_THREADS;   // pieces per thread: 1 .. 4
+  static_assert(MT * 16 * PER_ROW % GD_THREADS == 0 || MT == 1, "whole pieces per thread");
+  constexpr int XLN = XL > 0 ? XL : 1;
+  __shared__ __align__(16) unsigned char xs[2][MT * 16 * ROW];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lg = lane >> 4;
+  const int nb = blockIdx.x % NB, split = blockIdx.x / NB;
+  const int KT = Kp >> 8;
+  const int t_begin = (int)((int64_t)split * KT / S), t_end = (int)((int64_t)(split + 1) * KT / S);
+  const int NT16 = (N + 15) >> 4;
+  const int nt = nb * 4 + wave;
+  const int a_row_bytes = A4 ? (Kp >> 1) : Kp;
+  const unsigned char* w_src = Wp + (size_t)min(nt, NT16 - 1) * KT * 1024 + lane * 16;
+  // piece j of this thread: row (tid + 256 j) / PER_ROW, piece (tid + 256 j) % PER_ROW
+  const unsigned char* x_src[XLN];
+  int x_dst[XLN];
+  bool x_on[XLN];
+#pragma unroll
+  for (int j = 0; j < XLN; ++j) {
+    const int idx = tid + GD_THREADS * j;
+    const int row = idx / PER_ROW, pc = idx % PER_ROW;
+    x_on[j] = row < MT * 16;                     // (MT == 1 with 128-byte rows: half the threads)
+    x_src[j] = A + (size_t)min(row, M - 1) * a_row_bytes + pc * 16;
+    x_dst[j] = min(row, MT * 16 - 1) * ROW + pc * 16;
+  }
+  v4i acc[MT];
+#pragma unroll
+  for (int b = 0; b < MT; ++b) acc[b] = (v4i){0, 0, 0, 0};
+
+  constexpr int WD = 4;
+  uint4 wq[WD], xn[XLN];
+  auto load_x = [&](int t) {
+#pragma unroll
+    for (int j = 0; j < XLN; ++j)
+      if (x_on[j]) xn[j] = *reinterpret_cast<const uint4*>(x_src[j] + (size_t)t * TB);
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < XLN; ++j)
+      if (x_on[j]) *reinterpret_cast<uint4*>(&xs[buf][x_dst[j]]) = xn[j];
+  };
+  if (t_begin < t_end) {                         // block-uniform
+#pragma unroll
+    for (int j = 0; j < WD; ++j)
+      wq[j] = *reinterpret_cast<const uint4*>(w_src + (size_t)min(t_begin + j, t_end - 1) * 1024);
+    load_x(t_begin);
+    store_x(0);
+    __syncthreads();
+  }
+  const int frag = li * ROW + lg * (A4 ? 32 : 64);
+  int buf = 0;
+  for (int t0 = t_begin; t0 < t_end; t0 += WD) {
+#pragma unroll
+    for (int j = 0; j < WD; ++j) {
+      const int t = t0 + j;
+      if (t < t_end) {                           // block-uniform
+        const uint4 wc = wq[j];
+        if (t + 1 < t_end) load_x(t + 1);
+        if (t + WD < t_end) wq[j] = *reinterpret_cast<const uint4*>(w_src + (size_t)(t + WD) * 1024);
+        const unsigned char* xb = &xs[buf][frag];
+#pragma unroll
+        for (int t4 = 0; t4 < 4; ++t4) {
+          const u32 w = t4 == 0 ? wc.x : t4 == 1 ? wc.y : t4 == 2 ? wc.z : wc.w;
+          const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
+                               (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+#pragma unroll
+          for (int b = 0; b < MT; ++b) {
+            v4i xo;
+            if (A4) {
+              // a lane's 64 channels = 8 words; MFMA step t4 takes words 2*t4 and 2*t4+1
+              const uint2 v = *reinterpret_cast<const uint2*>(xb + b * 16 * ROW + t4 * 8);
+              xo = (v4i){(int)((v.x << 4) & 0xF0F0F0F0u), (int)(v.x & 0xF0F0F0F0u),
+                         (int)((v.y << 4) & 0xF0F0F0F0u), (int)(v.y & 0xF0F0F0F0u)};
+            } else {
+              xo = *reinterpret_cast<const v4i*>(xb + b * 16 * ROW + t4 * 16);
+            }
+            acc[b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo, acc[b], 0, 0, 0);
+          }
+        }
+        // the other buffer was last read one tile ago, before the barrier every wave has passed
+        if (t + 1 < t_end) store_x(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+      }
+    }
+  }
+
+  if (nt >= NT16) return;
+  const float alpha = alpha_p[0];
+  constexpr int SHIFT = A4 ? 10 : 6;
+#pragma unroll
+  for (int b = 0; b < MT; ++b) {
+    const int m = b * 16 + li;
+    const int n = nt * 16 + 4 * lg;
+    if (m >= M || n >= N) continue;
+    const size_t o = (size_t)m * N + n;
+    if (S == 1) {
+      const int iv[4] = {acc[b][0] >> SHIFT, acc[b][1] >> SHIFT, acc[b][2] >> SHIFT, acc[b][3] >> SHIFT};
+      gd_store4(Y, y_bf16, acc_out, o, n, N, iv, scale[m], alpha);
+    } else {
+      int32_t* p = partial + (size_t)split * M * N + o;
+      if ((N & 3) == 0) {
+        *reinterpret_cast<int4*>(p) = make_int4(acc[b][0], acc[b][1], acc[b][2], acc[b][3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (n + r < N) p[r] = acc[b][r];
+      }
+    }
+  }
+}
+
+// 17 to 64 tokens.  The tokens' codes are the larger stream here (a block of 16 outputs reads 4 KB
+// of weights per 1024 channels but 32 to 64 KB of codes), and split-K partial sums cost as much
+// again.  So the codes stay put: one block of 16 waves per CU keeps the codes of all tokens for its
+// slice of K in LDS (up to 128 KB: all of K for INT4 codes at 4096 channels) and streams the weight
+// tiles of its share of the outputs past them.  Wave u works on output tile u / KS of the block and
+// on part u % KS of the slice; the parts are added through LDS (in the space of the codes) at the end.
+#define GR_THREADS 1024
+#define GR_WAVES 16
+#define GR_X_BYTES 131072                        // LDS for the codes (pitch = row bytes + 16)
+template <int MT, bool A4>
+__global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
+    const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
+    const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
+    void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out, int32_t* __restrict__ partial,
+    int NBn, int S, int NWT, int KS) {
+  extern __shared__ __align__(16) unsigned char gr_smem[];
+  constexpr int TB = A4 ? 128 : 256;             // bytes of one token row per K tile
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lg = lane >> 4;
+  const int nbk = blockIdx.x % NBn, split = blockIdx.x / NBn;
+  const int KT = Kp >> 8;
+  const int t_begin = (int)((int64_t)split * KT / S), t_end = (int)((int64_t)(split + 1) * KT / S);
+  const int L = t_end - t_begin;                 // tiles of this slice: L * TB * MT * 16 <= GR_X_BYTES
+  const int NT16 = (N + 15) >> 4;
+  const int a_row_bytes = A4 ? (Kp >> 1) : Kp;
+  const int RB = L * TB, pitch = RB + 16, ppr = RB >> 4;
+
+  // this wave's part of the work, and its first weight tiles (issued before the codes are staged)
+  const int nt = nbk * NWT + wave / KS, ks = wave % KS;
+  const bool works = wave < NWT * KS && nt < NT16;
+  const int my_begin = t_begin + (int)((int64_t)ks * L / KS), my_end = t_begin + (int)((int64_t)(ks + 1) * L / KS);
+  const unsigned char* w_src = Wp + (size_t)min(nt, NT16 - 1) * KT * 1024 + lane * 16;
+  constexpr int WD = 8;
+  uint4 wq[WD];
+  if (works && my_begin < my_end) {
+#pragma unroll
+    for (int j = 0; j < WD; ++j)
+      wq[j] = *reinterpret_cast<const uint4*>(w_src + (size_t)min(my_begin + j, my_end - 1) * 1024);
+  }
+
+  // codes of all tokens for tiles t_begin .. t_end: wave w stages rows w, w + 16, ...
+  {
+    uint4 v[MT][4];
+#pragma unroll
+    for (int r = 0; r < MT; ++r) {
+      const unsigned char* src = A + (size_t)min(wave + GR_WAVES * r, M - 1) * a_row_bytes + (size_t)t_begin * TB;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int pc = lane + 64 * j;
+        v[r][j] = make_uint4(0u, 0u, 0u, 0u);
+        if (pc < ppr) v[r][j] = *reinterpret_cast<const uint4*>(src + pc * 16);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < MT; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int pc = lane + 64 * j;
+        if (pc < ppr) *reinterpret_cast<uint4*>(gr_smem + (wave + GR_WAVES * r) * pitch + pc * 16) = v[r][j];
+      }
+  }
+  __syncthreads();
+
+  v4i acc[MT];
+#pragma unroll
+  for (int b = 0; b < MT; ++b) acc[b] = (v4i){0, 0, 0, 0};
+  if (works) {
+    const unsigned char* xrow = gr_smem + li * pitch + lg * (A4 ? 32 : 64);
+    for (int t0 = my_begin; t0 < my_end; t0 += WD) {
+#pragma unroll
+      for (int j = 0; j < WD; ++j) {
+        const int t = t0 + j;
+        if (t < my_end) {                        // wave-uniform
+          const uint4 wc = wq[j];
+          if (t + WD < my_end) wq[j] = *reinterpret_cast<const uint4*>(w_src + (size_t)(t + WD) * 1024);
+          const unsigned char* xb = xrow + (t - t_begin) * TB;
+#pragma unroll
+          for (int t4 = 0; t4 < 4; ++t4) {
+            const u32 w = t4 == 0 ? wc.x : t4 == 1 ? wc.y : t4 == 2 ? wc.z : wc.w;
+            const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
+                                 (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+              v4i xo;
+              if (A4) {
+                // a lane's 64 channels = 8 words; MFMA step t4 takes words 2*t4 and 2*t4+1
+                const uint2 v = *reinterpret_cast<const uint2*>(xb + b * 16 * pitch + t4 * 8);
+                xo = (v4i){(int)((v.x << 4) & 0xF0F0F0F0u), (int)(v.x & 0xF0F0F0F0u),
+                           (int)((v.y << 4) & 0xF0F0F0F0u), (int)(v.y & 0xF0F0F0F0u)};
+              } else {
+                xo = *reinterpret_cast<const v4i*>(xb + b * 16 * pitch + t4 * 16);
+              }
+              acc[b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo, acc[b], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // add the KS parts of every output tile: all waves leave their sums where the codes were
+  if (KS > 1) {
+    __syncthreads();
+    v4i* red = reinterpret_cast<v4i*>(gr_smem);  // [wave][b][lane]
+#pragma unroll
+    for (int b = 0; b < MT; ++b) red[(wave * MT + b) * 64 + lane] = acc[b];
+    __syncthreads();
+    if (ks == 0) {
+      for (int k = 1; k < KS; ++k)
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[b] += red[((wave + k) * MT + b) * 64 + lane];
+    }
+  }
+  if (!works || ks != 0) return;
+  const float alpha = alpha_p[0];
+  constexpr int SHIFT = A4 ? 10 : 6;
+#pragma unroll
+  for (int b = 0; b < MT; ++b) {
+    const int m = b * 16 + li;
+    const int n = nt * 16 + 4 * lg;
+    if (m >= M || n >= N) continue;
+    const size_t o = (size_t)m * N + n;
+    if (S == 1) {
+      const int iv[4] = {acc[b][0] >> SHIFT, acc[b][1] >> SHIFT, acc[b][2] >> SHIFT, acc[b][3] >> SHIFT};
+      gd_store4(Y, y_bf16, acc_out, o, n, N, iv, scale[m], alpha);
+    } else {
+      int32_t* p = partial + (size_t)split * M * N + o;
+      if ((N & 3) == 0) {
+        *reinterpret_cast<int4*>(p) = make_int4(acc[b][0], acc[b][1], acc[b][2], acc[b][3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (n + r < N) p[r] = acc[b][r];
+      }
+    }
+  }
+}
+
 // Sum S integer partials, shift back, rescale.  One thread per 4 consecutive outputs.
 __global__ __launch_bounds__(GD_THREADS) void decode_reduce_kernel(
     const int32_t* __restrict__ partial, int S, int M, int N, int shift,
@@ -204,12 +471,29 @@ __global__ __launch_bounds__(GD_THREADS) void decode_reduce_kernel(
   gd_store4(Y, y_bf16, acc_out, (size_t)m * N + n, n, N, iv, scale[m], alpha_p[0]);
 }
 
-// Up to 16 tokens (one MFMA tile of tokens) with enough output tiles to fill the chip: one
-// 16-output tile per block, no split of K, one launch.  Otherwise 64 outputs per block and K split
-// until the grid is large.
+// Kernel choice.  Up to 16 tokens (one MFMA tile of tokens) with enough output tiles to fill the
+// chip: one 16-output tile per block, no split of K, one launch.  Up to 16 tokens and few outputs:
+// 64 outputs per block and K split until the grid is large.  More tokens: codes resident in LDS.
 static bool gd_single_tile(int M, int N) { return M <= 16 && (N + 15) / 16 >= 128; }
-static int gd_pick_split(int M, int N, int KT) {
+static int gd_num_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  return cus;
+}
+// resident kernel: tiles of K per slice so that 16 * MT rows of codes fit
+static int gr_slice_tiles(int MT, bool a4) { return GR_X_BYTES / (MT * 16) / (a4 ? 128 : 256); }
+static int gd_pick_split(int M, int N, int KT, bool a4) {
   if (gd_single_tile(M, N)) return 1;
+  if (M > 16) {
+    const int MT = M > 32 ? 4 : 2;
+    const int tmax = gr_slice_tiles(MT, a4);
+    return (KT + tmax - 1) / tmax;
+  }
   const int NB = (N + GD_BN - 1) / GD_BN;
   int S = 1;
   while (NB * S < 512 && S * 2 <= KT && S < 32) S *= 2;
@@ -218,34 +502,69 @@ static int gd_pick_split(int M, int N, int KT) {
 
 size_t bl_gemm_decode_ws_bytes(int64_t M, int64_t N, int64_t K) {
   const int KT = (int)(bl_round_up(K, BL_KPAD) >> 8);
-  const int S = gd_pick_split((int)M, (int)N, KT);
+  // (the larger of the two code widths: the workspace is sized before the mode is known)
+  const int S = max(gd_pick_split((int)M, (int)N, KT, false), gd_pick_split((int)M, (int)N, KT, true));
   return S > 1 ? (size_t)S * M * N * sizeof(int32_t) : 0;
 }
 
-template <int MT, bool A4, int NTB>
+static int gd_reduce(int S, int M, int N, int shift, const float* scale, const float* alpha, void* Y,
+                     int ybf, int32_t* acc_out, void* ws, hipStream_t s) {
+  const int64_t n_thr = (int64_t)M * ((N + 3) >> 2);
+  decode_reduce_kernel<<<(unsigned)((n_thr + GD_THREADS - 1) / GD_THREADS), GD_THREADS, 0, s>>>(
+      (const int32_t*)ws, S, M, N, shift, scale, alpha, Y, ybf, acc_out);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}
+
+template <int MT, bool A4, bool SINGLE>
 static int gd_run(const void* q, const float* scale, int M, int Kp, const void* Wp,
                   const float* alpha, int N, void* Y, bl_dtype ydt, int32_t* acc_out, void* ws,
                   hipStream_t s) {
-  const int NB = (N + 16 * NTB - 1) / (16 * NTB), KT = Kp >> 8;
-  const int S = gd_pick_split(M, N, KT);
+  const int KT = Kp >> 8;
+  const int S = gd_pick_split(M, N, KT, A4);
   if (S > 1 && !ws) return BL_EWORKSPACE;
-  const size_t smem = (size_t)4 * NTB * MT * 64 * sizeof(v4i);
-  auto kern = gemm_decode_kernel<MT, A4, NTB>;
-  if (smem > 48 * 1024 &&
-      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+  const int ybf = ydt == BL_BF16 ? 1 : 0;
+  if (SINGLE) {
+    const int NB = (N + 15) / 16;
+    const size_t smem = (size_t)4 * MT * 64 * sizeof(v4i);
+    gemm_decode_kernel<MT, A4><<<(unsigned)(NB * S), GD_THREADS, smem, s>>>(
+        (const unsigned char*)q, scale, M, Kp, (const unsigned char*)Wp, alpha, N, Y, ybf, acc_out,
+        (int32_t*)ws, NB, S);
+  } else {
+    const int NB = (N + GD_BN - 1) / GD_BN;
+    gemm_decode_rows_kernel<MT, A4><<<(unsigned)(NB * S), GD_THREADS, 0, s>>>(
+        (const unsigned char*)q, scale, M, Kp, (const unsigned char*)Wp, alpha, N, Y, ybf, acc_out,
+        (int32_t*)ws, NB, S);
+  }
+  BL_HIP_CHECK_LAUNCH();
+  return S > 1 ? gd_reduce(S, M, N, A4 ? 10 : 6, scale, alpha, Y, ybf, acc_out, ws, s) : BL_OK;
+}
+
+template <int MT, bool A4>
+static int gr_run(const void* q, const float* scale, int M, int Kp, const void* Wp,
+                  const float* alpha, int N, void* Y, bl_dtype ydt, int32_t* acc_out, void* ws,
+                  hipStream_t s) {
+  const int KT = Kp >> 8, NT16 = (N + 15) / 16;
+  const int S = gd_pick_split(M, N, KT, A4);
+  if (S > 1 && !ws) return BL_EWORKSPACE;
+  const int L = (KT + S - 1) / S;                        // tiles of the longest slice
+  // output tiles per block: as few as still give at most one block per CU (one block takes most
+  // of a CU's LDS), at most one per wave
+  int NWT = 1;
+  while (NWT < GR_WAVES && ((NT16 + NWT - 1) / NWT) * S > gd_num_cus()) ++NWT;
+  const int NBn = (NT16 + NWT - 1) / NWT;
+  const int KS = max(1, min(GR_WAVES / NWT, KT / S));    // (every part gets at least one tile)
+  size_t smem = (size_t)MT * 16 * ((size_t)L * (A4 ? 128 : 256) + 16);
+  if (KS > 1) smem = max(smem, (size_t)GR_WAVES * MT * 64 * sizeof(v4i));
+  auto kern = gemm_decode_resident_kernel<MT, A4>;
+  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
     return BL_EHIP;
   const int ybf = ydt == BL_BF16 ? 1 : 0;
-  kern<<<(unsigned)(NB * S), GD_THREADS, smem, s>>>((const unsigned char*)q, scale, M, Kp,
-                                                    (const unsigned char*)Wp, alpha, N, Y, ybf,
-                                                    acc_out, (int32_t*)ws, NB, S);
+  kern<<<(unsigned)(NBn * S), GR_THREADS, smem, s>>>((const unsigned char*)q, scale, M, Kp,
+                                                     (const unsigned char*)Wp, alpha, N, Y, ybf,
+                                                     acc_out, (int32_t*)ws, NBn, S, NWT, KS);
   BL_HIP_CHECK_LAUNCH();
-  if (S > 1) {
-    const int64_t n_thr = (int64_t)M * ((N + 3) >> 2);
-    decode_reduce_kernel<<<(unsigned)((n_thr + GD_THREADS - 1) / GD_THREADS), GD_THREADS, 0, s>>>(
-        (const int32_t*)ws, S, M, N, A4 ? 10 : 6, scale, alpha, Y, ybf, acc_out);
-    BL_HIP_CHECK_LAUNCH();
-  }
-  return BL_OK;
+  return S > 1 ? gd_reduce(S, M, N, A4 ? 10 : 6, scale, alpha, Y, ybf, acc_out, ws, s) : BL_OK;
 }
 
 int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, int64_t M,
@@ -253,17 +572,12 @@ int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, i
                           bl_dtype ydt, int32_t* acc_out, void* ws, hipStream_t s) {
   const int Kp = (int)bl_round_up(K, BL_KPAD);
   const bool a4 = mode == BL_ACT_INT4_ABSMEAN;
-  const int MT = (int)((M + 15) / 16);
-#define GD_CASE(mt)                                                                                 \
-  return a4 ? gd_run<mt, true, 4>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)  \
-            : gd_run<mt, false, 4>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)
-  if (gd_single_tile((int)M, (int)N))
-    return a4 ? gd_run<1, true, 1>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s)
-              : gd_run<1, false, 1>(q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s);
-  if (MT <= 1) { GD_CASE(1); }
-  if (MT == 2) { GD_CASE(2); }
-  GD_CASE(4);
-#undef GD_CASE
+#define GD_ARGS q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s
+  if (gd_single_tile((int)M, (int)N)) return a4 ? gd_run<1, true, true>(GD_ARGS) : gd_run<1, false, true>(GD_ARGS);
+  if (M <= 16) return a4 ? gd_run<1, true, false>(GD_ARGS) : gd_run<1, false, false>(GD_ARGS);
+  if (M <= 32) return a4 ? gr_run<2, true>(GD_ARGS) : gr_run<2, false>(GD_ARGS);
+  return a4 ? gr_run<4, true>(GD_ARGS) : gr_run<4, false>(GD_ARGS);
+#undef GD_ARGS
 }
 
 // ---------------------------------------------------------------- sparse row-skipping GEMV
