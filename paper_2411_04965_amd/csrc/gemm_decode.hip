@@ -309,10 +309,13 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_rows_kernel(
 // of weights per 1024 channels but 32 to 64 KB of codes), and split-K partial sums cost as much
 // again.  So the codes stay put: one block of 16 waves per CU keeps the codes of all tokens for its
 // slice of K in LDS (up to 128 KB: all of K for INT4 codes at 4096 channels) and streams the weight
-// tiles of its share of the outputs past them.  Wave u works on output tile u / KS of the block and
-// on part u % KS of the slice; the parts are added through LDS (in the space of the codes) at the end.
+// tiles of its NWT output tiles past them.  The output tiles go in groups of up to GR_G to the
+// waves, so that one expansion of a token fragment (nibbles to bytes) serves GR_G matrix
+// instructions; wave u works on group u / KS and on part u % KS of the slice.  The parts are added
+// in LDS (integer adds, in the space of the codes), from where whole row segments are stored.
 #define GR_THREADS 1024
 #define GR_WAVES 16
+#define GR_G 3
 #define GR_X_BYTES 131072                        // LDS for the codes (pitch = row bytes + 16)
 template <int MT, bool A4>
 __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
@@ -333,16 +336,22 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
   const int RB = L * TB, pitch = RB + 16, ppr = RB >> 4;
 
   // this wave's part of the work, and its first weight tiles (issued before the codes are staged)
-  const int nt = nbk * NWT + wave / KS, ks = wave % KS;
-  const bool works = wave < NWT * KS && nt < NT16;
+  const int NG = (NWT + GR_G - 1) / GR_G;
+  const int grp = wave / KS, ks = wave % KS;
+  const int g0 = grp * GR_G;                     // first output tile of the group, within the block
+  const int nt0 = nbk * NWT + g0;
+  const int ng = grp < NG ? max(0, min(min(GR_G, NWT - g0), NT16 - nt0)) : 0;
   const int my_begin = t_begin + (int)((int64_t)ks * L / KS), my_end = t_begin + (int)((int64_t)(ks + 1) * L / KS);
-  const unsigned char* w_src = Wp + (size_t)min(nt, NT16 - 1) * KT * 1024 + lane * 16;
-  constexpr int WD = 8;
-  uint4 wq[WD];
-  if (works && my_begin < my_end) {
+  const unsigned char* w_src[GR_G];
 #pragma unroll
-    for (int j = 0; j < WD; ++j)
-      wq[j] = *reinterpret_cast<const uint4*>(w_src + (size_t)min(my_begin + j, my_end - 1) * 1024);
+  for (int g = 0; g < GR_G; ++g) w_src[g] = Wp + (size_t)min(nt0 + g, NT16 - 1) * KT * 1024 + lane * 16;
+  uint4 wq[2][GR_G];
+  if (ng > 0 && my_begin < my_end) {
+#pragma unroll
+    for (int d = 0; d < 2; ++d)
+#pragma unroll
+      for (int g = 0; g < GR_G; ++g)
+        wq[d][g] = *reinterpret_cast<const uint4*>(w_src[g] + (size_t)min(my_begin + d, my_end - 1) * 1024);
   }
 
   // codes of all tokens for tiles t_begin .. t_end: wave w stages rows w, w + 16, ...
@@ -368,36 +377,51 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
   }
   __syncthreads();
 
-  v4i acc[MT];
+  v4i acc[GR_G][MT];
 #pragma unroll
-  for (int b = 0; b < MT; ++b) acc[b] = (v4i){0, 0, 0, 0};
-  if (works) {
+  for (int g = 0; g < GR_G; ++g)
+#pragma unroll
+    for (int b = 0; b < MT; ++b) acc[g][b] = (v4i){0, 0, 0, 0};
+  if (ng > 0) {
     const unsigned char* xrow = gr_smem + li * pitch + lg * (A4 ? 32 : 64);
-    for (int t0 = my_begin; t0 < my_end; t0 += WD) {
+    for (int t0 = my_begin; t0 < my_end; t0 += 2) {
 #pragma unroll
-      for (int j = 0; j < WD; ++j) {
-        const int t = t0 + j;
+      for (int d = 0; d < 2; ++d) {
+        const int t = t0 + d;
         if (t < my_end) {                        // wave-uniform
-          const uint4 wc = wq[j];
-          if (t + WD < my_end) wq[j] = *reinterpret_cast<const uint4*>(w_src + (size_t)(t + WD) * 1024);
+          uint4 wc[GR_G];
+#pragma unroll
+          for (int g = 0; g < GR_G; ++g) wc[g] = wq[d][g];
+          if (t + 2 < my_end) {
+#pragma unroll
+            for (int g = 0; g < GR_G; ++g)
+              wq[d][g] = *reinterpret_cast<const uint4*>(w_src[g] + (size_t)(t + 2) * 1024);
+          }
           const unsigned char* xb = xrow + (t - t_begin) * TB;
 #pragma unroll
           for (int t4 = 0; t4 < 4; ++t4) {
-            const u32 w = t4 == 0 ? wc.x : t4 == 1 ? wc.y : t4 == 2 ? wc.z : wc.w;
-            const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
-                                 (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+            v4i xo[MT];
 #pragma unroll
             for (int b = 0; b < MT; ++b) {
-              v4i xo;
               if (A4) {
                 // a lane's 64 channels = 8 words; MFMA step t4 takes words 2*t4 and 2*t4+1
                 const uint2 v = *reinterpret_cast<const uint2*>(xb + b * 16 * pitch + t4 * 8);
-                xo = (v4i){(int)((v.x << 4) & 0xF0F0F0F0u), (int)(v.x & 0xF0F0F0F0u),
-                           (int)((v.y << 4) & 0xF0F0F0F0u), (int)(v.y & 0xF0F0F0F0u)};
+                xo[b] = (v4i){(int)((v.x << 4) & 0xF0F0F0F0u), (int)(v.x & 0xF0F0F0F0u),
+                              (int)((v.y << 4) & 0xF0F0F0F0u), (int)(v.y & 0xF0F0F0F0u)};
               } else {
-                xo = *reinterpret_cast<const v4i*>(xb + b * 16 * pitch + t4 * 16);
+                xo[b] = *reinterpret_cast<const v4i*>(xb + b * 16 * pitch + t4 * 16);
               }
-              acc[b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo, acc[b], 0, 0, 0);
+            }
+#pragma unroll
+            for (int g = 0; g < GR_G; ++g) {
+              if (g < ng) {                      // wave-uniform
+                const u32 w = t4 == 0 ? wc[g].x : t4 == 1 ? wc[g].y : t4 == 2 ? wc[g].z : wc[g].w;
+                const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
+                                     (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+#pragma unroll
+                for (int b = 0; b < MT; ++b)
+                  acc[g][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo[b], acc[g][b], 0, 0, 0);
+              }
             }
           }
         }
@@ -405,39 +429,56 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
     }
   }
 
-  // add the KS parts of every output tile: all waves leave their sums where the codes were
-  if (KS > 1) {
-    __syncthreads();
-    v4i* red = reinterpret_cast<v4i*>(gr_smem);  // [wave][b][lane]
+  // Sums of the block, where the codes were.  Parts 1 .. KS-1 of every group leave their
+  // accumulators in fragment order (one KB per tile, lane-contiguous); part 0 adds them to its own
+  // and writes the totals as int32 [MT * 16 tokens][NWT * 16 outputs (+ 4)] behind them.
+  const int OP = NWT * 16 + 4;                   // row pitch in words
+  v4i* parts = reinterpret_cast<v4i*>(gr_smem);  // [working wave][g][b][lane]
+  int32_t* sums = reinterpret_cast<int32_t*>(gr_smem) + (size_t)NG * KS * GR_G * MT * 256;
+  __syncthreads();
+  if (ks != 0 && ng > 0) {
 #pragma unroll
-    for (int b = 0; b < MT; ++b) red[(wave * MT + b) * 64 + lane] = acc[b];
-    __syncthreads();
-    if (ks == 0) {
-      for (int k = 1; k < KS; ++k)
+    for (int g = 0; g < GR_G; ++g)
 #pragma unroll
-        for (int b = 0; b < MT; ++b) acc[b] += red[((wave + k) * MT + b) * 64 + lane];
-    }
+      for (int b = 0; b < MT; ++b) parts[((wave * GR_G + g) * MT + b) * 64 + lane] = acc[g][b];
   }
-  if (!works || ks != 0) return;
+  __syncthreads();
+  if (ks == 0 && ng > 0) {
+    for (int k = 1; k < KS; ++k)
+#pragma unroll
+      for (int g = 0; g < GR_G; ++g)
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[g][b] += parts[(((wave + k) * GR_G + g) * MT + b) * 64 + lane];
+#pragma unroll
+    for (int g = 0; g < GR_G; ++g)
+      if (g < ng)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+          *reinterpret_cast<v4i*>(sums + (b * 16 + li) * OP + (g0 + g) * 16 + 4 * lg) = acc[g][b];
+  }
+  __syncthreads();
+
+  // one thread per token and 4 consecutive outputs of the block's NWT * 16
   const float alpha = alpha_p[0];
   constexpr int SHIFT = A4 ? 10 : 6;
-#pragma unroll
-  for (int b = 0; b < MT; ++b) {
-    const int m = b * 16 + li;
-    const int n = nt * 16 + 4 * lg;
-    if (m >= M || n >= N) continue;
+  const int qpr = NWT * 4;                       // groups of 4 outputs per row
+  for (int i = tid; i < M * qpr; i += GR_THREADS) {
+    const int m = i / qpr, c = (i % qpr) * 4;
+    const int n = nbk * NWT * 16 + c;
+    if (n >= N) continue;
+    const v4i v = *reinterpret_cast<const v4i*>(sums + m * OP + c);
     const size_t o = (size_t)m * N + n;
     if (S == 1) {
-      const int iv[4] = {acc[b][0] >> SHIFT, acc[b][1] >> SHIFT, acc[b][2] >> SHIFT, acc[b][3] >> SHIFT};
+      const int iv[4] = {v[0] >> SHIFT, v[1] >> SHIFT, v[2] >> SHIFT, v[3] >> SHIFT};
       gd_store4(Y, y_bf16, acc_out, o, n, N, iv, scale[m], alpha);
     } else {
       int32_t* p = partial + (size_t)split * M * N + o;
       if ((N & 3) == 0) {
-        *reinterpret_cast<int4*>(p) = make_int4(acc[b][0], acc[b][1], acc[b][2], acc[b][3]);
+        *reinterpret_cast<v4i*>(p) = v;
       } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          if (n + r < N) p[r] = acc[b][r];
+          if (n + r < N) p[r] = v[r];
       }
     }
   }
@@ -553,9 +594,12 @@ static int gr_run(const void* q, const float* scale, int M, int Kp, const void* 
   int NWT = 1;
   while (NWT < GR_WAVES && ((NT16 + NWT - 1) / NWT) * S > gd_num_cus()) ++NWT;
   const int NBn = (NT16 + NWT - 1) / NWT;
-  const int KS = max(1, min(GR_WAVES / NWT, KT / S));    // (every part gets at least one tile)
-  size_t smem = (size_t)MT * 16 * ((size_t)L * (A4 ? 128 : 256) + 16);
-  if (KS > 1) smem = max(smem, (size_t)GR_WAVES * MT * 64 * sizeof(v4i));
+  const int NG = (NWT + GR_G - 1) / GR_G;                // groups of output tiles, one per wave
+  // parts of the slice per group: every part gets at least one tile; at most 8 working waves (two
+  // per SIMD keep the matrix unit busy, and their sums must fit beside each other in LDS)
+  const int KS = max(1, min(max(1, 8 / NG), KT / S));
+  const size_t smem = max((size_t)MT * 16 * ((size_t)L * (A4 ? 128 : 256) + 16),
+                          (size_t)NG * KS * GR_G * MT * 1024 + (size_t)MT * 16 * (NWT * 16 + 4) * sizeof(int32_t));
   auto kern = gemm_decode_resident_kernel<MT, A4>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
     return BL_EHIP;
