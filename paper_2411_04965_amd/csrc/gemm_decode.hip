@@ -176,6 +176,162 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
   }
 }
 
+// Up to 4 tokens, INT4 activations: eq. 7 inside the same launch.  Every block quantizes the
+// tokens itself (their rows are a few KB and come out of the cache; the statistics and the codes
+// take a few hundred instructions per thread), which saves the quantizer's launch: at these sizes a
+// launch costs as much as streaming the weights.  The arithmetic is that of the stand-alone
+// quantizer (float64 sum of |x|, one rounding to float32, one float32 multiply per element), so
+// the codes are the same bit for bit.  Codes are kept as int8 in LDS, one row per token.
+#define GF_NV 4                                  // 16-byte pieces of a row per thread: K <= 8192
+__device__ __forceinline__ double gf_wave_sum_f64(double v) {
+  // sum over the 64 lanes: 16-lane rows with DPP (two 32-bit moves per step), rows with readlane
+  auto step = [&](auto ctrl) {
+    constexpr int C = decltype(ctrl)::value;
+    const u32 lo = (u32)__double_as_longlong(v), hi = (u32)(__double_as_longlong(v) >> 32);
+    const u32 plo = (u32)__builtin_amdgcn_update_dpp(0, (int)lo, C, 0xF, 0xF, false);
+    const u32 phi = (u32)__builtin_amdgcn_update_dpp(0, (int)hi, C, 0xF, 0xF, false);
+    v += __longlong_as_double((long long)(((unsigned long long)phi << 32) | plo));
+  };
+  step(std::integral_constant<int, 0x121>{});    // row_ror:1
+  step(std::integral_constant<int, 0x122>{});    // row_ror:2
+  step(std::integral_constant<int, 0x124>{});    // row_ror:4
+  step(std::integral_constant<int, 0x128>{});    // row_ror:8
+  const u32 lo = (u32)__double_as_longlong(v), hi = (u32)(__double_as_longlong(v) >> 32);
+  double t = 0.0;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const u32 a = (u32)__builtin_amdgcn_readlane((int)lo, 16 * r), b = (u32)__builtin_amdgcn_readlane((int)hi, 16 * r);
+    t += __longlong_as_double((long long)(((unsigned long long)b << 32) | a));
+  }
+  return t;
+}
+
+__global__ __launch_bounds__(GD_THREADS) void gemv_a4_fused_kernel(
+    const uint16_t* __restrict__ X, int M, int K, int Kp, float eps,
+    const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
+    void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out) {
+  extern __shared__ __align__(16) unsigned char gf_smem[];
+  unsigned char* codes = gf_smem;                                  // [M][Kp] int8
+  __shared__ double red[4][GD_THREADS / 64];
+  __shared__ __align__(16) v4i wsum[GD_THREADS / 64][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lg = lane >> 4;
+  const int KT = Kp >> 8;
+  const int nt = blockIdx.x;                     // grid = tiles of 16 outputs
+  const unsigned char* w_src = Wp + (size_t)nt * KT * 1024 + lane * 16;
+
+  // weights first: tiles wave, wave + 4, ... in groups of 4 (the next group is fetched while one
+  // is multiplied)
+  constexpr int UNR = 4;
+  uint4 wr[UNR];
+  auto load_group = [&](int t) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      wr[u] = *reinterpret_cast<const uint4*>(w_src + (size_t)min(t + 4 * u, KT - 1) * 1024);
+  };
+  int t = wave;
+  if (t < KT) load_group(t);
+
+  // the rows, 8 channels per piece, pieces tid, tid + 256, ... of every token (zero beyond K; K % 8
+  // == 0 by dispatch), all loads in flight together; beta = mean |x| per token from the registers
+  uint4 xr[4][GF_NV];
+  const int nv = K >> 3;
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int j = 0; j < GF_NV; ++j) {
+      xr[m][j] = make_uint4(0u, 0u, 0u, 0u);
+      const int pc = tid + GD_THREADS * j;
+      if (m < M && pc < nv) xr[m][j] = reinterpret_cast<const uint4*>(X + (size_t)m * K)[pc];
+    }
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    if (m < M) {                                 // block-uniform
+      double a = 0.0;
+#pragma unroll
+      for (int j = 0; j < GF_NV; ++j) {
+        const u32 w4[4] = {xr[m][j].x, xr[m][j].y, xr[m][j].z, xr[m][j].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a += (double)fabsf(__uint_as_float(w4[e] << 16));
+          a += (double)fabsf(__uint_as_float(w4[e] & 0xFFFF0000u));
+        }
+      }
+      a = gf_wave_sum_f64(a);
+      if (lane == 0) red[m][wave] = a;
+    }
+  }
+  __syncthreads();
+  const float sqrt7 = 2.6457512f;                // float32(sqrt(7))
+  float dq[4];
+  // codes: RoundClip(x * s, -8, 7), eight to a piece
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    double tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < GD_THREADS / 64; ++w) tot += red[m < M ? m : 0][w];
+    const float beta = (float)(tot / (double)K);
+    const float s = sqrt7 / (beta + eps);
+    dq[m] = beta / sqrt7;
+    if (m < M) {
+#pragma unroll
+      for (int j = 0; j < GF_NV; ++j) {
+        const int pc = tid + GD_THREADS * j;
+        if (pc < (Kp >> 3)) {
+          const u32 w4[4] = {xr[m][j].x, xr[m][j].y, xr[m][j].z, xr[m][j].w};
+          u32 cw[2] = {0u, 0u};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float p0 = fminf(fmaxf(rintf(__uint_as_float(w4[e] << 16) * s), -8.0f), 7.0f);
+            const float p1 = fminf(fmaxf(rintf(__uint_as_float(w4[e] & 0xFFFF0000u) * s), -8.0f), 7.0f);
+            cw[e >> 1] |= (((u32)(int)p0 & 0xFFu) | (((u32)(int)p1 & 0xFFu) << 8)) << (16 * (e & 1));
+          }
+          *reinterpret_cast<uint2*>(codes + (size_t)m * Kp + pc * 8) = make_uint2(cw[0], cw[1]);
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // lane (li, lg) holds, for token li, the 64 channels lg * 64 .. of a tile, 16 per MFMA step
+  v4i acc = (v4i){0, 0, 0, 0};
+  const unsigned char* xrow = codes + (size_t)min(li, M - 1) * Kp + lg * 64;
+  while (t < KT) {
+    uint4 wc[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) wc[u] = wr[u];
+    const int tn = t + 4 * UNR;
+    if (tn < KT) load_group(tn);
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int tt = t + 4 * u;
+      if (tt < KT) {                             // wave-uniform
+#pragma unroll
+        for (int t4 = 0; t4 < 4; ++t4) {
+          v4i xo = (v4i){0, 0, 0, 0};
+          if (li < M) xo = *reinterpret_cast<const v4i*>(xrow + (size_t)tt * 256 + t4 * 16);
+          const u32 w = t4 == 0 ? wc[u].x : t4 == 1 ? wc[u].y : t4 == 2 ? wc[u].z : wc[u].w;
+          const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
+                               (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+          acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo, acc, 0, 0, 0);
+        }
+      }
+    }
+    t = tn;
+  }
+
+  // add the four waves' sums; wave 0 rescales and stores
+  wsum[wave][lane] = acc;
+  __syncthreads();
+  if (wave != 0) return;
+  v4i sum = wsum[0][lane] + wsum[1][lane] + wsum[2][lane] + wsum[3][lane];
+  const int m = li, n = nt * 16 + 4 * lg;
+  if (m >= M || n >= N) return;
+  const int iv[4] = {sum[0] >> 6, sum[1] >> 6, sum[2] >> 6, sum[3] >> 6};
+  const float d = m == 0 ? dq[0] : m == 1 ? dq[1] : m == 2 ? dq[2] : dq[3];
+  gd_store4(Y, y_bf16, acc_out, (size_t)m * N + n, n, N, iv, d, alpha_p[0]);
+}
+
 // More than one MFMA tile of tokens, or too few output tiles for the kernel above: block = 4 waves
 // = 64 outputs, every wave owns one tile of 16 outputs and walks the block's whole K range (a
 // slice of K when the grid would otherwise be small), so there is no reduction inside the block.
@@ -609,6 +765,26 @@ static int gr_run(const void* q, const float* scale, int M, int Kp, const void* 
                                                      acc_out, (int32_t*)ws, NBn, S, NWT, KS);
   BL_HIP_CHECK_LAUNCH();
   return S > 1 ? gd_reduce(S, M, N, A4 ? 10 : 6, scale, alpha, Y, ybf, acc_out, ws, s) : BL_OK;
+}
+
+// The fused INT4 linear is used for bfloat16 rows of up to 4 tokens when the one-tile-per-block
+// kernel would be (enough output tiles) and the rows are 16-byte aligned and at most 8192 channels long.
+bool bl_gemv_a4_fused_ok(int64_t M, int64_t N, int64_t K) {
+  const int64_t Kp = bl_round_up(K, BL_KPAD);
+  return M <= 4 && gd_single_tile((int)M, (int)N) && K % 8 == 0 && Kp <= 8 * GD_THREADS * GF_NV;
+}
+
+int bl_launch_gemv_a4_fused(const void* X, int64_t M, int64_t K, float eps, const void* Wp,
+                            const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,
+                            hipStream_t s) {
+  if (!bl_gemv_a4_fused_ok(M, N, K)) return BL_EUNSUPPORTED;
+  const int Kp = (int)bl_round_up(K, BL_KPAD);
+  const size_t smem = (size_t)M * Kp;            // <= 32 KB
+  gemv_a4_fused_kernel<<<(unsigned)((N + 15) / 16), GD_THREADS, smem, s>>>(
+      (const uint16_t*)X, (int)M, (int)K, Kp, eps, (const unsigned char*)Wp, alpha, (int)N, Y,
+      ydt == BL_BF16 ? 1 : 0, acc_out);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
 }
 
 int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, int64_t M,

@@ -254,6 +254,19 @@ def test_decode_odd_shapes(M):
         _check_linear(B.bitlinear_a8_sparse(dev(X, BF16), 700, pk, ak, N, EPS, B.BL_W_KMAJOR, F32, True), ref, F32)
 
 
+@pytest.mark.parametrize("M,N,K", [(2, 2064, 1500), (3, 4096, 2056), (4, 2050, 4096), (1, 2048, 256)])
+def test_decode_fused_int4(M, N, K):
+    """Up to 4 tokens with at least 128 output tiles: eq. 7 runs inside the GEMV launch.  Rows that
+    are 8- and 16-byte aligned, K with and without a ragged last tile, N ragged."""
+    say("decode fused int4 M=%d N=%d K=%d" % (M, N, K))
+    X = S.heavy(M, K, S.seed_for(2, 500 + M))
+    W = S.latent_weights(N, K, S.seed_for(2, 501 + N))
+    p, a = pack(W)
+    for dt, name in ((F32, "f32"), (BF16, "bf16")):
+        _check_linear(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=dt, want_acc=True),
+                      O.bitlinear_a4(X, W, EPS, name), dt)
+
+
 # ------------------------------------------------------------------ full prefill size (config 3), sampled rows
 @pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (300, 520, 1000, BF16), (130, 2048, 5460, BF16),
                                          (257, 5460, 2048, BF16), (1100, 1100, 768, BF16),
