@@ -30,10 +30,11 @@ EPS = 1e-5
 INT8_PEAK_TOPS = 5033.0      # MI355X dense int8 MFMA
 FP6_FP4_PEAK_TOPS = 10066.0  # MI355X dense fp6 / fp4 MFMA (the INT4 GEMM runs on E3M2 x E2M1 operands)
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the W1.58A4 prefill GEMM at the benchmark shapes, from the rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/gemm_prefill_7b_hbm_traffic.txt
-# (calibrated against a 1 GiB device copy): 386.5 MB fetched + 374.7 MB written.
-A4_GEMM_TRAFFIC_BYTES = 1052.4e6
+# Bytes between L2 and the memory fabric per launch of the W1.58A4 prefill GEMM at the benchmark
+# shapes, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/gemm_7b_prefill_hbm_traffic.txt (calibrated against a 1 GiB device copy):
+# 677.6 MB fetched + 374.7 MB written.
+A4_GEMM_TRAFFIC_BYTES = 1052.3e6
 HIDDEN, FFN = 4096, 11008
 
 
