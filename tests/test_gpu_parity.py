@@ -100,6 +100,23 @@ def test_quantize_topk_int8(kind, M, K, topk, dtype):
     assert np.array_equal(host(r["rowsum"]), q_ref.sum(1, dtype=np.int32))
 
 
+@pytest.mark.parametrize("kind,M,K,topk", [
+    ("ties", 2051, 1000, 500), ("heavy", 2051, 4096, 2048), ("glu", 2050, 5460, 2730), ("ties", 2049, 5460, 1),
+    ("heavy", 2051, 8640, 4320), ("glu", 2051, 11008, 5504), ("ties", 2048, 12288, 12288), ("ties", 2051, 11008, 5504),
+    ("heavy", 2049, 8000, 4000)])
+def test_quantize_topk_int8_many_tokens(kind, M, K, topk):
+    """From 2048 tokens on the selection runs with one or two waves per token (no index lists asked for):
+    every register-block count, a last workgroup that is not full, heavy ties, topk = 1 and = K."""
+    say("quantize_act TOPK many tokens %s M=%d K=%d topk=%d" % (kind, M, K, topk))
+    x = _x(kind, M, K, S.seed_for(0, 13 * M + K + topk), BF16)
+    rows = np.unique(np.concatenate([np.arange(0, M, 9), [1, 2, M - 3, M - 2, M - 1]]))
+    q_ref, d_ref, _ = O.quant_topk_int8(x[rows], topk, EPS)
+    r = B.quantize_act(dev(x, BF16), B.BL_ACT_TOPK_INT8_ABSMAX, topk, EPS, want_rowsum=True)
+    assert np.array_equal(host(r["scale"])[rows], d_ref)
+    assert np.array_equal(decode_int8(host(r["q"]), M, K)[rows], q_ref)
+    assert np.array_equal(host(r["rowsum"])[rows], q_ref.sum(1, dtype=np.int32))
+
+
 @pytest.mark.parametrize("kind,M,K,dtype", [("gauss", 16, 256, F32), ("heavy", 20, 3200, BF16),
                                             ("glu", 6, 8640, BF16), ("ties", 9, 992, F32)])
 def test_quantize_fp4(kind, M, K, dtype):
