@@ -187,10 +187,15 @@ static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, 
   if ((mode == BL_ACT_INT4_ABSMEAN_MX6) != (layout == BL_W_MX4)) return BL_EINVAL;
   if (layout == BL_W_KMAJOR && (mode != BL_ACT_TOPK_INT8_ABSMAX || M > 8)) return BL_EUNSUPPORTED;
 
-  // a few tokens, INT4: quantizer and product in one launch
+  // a few tokens: quantizer and product in one launch
   if (mode == BL_ACT_INT4_ABSMEAN && layout == BL_W_GEMM && x_dtype == BL_BF16 &&
       bl_gemv_a4_fused_ok(M, N, K))
     return bl_launch_gemv_a4_fused(X, M, K, eps, W_packed, alpha, N, Y, y_dtype, acc_out,
+                                   (hipStream_t)stream);
+
+  if (mode == BL_ACT_TOPK_INT8_ABSMAX && layout == BL_W_GEMM && x_dtype == BL_BF16 &&
+      bl_gemv_a8_fused_ok(M, N, K))
+    return bl_launch_gemv_a8_fused(X, K, topk, eps, W_packed, alpha, N, Y, y_dtype, acc_out,
                                    (hipStream_t)stream);
 
   unsigned char* p = (unsigned char*)workspace;

@@ -4,6 +4,7 @@
 //                                    channels whose INT8 code is non-zero in some token are read.
 // Integer partial sums are exact, so any split of K gives the same accumulators.
 #include "common.h"
+#include "topk_regs.h"
 
 #define GD_THREADS 256
 #define GD_BN 64           // outputs per block (4 MFMA tiles of 16)
@@ -330,6 +331,70 @@ __global__ __launch_bounds__(GD_THREADS) void gemv_a4_fused_kernel(
   const int iv[4] = {sum[0] >> 6, sum[1] >> 6, sum[2] >> 6, sum[3] >> 6};
   const float d = m == 0 ? dq[0] : m == 1 ? dq[1] : m == 2 ? dq[2] : dq[3];
   gd_store4(Y, y_bf16, acc_out, (size_t)m * N + n, n, N, iv, d, alpha_p[0]);
+}
+
+// One token, top-K + INT8 activations: eq. 1 and eq. 3 inside the same launch, for the same reason.
+// Every block selects and quantizes the token itself with the four-wave register kernel's body
+// (topk_regs.h) while its first weight tiles are on their way, and leaves the int8 codes in LDS.
+template <int CPW>
+__global__ __launch_bounds__(GD_THREADS) void gemv_a8_fused_kernel(
+    const uint16_t* __restrict__ X, int K, int Kp, int topk, float eps,
+    const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
+    void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out) {
+  extern __shared__ __align__(16) unsigned char gf_smem[];         // [Kp] int8
+  __shared__ float dq;
+  __shared__ __align__(16) v4i wsum[GD_THREADS / 64][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lg = lane >> 4;
+  const int KT = Kp >> 8;
+  const int nt = blockIdx.x;                     // grid = tiles of 16 outputs
+  const unsigned char* w_src = Wp + (size_t)nt * KT * 1024 + lane * 16;
+  constexpr int UNR = 4;
+  uint4 wr[UNR];
+  auto load_group = [&](int t) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      wr[u] = *reinterpret_cast<const uint4*>(w_src + (size_t)min(t + 4 * u, KT - 1) * 1024);
+  };
+  int t = wave;
+  if (t < KT) load_group(t);
+
+  qa_topk_row_regs<CPW>(X, K, Kp, topk, eps, reinterpret_cast<u32*>(gf_smem), &dq, nullptr);
+  __syncthreads();
+
+  v4i acc = (v4i){0, 0, 0, 0};
+  const unsigned char* xrow = gf_smem + lg * 64;
+  while (t < KT) {
+    uint4 wc[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) wc[u] = wr[u];
+    const int tn = t + 4 * UNR;
+    if (tn < KT) load_group(tn);
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int tt = t + 4 * u;
+      if (tt < KT) {                             // wave-uniform
+#pragma unroll
+        for (int t4 = 0; t4 < 4; ++t4) {
+          v4i xo = (v4i){0, 0, 0, 0};
+          if (li == 0) xo = *reinterpret_cast<const v4i*>(xrow + (size_t)tt * 256 + t4 * 16);
+          const u32 w = t4 == 0 ? wc[u].x : t4 == 1 ? wc[u].y : t4 == 2 ? wc[u].z : wc[u].w;
+          const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
+                               (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+          acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo, acc, 0, 0, 0);
+        }
+      }
+    }
+    t = tn;
+  }
+  wsum[wave][lane] = acc;
+  __syncthreads();
+  if (wave != 0) return;
+  v4i sum = wsum[0][lane] + wsum[1][lane] + wsum[2][lane] + wsum[3][lane];
+  const int n = nt * 16 + 4 * lg;
+  if (li != 0 || n >= N) return;
+  const int iv[4] = {sum[0] >> 6, sum[1] >> 6, sum[2] >> 6, sum[3] >> 6};
+  gd_store4(Y, y_bf16, acc_out, (size_t)n, n, N, iv, dq, alpha_p[0]);
 }
 
 // More than one MFMA tile of tokens, or too few output tiles for the kernel above: block = 4 waves
@@ -783,6 +848,31 @@ int bl_launch_gemv_a4_fused(const void* X, int64_t M, int64_t K, float eps, cons
   gemv_a4_fused_kernel<<<(unsigned)((N + 15) / 16), GD_THREADS, smem, s>>>(
       (const uint16_t*)X, (int)M, (int)K, Kp, eps, (const unsigned char*)Wp, alpha, (int)N, Y,
       ydt == BL_BF16 ? 1 : 0, acc_out);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}
+
+// The fused top-K + INT8 linear: one bfloat16 token whose keys fit the register kernel, enough
+// output tiles for the one-tile-per-block kernel.
+bool bl_gemv_a8_fused_ok(int64_t M, int64_t N, int64_t K) {
+  return M == 1 && gd_single_tile(1, (int)N) && K % 4 == 0 && bl_round_up(K, BL_KPAD) <= 12288;
+}
+
+int bl_launch_gemv_a8_fused(const void* X, int64_t K, int64_t topk, float eps, const void* Wp,
+                            const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,
+                            hipStream_t s) {
+  if (!bl_gemv_a8_fused_ok(1, N, K)) return BL_EUNSUPPORTED;
+  const int Kp = (int)bl_round_up(K, BL_KPAD);
+  const int cpw = (Kp / 256 + 3) / 4;
+  const unsigned grid = (unsigned)((N + 15) / 16);
+  const int ybf = ydt == BL_BF16 ? 1 : 0;
+#define GF_A8(CPW)                                                                                     \
+  gemv_a8_fused_kernel<CPW><<<grid, GD_THREADS, (size_t)Kp, s>>>(                                      \
+      (const uint16_t*)X, (int)K, Kp, (int)topk, eps, (const unsigned char*)Wp, alpha, (int)N, Y, ybf, acc_out)
+  if (cpw <= 4) GF_A8(4);
+  else if (cpw <= 8) GF_A8(8);
+  else GF_A8(12);
+#undef GF_A8
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;
 }

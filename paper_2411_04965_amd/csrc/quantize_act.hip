@@ -4,6 +4,7 @@
 // One workgroup handles one token: the row is read from HBM once, kept in LDS, and every
 // later pass (statistics, selection, coding) runs out of LDS.
 #include "common.h"
+#include "topk_regs.h"
 
 #define QA_THREADS 256
 #define QA_WAVES (QA_THREADS / BL_WAVE)
@@ -316,232 +317,14 @@ __global__ __launch_bounds__(NT) void quant_topk_int8_kernel(
 }
 
 // ---------------------------------------------------------------- Top_k + INT8, keys in registers
-// Same selection as above for bfloat16 rows of up to 4 * CPW * 256 channels, with the token held
-// in registers instead of LDS and counted on the vector ALU instead of through ballots (the
-// scalar unit is shared by the four SIMDs of a compute unit and limits the ballot version).
-// A lane keeps its 4 * CPW channels as 2 * CPW words of two 15-bit keys, each with bit 15 set
-// as a guard: (word - cand * 0x10001) then has bit 15 / bit 31 set exactly where key >= cand,
-// with no borrow between the halves, and v_bcnt accumulates the two flags in one instruction:
-// 1.5 vector instructions per key and pass.  Lane counts are summed inside the wave with DPP
-// adds, across the 4 waves through LDS with one barrier per pass.
-__device__ __forceinline__ int qa_wave_sum_dpp(int v) {
-  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
-  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
-  v += __builtin_amdgcn_update_dpp(0, v, 0x124, 0xF, 0xF, false);   // row_ror:4
-  v += __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, false);   // row_ror:8
-  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
-         __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
-}
-
-#define QA_GUARD 0x80008000u
-
-// Bit planes.  The search for tau looks at one bit of every key per pass, so the keys of a lane are
-// turned into bit planes once: 16 keys (8 words of two 16-bit rows) -> 16 planes of 16 bits (word
-// p / 2, half p % 2 holds bit p of the 16 keys, key r in bit r).  The usual recursive block swap, on
-// packed halves: byte blocks with v_perm, 4-, 2- and 1-bit blocks with shift / xor / mask.
-__device__ __forceinline__ void qa_bit_transpose16(u32 (&w)[8]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const u32 a = w[i], b = w[i + 4];
-    w[i] = __builtin_amdgcn_perm(b, a, 0x06020400u);        // a.b0 b.b0 a.b2 b.b2
-    w[i + 4] = __builtin_amdgcn_perm(b, a, 0x07030501u);    // a.b1 b.b1 a.b3 b.b3
-  }
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int i = (k & 1) + 4 * (k >> 1);                   // 0, 1, 4, 5
-    const u32 t = ((w[i] >> 4) ^ w[i + 2]) & 0x0F0F0F0Fu;
-    w[i + 2] ^= t;
-    w[i] ^= t << 4;
-  }
-#pragma unroll
-  for (int i = 0; i < 8; i += 2) {
-    const u32 t = ((w[i] >> 2) ^ w[i + 1]) & 0x33333333u;
-    w[i + 1] ^= t;
-    w[i] ^= t << 2;
-  }
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const u32 t = ((w[i] >> 1) ^ (w[i] >> 16)) & 0x5555u;
-    w[i] ^= (t << 16) | (t << 1);
-  }
-}
-
+// (helpers and the four-wave body: topk_regs.h)
 template <int CPW>
 __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
     const uint16_t* __restrict__ X, int K, int Kp, int topk, float eps, u32* __restrict__ q_out,
     float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out) {
-  constexpr int NW = QA_WAVES;
-  static_assert(NW == 4, "one 16-byte LDS read fetches the four wave counts");
-  __shared__ __align__(16) u32 sh_a[2][NW];
-  __shared__ __align__(16) u32 sh_b[NW];
-  __shared__ __align__(16) u32 sh_c[NW];
   const int64_t m = blockIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n_chunks = Kp / 256;
-  const int per_wave = (n_chunks + NW - 1) / NW;          // <= CPW by dispatch
-  const int c_begin = min(wave * per_wave, n_chunks), c_end = min(c_begin + per_wave, n_chunks);
-  const int nc = c_end - c_begin;                         // chunks of this wave; the rest hold key 0
-
-  // one pass over the row: 4 consecutive channels (8 bytes) per lane and chunk, zero beyond K
-  u32 raw[CPW][2], pg[CPW][2];
-  const uint16_t* x = X + m * (int64_t)K;
-  u32 km2 = QA_GUARD;
-#pragma unroll
-  for (int i = 0; i < CPW; ++i) {
-    uint2 v = make_uint2(0u, 0u);
-    const int ch = (c_begin + i) * 256 + lane * 4;
-    if (i < nc && ch < K) v = *reinterpret_cast<const uint2*>(x + ch);   // K % 4 == 0 by dispatch
-    raw[i][0] = v.x; raw[i][1] = v.y;
-    pg[i][0] = v.x | QA_GUARD; pg[i][1] = v.y | QA_GUARD;
-  }
-  {
-    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-    us2 km = __builtin_bit_cast(us2, km2);
-#pragma unroll
-    for (int i = 0; i < CPW; ++i)
-#pragma unroll
-      for (int h = 0; h < 2; ++h) km = __builtin_elementwise_max(km, __builtin_bit_cast(us2, pg[i][h]));   // v_pk_max_u16
-    km2 = __builtin_bit_cast(u32, km);
-  }
-  u32 kmax = max(km2 & 0x7FFFu, (km2 >> 16) & 0x7FFFu);
-  kmax = bl_wave_max_u32(kmax);
-  if (lane == 0) sh_b[wave] = kmax;
-  __syncthreads();
-  {
-    const uint4 t = *reinterpret_cast<const uint4*>(sh_b);
-    kmax = (u32)__builtin_amdgcn_readfirstlane((int)max(max(t.x, t.y), max(t.z, t.w)));
-  }
-  const float gamma = __uint_as_float(kmax << 16);
-  const float s = 127.0f / (gamma + eps);
-  if (threadIdx.x == 0) scale_out[m] = gamma / 127.0f;
-
-  // tau = topk-th largest key, bit by bit from the top, on bit planes.  `act` marks the keys whose
-  // bits above the current one equal tau's; `above` counts the keys already known to be larger.
-  // A bit of tau is 1 iff at least topk keys are >= the candidate, i.e. above + #(active keys with
-  // the bit set) >= topk; then those keys stay active, otherwise they join `above`.  Cost per pass:
-  // a handful of instructions per lane instead of 1.5 per key.
-  constexpr int NBK = CPW / 4;                            // blocks of 16 keys per lane
-  static_assert(CPW % 4 == 0 && NBK >= 1 && NBK <= 3, "16 keys per block, at most 48 keys per lane");
-  u32 pl[NBK][8];
-#pragma unroll
-  for (int B = 0; B < NBK; ++B) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) pl[B][i] = raw[4 * B + (i >> 1)][i & 1] & 0x7FFF7FFFu;
-    qa_bit_transpose16(pl[B]);
-  }
-  // keys of chunks this wave does not have (key 0) stay out: they would count as equal to tau = 0
-  const unsigned long long real = nc >= 16 ? ~0ull : ((1ull << (4 * nc)) - 1ull);
-  u32 act_lo = (u32)real, act_hi = (u32)(real >> 32) & 0xFFFFu;
-  if (NBK == 1) act_lo &= 0xFFFFu;
-  u32 tau = 0;
-  int above = 0;
-  int pass = 0;
-  const int top_bit = 31 - __clz((int)(kmax | 1u));
-#pragma unroll
-  for (int bit = 14; bit >= 0; --bit) {
-    if (bit <= top_bit) {                                 // wave-uniform
-      u32 p_lo, p_hi = 0;
-      if (NBK == 1) p_lo = (bit & 1) ? pl[0][bit >> 1] >> 16 : pl[0][bit >> 1] & 0xFFFFu;
-      else p_lo = __builtin_amdgcn_perm(pl[1][bit >> 1], pl[0][bit >> 1], (bit & 1) ? 0x07060302u : 0x05040100u);
-      if (NBK == 3) p_hi = (bit & 1) ? pl[2][bit >> 1] >> 16 : pl[2][bit >> 1] & 0xFFFFu;
-      const u32 x_lo = act_lo & p_lo, x_hi = act_hi & p_hi;
-      const int cnt = qa_wave_sum_dpp(__popc(x_lo) + __popc(x_hi));
-      if (lane == 0) sh_a[pass & 1][wave] = (u32)cnt;
-      __syncthreads();                                    // one barrier per pass: slots alternate
-      const uint4 t = *reinterpret_cast<const uint4*>(sh_a[pass & 1]);
-      const int total = __builtin_amdgcn_readfirstlane((int)(t.x + t.y + t.z + t.w));
-      if (above + total >= topk) {
-        tau |= 1u << bit;
-        act_lo = x_lo;
-        act_hi = x_hi;
-      } else {
-        above += total;
-        act_lo ^= x_lo;
-        act_hi ^= x_hi;
-      }
-      ++pass;
-    }
-  }
-
-  // keys equal to tau per wave (the active ones); `above` is the number of keys larger than tau
-  {
-    const int eq = qa_wave_sum_dpp(__popc(act_lo) + __popc(act_hi));
-    __syncthreads();                                      // sh_b was read above by every thread
-    if (lane == 0) sh_c[wave] = (u32)eq;
-    __syncthreads();
-  }
-  const uint4 eqw4 = *reinterpret_cast<const uint4*>(sh_c);
-  const int r = topk - above;
-  const u32 eqs[4] = {eqw4.x, eqw4.y, eqw4.z, eqw4.w};
-  int eq_base = 0;                                        // keys equal to tau in earlier waves
-#pragma unroll
-  for (int w = 0; w < NW - 1; ++w)
-    if (w < wave) eq_base += (int)eqs[w];
-  eq_base = __builtin_amdgcn_readfirstlane(eq_base);
-  const int eq_here = __builtin_amdgcn_readfirstlane((int)sh_c[wave]);
-  // Of the keys equal to tau the first r in channel order are kept.  For a whole wave that is
-  // all of them, none of them, or (for one wave of the token) a prefix found with ballots.
-  const bool eq_all = eq_base + eq_here <= r;
-  const bool eq_none = eq_base >= r;
-  const u32 t1 = (tau + 1u) * 0x10001u, t0 = tau * 0x10001u;
-  const u32 tk = eq_all ? t0 : t1;
-  const uint64_t lt_mask = (1ull << lane) - 1ull;
-  int sum = 0;
-  u32* out = q_out + m * (int64_t)(Kp / 4);
-#pragma unroll
-  for (int i = 0; i < CPW; ++i) {
-    if (i < nc) {                                         // wave-uniform
-      const int c = c_begin + i;
-      // kept keys as guard-bit flags: key >= tau where the wave keeps all its keys equal to tau,
-      // key > tau where it keeps none of them
-      u32 k0 = (pg[i][0] - tk) & QA_GUARD, k1 = (pg[i][1] - tk) & QA_GUARD;
-      if (!eq_all && !eq_none) {                          // the wave that holds the r-th equal key
-        const u32 e0 = ((pg[i][0] - t0) & QA_GUARD) ^ k0, e1 = ((pg[i][1] - t0) & QA_GUARD) ^ k1;
-        const bool eqf[4] = {(e0 & 0x8000u) != 0, (e0 >> 31) != 0, (e1 & 0x8000u) != 0, (e1 >> 31) != 0};
-        uint64_t beq[4], any_eq = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { beq[j] = __ballot(eqf[j]); any_eq |= beq[j]; }
-        if (any_eq) {
-          int rank = eq_base, in_chunk = 0;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            rank += __popcll(beq[j] & lt_mask);
-            in_chunk += __popcll(beq[j]);
-          }
-          if (eqf[0]) { if (rank < r) k0 |= 0x8000u; ++rank; }
-          if (eqf[1]) { if (rank < r) k0 |= 0x80000000u; ++rank; }
-          if (eqf[2]) { if (rank < r) k1 |= 0x8000u; ++rank; }
-          if (eqf[3]) { if (rank < r) k1 |= 0x80000000u; ++rank; }
-          eq_base += in_chunk;
-        }
-      }
-      // codes: |x * s| <= 127 for every finite row, so RoundClip is the rounding alone, taken
-      // from the low byte of (x * s) + 1.5 * 2^23 (round to nearest even at integer spacing)
-      const float xs[4] = {__uint_as_float(raw[i][0] << 16), __uint_as_float(raw[i][0] & 0xFFFF0000u),
-                           __uint_as_float(raw[i][1] << 16), __uint_as_float(raw[i][1] & 0xFFFF0000u)};
-      u32 rb[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) rb[j] = __float_as_uint(xs[j] * s + 12582912.0f);
-      const u32 w01 = __builtin_amdgcn_perm(rb[1], rb[0], 0x0c0c0400u);   // bytes: rb0.b0, rb1.b0, 0, 0
-      const u32 w23 = __builtin_amdgcn_perm(rb[3], rb[2], 0x04000c0cu);   // bytes: 0, 0, rb2.b0, rb3.b0
-      // the four flags (bits 15 and 31 of k0, k1) as a byte mask: bytes 1 and 3 of each word hold
-      // 0x80 or 0; shifted down that is 1 or 0 per byte, times 255 it is the mask
-      const u32 keep4 = (__builtin_amdgcn_perm(k1, k0, 0x07050301u) >> 7) * 255u;
-      const u32 word = (w01 | w23) & keep4;
-      sum = __builtin_amdgcn_sdot4((int)word, 0x01010101, sum, false);
-      out[c * 64 + lane] = word;
-    }
-  }
-  if (rowsum_out) {
-    sum = qa_wave_sum_dpp(sum);
-    __syncthreads();
-    if (lane == 0) sh_a[0][wave] = (u32)sum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      const uint4 t = *reinterpret_cast<const uint4*>(sh_a[0]);
-      rowsum_out[m] = (int32_t)(t.x + t.y + t.z + t.w);
-    }
-  }
+  qa_topk_row_regs<CPW>(X + m * (int64_t)K, K, Kp, topk, eps, q_out + m * (int64_t)(Kp / 4), scale_out + m,
+                        rowsum_out ? rowsum_out + m : nullptr);
 }
 
 // The same selection with one wave per token, for many tokens of moderate width: the fixed cost of a

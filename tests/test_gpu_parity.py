@@ -284,6 +284,21 @@ def test_decode_fused_int4(M, N, K):
                       O.bitlinear_a4(X, W, EPS, name), dt)
 
 
+@pytest.mark.parametrize("kind,N,K,topk", [("heavy", 2050, 1500, 700), ("glu", 2048, 5460, 2730),
+                                           ("glu", 4096, 8640, 4320), ("ties", 2064, 1000, 500),
+                                           ("ties", 2048, 4096, 1)])
+def test_decode_fused_topk_int8(kind, N, K, topk):
+    """One token with at least 128 output tiles: eq. 1 + eq. 3 run inside the GEMV launch, for every
+    register-block count of the selection, ragged K and N, ties at the threshold."""
+    say("decode fused topk %s N=%d K=%d topk=%d" % (kind, N, K, topk))
+    W = S.latent_weights(N, K, S.seed_for(2, 601 + N))
+    p, a = pack(W)
+    for row in (0, 1, 2, 3):                              # "ties": all-zero row, all-equal row, -0.0 row
+        X = _x(kind, 4, K, S.seed_for(2, 600 + K), BF16)[row:row + 1]
+        ref = O.bitlinear_a8_sparse(X, W, topk, EPS, "f32")
+        _check_linear(B.bitlinear_a8_sparse(dev(X, BF16), topk, p, a, N, EPS, B.BL_W_GEMM, F32, True), ref, F32)
+
+
 # ------------------------------------------------------------------ full prefill size (config 3), sampled rows
 @pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (300, 520, 1000, BF16), (130, 2048, 5460, BF16),
                                          (257, 5460, 2048, BF16), (1100, 1100, 768, BF16),
