@@ -60,6 +60,14 @@
  *               k0 + 8*(j%2) + j/2, nibble j of word 1 holds channel k0 + 4 + 8*(j%2) + j/2.
  *               Block scales: one E8M0 byte (value 2^(byte-127)) per 32 channels,
  *               [M][Kp/32] bytes.
+ *   FP4 activations, MX form: the same nibbles and scales in blocks of 32 tokens x 128
+ *               channels.  Codes: 2048 bytes per block, block (mb, kb) at byte
+ *               (mb * Kp/128 + kb) * 2048 (M rounded up to 32; rows past M are not written);
+ *               token row r = m % 32 takes 64 bytes, its 16-byte piece p holds unit
+ *               u = p ^ ((r / 4) % 4), i.e. channels 128*kb + 32*u ... + 31, channel i of the unit
+ *               in nibble i (low nibble of a byte first) -- the geometry of BL_W_MX4.
+ *               Scales: 128 bytes per block at (mb * Kp/128 + kb) * 128, the E8M0 byte of
+ *               unit u of token row r at r*4 + u.
  */
 #ifndef BITLINEAR_H_
 #define BITLINEAR_H_
@@ -77,7 +85,8 @@ typedef enum {
   BL_ACT_INT4_ABSMEAN = 0,     /* eq. 7 */
   BL_ACT_TOPK_INT8_ABSMAX = 1, /* eq. 1 + eq. 3 */
   BL_ACT_FP4_E2M1_B32 = 2,     /* eq. 8-9 with one power-of-two scale per 32 channels */
-  BL_ACT_INT4_ABSMEAN_MX6 = 3  /* eq. 7, levels stored as E3M2 codes for the block-float GEMM */
+  BL_ACT_INT4_ABSMEAN_MX6 = 3, /* eq. 7, levels stored as E3M2 codes for the block-float GEMM */
+  BL_ACT_FP4_E2M1_B32_MX = 4   /* eq. 8-9, codes and scales in the block order of the block-float GEMM */
 } bl_act_mode;
 
 typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1, BL_W_MX4 = 2 } bl_w_layout;
@@ -126,9 +135,11 @@ int pack_ternary(const void* W, bl_dtype w_dtype, int64_t N, int64_t K, float ep
  *       2^e with max|x| / 2^e <= 6 (e = 0 for an all-zero block, clamped to [-127, 127]);
  *       codes = x / 2^e rounded to the nearest E2M1 value, ties to the even code, zero
  *       always stored as +0; scale_out = E8M0 bytes (e + 127), [M][Kp/32]; eps unused.
+ *   BL_ACT_FP4_E2M1_B32_MX: the same quantizer, codes and scales in the MX form (for BL_W_MX4
+ *       weights); scale_out then takes round_up(M, 32) * Kp/32 bytes.
  *   X           device, [M, K] of x_dtype
  *   q_out       device, quantize_act_bytes(mode, M, K) bytes, fully overwritten
- *   scale_out   device, float32[M] (INT modes) or uint8[M * Kp/32] (FP4)
+ *   scale_out   device, float32[M] (INT modes) or uint8[M * Kp/32] (FP4; MX form: M rounded up to 32)
  *   rowsum_out  nullable; int32[M] = sum of the token's codes (INT modes only)
  *   sel_idx_out nullable; TOPK mode only: int32[M, topk], the masked channel indices of
  *               each token in ascending order
@@ -152,7 +163,9 @@ int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, bl_act_m
  *              product runs on the 6-bit x 4-bit block-float matrix instruction at twice the
  *              INT8 rate; every product and every partial sum is an integer below 2^24, so the
  *              float32 accumulator equals the int32 one bit for bit.  Size the workspace with
- *              mode BL_ACT_INT4_ABSMEAN_MX6 in that case.
+ *              mode BL_ACT_INT4_ABSMEAN_MX6 in that case.  With act_fp4 = 1 and BL_W_MX4 the
+ *              activations go to the FP4 MX form and the product runs on the same instruction
+ *              with the block scales as its scale operand (mode BL_ACT_FP4_E2M1_B32_MX).
  *   alpha      device, float32[1]
  *   Y          device, [M, N] of y_dtype
  *   acc_out    nullable; device int32[M, N], receives the integer accumulators
@@ -178,8 +191,8 @@ int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, i
 
 /* The matmul + rescale stage alone, on activations already quantized by quantize_act
  * (what the two calls above run after their quantize kernel).  q and scale are the
- * outputs of quantize_act in `mode`; BL_ACT_INT4_ABSMEAN_MX6 goes with BL_W_MX4 and with
- * nothing else.  `workspace` must hold bitlinear_workspace_bytes(mode, M, N, K) bytes when
+ * outputs of quantize_act in `mode`; BL_ACT_INT4_ABSMEAN_MX6 and BL_ACT_FP4_E2M1_B32_MX go with
+ * BL_W_MX4 and with nothing else.  `workspace` must hold bitlinear_workspace_bytes(mode, M, N, K) bytes when
  * M <= BL_DECODE_MAX_M (partial sums of the split-K decode kernels) or the layout is
  * BL_W_KMAJOR; otherwise it may be NULL. */
 int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M, int64_t K,

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libbitlinear.so")
 
 BL_F32, BL_BF16 = 0, 1
 BL_ACT_INT4_ABSMEAN, BL_ACT_TOPK_INT8_ABSMAX, BL_ACT_FP4_E2M1_B32, BL_ACT_INT4_ABSMEAN_MX6 = 0, 1, 2, 3
+BL_ACT_FP4_E2M1_B32_MX = 4
 BL_W_GEMM, BL_W_KMAJOR, BL_W_MX4 = 0, 1, 2
 BL_DECODE_MAX_M = 64
 DEFAULT_EPS = 1e-5
@@ -127,6 +128,8 @@ def quantize_act(X, mode, topk=0, eps=DEFAULT_EPS, want_rowsum=False, want_sel=F
     q = torch.empty(L.quantize_act_bytes(mode, M, K), dtype=torch.uint8, device=X.device)
     if mode == BL_ACT_FP4_E2M1_B32:
         scale = torch.empty(M * (L.bl_padded_k(K) // 32), dtype=torch.uint8, device=X.device)
+    elif mode == BL_ACT_FP4_E2M1_B32_MX:
+        scale = torch.empty((M + 31) // 32 * 32 * (L.bl_padded_k(K) // 32), dtype=torch.uint8, device=X.device)
     else:
         scale = torch.empty(M, dtype=torch.float32, device=X.device)
     rowsum = torch.empty(M, dtype=torch.int32, device=X.device) if want_rowsum else None
@@ -157,8 +160,10 @@ def bitlinear_a4(X, W_packed, alpha, N, eps=DEFAULT_EPS, act_fp4=False, y_dtype=
                  want_acc=False, ws=None, out=None, layout=BL_W_GEMM):
     _dev(X)
     M, K = X.shape
-    mode = BL_ACT_FP4_E2M1_B32 if act_fp4 else (
-        BL_ACT_INT4_ABSMEAN_MX6 if layout == BL_W_MX4 else BL_ACT_INT4_ABSMEAN)
+    if act_fp4:
+        mode = BL_ACT_FP4_E2M1_B32_MX if layout == BL_W_MX4 else BL_ACT_FP4_E2M1_B32
+    else:
+        mode = BL_ACT_INT4_ABSMEAN_MX6 if layout == BL_W_MX4 else BL_ACT_INT4_ABSMEAN
     if ws is None:
         ws = workspace(mode, M, N, K, X.device)
     Y, acc = _out(M, N, y_dtype, X.device, want_acc) if out is None else (out, None)

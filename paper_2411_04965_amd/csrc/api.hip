@@ -6,7 +6,9 @@ static inline size_t ws_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static bool valid_dtype(int d) { return d == BL_F32 || d == BL_BF16; }
 static bool valid_layout(int l) { return l == BL_W_GEMM || l == BL_W_KMAJOR || l == BL_W_MX4; }
-static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_INT4_ABSMEAN_MX6; }
+static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_FP4_E2M1_B32_MX; }
+static bool mx_mode(int m) { return m == BL_ACT_INT4_ABSMEAN_MX6 || m == BL_ACT_FP4_E2M1_B32_MX; }
+static bool fp4_mode(int m) { return m == BL_ACT_FP4_E2M1_B32 || m == BL_ACT_FP4_E2M1_B32_MX; }
 
 static int check_sizes(int64_t M, int64_t N, int64_t K) {
   if (M < 1 || N < 1 || K < 1) return BL_EINVAL;
@@ -71,12 +73,14 @@ extern "C" size_t quantize_act_bytes(bl_act_mode mode, int64_t M, int64_t K) {
     case BL_ACT_TOPK_INT8_ABSMAX: return (size_t)(M * Kp);
     case BL_ACT_FP4_E2M1_B32: return (size_t)(M * Kp / 2);
     case BL_ACT_INT4_ABSMEAN_MX6: return (size_t)(bl_round_up(M, 32) * Kp / 4 * 3);
+    case BL_ACT_FP4_E2M1_B32_MX: return (size_t)(bl_round_up(M, 32) * Kp / 2);
     default: return 0;
   }
 }
 
 static size_t act_scale_bytes(bl_act_mode mode, int64_t M, int64_t K) {
   if (mode == BL_ACT_FP4_E2M1_B32) return (size_t)(M * (bl_round_up(K, BL_KPAD) / 32));
+  if (mode == BL_ACT_FP4_E2M1_B32_MX) return (size_t)(bl_round_up(M, 32) * (bl_round_up(K, BL_KPAD) / 32));
   return (size_t)M * sizeof(float);
 }
 
@@ -90,7 +94,7 @@ extern "C" int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t 
   if (rc) return rc;
   if (mode == BL_ACT_TOPK_INT8_ABSMAX && (topk < 1 || topk > K)) return BL_EINVAL;
   if (mode != BL_ACT_TOPK_INT8_ABSMAX && sel_idx_out) return BL_EINVAL;
-  if (mode == BL_ACT_FP4_E2M1_B32 && rowsum_out) return BL_EINVAL;
+  if (fp4_mode(mode) && rowsum_out) return BL_EINVAL;
   if (!bl_aligned16(X) || !bl_aligned16(q_out)) return BL_EALIGN;
   return bl_launch_quantize(X, x_dtype, M, K, mode, topk, eps, q_out, scale_out, rowsum_out,
                             sel_idx_out, (hipStream_t)stream);
@@ -107,7 +111,7 @@ extern "C" int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K,
 // ---------------------------------------------------------------- linear layers
 // Workspace layout: [codes | scales | stage-2 scratch], each part 256-byte aligned.
 static size_t stage2_ws_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K) {
-  if (mode == BL_ACT_FP4_E2M1_B32 || mode == BL_ACT_INT4_ABSMEAN_MX6 || M > BL_DECODE_MAX_M) return 0;
+  if (fp4_mode(mode) || mx_mode(mode) || M > BL_DECODE_MAX_M) return 0;
   size_t a = bl_gemm_decode_ws_bytes(M, N, K);
   if (mode == BL_ACT_TOPK_INT8_ABSMAX && M <= 8) {
     const size_t b = bl_gemv_sparse_ws_bytes(M, N, K);
@@ -127,9 +131,13 @@ static int gemm_dispatch(const void* q, const void* scale, bl_act_mode mode, int
                          void* Y, bl_dtype y_dtype, int32_t* acc_out, void* ws, size_t ws_bytes,
                          hipStream_t s) {
   // the block-float forms of activations and weights go together and with nothing else
-  if ((mode == BL_ACT_INT4_ABSMEAN_MX6) != (layout == BL_W_MX4)) return BL_EINVAL;
+  if (mx_mode(mode) != (layout == BL_W_MX4)) return BL_EINVAL;
   if (mode == BL_ACT_INT4_ABSMEAN_MX6)
     return bl_launch_gemm_a4_mx(q, (const float*)scale, M, K, W_packed, alpha, N, Y, y_dtype, acc_out, s);
+  if (mode == BL_ACT_FP4_E2M1_B32_MX) {
+    if (acc_out) return BL_EINVAL;
+    return bl_launch_gemm_fp4_mx(q, (const uint8_t*)scale, M, K, W_packed, alpha, N, Y, y_dtype, s);
+  }
   if (mode == BL_ACT_FP4_E2M1_B32) {
     if (layout != BL_W_GEMM || acc_out) return BL_EINVAL;
     return bl_launch_gemm_fp4(q, (const uint8_t*)scale, M, K, W_packed, alpha, N, Y, y_dtype, s);
@@ -184,7 +192,8 @@ static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, 
   if (!bl_aligned16(workspace)) return BL_EALIGN;
   // reject what the second stage would reject, before the first kernel is enqueued
   if (mode == BL_ACT_FP4_E2M1_B32 && (layout != BL_W_GEMM || acc_out)) return BL_EINVAL;
-  if ((mode == BL_ACT_INT4_ABSMEAN_MX6) != (layout == BL_W_MX4)) return BL_EINVAL;
+  if (mode == BL_ACT_FP4_E2M1_B32_MX && acc_out) return BL_EINVAL;
+  if (mx_mode(mode) != (layout == BL_W_MX4)) return BL_EINVAL;
   if (layout == BL_W_KMAJOR && (mode != BL_ACT_TOPK_INT8_ABSMAX || M > 8)) return BL_EUNSUPPORTED;
 
   // a few tokens: quantizer and product in one launch
@@ -219,9 +228,9 @@ extern "C" int bitlinear_a4(const void* X, bl_dtype x_dtype, int64_t M, int64_t 
                             void* stream) {
   if (act_fp4 != 0 && act_fp4 != 1) return BL_EINVAL;
   if (layout != BL_W_GEMM && layout != BL_W_MX4) return valid_layout(layout) ? BL_EUNSUPPORTED : BL_EINVAL;
-  if (layout == BL_W_MX4 && act_fp4) return BL_EINVAL;
   const bl_act_mode int4_mode = layout == BL_W_MX4 ? BL_ACT_INT4_ABSMEAN_MX6 : BL_ACT_INT4_ABSMEAN;
-  return linear_common(X, x_dtype, M, K, act_fp4 ? BL_ACT_FP4_E2M1_B32 : int4_mode, 0,
+  const bl_act_mode fp4_mode_ = layout == BL_W_MX4 ? BL_ACT_FP4_E2M1_B32_MX : BL_ACT_FP4_E2M1_B32;
+  return linear_common(X, x_dtype, M, K, act_fp4 ? fp4_mode_ : int4_mode, 0,
                        W_packed, layout, alpha, N, eps, Y, y_dtype, acc_out, workspace,
                        workspace_bytes, stream);
 }

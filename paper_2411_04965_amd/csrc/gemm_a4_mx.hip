@@ -64,9 +64,15 @@ __device__ __forceinline__ u32 gx_pack_bf16(float lo, float hi) {
 
 // OUT: 0 = bf16 rows through the LDS transpose (N % 8 == 0), 1 = 4 outputs per store (N % 4 == 0),
 // 2 = one output per store (any N).  ACC: also write the integer accumulators (tests).
-template <int OUT, bool ACC>
+// FP4: the activations are E2M1 codes with one E8M0 scale per token and 32 channels (eq. 8-9)
+// instead of E3M2 codes of INT4 levels: 2 KB instead of 3 KB per block, the same instruction in its
+// scaled form with the block scales as the column operand's scale (`xsc`, 128 bytes per block in
+// block order; each lane holds exactly one 32-channel block of one token per instruction), no
+// per-token scale, float32 sums that are no longer integers.
+template <int OUT, bool ACC, bool FP4>
 __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
-    const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int KB,
+    const unsigned char* __restrict__ A, const float* __restrict__ scale,
+    const unsigned char* __restrict__ xsc, int M, int KB,
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N, void* __restrict__ Y,
     int y_bf16, int32_t* __restrict__ acc_out, int MT, int NTB) {
   extern __shared__ __align__(16) unsigned char gx_smem[];
@@ -77,7 +83,8 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   const int n_tiles = MT * NTB;
   const int MB = (M + 31) >> 5, NB = (N + 31) >> 5;           // 32-row blocks of the operands
   constexpr int WM = 128, WN = 128, TM = 4, TN = 4;
-  constexpr int LA = 6, LB = 4;                  // 1 KB pieces per wave and step: activations, weights
+  constexpr int LA = FP4 ? 4 : 6, LB = 4;        // 1 KB pieces per wave and step: activations, weights
+  constexpr int A_BLOCK = FP4 ? 2048 : GX_A_BLOCK;
 
   // ---- global loads.  One cursor per operand names the (tile, K step) that is loaded next and
   // moves on along the block's stream of tiles by itself; weights run two steps ahead of the
@@ -94,7 +101,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       // row blocks past the end of an operand re-read its last block (their results are never stored)
-      if (is_a) c.p[i] = A + (size_t)min((m0 >> 5) + 2 * wave + i, MB - 1) * KB * GX_A_BLOCK;
+      if (is_a) c.p[i] = A + (size_t)min((m0 >> 5) + 2 * wave + i, MB - 1) * KB * A_BLOCK;
       else c.p[i] = Wp + (size_t)min((n0 >> 5) + 2 * wave + i, NB - 1) * KB * GX_W_BLOCK;
     }
   };
@@ -106,7 +113,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     } else {
       ++c.kb;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) c.p[i] += is_a ? GX_A_BLOCK : GX_W_BLOCK;
+      for (int i = 0; i < 2; ++i) c.p[i] += is_a ? A_BLOCK : GX_W_BLOCK;
     }
   };
   // Two sets of staging registers, used by even and odd steps in turn: a register is refilled
@@ -114,20 +121,53 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   // load has two steps (about 1.5 microseconds) to arrive.
   v4i a_reg[2][LA], b_reg[2][LB];
   const int lane16 = lane * 16;
-  // piece j of the activations: row block 2w + j / 3, there XP (2 KB) then XQ (1 KB)
+  // piece j of the activations: row block 2w + j / 3, there XP (2 KB) then XQ (1 KB); FP4 blocks
+  // are 2 KB and go where XP goes
+  constexpr int PA = LA / 2;                     // pieces per row block
   auto load_a = [&](const Cursor& c, int set, int j) {
-    a_reg[set][j] = *reinterpret_cast<const v4i*>(c.p[j / 3] + (j % 3) * 1024 + lane16);
+    a_reg[set][j] = *reinterpret_cast<const v4i*>(c.p[j / PA] + (j % PA) * 1024 + lane16);
   };
   auto load_b = [&](const Cursor& c, int set, int j) {
     b_reg[set][j] = *reinterpret_cast<const v4i*>(c.p[j / 2] + (j % 2) * 1024 + lane16);
   };
   auto store_a = [&](unsigned char* st, int set, int j) {
-    const int rb = 2 * wave + j / 3, i = j % 3;
+    const int rb = 2 * wave + j / PA, i = j % PA;
     unsigned char* dst = i < 2 ? st + rb * 2048 + i * 1024 : st + GX_XQ + rb * 1024;
     *reinterpret_cast<v4i*>(dst + lane16) = a_reg[set][j];
   };
   auto store_b = [&](unsigned char* st, int set, int j) {
     *reinterpret_cast<v4i*>(st + GX_W + (2 * wave + j / 2) * 2048 + (j % 2) * 1024 + lane16) = b_reg[set][j];
+  };
+
+  // ---- FP4: block scales of the wave's four token blocks, one word (4 units) per lane and step,
+  // fetched two steps ahead into two register sets like the operands
+  struct SCursor {
+    const unsigned char* p[TM];
+    int kb, tile;
+  };
+  auto point_s = [&](SCursor& c, int tile) {
+    int m0, n0;
+    bl_tile_origin(tile, n_tiles, MT, NTB, GX_BM, GX_BN, m0, n0);
+    c.tile = tile;
+    c.kb = 0;
+#pragma unroll
+    for (int b = 0; b < TM; ++b)
+      c.p[b] = xsc + (size_t)min((m0 >> 5) + wm * 4 + b, MB - 1) * KB * 128 + l32 * 4;
+  };
+  auto advance_s = [&](SCursor& c) {
+    if (c.kb + 1 == KB) {
+      const int nt = c.tile + (int)gridDim.x;
+      if (nt < n_tiles) point_s(c, nt);
+    } else {
+      ++c.kb;
+#pragma unroll
+      for (int b = 0; b < TM; ++b) c.p[b] += 128;
+    }
+  };
+  u32 sc_reg[2][TM];
+  auto load_s = [&](const SCursor& c, int set) {
+#pragma unroll
+    for (int b = 0; b < TM; ++b) sc_reg[set][b] = *reinterpret_cast<const u32*>(c.p[b]);
   };
 
   // ---- fragment addresses (within a stage): lane (l32, lh) reads unit u = 2 s + lh of its row
@@ -139,14 +179,19 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     xq_off[s] = GX_XQ + (wm * WM + l32) * 32 + ((u ^ ((l32 >> 3) & 3)) << 3);
     w_off[s] = GX_W + (wn * WN + l32) * 64 + ((u ^ ((l32 >> 2) & 3)) << 4);
   }
+  typedef typename std::conditional<FP4, v4i, v6i>::type XFrag;
   struct Frags {
-    v6i x[TM];
+    XFrag x[TM];
     v4i w[TN];
   };
-  auto read_x = [&](const unsigned char* st, int s, int b) -> v6i {
+  auto read_x = [&](const unsigned char* st, int s, int b) -> XFrag {
     const v4i p = *reinterpret_cast<const v4i*>(st + xp_off[s] + b * 2048);
-    const v2i q = *reinterpret_cast<const v2i*>(st + xq_off[s] + b * 1024);
-    return (v6i){p[0], p[1], p[2], p[3], q[0], q[1]};
+    if constexpr (FP4) {
+      return p;
+    } else {
+      const v2i q = *reinterpret_cast<const v2i*>(st + xq_off[s] + b * 1024);
+      return (v6i){p[0], p[1], p[2], p[3], q[0], q[1]};
+    }
   };
   auto read_w = [&](const unsigned char* st, int s, int a) -> v4i {
     return *reinterpret_cast<const v4i*>(st + w_off[s] + a * 2048);
@@ -161,10 +206,21 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 // first MFMA on an accumulator tile: C = 0 (saves clearing 256 registers per output tile)
 #define GX_MFMA0(C, WF, XF) \
   asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0 cbsz:4 blgp:3" : "=a"(C) : "v"(WF), "v"(XF))
+// scaled form, both operands E2M1: SA / SX = scale words of the row / column operand, of which the
+// instruction takes byte 0 (HI = 0) or byte 2 (HI = 1) of SX and byte 0 of SA
+#define GX_MFMA_S(C, WF, XF, SA, SX, HI)                                                              \
+  asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel_hi:[0," #HI ",0] cbsz:4 blgp:4" \
+               : "+a"(C) : "v"(WF), "v"(XF), "v"(SA), "v"(SX))
+#define GX_MFMA0_S(C, WF, XF, SA, SX, HI)                                                             \
+  asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, 0, %3, %4 op_sel_hi:[0," #HI ",0] cbsz:4 blgp:4" \
+               : "=a"(C) : "v"(WF), "v"(XF), "v"(SA), "v"(SX))
 #else
 #define GX_MFMA(C, WF, XF) ((void)0)
 #define GX_MFMA0(C, WF, XF) ((void)0)
+#define GX_MFMA_S(C, WF, XF, SA, SX, HI) ((void)0)
+#define GX_MFMA0_S(C, WF, XF, SA, SX, HI) ((void)0)
 #endif
+  [[maybe_unused]] const u32 one_scale = 127u;   // E8M0 of 2^0 for the ternary weights
 
   const float alpha = alpha_p[0];
 
@@ -176,6 +232,14 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   Cursor ca, cb;
   point(ca, tile, true);
   point(cb, tile, false);
+  SCursor cs;
+  if constexpr (FP4) {                           // scales of steps 0 and 1
+    point_s(cs, tile);
+    load_s(cs, 0);
+    advance_s(cs);
+    load_s(cs, 1);
+    advance_s(cs);
+  }
 #pragma unroll
   for (int j = 0; j < LA; ++j) load_a(ca, 0, j);
 #pragma unroll
@@ -225,7 +289,8 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
       const int m = m0 + wm * WM + b * 32 + l32;
-      dsc[b] = m < M ? scale[m] : 0.0f;
+      if constexpr (FP4) dsc[b] = 1.0f;          // (acc * 1) * alpha: the scales are inside acc
+      else dsc[b] = m < M ? scale[m] : 0.0f;
     }
 
     // One step; PAR = parity of the step = its stage and its set of staging registers (KB is
@@ -234,6 +299,11 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       constexpr int PAR = decltype(par)::value;
       unsigned char* st_own = gx_smem + PAR * GX_STAGE;
       unsigned char* st_other = gx_smem + (PAR ^ 1) * GX_STAGE;
+      // FP4: this step's scale words; a lane of the upper half (units 1 and 3) moves its bytes down,
+      // so that the instruction takes byte 0 in sub-step 0 and byte 2 in sub-step 1
+      u32 sx[TM];
+#pragma unroll
+      for (int b = 0; b < TM; ++b) sx[b] = FP4 ? sc_reg[PAR][b] >> (8 * lh) : 0u;
       // ---- sub-step 0.  Slots behind the MFMAs: fragment reads first, then one LDS write and
       // the global load that refills its register (a 16-byte LDS write costs the MFMA stream
       // least directly behind the reads, and nothing here is vector arithmetic).
@@ -241,8 +311,13 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       for (int a = 0; a < TN; ++a) {
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
-          if (first) GX_MFMA0(acc[a][b], F[0].w[a], F[0].x[b]);
-          else GX_MFMA(acc[a][b], F[0].w[a], F[0].x[b]);
+          if constexpr (FP4) {
+            if (first) GX_MFMA0_S(acc[a][b], F[0].w[a], F[0].x[b], one_scale, sx[b], 0);
+            else GX_MFMA_S(acc[a][b], F[0].w[a], F[0].x[b], one_scale, sx[b], 0);
+          } else {
+            if (first) GX_MFMA0(acc[a][b], F[0].w[a], F[0].x[b]);
+            else GX_MFMA(acc[a][b], F[0].w[a], F[0].x[b]);
+          }
           const int i = a * TM + b;              // one slot behind each MFMA
           if (i < 4) F[1].x[i] = read_x(st_own, 1, i);
           else if (i < 8) F[1].w[i - 4] = read_w(st_own, 1, i - 4);
@@ -259,17 +334,22 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       for (int a = 0; a < TN; ++a) {
 #pragma unroll
         for (int b = 0; b < TM; ++b) {
-          GX_MFMA(acc[a][b], F[1].w[a], F[1].x[b]);
+          if constexpr (FP4) GX_MFMA_S(acc[a][b], F[1].w[a], F[1].x[b], one_scale, sx[b], 1);
+          else GX_MFMA(acc[a][b], F[1].w[a], F[1].x[b]);
           const int i = a * TM + b;
           if (i < 4) F[0].x[i] = read_x(st_other, 0, i);
           else if (i < 8) F[0].w[i - 4] = read_w(st_other, 0, i - 4);
-          else if (i < 14) {                     // slots 8 .. 13: activations of the step after next
+          else if (i < 8 + LA) {                 // slots 8 ..: activations of the step after next
             store_a(st_own, PAR, i - 8);
             load_a(ca, PAR, i - 8);
           }
         }
       }
       advance(ca, true);
+      if constexpr (FP4) {                       // scales of the step after next
+        load_s(cs, PAR);
+        advance_s(cs);
+      }
     };
     for (int kb = 0; kb < KB; kb += 2) {
       step(std::integral_constant<int, 0>{}, kb == 0);
@@ -417,15 +497,17 @@ static int gx_num_cus() {
   return cus;
 }
 
-template <int OUT, bool ACC>
-static int gx_go(const void* q, const float* scale, int M, int KB, const void* Wp, const float* alpha,
-                 int N, void* Y, int y_bf16, int32_t* acc_out, int MT, int NTB, hipStream_t s) {
-  if (hipFuncSetAttribute((const void*)gemm_a4_mx_kernel<OUT, ACC>,
+template <int OUT, bool ACC, bool FP4>
+static int gx_go(const void* q, const float* scale, const uint8_t* xsc, int M, int KB, const void* Wp,
+                 const float* alpha, int N, void* Y, int y_bf16, int32_t* acc_out, int MT, int NTB,
+                 hipStream_t s) {
+  if (hipFuncSetAttribute((const void*)gemm_a4_mx_kernel<OUT, ACC, FP4>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, GX_LDS) != hipSuccess)
     return BL_EHIP;
   const int grid = min(MT * NTB, gx_num_cus());      // persistent blocks, one per CU (all of its LDS)
-  gemm_a4_mx_kernel<OUT, ACC><<<(unsigned)grid, GX_THREADS, GX_LDS, s>>>(
-      (const unsigned char*)q, scale, M, KB, (const unsigned char*)Wp, alpha, N, Y, y_bf16, acc_out, MT, NTB);
+  gemm_a4_mx_kernel<OUT, ACC, FP4><<<(unsigned)grid, GX_THREADS, GX_LDS, s>>>(
+      (const unsigned char*)q, scale, (const unsigned char*)xsc, M, KB, (const unsigned char*)Wp, alpha, N, Y,
+      y_bf16, acc_out, MT, NTB);
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;
 }
@@ -437,8 +519,20 @@ int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K
   const int MT = (int)((M + GX_BM - 1) / GX_BM), NTB = (int)((N + GX_BN - 1) / GX_BN);
   const int out = (ydt == BL_BF16 && (N & 7) == 0) ? 0 : ((N & 3) == 0 ? 1 : 2);
   const int yb = ydt == BL_BF16 ? 1 : 0;
-#define GX_CALL(OUT, ACC) gx_go<OUT, ACC>(q, scale, (int)M, KB, Wp, alpha, (int)N, Y, yb, acc_out, MT, NTB, s)
+#define GX_CALL(OUT, ACC) gx_go<OUT, ACC, false>(q, scale, nullptr, (int)M, KB, Wp, alpha, (int)N, Y, yb, acc_out, MT, NTB, s)
   if (acc_out) return out == 0 ? GX_CALL(0, true) : out == 1 ? GX_CALL(1, true) : GX_CALL(2, true);
   return out == 0 ? GX_CALL(0, false) : out == 1 ? GX_CALL(1, false) : GX_CALL(2, false);
 #undef GX_CALL
+}
+
+// FP4 activations (E2M1 codes and E8M0 block scales in the MX form) x BL_W_MX4 weights.
+int bl_launch_gemm_fp4_mx(const void* q, const uint8_t* xscale, int64_t M, int64_t K, const void* Wp,
+                          const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s) {
+  const int KB = (int)(bl_round_up(K, BL_KPAD) / 128);
+  const int MT = (int)((M + GX_BM - 1) / GX_BM), NTB = (int)((N + GX_BN - 1) / GX_BN);
+  const int out = (ydt == BL_BF16 && (N & 7) == 0) ? 0 : ((N & 3) == 0 ? 1 : 2);
+  const int yb = ydt == BL_BF16 ? 1 : 0;
+#define GX_CALL4(OUT) gx_go<OUT, false, true>(q, nullptr, xscale, (int)M, KB, Wp, alpha, (int)N, Y, yb, nullptr, MT, NTB, s)
+  return out == 0 ? GX_CALL4(0) : out == 1 ? GX_CALL4(1) : GX_CALL4(2);
+#undef GX_CALL4
 }

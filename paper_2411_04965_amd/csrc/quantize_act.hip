@@ -475,7 +475,9 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
 
 // ---------------------------------------------------------------- FP4 E2M1, block of 32 (eq. 8-9)
 // One thread per block of 32 channels.
-template <typename RawT>
+// MX: codes and scales in the block order of the block-float GEMM (32 tokens x 128 channels per
+// block, channels of a unit in natural nibble order) instead of token-major.
+template <typename RawT, bool MX>
 __global__ __launch_bounds__(QA_THREADS) void quant_fp4_kernel(
     const RawT* __restrict__ X, int64_t M, int K, int Kp, u32* __restrict__ q_out,
     uint8_t* __restrict__ scale_out) {
@@ -487,10 +489,28 @@ __global__ __launch_bounds__(QA_THREADS) void quant_fp4_kernel(
   const RawT* x = X + m * (int64_t)K + blk * 32;
   float v[32];
   float a = 0.0f;
+  if (sizeof(RawT) == 2 && (K & 31) == 0 && blk * 32 < K) {
+    // whole block of a bfloat16 row that is 64-byte aligned: four 16-byte loads
+    uint4 w[4];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) {
-    v[j] = (blk * 32 + j < K) ? qa_to_f32<RawT>(x[j]) : 0.0f;
-    a = fmaxf(a, fabsf(v[j]));
+    for (int i = 0; i < 4; ++i) w[i] = reinterpret_cast<const uint4*>(x)[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u32 ww[4] = {w[i].x, w[i].y, w[i].z, w[i].w};
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        v[8 * i + 2 * e2] = __uint_as_float(ww[e2] << 16);
+        v[8 * i + 2 * e2 + 1] = __uint_as_float(ww[e2] & 0xFFFF0000u);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 32; ++j) a = fmaxf(a, fabsf(v[j]));
+  } else {
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      v[j] = (blk * 32 + j < K) ? qa_to_f32<RawT>(x[j]) : 0.0f;
+      a = fmaxf(a, fabsf(v[j]));
+    }
   }
   // smallest e with a / 2^e <= 6 = 1.5 * 2^2
   int e = 0;
@@ -502,7 +522,11 @@ __global__ __launch_bounds__(QA_THREADS) void quant_fp4_kernel(
     if (be == 0) e = -127;                                // subnormal maximum: below the clamp
     e = max(-127, min(127, e));
   }
-  scale_out[m * bpr + blk] = (uint8_t)(e + 127);
+  // block (m / 32, blk / 4): token row r = m % 32, unit u = blk % 4
+  const int64_t mxb = (m >> 5) * (int64_t)(Kp / 128) + (blk >> 2);
+  const int r = (int)(m & 31), u = blk & 3;
+  if (MX) scale_out[mxb * 128 + r * 4 + u] = (uint8_t)(e + 127);
+  else scale_out[m * bpr + blk] = (uint8_t)(e + 127);
   u32 nib[32];
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
@@ -518,6 +542,14 @@ __global__ __launch_bounds__(QA_THREADS) void quant_fp4_kernel(
     else if (r < 4.0f) code = (int)r + 2;
     else code = (int)(r * 0.5f) + 4;
     nib[j] = (u32)code | ((sv < 0.0f && code != 0) ? 8u : 0u);
+  }
+  if (MX) {
+    u32 w4[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 32; ++j) w4[j >> 3] |= nib[j] << (4 * (j & 7));
+    unsigned char* dst = reinterpret_cast<unsigned char*>(q_out) + mxb * 2048 + r * 64 + ((u ^ ((r >> 2) & 3)) << 4);
+    *reinterpret_cast<uint4*>(dst) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+    return;
   }
   u32* out = q_out + m * (int64_t)(Kp / 8) + blk * 4;
 #pragma unroll
@@ -570,6 +602,12 @@ __global__ __launch_bounds__(QA_THREADS) void unpack_act_kernel(const u32* __res
     // levels are integers: 2^(e-3) * (1 + mant/4) for e >= 1, zero otherwise
     const int mag = e == 0 ? 0 : (((4 + mant) << e) >> 5);
     v = (c & 32u) ? -mag : mag;
+  } else if (mode == BL_ACT_FP4_E2M1_B32_MX) {
+    const unsigned char* blk = reinterpret_cast<const unsigned char*>(q) +
+                               ((m >> 5) * (int64_t)(Kp / 128) + (k >> 7)) * 2048;
+    const int r = (int)(m & 31), u = (k >> 5) & 3, i = k & 31;
+    const unsigned char b = blk[r * 64 + ((u ^ ((r >> 2) & 3)) << 4) + (i >> 1)];
+    v = (int)((b >> (4 * (i & 1))) & 15u);
   } else {
     const int kk = k & 15;
     const int wsel = (kk >> 2) & 1;
@@ -614,13 +652,17 @@ int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K64, bl_ac
                        int64_t topk, float eps, void* q, void* scale, int32_t* rowsum,
                        int32_t* sel_idx, hipStream_t s) {
   const int K = (int)K64, Kp = (int)bl_round_up(K64, BL_KPAD);
-  if (mode == BL_ACT_FP4_E2M1_B32) {
+  if (mode == BL_ACT_FP4_E2M1_B32 || mode == BL_ACT_FP4_E2M1_B32_MX) {
     const int64_t n = M * (Kp / 32);
-    const int64_t blocks = (n + QA_THREADS - 1) / QA_THREADS;
-    if (dt == BL_BF16)
-      quant_fp4_kernel<uint16_t><<<(unsigned)blocks, QA_THREADS, 0, s>>>((const uint16_t*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
-    else
-      quant_fp4_kernel<u32><<<(unsigned)blocks, QA_THREADS, 0, s>>>((const u32*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
+    const unsigned blocks = (unsigned)((n + QA_THREADS - 1) / QA_THREADS);
+    const bool mx = mode == BL_ACT_FP4_E2M1_B32_MX;
+    if (dt == BL_BF16) {
+      if (mx) quant_fp4_kernel<uint16_t, true><<<blocks, QA_THREADS, 0, s>>>((const uint16_t*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
+      else quant_fp4_kernel<uint16_t, false><<<blocks, QA_THREADS, 0, s>>>((const uint16_t*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
+    } else {
+      if (mx) quant_fp4_kernel<u32, true><<<blocks, QA_THREADS, 0, s>>>((const u32*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
+      else quant_fp4_kernel<u32, false><<<blocks, QA_THREADS, 0, s>>>((const u32*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
+    }
     BL_HIP_CHECK_LAUNCH();
     return BL_OK;
   }

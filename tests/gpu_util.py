@@ -129,6 +129,24 @@ def decode_fp4(q, M, K):
     return full[:, :K]
 
 
+def decode_fp4_mx(q, sc, M, K):
+    """FP4 MX form (32-token blocks, natural nibble order; scales 128 bytes per block) ->
+    nibble codes uint8 [M, K] and E8M0 bytes uint8 [M, Kp/32]."""
+    Kp = (K + 255) // 256 * 256
+    Mp = (M + 31) // 32 * 32
+    b = np.frombuffer(q.tobytes(), dtype=np.uint8).reshape(Mp // 32, Kp // 128, 32, 4, 16)
+    r = np.arange(32)
+    u = np.arange(4)
+    piece = u[None, :] ^ ((r[:, None] >> 2) & 3)                    # [r, u] -> piece that holds unit u
+    units = b[:, :, r[:, None], piece, :]                           # [mb, kb, r, u, 16]
+    nib = np.stack([units & 15, units >> 4], axis=-1).reshape(Mp // 32, Kp // 128, 32, 4, 32)
+    full = np.transpose(nib, (0, 2, 1, 3, 4)).reshape(Mp, Kp)       # m = 32 mb + r, k = 128 kb + 32 u + i
+    assert not full[:M, K:].any()
+    e = np.frombuffer(sc.tobytes(), dtype=np.uint8).reshape(Mp // 32, Kp // 128, 32, 4)
+    e = np.transpose(e, (0, 2, 1, 3)).reshape(Mp, Kp // 32)
+    return full[:M, :K], e[:M]
+
+
 def assert_close_rel(y_gpu, y_ref, tol=REL_TOL):
     """|gpu - ref| <= tol * |ref| element-wise (plus a denormal-sized floor)."""
     y_gpu = np.asarray(y_gpu, dtype=np.float64)

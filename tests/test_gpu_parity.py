@@ -9,7 +9,7 @@ import torch
 from oracle import bitnet_a48 as O
 from paper_2411_04965_amd import binding as B
 from paper_2411_04965_amd import synth as S
-from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_int4, decode_int4_mx6,
+from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_fp4_mx, decode_int4, decode_int4_mx6,
                             decode_int8, decode_w_gemm, decode_w_kmajor, decode_w_mx4, dev, host,
                             pack)
 
@@ -133,6 +133,14 @@ def test_quantize_fp4(kind, M, K, dtype):
     assert np.all(sc[:, K // 32:] == 127)
     assert np.array_equal(decode_fp4(host(r["q"]), M, K), codes_ref)
     lib_codes = host(B.unpack_act(r["q"], B.BL_ACT_FP4_E2M1_B32, M, K)).view(np.uint8)
+    assert np.array_equal(lib_codes, codes_ref)
+    # the same codes and scales in the block order of the block-float GEMM
+    r = B.quantize_act(dev(x, dtype), B.BL_ACT_FP4_E2M1_B32_MX)
+    codes_mx, e_mx = decode_fp4_mx(host(r["q"]), host(r["scale"]), M, K)
+    assert np.array_equal(codes_mx, codes_ref)
+    assert np.array_equal(e_mx[:, :K // 32].astype(np.int16) - 127, e_ref)
+    assert np.all(e_mx[:, K // 32:] == 127)
+    lib_codes = host(B.unpack_act(r["q"], B.BL_ACT_FP4_E2M1_B32_MX, M, K)).view(np.uint8)
     assert np.array_equal(lib_codes, codes_ref)
 
 
@@ -382,22 +390,26 @@ def _check_fp4(Y, ref, rows=None):
     assert np.all(err <= bound + 1e-30), "max err/bound %g" % (err / (bound + 1e-30)).max()
 
 
-@pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (130, 200, 992, BF16), (300, 1100, 3200, BF16)])
-def test_fp4_linear(M, N, K, dtype):
-    say("fp4 linear M=%d N=%d K=%d" % (M, N, K))
+@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_MX4])
+@pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (130, 200, 992, BF16), (300, 1100, 3200, BF16),
+                                         (257, 1030, 288, BF16), (600, 257, 1504, BF16)])
+def test_fp4_linear(M, N, K, dtype, layout):
+    """Both FP4 GEMMs: 2-bit weights on the 16x16x128 instruction, and E2M1 weights in LDS tile
+    order on the 32x32x64 instruction (the prefill kernel; ragged M / N / K, every store path)."""
+    say("fp4 linear M=%d N=%d K=%d layout=%d" % (M, N, K, layout))
     X = S.heavy(M, K, S.seed_for(4, M + N)) if dtype == BF16 else S.gauss_outlier(M, K, 4, 20.0, S.seed_for(4, M))
     W = S.latent_weights(N, K, S.seed_for(4, N + K))
     ref = O.bitlinear_fp4(X, W, EPS)
-    p, a = pack(W)
+    p, a = pack(W, layout)
     for ydt in (F32, BF16):
-        Y = B.bitlinear_a4(dev(X, dtype), p, a, N, EPS, act_fp4=True, y_dtype=ydt)
+        Y = B.bitlinear_a4(dev(X, dtype), p, a, N, EPS, act_fp4=True, y_dtype=ydt, layout=layout)
         _check_fp4(Y, ref)
     # an exactly representable case must be exact: integers up to 6 times ternary weights
     Xi = np.random.default_rng(5).integers(-6, 7, (M, K)).astype(np.float32)
     Xi[np.abs(Xi) == 5] = 4
     Xi[:, ::32] = 6                                         # every block has scale 2^0
     refi = O.bitlinear_fp4(Xi, W, EPS)
-    Yi = B.bitlinear_a4(dev(Xi, dtype), p, a, N, EPS, act_fp4=True, y_dtype=F32)
+    Yi = B.bitlinear_a4(dev(Xi, dtype), p, a, N, EPS, act_fp4=True, y_dtype=F32, layout=layout)
     acc_exact = refi["y"] / np.float64(refi["alpha"])       # integers
     assert np.array_equal(host(Yi), (acc_exact.astype(np.float32) * refi["alpha"]).astype(np.float32))
 
@@ -415,6 +427,11 @@ def test_config4_fp4_sampled_rows(name, N, K):
     Y = B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, act_fp4=True, y_dtype=F32)
     ref = O.bitlinear_fp4(X[rows], W, EPS)
     _check_fp4(Y[torch.from_numpy(rows).cuda()], ref)
+    # and on the prefill kernel (E2M1 weights in LDS tile order), in the launch configuration the
+    # FP4 / INT4 comparison is timed in
+    pm, am = pack(W, B.BL_W_MX4)
+    Ym = B.bitlinear_a4(dev(X, BF16), pm, am, N, EPS, act_fp4=True, y_dtype=F32, layout=B.BL_W_MX4)
+    _check_fp4(Ym[torch.from_numpy(rows).cuda()], ref)
     # the INT4 path on identical inputs (the comparison the paper makes): both are reported
     # against the product of the raw activations with the same ternary weights; with
     # heavy-tailed outlier channels the FP4 grid, which never clips, must be the closer one
