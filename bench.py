@@ -12,7 +12,8 @@ All inputs and packed weights are resident in HBM before the timed region.  `val
 dense-equivalent int8 TOPS (2*M*N*K per projection) over the whole step, quantize kernels
 included.  The roofline object covers the dominant kernel, the W1.58A4 prefill GEMM, timed
 with events on the launch stream inside the timed region.  Decode-shape weight bandwidth
-(packed-weight GB/s at 1/8/32/64 tokens) is reported in the same JSON line under "decode".
+(packed-weight GB/s at 1/8/32/64 tokens) is reported in the same JSON line under "decode", and
+the FP4 activation variant against the INT4 path at 3B-like shapes under "fp4_variant".
 """
 import argparse
 import json
@@ -46,6 +47,7 @@ def parse():
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-fp4", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for the HBM traffic counters)")
     return ap.parse_args()
@@ -214,9 +216,40 @@ def main():
     }
     if not args.no_decode:
         out["decode"] = decode_bench(B, S, torch, dev)
+    if not args.no_fp4:
+        out["fp4_variant"] = fp4_compare(B, S, torch, dev)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
+
+
+def fp4_compare(B, S, torch, dev, M=8192, hidden=3200, ffn=8640, iters=20):
+    """The FP4 (E2M1 + E8M0 per 32 channels) activation variant against the INT4 path on identical
+    seeded inputs at 3B-like shapes: quantizer + GEMM per projection, dense TOPS."""
+    res = {"tokens": M}
+    for name, N, K in (("qkv", 3 * hidden, hidden), ("gate", ffn, hidden)):
+        w = torch.from_numpy(S.latent_weights(N, K, S.seed_for(4, 20 + len(name)))).to(dev)
+        p, a = B.pack_ternary(w, EPS, B.BL_W_MX4)
+        del w
+        X = torch.from_numpy(S.heavy(M, K, S.seed_for(4, 21))).to(dev).to(torch.bfloat16)
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        row = {}
+        for label, fp4, mode in (("fp4", True, B.BL_ACT_FP4_E2M1_B32_MX), ("int4", False, B.BL_ACT_INT4_ABSMEAN_MX6)):
+            ws = B.workspace(mode, M, N, K, dev)
+            for _ in range(3):
+                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=B.BL_W_MX4)
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=B.BL_W_MX4)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / iters
+            row[label] = {"ms": round(ms, 4), "tops": round(2.0 * M * N * K / ms / 1e9, 1)}
+        res[name] = row
+    return res
 
 
 def bl_code_bytes(kind, K):
