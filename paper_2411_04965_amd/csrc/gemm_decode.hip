@@ -397,8 +397,8 @@ __global__ __launch_bounds__(GD_THREADS) void gemv_a8_fused_kernel(
   gd_store4(Y, y_bf16, acc_out, (size_t)n, n, N, iv, dq, alpha_p[0]);
 }
 
-// More than one MFMA tile of tokens, or too few output tiles for the kernel above: block = 4 waves
-// = 64 outputs, every wave owns one tile of 16 outputs and walks the block's whole K range (a
+// Up to 16 tokens with too few output tiles for the kernel above (written for any number of token
+// tiles): block = 4 waves = 64 outputs, every wave owns one tile of 16 outputs and walks the block's whole K range (a
 // slice of K when the grid would otherwise be small), so there is no reduction inside the block.
 // The tokens' codes of one K tile (M rows of 128 or 256 bytes, far apart in memory) are fetched
 // once per block with whole-line loads and passed through LDS (rows padded by 16 bytes, so the
@@ -891,77 +891,67 @@ int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, i
 }
 
 // ---------------------------------------------------------------- sparse row-skipping GEMV
-// Step 1: ascending list of the channels with a non-zero code in at least one token, padded
-// to a multiple of 4 entries (padding repeats a valid channel with code 0), plus, per token,
-// the codes of the listed channels packed 4 to a word.
-#define GS_LIST_THREADS 1024
-__global__ __launch_bounds__(GS_LIST_THREADS) void nz_union_kernel(
-    const int8_t* __restrict__ q, int M, int K, int Kp, int Lmax, int32_t* __restrict__ count_out,
-    int32_t* __restrict__ list, u32* __restrict__ qpack) {
-  __shared__ int wave_cnt[GS_LIST_THREADS / 64];
-  __shared__ int base_sh;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (threadIdx.x == 0) base_sh = 0;
-  __syncthreads();
-  for (int k0 = 0; k0 < K; k0 += GS_LIST_THREADS) {
-    const int k = k0 + threadIdx.x;
-    bool nz = false;
-    if (k < K)
-      for (int m = 0; m < M; ++m) nz |= q[(size_t)m * Kp + k] != 0;
-    const uint64_t b = __ballot(nz);
-    if (lane == 0) wave_cnt[wave] = __popcll(b);
-    __syncthreads();
-    int before = base_sh;
-    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
-    if (nz) list[before + __popcll(b & ((1ull << lane) - 1ull))] = k;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int t = 0;
-      for (int w = 0; w < GS_LIST_THREADS / 64; ++w) t += wave_cnt[w];
-      base_sh += t;
-    }
-    __syncthreads();
-  }
-  const int L = base_sh;
-  const int Lp = (L + 3) & ~3;
-  if (threadIdx.x == 0) count_out[0] = L;
-  // padding entries: channel 0 with code 0
-  if (threadIdx.x < Lp - L) list[L + threadIdx.x] = -1;
-  __syncthreads();
-  __threadfence_block();
-  for (int i = threadIdx.x; i < M * (Lp >> 2); i += GS_LIST_THREADS) {
-    const int m = i / (Lp >> 2), g = i % (Lp >> 2);
-    u32 word = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = list[4 * g + j];
-      const u32 c = k >= 0 ? (u32)(uint8_t)q[(size_t)m * Kp + k] : 0u;
-      word |= c << (8 * j);
-    }
-    qpack[(size_t)m * (Lmax >> 2) + g] = word;
-  }
-  __syncthreads();
-  if (threadIdx.x < Lp - L) list[L + threadIdx.x] = 0;
-}
-
-// Step 2: block = 4 waves, one 512-output column block and one slice of the channel list.
-// A half wave reads one 128-byte weight row segment per load (32 lanes x 4 bytes); each lane
-// gathers 4 listed rows, byte-transposes the four raw words so that a byte lane holds the
-// four rows of one group of outputs, expands the 2-bit fields, and feeds v_dot4 with the
-// four matching codes.
+// Block = 4 waves, one 512-output column block and one slice of K.  The block first lists, in LDS,
+// the channels of its slice with a non-zero code in at least one token (ballot compaction; padded
+// to a multiple of 4 entries with a valid channel and code 0), and per token the codes of the
+// listed channels packed 4 to a word.  Then a half wave reads one 128-byte weight row segment per
+// load (32 lanes x 4 bytes); each lane gathers 4 listed rows, byte-transposes the four raw words so
+// that a byte lane holds the four rows of one group of outputs, expands the 2-bit fields, and
+// feeds v_dot4 with the four matching codes.  Rows of channels that are not listed are never read.
 template <int MV>
 __global__ __launch_bounds__(GD_THREADS) void gemv_sparse_kernel(
-    const u32* __restrict__ Wk, int Np, int K, const int32_t* __restrict__ count_p,
-    const int32_t* __restrict__ list, const u32* __restrict__ qpack, int Lmax, int M, int S,
-    int32_t* __restrict__ partial) {
+    const u32* __restrict__ Wk, int Np, int K, int Kp, const int8_t* __restrict__ q, int M, int S,
+    int per, int32_t* __restrict__ partial) {
+  extern __shared__ __align__(16) unsigned char gs_smem[];
+  int* lst = reinterpret_cast<int*>(gs_smem);                    // [per + 4]
+  u32* qp = reinterpret_cast<u32*>(gs_smem) + (per + 4);         // [MV][per / 4 + 1]
+  const int qstride = (per >> 2) + 1;
   __shared__ int red[MV][16][32];
+  __shared__ int wave_cnt[GD_THREADS / 64];
+  __shared__ int base_sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, hl = lane & 31;
   const int CB = Np >> 9;
   const int cb = blockIdx.x % CB, split = blockIdx.x / CB;
-  const int groups = (count_p[0] + 3) >> 2;               // groups of 4 listed channels
-  const int g_begin = (int)((int64_t)split * groups / S), g_end = (int)((int64_t)(split + 1) * groups / S);
+  const int k_begin = min(split * per, K), k_end = min(k_begin + per, K);   // per % 4 == 0
   const u32* wbase = Wk + (size_t)cb * K * 32 + hl;     // 128-byte row segments of this column block
+
+  // ---- the slice's list
+  if (tid == 0) base_sh = 0;
+  __syncthreads();
+  for (int k0 = k_begin; k0 < k_end; k0 += GD_THREADS) {
+    const int k = k0 + tid;
+    bool nz = false;
+    if (k < k_end)
+      for (int m = 0; m < M; ++m) nz |= q[(size_t)m * Kp + k] != 0;
+    const uint64_t bal = __ballot(nz);
+    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    __syncthreads();
+    int before = base_sh;
+    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+    if (nz) lst[before + __popcll(bal & ((1ull << lane) - 1ull))] = k;
+    __syncthreads();
+    if (tid == 0) base_sh += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    __syncthreads();
+  }
+  const int L = base_sh;
+  const int groups = (L + 3) >> 2;                        // groups of 4 listed channels
+  if (tid < 4 * groups - L) lst[L + tid] = -1;            // padding: marked, so that its code reads 0
+  __syncthreads();
+  for (int i = tid; i < M * groups; i += GD_THREADS) {
+    const int m = i / groups, g = i % groups;
+    u32 word = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = lst[4 * g + j];
+      const u32 c = k >= 0 ? (u32)(uint8_t)q[(size_t)m * Kp + k] : 0u;
+      word |= c << (8 * j);
+    }
+    qp[m * qstride + g] = word;
+  }
+  __syncthreads();
+  if (tid < 4 * groups - L) lst[L + tid] = k_begin;       // (any valid channel: its code is 0)
+  __syncthreads();
 
   int acc[MV][16];
 #pragma unroll
@@ -969,10 +959,10 @@ __global__ __launch_bounds__(GD_THREADS) void gemv_sparse_kernel(
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[m][j] = 0;
 
-  for (int g = g_begin + wave * 2 + half; g < g_end; g += 8) {
+  for (int g = wave * 2 + half; g < groups; g += 8) {
     u32 w[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) w[r] = wbase[(size_t)list[4 * g + r] * 32];
+    for (int r = 0; r < 4; ++r) w[r] = wbase[(size_t)lst[4 * g + r] * 32];
     // 4x4 byte transpose: x[b] = byte b of (w0, w1, w2, w3)
     const u32 t01l = __builtin_amdgcn_perm(w[1], w[0], 0x05010400u);  // w0.b0 w1.b0 w0.b1 w1.b1
     const u32 t01h = __builtin_amdgcn_perm(w[1], w[0], 0x07030602u);  // w0.b2 w1.b2 w0.b3 w1.b3
@@ -985,7 +975,7 @@ __global__ __launch_bounds__(GD_THREADS) void gemv_sparse_kernel(
     x[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
     u32 qv[MV];
 #pragma unroll
-    for (int m = 0; m < MV; ++m) qv[m] = m < M ? qpack[(size_t)m * (Lmax >> 2) + g] : 0u;
+    for (int m = 0; m < MV; ++m) qv[m] = m < M ? qp[m * qstride + g] : 0u;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
 #pragma unroll
@@ -1048,12 +1038,12 @@ __global__ __launch_bounds__(GD_THREADS) void sparse_reduce_kernel(
 }
 
 #define GS_SPLIT 32
-static inline size_t gs_align(size_t x) { return (x + 255) & ~(size_t)255; }
+// channels per block: K dealt to GS_SPLIT slices, a multiple of 4
+static int gs_per(int64_t K) { return (int)(((K + GS_SPLIT - 1) / GS_SPLIT + 3) & ~(int64_t)3); }
 
 size_t bl_gemv_sparse_ws_bytes(int64_t M, int64_t N, int64_t K) {
-  const size_t Np = (size_t)bl_round_up(N, 512), Lmax = (size_t)bl_round_up(K, 4);
-  return gs_align(16) + gs_align(Lmax * 4) + gs_align((size_t)M * Lmax) +
-         gs_align((size_t)GS_SPLIT * M * Np * 4);
+  (void)K;
+  return (size_t)GS_SPLIT * M * bl_round_up(N, 512) * 4;          // integer partials
 }
 
 int bl_launch_gemv_sparse(const void* q, const float* scale, int64_t M, int64_t K,
@@ -1062,22 +1052,20 @@ int bl_launch_gemv_sparse(const void* q, const float* scale, int64_t M, int64_t 
   if (!ws) return BL_EWORKSPACE;
   if (M > 8) return BL_EUNSUPPORTED;
   const int Kp = (int)bl_round_up(K, BL_KPAD), Np = (int)bl_round_up(N, 512);
-  const int Lmax = (int)bl_round_up(K, 4);
-  unsigned char* p = (unsigned char*)ws;
-  int32_t* count = (int32_t*)p;            p += gs_align(16);
-  int32_t* list = (int32_t*)p;             p += gs_align((size_t)Lmax * 4);
-  u32* qpack = (u32*)p;                    p += gs_align((size_t)M * Lmax);
-  int32_t* partial = (int32_t*)p;
-  nz_union_kernel<<<1, GS_LIST_THREADS, 0, s>>>((const int8_t*)q, (int)M, (int)K, Kp, Lmax, count, list, qpack);
-  BL_HIP_CHECK_LAUNCH();
+  const int per = gs_per(K);
+  int32_t* partial = (int32_t*)ws;
   const int CB = Np >> 9;
   const unsigned grid = (unsigned)(CB * GS_SPLIT);
-  if (M <= 1)
-    gemv_sparse_kernel<1><<<grid, GD_THREADS, 0, s>>>((const u32*)Wk, Np, (int)K, count, list, qpack, Lmax, (int)M, GS_SPLIT, partial);
-  else if (M <= 4)
-    gemv_sparse_kernel<4><<<grid, GD_THREADS, 0, s>>>((const u32*)Wk, Np, (int)K, count, list, qpack, Lmax, (int)M, GS_SPLIT, partial);
-  else
-    gemv_sparse_kernel<8><<<grid, GD_THREADS, 0, s>>>((const u32*)Wk, Np, (int)K, count, list, qpack, Lmax, (int)M, GS_SPLIT, partial);
+  const int MV = M <= 1 ? 1 : M <= 4 ? 4 : 8;
+  const size_t smem = (size_t)(per + 4) * 4 + (size_t)MV * (per / 4 + 1) * 4;
+  if (smem > 48 * 1024) return BL_EUNSUPPORTED;           // K above 300000 channels
+#define GS_CALL(MVV)                                                                               \
+  gemv_sparse_kernel<MVV><<<grid, GD_THREADS, smem, s>>>((const u32*)Wk, Np, (int)K, Kp, (const int8_t*)q, \
+                                                        (int)M, GS_SPLIT, per, partial)
+  if (MV == 1) GS_CALL(1);
+  else if (MV == 4) GS_CALL(4);
+  else GS_CALL(8);
+#undef GS_CALL
   BL_HIP_CHECK_LAUNCH();
   const int64_t n_thr = M * ((N + 3) >> 2);
   sparse_reduce_kernel<<<(unsigned)((n_thr + GD_THREADS - 1) / GD_THREADS), GD_THREADS, 0, s>>>(
