@@ -205,6 +205,16 @@ int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M
 int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,
               void* H, void* stream);
 
+/* eq. 5 followed by eq. 1 / eq. 3 in one pass over G and U: the tokens that are quantized are the
+ * rows of H = bf16(U * max(G, 0)^2) as relu2_glu would write them, but H never goes to memory.
+ * Outputs as quantize_act with mode BL_ACT_TOPK_INT8_ABSMAX (same formats, bit for bit the same
+ * codes as relu2_glu followed by quantize_act).  G, U device [M, K] of in_dtype, 16-byte aligned;
+ * K % 4 == 0 and K <= 12288 (the rows are held in registers), otherwise BL_EUNSUPPORTED: then
+ * call relu2_glu and quantize_act.  rowsum_out nullable. */
+int quantize_act_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t K,
+                     int64_t topk, float eps, void* q_out, float* scale_out, int32_t* rowsum_out,
+                     void* stream);
+
 /* ---------------------------------------------------------------- format helpers
  * Expand packed data back to one int8 per element so that tests can compare codes
  * without knowing the byte order: T_out int8[N, K]; codes_out int8[M, K] (INT modes)

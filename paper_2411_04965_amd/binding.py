@@ -39,6 +39,7 @@ _SIGNATURES = {
     "bitlinear_gemm": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _int, _vp, _i64, _vp, _int, _vp,
                               _vp, _sz, _vp]),
     "relu2_glu": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _vp]),
+    "quantize_act_glu": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
     "unpack_ternary": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
     "unpack_act": (_int, [_vp, _int, _i64, _i64, _vp, _vp]),
     "bl_status_string": (ctypes.c_char_p, [_int]),
@@ -195,6 +196,20 @@ def bitlinear_gemm(q, scale, mode, M, K, W_packed, alpha, N, layout=BL_W_GEMM,
         _ptr(q), _ptr(scale), mode, M, K, _ptr(W_packed), layout, _ptr(alpha), N, _ptr(Y),
         _dt(Y), _ptr(acc), _ptr(ws), ws.numel(), _stream()))
     return (Y, acc) if want_acc else Y
+
+
+def quantize_act_glu(G, U, topk, eps=DEFAULT_EPS, want_rowsum=False):
+    """Rows of bf16(U * max(G, 0)^2) -> top-K + INT8 codes, without writing the rows out."""
+    _dev(G), _dev(U)
+    assert G.shape == U.shape and G.dtype == U.dtype
+    M, K = G.shape
+    L = lib()
+    q = torch.empty(L.quantize_act_bytes(BL_ACT_TOPK_INT8_ABSMAX, M, K), dtype=torch.uint8, device=G.device)
+    scale = torch.empty(M, dtype=torch.float32, device=G.device)
+    rowsum = torch.empty(M, dtype=torch.int32, device=G.device) if want_rowsum else None
+    _check("quantize_act_glu", L.quantize_act_glu(_ptr(G), _ptr(U), _dt(G), M, K, topk, eps, _ptr(q),
+                                                  _ptr(scale), _ptr(rowsum), _stream()))
+    return dict(q=q, scale=scale, rowsum=rowsum)
 
 
 def relu2_glu(G, U):

@@ -100,6 +100,19 @@ extern "C" int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t 
                             sel_idx_out, (hipStream_t)stream);
 }
 
+extern "C" int quantize_act_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t K,
+                                int64_t topk, float eps, void* q_out, float* scale_out,
+                                int32_t* rowsum_out, void* stream) {
+  if (!G || !U || !q_out || !scale_out) return BL_EINVAL;
+  if (!valid_dtype(in_dtype) || !(eps >= 0.0f)) return BL_EINVAL;
+  int rc = check_sizes(M, 1, K);
+  if (rc) return rc;
+  if (topk < 1 || topk > K) return BL_EINVAL;
+  if (!bl_aligned16(G) || !bl_aligned16(U) || !bl_aligned16(q_out)) return BL_EALIGN;
+  return bl_launch_quantize_glu(G, U, in_dtype, M, K, topk, eps, q_out, scale_out, rowsum_out,
+                                (hipStream_t)stream);
+}
+
 extern "C" int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K,
                           int8_t* codes_out, void* stream) {
   if (!q || !codes_out || !valid_mode(mode)) return BL_EINVAL;

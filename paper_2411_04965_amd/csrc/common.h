@@ -71,6 +71,8 @@ int bl_launch_pack_ternary(const void* W, bl_dtype dt, int64_t N, int64_t K, flo
                            bl_w_layout layout, void* out, float* alpha, void* ws, hipStream_t s);
 int bl_launch_unpack_ternary(const void* packed, int64_t N, int64_t K, bl_w_layout layout,
                              int8_t* T, hipStream_t s);
+int bl_launch_quantize_glu(const void* G, const void* U, bl_dtype dt, int64_t M, int64_t K, int64_t topk,
+                           float eps, void* q, void* scale, int32_t* rowsum, hipStream_t s);
 int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K, bl_act_mode mode,
                        int64_t topk, float eps, void* q, void* scale, int32_t* rowsum,
                        int32_t* sel_idx, hipStream_t s);

@@ -359,7 +359,7 @@ __global__ __launch_bounds__(GD_THREADS) void gemv_a8_fused_kernel(
   int t = wave;
   if (t < KT) load_group(t);
 
-  qa_topk_row_regs<CPW>(X, K, Kp, topk, eps, reinterpret_cast<u32*>(gf_smem), &dq, nullptr);
+  qa_topk_row_regs<CPW>(X, nullptr, K, Kp, topk, eps, reinterpret_cast<u32*>(gf_smem), &dq, nullptr);
   __syncthreads();
 
   v4i acc = (v4i){0, 0, 0, 0};

@@ -318,13 +318,17 @@ __global__ __launch_bounds__(NT) void quant_topk_int8_kernel(
 
 // ---------------------------------------------------------------- Top_k + INT8, keys in registers
 // (helpers and the four-wave body: topk_regs.h)
-template <int CPW>
+// GLU: 0 = X is the token matrix (bfloat16); 1 / 2 = the tokens are bf16(X2 * max(X, 0)^2) of a gate
+// matrix X and an up matrix X2, bfloat16 / float32 (eq. 5 folded into the load)
+template <int CPW, int GLU>
 __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
-    const uint16_t* __restrict__ X, int K, int Kp, int topk, float eps, u32* __restrict__ q_out,
-    float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out) {
+    const void* __restrict__ X, const void* __restrict__ X2, int K, int Kp, int topk, float eps,
+    u32* __restrict__ q_out, float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out) {
   const int64_t m = blockIdx.x;
-  qa_topk_row_regs<CPW>(X + m * (int64_t)K, K, Kp, topk, eps, q_out + m * (int64_t)(Kp / 4), scale_out + m,
-                        rowsum_out ? rowsum_out + m : nullptr);
+  const size_t row = (size_t)m * K * (GLU == 2 ? 4 : 2);
+  qa_topk_row_regs<CPW, GLU>(reinterpret_cast<const unsigned char*>(X) + row,
+                             GLU ? reinterpret_cast<const unsigned char*>(X2) + row : nullptr, K, Kp, topk, eps,
+                             q_out + m * (int64_t)(Kp / 4), scale_out + m, rowsum_out ? rowsum_out + m : nullptr);
 }
 
 // The same selection with one wave per token, for many tokens of moderate width: the fixed cost of a
@@ -332,9 +336,9 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
 // traffic and no barrier at all.  A lane holds up to 4 * NB chunks' worth of keys (NB blocks of 16
 // keys); a workgroup is four tokens.  (Wider rows need too many registers for that: one wave per
 // SIMD, or two waves per token, measured slower than the four-wave kernel above.)
-template <int NB>
+template <int NB, int GLU>
 __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
-    const uint16_t* __restrict__ X, int64_t M, int K, int Kp, int topk, float eps,
+    const void* __restrict__ X, const void* __restrict__ X2, int64_t M, int K, int Kp, int topk, float eps,
     u32* __restrict__ q_out, float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out) {
   constexpr int NC = 4 * NB;                              // chunks of 256 channels a lane can hold
   constexpr int NWD = (NB + 1) / 2;                       // mask words: 32 keys each
@@ -346,12 +350,14 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
 
   // one pass over the row: 4 consecutive channels (8 bytes) per lane and chunk, zero beyond K
   u32 raw[NC][2];
-  const uint16_t* x = X + m * (int64_t)K;
+  const size_t row = (size_t)m * K * (GLU == 2 ? 4 : 2);
+  const unsigned char* x = reinterpret_cast<const unsigned char*>(X) + row;
+  const unsigned char* x2 = GLU ? reinterpret_cast<const unsigned char*>(X2) + row : nullptr;
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
     uint2 v = make_uint2(0u, 0u);
     const int ch = (c_begin + i) * 256 + lane * 4;
-    if (i < nc && ch < K) v = *reinterpret_cast<const uint2*>(x + ch);   // K % 4 == 0 by dispatch
+    if (i < nc && ch < K) v = qa_load4<GLU>(x, x2, ch);       // K % 4 == 0 by dispatch
     raw[i][0] = v.x; raw[i][1] = v.y;
   }
   u32 kmax;
@@ -648,6 +654,40 @@ static int qa_run_row_kernels(const RawT* X, int64_t M, int K, int Kp, bl_act_mo
   return BL_OK;
 }
 
+// Top_k + INT8 with the keys in registers, one memory pass (K % 4 == 0, Kp <= 12288).
+template <int GLU>
+static int qa_run_topk_regs(const void* x, const void* x2, int64_t M, int K, int Kp, int topk, float eps,
+                            void* q, void* scale, int32_t* rowsum, hipStream_t s) {
+  const int cpw = (Kp / 256 + QA_WAVES - 1) / QA_WAVES;
+  // many tokens of up to 6144 channels: one wave per token (measured at 16384 tokens: 0.051 against
+  // 0.075 ms at 4096 channels, 0.077 against 0.110 ms at 5460; from 8 register blocks on it loses)
+  const int nb = (Kp / 256 + 3) / 4;
+  if (M >= 2048 && nb <= 6) {
+    const unsigned grid = (unsigned)((M + QA_WAVES - 1) / QA_WAVES);
+    if (nb <= 4)
+      quant_topk_int8_wave_kernel<4, GLU><<<grid, QA_THREADS, 0, s>>>(x, x2, M, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum);
+    else
+      quant_topk_int8_wave_kernel<6, GLU><<<grid, QA_THREADS, 0, s>>>(x, x2, M, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum);
+  } else if (cpw <= 4) {
+    quant_topk_int8_regs_kernel<4, GLU><<<(unsigned)M, QA_THREADS, 0, s>>>(x, x2, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum);
+  } else if (cpw <= 8) {
+    quant_topk_int8_regs_kernel<8, GLU><<<(unsigned)M, QA_THREADS, 0, s>>>(x, x2, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum);
+  } else {
+    quant_topk_int8_regs_kernel<12, GLU><<<(unsigned)M, QA_THREADS, 0, s>>>(x, x2, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum);
+  }
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}
+
+// eq. 5 + eq. 1 + eq. 3 in one pass: the tokens are bf16(U * max(G, 0)^2)
+int bl_launch_quantize_glu(const void* G, const void* U, bl_dtype dt, int64_t M, int64_t K64, int64_t topk,
+                           float eps, void* q, void* scale, int32_t* rowsum, hipStream_t s) {
+  const int K = (int)K64, Kp = (int)bl_round_up(K64, BL_KPAD);
+  if (K % 4 != 0 || Kp > 12288) return BL_EUNSUPPORTED;
+  return dt == BL_BF16 ? qa_run_topk_regs<1>(G, U, M, K, Kp, (int)topk, eps, q, scale, rowsum, s)
+                       : qa_run_topk_regs<2>(G, U, M, K, Kp, (int)topk, eps, q, scale, rowsum, s);
+}
+
 int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K64, bl_act_mode mode,
                        int64_t topk, float eps, void* q, void* scale, int32_t* rowsum,
                        int32_t* sel_idx, hipStream_t s) {
@@ -667,31 +707,8 @@ int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K64, bl_ac
     return BL_OK;
   }
   if (dt == BL_BF16 && mode == BL_ACT_TOPK_INT8_ABSMAX && K % 4 == 0 && Kp <= 12288 &&
-      sel_idx == nullptr) {
-    // keys in registers, one memory pass
-    const uint16_t* x = (const uint16_t*)X;
-    const int cpw = (Kp / 256 + QA_WAVES - 1) / QA_WAVES;
-    // many tokens of up to 6144 channels: one wave per token (measured at 16384 tokens: 0.051 against
-    // 0.075 ms at 4096 channels, 0.077 against 0.110 ms at 5460; from 8 register blocks on it loses)
-    const int nb = (Kp / 256 + 3) / 4;
-    if (M >= 2048 && nb <= 6) {
-      const unsigned grid = (unsigned)((M + QA_WAVES - 1) / QA_WAVES);
-      if (nb <= 4)
-        quant_topk_int8_wave_kernel<4><<<grid, QA_THREADS, 0, s>>>(x, M, K, Kp, (int)topk, eps, (u32*)q, (float*)scale, rowsum);
-      else
-        quant_topk_int8_wave_kernel<6><<<grid, QA_THREADS, 0, s>>>(x, M, K, Kp, (int)topk, eps, (u32*)q, (float*)scale, rowsum);
-      BL_HIP_CHECK_LAUNCH();
-      return BL_OK;
-    }
-    if (cpw <= 4)
-      quant_topk_int8_regs_kernel<4><<<(unsigned)M, QA_THREADS, 0, s>>>(x, K, Kp, (int)topk, eps, (u32*)q, (float*)scale, rowsum);
-    else if (cpw <= 8)
-      quant_topk_int8_regs_kernel<8><<<(unsigned)M, QA_THREADS, 0, s>>>(x, K, Kp, (int)topk, eps, (u32*)q, (float*)scale, rowsum);
-    else
-      quant_topk_int8_regs_kernel<12><<<(unsigned)M, QA_THREADS, 0, s>>>(x, K, Kp, (int)topk, eps, (u32*)q, (float*)scale, rowsum);
-    BL_HIP_CHECK_LAUNCH();
-    return BL_OK;
-  }
+      sel_idx == nullptr)
+    return qa_run_topk_regs<0>(X, nullptr, M, K, Kp, (int)topk, eps, q, scale, rowsum, s);
   if (dt == BL_BF16) {
     const uint16_t* x = (const uint16_t*)X;
     if (K % 8 == 0) return qa_run_row_kernels<uint16_t, 8>(x, M, K, Kp, mode, (int)topk, eps, q, scale, rowsum, sel_idx, s);

@@ -22,6 +22,36 @@ __device__ __forceinline__ int qa_wave_sum_dpp(int v) {
 
 #define QA_GUARD 0x80008000u
 
+// Four consecutive channels of a token as bfloat16 bit patterns (two words).  GLU = 0: the row
+// itself (`a`).  GLU = 1 / 2: the token is H = bf16(U * max(G, 0)^2) (eq. 5, float32 steps in that
+// order) of a gate row `a` and an up row `b`, bfloat16 / float32: the product never goes to memory.
+template <int GLU>
+__device__ __forceinline__ uint2 qa_load4(const void* a, const void* b, int ch) {
+  if (GLU == 0) return *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a) + ch);
+  float g[4], u[4];
+  if (GLU == 1) {
+    const uint2 gv = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a) + ch);
+    const uint2 uv = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(b) + ch);
+    g[0] = __uint_as_float(gv.x << 16); g[1] = __uint_as_float(gv.x & 0xFFFF0000u);
+    g[2] = __uint_as_float(gv.y << 16); g[3] = __uint_as_float(gv.y & 0xFFFF0000u);
+    u[0] = __uint_as_float(uv.x << 16); u[1] = __uint_as_float(uv.x & 0xFFFF0000u);
+    u[2] = __uint_as_float(uv.y << 16); u[3] = __uint_as_float(uv.y & 0xFFFF0000u);
+  } else {
+    const float4 gv = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a) + ch);
+    const float4 uv = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(b) + ch);
+    g[0] = gv.x; g[1] = gv.y; g[2] = gv.z; g[3] = gv.w;
+    u[0] = uv.x; u[1] = uv.y; u[2] = uv.z; u[3] = uv.w;
+  }
+  u32 h[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float r = fmaxf(g[j], 0.0f);
+    const float rr = r * r;
+    h[j] = bl_f32_to_bf16_rne(u[j] * rr);
+  }
+  return make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+}
+
 // Bit planes.  The search for tau looks at one bit of every key per pass, so the keys of a lane are
 // turned into bit planes once: 16 keys (8 words of two 16-bit rows) -> 16 planes of 16 bits (word
 // p / 2, half p % 2 holds bit p of the 16 keys, key r in bit r).  The usual recursive block swap, on
@@ -56,9 +86,9 @@ __device__ __forceinline__ void qa_bit_transpose16(u32 (&w)[8]) {
 // Body for one token and one workgroup of 4 waves: row x of K channels -> Kp / 4 code words at
 // `out`, the dequantization scale at `scale_out` (both may point into LDS), the sum of the codes at
 // `rowsum_out` if not null.  Every thread of the workgroup must call it (it has barriers).
-template <int CPW>
-__device__ __forceinline__ void qa_topk_row_regs(const uint16_t* __restrict__ x, int K, int Kp, int topk,
-                                                 float eps, u32* out, float* scale_out,
+template <int CPW, int GLU = 0>
+__device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, const void* __restrict__ x2, int K,
+                                                 int Kp, int topk, float eps, u32* out, float* scale_out,
                                                  int32_t* rowsum_out) {
   constexpr int NW = 4;
   __shared__ __align__(16) u32 sh_a[2][NW];
@@ -77,7 +107,7 @@ __device__ __forceinline__ void qa_topk_row_regs(const uint16_t* __restrict__ x,
   for (int i = 0; i < CPW; ++i) {
     uint2 v = make_uint2(0u, 0u);
     const int ch = (c_begin + i) * 256 + lane * 4;
-    if (i < nc && ch < K) v = *reinterpret_cast<const uint2*>(x + ch);   // K % 4 == 0 by dispatch
+    if (i < nc && ch < K) v = qa_load4<GLU>(x, x2, ch);      // K % 4 == 0 by dispatch
     raw[i][0] = v.x; raw[i][1] = v.y;
     pg[i][0] = v.x | QA_GUARD; pg[i][1] = v.y | QA_GUARD;
   }

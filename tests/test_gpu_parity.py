@@ -117,6 +117,28 @@ def test_quantize_topk_int8_many_tokens(kind, M, K, topk):
     assert np.array_equal(host(r["rowsum"])[rows], q_ref.sum(1, dtype=np.int32))
 
 
+@pytest.mark.parametrize("M,K,topk,dtype", [(9, 5460, 2730, F32), (2051, 5460, 2730, F32), (33, 11008, 5504, BF16),
+                                            (2050, 4096, 2048, BF16), (5, 1000, 1, BF16), (7, 12288, 12288, F32)])
+def test_quantize_glu_topk_int8(M, K, topk, dtype):
+    """eq. 5 folded into the top-K quantizer's load: codes, scales and code sums equal those of the
+    oracle's ReLU^2 GLU followed by its top-K + INT8 quantizer, and of the two separate kernels."""
+    say("quantize_act_glu M=%d K=%d topk=%d %s" % (M, K, topk, dtype))
+    g = S.heavy(M, K, S.seed_for(1, 70 + M))
+    u = S.heavy(M, K, S.seed_for(1, 71 + K))
+    g[0] = -np.abs(g[0])                                   # a token whose gate is closed everywhere
+    if dtype == BF16:
+        g, u = S.snap_bf16(g), S.snap_bf16(u)
+    rows = np.unique(np.concatenate([np.arange(0, M, 11), [0, M - 1]]))
+    h_ref = O.relu2_glu(g[rows], u[rows])
+    q_ref, d_ref, _ = O.quant_topk_int8(h_ref, topk, EPS)
+    r = B.quantize_act_glu(dev(g, dtype), dev(u, dtype), topk, EPS, want_rowsum=True)
+    assert np.array_equal(host(r["scale"])[rows], d_ref)
+    assert np.array_equal(decode_int8(host(r["q"]), M, K)[rows], q_ref)
+    assert np.array_equal(host(r["rowsum"])[rows], q_ref.sum(1, dtype=np.int32))
+    r2 = B.quantize_act(B.relu2_glu(dev(g, dtype), dev(u, dtype)), B.BL_ACT_TOPK_INT8_ABSMAX, topk, EPS)
+    assert torch.equal(r2["q"], r["q"]) and torch.equal(r2["scale"], r["scale"])
+
+
 @pytest.mark.parametrize("kind,M,K,dtype", [("gauss", 16, 256, F32), ("heavy", 20, 3200, BF16),
                                             ("glu", 6, 8640, BF16), ("ties", 9, 992, F32)])
 def test_quantize_fp4(kind, M, K, dtype):
