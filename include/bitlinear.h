@@ -42,6 +42,11 @@
  *               channel i of the unit in nibble i (low nibble of a byte first).  Used by the
  *               prefill GEMM of the INT4 path; twice the bytes of BL_W_GEMM.
  *
+ *   BL_W_ROWS   output-channel major: row n takes Kp/4 bytes at n * Kp/4; 32-bit word w of the
+ *               row holds channels 16w ... 16w+15, channel 16w + f in bits 2f, 2f+1 (so byte b of
+ *               the word holds channels 4b ... 4b+3).  A row can be fetched, or skipped, on its
+ *               own: the layout of the gate-first up projection (bitlinear_a4_up_gated).
+ *
  *   INT4 activations  [M][Kp/2] bytes.  Channels are taken 8 at a time into one
  *               32-bit word; byte b (0..3) of the word is (q[k0+b] & 15) | (q[k0+4+b] << 4).
  *   INT4 activations, MX6 form: the same 16 levels, each stored as its 6-bit E3M2 code
@@ -89,7 +94,7 @@ typedef enum {
   BL_ACT_FP4_E2M1_B32_MX = 4   /* eq. 8-9, codes and scales in the block order of the block-float GEMM */
 } bl_act_mode;
 
-typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1, BL_W_MX4 = 2 } bl_w_layout;
+typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1, BL_W_MX4 = 2, BL_W_ROWS = 3 } bl_w_layout;
 
 typedef enum {
   BL_OK = 0,
@@ -199,6 +204,22 @@ int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M
                    const void* W_packed, bl_w_layout layout, const float* alpha, int64_t N,
                    void* Y, bl_dtype y_dtype, int32_t* acc_out,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Gate-first up projection of the FFN for a few tokens (Section 2.1's observation that the up
+ * projection is only needed where the gate is open, eq. 5): with G = the gate projection's
+ * outputs, H[m, n] = bf16(U[m, n] * max(G[m, n], 0)^2) where U = the INT4 linear (eq. 6, eq. 7) of
+ * X with the up weights -- but row n of the weights is read, and U[., n] computed, only if
+ * G[m, n] > 0 for some token m; elsewhere H = +0.  U is kept in float32 (never rounded to
+ * bfloat16) before the product, float32 steps in the order of relu2_glu.
+ *   X        device, [M, K] bfloat16, M <= 4, K % 8 == 0, K <= 8192 and M * K <= 16384
+ *   W_rows   device, output of pack_ternary in layout BL_W_ROWS for [N, K]
+ *   alpha    device, float32[1]
+ *   G        device, [M, N] of g_dtype
+ *   H        device, [M, N] bfloat16, fully overwritten
+ * Other shapes: BL_EUNSUPPORTED (run bitlinear_a4 and relu2_glu). */
+int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const void* W_rows,
+                          const float* alpha, int64_t N, float eps, const void* G,
+                          bl_dtype g_dtype, void* H, void* stream);
 
 /* ReLU^2 GLU combine (eq. 5): H = bf16(U * max(G, 0)^2), float32 steps in that order.
  * G, U device [M, N] of in_dtype; H device [M, N] bfloat16. */

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libbitlinear.so")
 BL_F32, BL_BF16 = 0, 1
 BL_ACT_INT4_ABSMEAN, BL_ACT_TOPK_INT8_ABSMAX, BL_ACT_FP4_E2M1_B32, BL_ACT_INT4_ABSMEAN_MX6 = 0, 1, 2, 3
 BL_ACT_FP4_E2M1_B32_MX = 4
-BL_W_GEMM, BL_W_KMAJOR, BL_W_MX4 = 0, 1, 2
+BL_W_GEMM, BL_W_KMAJOR, BL_W_MX4, BL_W_ROWS = 0, 1, 2, 3
 BL_DECODE_MAX_M = 64
 DEFAULT_EPS = 1e-5
 
@@ -40,6 +40,7 @@ _SIGNATURES = {
                               _vp, _sz, _vp]),
     "relu2_glu": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _vp]),
     "quantize_act_glu": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
+    "bitlinear_a4_up_gated": (_int, [_vp, _i64, _i64, _vp, _vp, _i64, _f32, _vp, _int, _vp, _vp]),
     "unpack_ternary": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
     "unpack_act": (_int, [_vp, _int, _i64, _i64, _vp, _vp]),
     "bl_status_string": (ctypes.c_char_p, [_int]),
@@ -210,6 +211,17 @@ def quantize_act_glu(G, U, topk, eps=DEFAULT_EPS, want_rowsum=False):
     _check("quantize_act_glu", L.quantize_act_glu(_ptr(G), _ptr(U), _dt(G), M, K, topk, eps, _ptr(q),
                                                   _ptr(scale), _ptr(rowsum), _stream()))
     return dict(q=q, scale=scale, rowsum=rowsum)
+
+
+def bitlinear_a4_up_gated(X, W_rows, alpha, N, G, eps=DEFAULT_EPS):
+    """Gate-first up projection: H = bf16(U * max(G, 0)^2), U computed only where a gate is open."""
+    _dev(X), _dev(G)
+    assert X.dtype == torch.bfloat16
+    M, K = X.shape
+    H = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    _check("bitlinear_a4_up_gated", lib().bitlinear_a4_up_gated(
+        _ptr(X), M, K, _ptr(W_rows), _ptr(alpha), N, eps, _ptr(G), _dt(G), _ptr(H), _stream()))
+    return H
 
 
 def relu2_glu(G, U):

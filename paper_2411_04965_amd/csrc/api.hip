@@ -5,7 +5,7 @@
 static inline size_t ws_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static bool valid_dtype(int d) { return d == BL_F32 || d == BL_BF16; }
-static bool valid_layout(int l) { return l == BL_W_GEMM || l == BL_W_KMAJOR || l == BL_W_MX4; }
+static bool valid_layout(int l) { return l >= BL_W_GEMM && l <= BL_W_ROWS; }
 static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_FP4_E2M1_B32_MX; }
 static bool mx_mode(int m) { return m == BL_ACT_INT4_ABSMEAN_MX6 || m == BL_ACT_FP4_E2M1_B32_MX; }
 static bool fp4_mode(int m) { return m == BL_ACT_FP4_E2M1_B32 || m == BL_ACT_FP4_E2M1_B32_MX; }
@@ -39,6 +39,7 @@ extern "C" size_t pack_ternary_bytes(int64_t N, int64_t K, bl_w_layout layout) {
   if (layout == BL_W_GEMM) return (size_t)(bl_round_up(N, 16) * bl_round_up(K, BL_KPAD) / 4);
   if (layout == BL_W_KMAJOR) return (size_t)(bl_round_up(N, 512) / 4 * K);
   if (layout == BL_W_MX4) return (size_t)(bl_round_up(N, 32) * bl_round_up(K, BL_KPAD) / 2);
+  if (layout == BL_W_ROWS) return (size_t)(N * bl_round_up(K, BL_KPAD) / 4);
   return 0;
 }
 
@@ -144,6 +145,7 @@ static int gemm_dispatch(const void* q, const void* scale, bl_act_mode mode, int
                          void* Y, bl_dtype y_dtype, int32_t* acc_out, void* ws, size_t ws_bytes,
                          hipStream_t s) {
   // the block-float forms of activations and weights go together and with nothing else
+  if (layout == BL_W_ROWS) return BL_EUNSUPPORTED;       // only the gate-first up projection reads rows
   if (mx_mode(mode) != (layout == BL_W_MX4)) return BL_EINVAL;
   if (mode == BL_ACT_INT4_ABSMEAN_MX6)
     return bl_launch_gemm_a4_mx(q, (const float*)scale, M, K, W_packed, alpha, N, Y, y_dtype, acc_out, s);
@@ -208,6 +210,7 @@ static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, 
   if (mode == BL_ACT_FP4_E2M1_B32_MX && acc_out) return BL_EINVAL;
   if (mx_mode(mode) != (layout == BL_W_MX4)) return BL_EINVAL;
   if (layout == BL_W_KMAJOR && (mode != BL_ACT_TOPK_INT8_ABSMAX || M > 8)) return BL_EUNSUPPORTED;
+  if (layout == BL_W_ROWS) return BL_EUNSUPPORTED;
 
   // a few tokens: quantizer and product in one launch
   if (mode == BL_ACT_INT4_ABSMEAN && layout == BL_W_GEMM && x_dtype == BL_BF16 &&
@@ -255,6 +258,17 @@ extern "C" int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, i
                                    size_t workspace_bytes, void* stream) {
   return linear_common(X, x_dtype, M, K, BL_ACT_TOPK_INT8_ABSMAX, topk, W_packed, layout, alpha,
                        N, eps, Y, y_dtype, acc_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const void* W_rows,
+                                     const float* alpha, int64_t N, float eps, const void* G,
+                                     bl_dtype g_dtype, void* H, void* stream) {
+  if (!X || !W_rows || !alpha || !G || !H) return BL_EINVAL;
+  if (!valid_dtype(g_dtype) || !(eps >= 0.0f)) return BL_EINVAL;
+  int rc = check_sizes(M, N, K);
+  if (rc) return rc;
+  if (!bl_aligned16(X) || !bl_aligned16(W_rows)) return BL_EALIGN;
+  return bl_launch_up_gated(X, M, K, eps, W_rows, alpha, N, G, g_dtype, H, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------- ReLU^2 GLU (eq. 5)

@@ -86,6 +86,8 @@ int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, i
                           bl_dtype ydt, int32_t* acc_out, void* ws, hipStream_t s);
 size_t bl_gemm_decode_ws_bytes(int64_t M, int64_t N, int64_t K);
 bool bl_gemv_a4_fused_ok(int64_t M, int64_t N, int64_t K);
+int bl_launch_up_gated(const void* X, int64_t M, int64_t K, float eps, const void* Wr, const float* alpha,
+                       int64_t N, const void* G, bl_dtype gdt, void* H, hipStream_t s);
 bool bl_gemv_a8_fused_ok(int64_t M, int64_t N, int64_t K);
 int bl_launch_gemv_a8_fused(const void* X, int64_t K, int64_t topk, float eps, const void* Wp,
                             const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,

@@ -207,34 +207,15 @@ __device__ __forceinline__ double gf_wave_sum_f64(double v) {
   return t;
 }
 
-__global__ __launch_bounds__(GD_THREADS) void gemv_a4_fused_kernel(
-    const uint16_t* __restrict__ X, int M, int K, int Kp, float eps,
-    const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
-    void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out) {
-  extern __shared__ __align__(16) unsigned char gf_smem[];
-  unsigned char* codes = gf_smem;                                  // [M][Kp] int8
+// eq. 7 for up to 4 bfloat16 token rows by one workgroup of 256 threads: int8 codes to `codes`
+// ([M][Kp], LDS), the dequantization scales beta / sqrt(7) to dq (the same in every thread).  The
+// rows are read 8 channels per piece, pieces tid, tid + 256, ... of every token (zero beyond K;
+// K % 8 == 0, K <= 8192), all loads in flight together; beta = mean |x| comes from the registers
+// (float64 sums, exact, so their order does not matter).  Ends with a barrier.
+__device__ __forceinline__ void gf_quantize_rows(const uint16_t* __restrict__ X, int M, int K, int Kp,
+                                                 float eps, unsigned char* codes, float (&dq)[4]) {
   __shared__ double red[4][GD_THREADS / 64];
-  __shared__ __align__(16) v4i wsum[GD_THREADS / 64][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int li = lane & 15, lg = lane >> 4;
-  const int KT = Kp >> 8;
-  const int nt = blockIdx.x;                     // grid = tiles of 16 outputs
-  const unsigned char* w_src = Wp + (size_t)nt * KT * 1024 + lane * 16;
-
-  // weights first: tiles wave, wave + 4, ... in groups of 4 (the next group is fetched while one
-  // is multiplied)
-  constexpr int UNR = 4;
-  uint4 wr[UNR];
-  auto load_group = [&](int t) {
-#pragma unroll
-    for (int u = 0; u < UNR; ++u)
-      wr[u] = *reinterpret_cast<const uint4*>(w_src + (size_t)min(t + 4 * u, KT - 1) * 1024);
-  };
-  int t = wave;
-  if (t < KT) load_group(t);
-
-  // the rows, 8 channels per piece, pieces tid, tid + 256, ... of every token (zero beyond K; K % 8
-  // == 0 by dispatch), all loads in flight together; beta = mean |x| per token from the registers
   uint4 xr[4][GF_NV];
   const int nv = K >> 3;
 #pragma unroll
@@ -264,7 +245,6 @@ __global__ __launch_bounds__(GD_THREADS) void gemv_a4_fused_kernel(
   }
   __syncthreads();
   const float sqrt7 = 2.6457512f;                // float32(sqrt(7))
-  float dq[4];
   // codes: RoundClip(x * s, -8, 7), eight to a piece
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
@@ -293,6 +273,36 @@ __global__ __launch_bounds__(GD_THREADS) void gemv_a4_fused_kernel(
     }
   }
   __syncthreads();
+
+}
+
+__global__ __launch_bounds__(GD_THREADS) void gemv_a4_fused_kernel(
+    const uint16_t* __restrict__ X, int M, int K, int Kp, float eps,
+    const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
+    void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out) {
+  extern __shared__ __align__(16) unsigned char gf_smem[];
+  unsigned char* codes = gf_smem;                                  // [M][Kp] int8
+  __shared__ __align__(16) v4i wsum[GD_THREADS / 64][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lg = lane >> 4;
+  const int KT = Kp >> 8;
+  const int nt = blockIdx.x;                     // grid = tiles of 16 outputs
+  const unsigned char* w_src = Wp + (size_t)nt * KT * 1024 + lane * 16;
+
+  // weights first: tiles wave, wave + 4, ... in groups of 4 (the next group is fetched while one
+  // is multiplied)
+  constexpr int UNR = 4;
+  uint4 wr[UNR];
+  auto load_group = [&](int t) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      wr[u] = *reinterpret_cast<const uint4*>(w_src + (size_t)min(t + 4 * u, KT - 1) * 1024);
+  };
+  int t = wave;
+  if (t < KT) load_group(t);
+
+  float dq[4];
+  gf_quantize_rows(X, M, K, Kp, eps, codes, dq);
 
   // lane (li, lg) holds, for token li, the 64 channels lg * 64 .. of a tile, 16 per MFMA step
   v4i acc = (v4i){0, 0, 0, 0};
@@ -331,6 +341,118 @@ __global__ __launch_bounds__(GD_THREADS) void gemv_a4_fused_kernel(
   const int iv[4] = {sum[0] >> 6, sum[1] >> 6, sum[2] >> 6, sum[3] >> 6};
   const float d = m == 0 ? dq[0] : m == 1 ? dq[1] : m == 2 ? dq[2] : dq[3];
   gd_store4(Y, y_bf16, acc_out, (size_t)m * N + n, n, N, iv, d, alpha_p[0]);
+}
+
+// Gate-first up projection for a few tokens: U = INT4 linear of X with row-addressable weights
+// (BL_W_ROWS), computed only for the outputs whose gate is open for some token, and combined with
+// the gate at once: H = bf16(U * max(G, 0)^2) (eq. 5).  Every block quantizes the tokens itself
+// (as above), takes NPB consecutive outputs, lists the open ones in LDS and deals them to its
+// waves; a wave reads one weight row per pass (16 bytes = 64 channels per lane and 1 KB chunk),
+// the lane's token codes stay in registers, byte-transposed once so that v_dot4 pairs four
+// channels 4 apart (the fields of one bit position of a weight word) with their codes.
+template <int MV, int NCH>
+__global__ __launch_bounds__(GD_THREADS) void up_gated_kernel(
+    const uint16_t* __restrict__ X, int M, int K, int Kp, float eps, const u32* __restrict__ Wr,
+    const float* __restrict__ alpha_p, int N, const void* __restrict__ G, int g_f32,
+    uint16_t* __restrict__ H, int NPB) {
+  extern __shared__ __align__(16) unsigned char gf_smem[];
+  unsigned char* codes = gf_smem;                                  // [M][Kp] int8
+  __shared__ int lst[GD_THREADS];
+  __shared__ int wave_cnt[GD_THREADS / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float dq[4];
+  gf_quantize_rows(X, M, K, Kp, eps, codes, dq);
+
+  // this lane's codes: chunk c covers channels 4096 c + 64 lane ... + 63; word w of a chunk's
+  // 16-byte weight piece covers 16 of them, xq[..][w][j] = codes of channels j, 4+j, 8+j, 12+j of those
+  u32 xq[MV][NCH][4][4];
+#pragma unroll
+  for (int m = 0; m < MV; ++m)
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int ch = 4096 * c + 64 * lane;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (m < M && ch < Kp) v = *reinterpret_cast<const uint4*>(codes + (size_t)m * Kp + ch + 16 * w);
+        const u32 t01l = __builtin_amdgcn_perm(v.y, v.x, 0x05010400u);  // x.b0 y.b0 x.b1 y.b1
+        const u32 t01h = __builtin_amdgcn_perm(v.y, v.x, 0x07030602u);
+        const u32 t23l = __builtin_amdgcn_perm(v.w, v.z, 0x05010400u);
+        const u32 t23h = __builtin_amdgcn_perm(v.w, v.z, 0x07030602u);
+        xq[m][c][w][0] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);   // bytes 0 of x, y, z, w
+        xq[m][c][w][1] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
+        xq[m][c][w][2] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
+        xq[m][c][w][3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
+      }
+    }
+
+  // the block's outputs: open gates listed, closed ones written as zero
+  const int n_begin = blockIdx.x * NPB, n_end = min(n_begin + NPB, N);    // NPB <= 256
+  auto gate = [&](int m, int n) -> float {
+    return g_f32 ? reinterpret_cast<const float*>(G)[(size_t)m * N + n]
+                 : bl_bf16_to_f32(reinterpret_cast<const uint16_t*>(G)[(size_t)m * N + n]);
+  };
+  {
+    const int n = n_begin + tid;
+    bool open = false;
+    if (n < n_end)
+      for (int m = 0; m < M; ++m) open |= gate(m, n) > 0.0f;
+    const uint64_t bal = __ballot(open);
+    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+    if (open) lst[before + __popcll(bal & ((1ull << lane) - 1ull))] = n;
+    if (n < n_end && !open)
+      for (int m = 0; m < M; ++m) H[(size_t)m * N + n] = 0;
+    __syncthreads();
+  }
+  const int L = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+  const float alpha = alpha_p[0];
+  const int wpr = Kp >> 4;                       // words per weight row
+  auto load_row = [&](int idx, uint4 (&wv)[NCH]) {
+    const u32* row = Wr + (size_t)lst[min(idx, L - 1)] * wpr;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      wv[c] = make_uint4(0u, 0u, 0u, 0u);
+      if (1024 * c + 16 * lane < (Kp >> 2)) wv[c] = *reinterpret_cast<const uint4*>(row + 256 * c + 4 * lane);
+    }
+  };
+  uint4 wn[NCH];
+  if (wave < L) load_row(wave, wn);
+  for (int idx = wave; idx < L; idx += GD_THREADS / 64) {
+    uint4 wc[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) wc[c] = wn[c];
+    if (idx + GD_THREADS / 64 < L) load_row(idx + GD_THREADS / 64, wn);
+    int acc[MV];
+#pragma unroll
+    for (int m = 0; m < MV; ++m) acc[m] = 0;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const u32 ww[4] = {wc[c].x, wc[c].y, wc[c].z, wc[c].w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const u32 tw = (ww[w] << (6 - 2 * j)) & 0xC0C0C0C0u;     // channels j, 4+j, 8+j, 12+j, times 64
+#pragma unroll
+          for (int m = 0; m < MV; ++m) acc[m] = __builtin_amdgcn_sdot4((int)tw, (int)xq[m][c][w][j], acc[m], false);
+        }
+    }
+    const int n = lst[idx];
+#pragma unroll
+    for (int m = 0; m < MV; ++m) {
+      const int tot = qa_wave_sum_dpp(acc[m]) >> 6;
+      if (m < M && lane == 0) {
+        const float d = m == 0 ? dq[0] : m == 1 ? dq[1] : m == 2 ? dq[2] : dq[3];
+        const float u = ((float)tot * d) * alpha;
+        const float r = fmaxf(gate(m, n), 0.0f);
+        const float rr = r * r;
+        H[(size_t)m * N + n] = bl_f32_to_bf16_rne(u * rr);
+      }
+    }
+  }
 }
 
 // One token, top-K + INT8 activations: eq. 1 and eq. 3 inside the same launch, for the same reason.
@@ -848,6 +970,34 @@ int bl_launch_gemv_a4_fused(const void* X, int64_t M, int64_t K, float eps, cons
   gemv_a4_fused_kernel<<<(unsigned)((N + 15) / 16), GD_THREADS, smem, s>>>(
       (const uint16_t*)X, (int)M, (int)K, Kp, eps, (const unsigned char*)Wp, alpha, (int)N, Y,
       ydt == BL_BF16 ? 1 : 0, acc_out);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}
+
+int bl_launch_up_gated(const void* X, int64_t M, int64_t K, float eps, const void* Wr, const float* alpha,
+                       int64_t N, const void* G, bl_dtype gdt, void* H, hipStream_t s) {
+  const int Kp = (int)bl_round_up(K, BL_KPAD);
+  if (M > 4 || K % 8 != 0 || Kp > 8 * GD_THREADS * GF_NV || M * Kp > 16384) return BL_EUNSUPPORTED;
+  const int nch = (Kp + 4095) / 4096;            // 1 KB chunks of a weight row: 1 or 2
+  const int mv = M <= 1 ? 1 : M <= 2 ? 2 : 4;
+  // outputs per block: about two blocks per CU, at most one output per thread
+  int npb = (int)((N + 2 * gd_num_cus() - 1) / (2 * gd_num_cus()));
+  npb = max(16, min(GD_THREADS, npb));
+  const unsigned grid = (unsigned)((N + npb - 1) / npb);
+  const size_t smem = (size_t)M * Kp;
+#define GU_CALL(MVV, NCHH)                                                                             \
+  up_gated_kernel<MVV, NCHH><<<grid, GD_THREADS, smem, s>>>((const uint16_t*)X, (int)M, (int)K, Kp, eps, \
+                                                          (const u32*)Wr, alpha, (int)N, G,            \
+                                                          gdt == BL_F32 ? 1 : 0, (uint16_t*)H, npb)
+  if (nch == 1) {
+    if (mv == 1) GU_CALL(1, 1);
+    else if (mv == 2) GU_CALL(2, 1);
+    else GU_CALL(4, 1);
+  } else {
+    if (mv == 1) GU_CALL(1, 2);
+    else GU_CALL(2, 2);                          // (M * Kp <= 16384: at most 2 tokens here)
+  }
+#undef GU_CALL
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;
 }

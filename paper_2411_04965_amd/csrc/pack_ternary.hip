@@ -144,6 +144,27 @@ __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_mx4_kernel(
   out[w] = word;
 }
 
+// One thread per 32-bit word of the output-channel-major layout: row n, channels 16 w .. 16 w + 15,
+// channel 16 w + f in bits 2 f, 2 f + 1.
+template <typename T>
+__global__ __launch_bounds__(PT_THREADS) void ternarize_pack_rows_kernel(
+    const T* __restrict__ W, int64_t N, int64_t K, int64_t Kp, float eps,
+    const double* __restrict__ partial, int n_partial, u32* __restrict__ out,
+    float* __restrict__ alpha_out, int64_t n_words) {
+  __shared__ double red[PT_THREADS / BL_WAVE];
+  const float alpha = pt_alpha(partial, n_partial, N * K, red);
+  if (blockIdx.x == 0 && threadIdx.x == 0) alpha_out[0] = alpha;
+  const float t = alpha + eps;
+  const int64_t w = (int64_t)blockIdx.x * PT_THREADS + threadIdx.x;
+  if (w >= n_words) return;
+  const int64_t wpr = Kp / 16, n = w / wpr, k0 = (w % wpr) * 16;
+  u32 word = 0;
+#pragma unroll
+  for (int f = 0; f < 16; ++f)
+    if (k0 + f < K) word |= pt_code(pt_load<T>(W, n * K + k0 + f), t) << (2 * f);
+  out[w] = word;
+}
+
 __global__ __launch_bounds__(PT_THREADS) void unpack_ternary_kernel(const u32* __restrict__ packed,
                                                                     int64_t N, int64_t K,
                                                                     int64_t Kp, int64_t Np,
@@ -161,7 +182,10 @@ __global__ __launch_bounds__(PT_THREADS) void unpack_ternary_kernel(const u32* _
     T[id] = (int8_t)(c == 0 ? 0 : ((c & 8u) ? -1 : 1));
     return;
   }
-  if (layout == BL_W_GEMM) {
+  if (layout == BL_W_ROWS) {
+    word = packed[n * (Kp / 16) + (k >> 4)];
+    f = (int)(k & 15);
+  } else if (layout == BL_W_GEMM) {
     const int64_t nt = n >> 4, kt = k >> 8;
     const int i = (int)(n & 15), g = (int)((k >> 6) & 3), t = (int)((k >> 4) & 3);
     const int kk = (int)(k & 15);
@@ -200,6 +224,12 @@ static int pt_run(const T* W, int64_t N, int64_t K, float eps, bl_w_layout layou
     const int64_t n_words = Np * Kp / 8;
     const int64_t blocks = (n_words + PT_THREADS - 1) / PT_THREADS;
     ternarize_pack_mx4_kernel<T><<<(unsigned)blocks, PT_THREADS, 0, s>>>(
+        W, N, K, Kp, eps, partial, np, (u32*)out, alpha, n_words);
+  } else if (layout == BL_W_ROWS) {
+    const int64_t Kp = bl_round_up(K, BL_KPAD);
+    const int64_t n_words = N * Kp / 16;
+    const int64_t blocks = (n_words + PT_THREADS - 1) / PT_THREADS;
+    ternarize_pack_rows_kernel<T><<<(unsigned)blocks, PT_THREADS, 0, s>>>(
         W, N, K, Kp, eps, partial, np, (u32*)out, alpha, n_words);
   } else if (layout == BL_W_GEMM) {
     const int64_t Kp = bl_round_up(K, BL_KPAD), Np = bl_round_up(N, 16);

@@ -84,6 +84,17 @@ def decode_w_mx4(packed, N, K):
     return full[:N, :K]
 
 
+def decode_w_rows(packed, N, K):
+    """BL_W_ROWS bytes -> int8 [N, K]: row n = Kp/4 bytes, channel k in bits 2 (k % 16) of word k / 16."""
+    Kp = (K + 255) // 256 * 256
+    w = np.frombuffer(packed.tobytes(), dtype="<u4").reshape(N, Kp // 16)
+    f = np.arange(16, dtype=np.uint32)
+    c = ((w[:, :, None] >> (2 * f)) & 3).reshape(N, Kp).astype(np.int8)
+    T = np.where(c == 3, -1, c).astype(np.int8)
+    assert not (c == 2).any() and not T[:, K:].any()
+    return T[:, :K]
+
+
 def decode_int4_mx6(q, M, K):
     """INT4 levels in the MX6 form (E3M2 codes, 32-token blocks) -> int8 [M, K]."""
     Kp = (K + 255) // 256 * 256

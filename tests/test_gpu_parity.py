@@ -10,7 +10,7 @@ from oracle import bitnet_a48 as O
 from paper_2411_04965_amd import binding as B
 from paper_2411_04965_amd import synth as S
 from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_fp4_mx, decode_int4, decode_int4_mx6,
-                            decode_int8, decode_w_gemm, decode_w_kmajor, decode_w_mx4, dev, host,
+                            decode_int8, decode_w_gemm, decode_w_kmajor, decode_w_mx4, decode_w_rows, dev, host,
                             pack)
 
 pytestmark = pytest.mark.gpu
@@ -25,7 +25,7 @@ def say(msg):
 # ------------------------------------------------------------------ pack_ternary (eq. 2)
 @pytest.mark.parametrize("N,K,dtype", [(512, 256, F32), (256, 512, F32), (37, 100, F32),
                                        (1030, 5460, BF16), (2048, 5460, F32)])
-@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_KMAJOR, B.BL_W_MX4])
+@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_KMAJOR, B.BL_W_MX4, B.BL_W_ROWS])
 def test_pack_ternary(N, K, dtype, layout):
     say("pack_ternary N=%d K=%d %s layout=%d" % (N, K, dtype, layout))
     W = S.latent_weights(N, K, seed=S.seed_for(0, N + K))
@@ -36,7 +36,8 @@ def test_pack_ternary(N, K, dtype, layout):
     assert host(alpha)[0] == alpha_ref
     T_lib = host(B.unpack_ternary(packed, N, K, layout))
     assert np.array_equal(T_lib, T_ref)
-    dec = {B.BL_W_GEMM: decode_w_gemm, B.BL_W_KMAJOR: decode_w_kmajor, B.BL_W_MX4: decode_w_mx4}[layout]
+    dec = {B.BL_W_GEMM: decode_w_gemm, B.BL_W_KMAJOR: decode_w_kmajor, B.BL_W_MX4: decode_w_mx4,
+           B.BL_W_ROWS: decode_w_rows}[layout]
     assert np.array_equal(dec(host(packed), N, K), T_ref)
 
 
@@ -327,6 +328,29 @@ def test_decode_fused_topk_int8(kind, N, K, topk):
         X = _x(kind, 4, K, S.seed_for(2, 600 + K), BF16)[row:row + 1]
         ref = O.bitlinear_a8_sparse(X, W, topk, EPS, "f32")
         _check_linear(B.bitlinear_a8_sparse(dev(X, BF16), topk, p, a, N, EPS, B.BL_W_GEMM, F32, True), ref, F32)
+
+
+@pytest.mark.parametrize("M,N,K,gdt", [(1, 11008, 4096, F32), (4, 11008, 4096, BF16), (2, 1000, 8192, F32),
+                                       (3, 5460, 2048, F32), (1, 37, 256, BF16), (2, 2050, 1000, F32)])
+def test_up_gated(M, N, K, gdt):
+    """Gate-first up projection (decode): H = bf16(U * max(G, 0)^2) with the rows of the up weights
+    read only where some token's gate is open, against the oracle's dense up projection followed
+    by its ReLU^2 GLU (zeros compare equal whatever their sign)."""
+    say("up gated M=%d N=%d K=%d %s" % (M, N, K, gdt))
+    X = S.heavy(M, K, S.seed_for(2, 700 + M))
+    Wg = S.latent_weights(N, K, S.seed_for(2, 701 + N))
+    Wu = S.latent_weights(N, K, S.seed_for(2, 702 + K))
+    g = O.bitlinear_a4(X, Wg, EPS, "f32" if gdt == F32 else "bf16")["y"]
+    u = O.bitlinear_a4(X, Wu, EPS, "f32")["y"]
+    h_ref = O.relu2_glu(g, u)
+    pu, au = pack(Wu, B.BL_W_ROWS)
+    G = dev(g, gdt)
+    assert np.array_equal(host(G).astype(np.float32), g.astype(np.float32))
+    Hh = B.bitlinear_a4_up_gated(dev(X, BF16), pu, au, N, G, EPS)
+    assert np.array_equal(host(Hh), h_ref)
+    closed = ~(g > 0).any(axis=0)
+    assert closed.any() or N < 64                          # the case does skip rows
+    assert not host(Hh)[:, closed].any()
 
 
 # ------------------------------------------------------------------ full prefill size (config 3), sampled rows
