@@ -1,8 +1,11 @@
 // Per-token activation quantizers of BitNet a4.8:
 //   INT4 absmean (eq. 7), Top_k + INT8 absmax (eq. 1, eq. 3), FP4 E2M1 MinMax with one
 //   power-of-two scale per 32 channels (eq. 8-9).
-// One workgroup handles one token: the row is read from HBM once, kept in LDS, and every
-// later pass (statistics, selection, coding) runs out of LDS.
+// A token is read from HBM once.  INT4: one workgroup per token, the row kept in LDS.  Top_k + INT8:
+// the row in registers (four waves per token, or one wave per token for many tokens of moderate
+// width; topk_regs.h), optionally formed on the fly as the ReLU^2 GLU product of two rows (eq. 5);
+// an LDS-resident kernel for everything the register kernels do not take (float32 rows, index
+// lists, very wide rows).  FP4: one thread per block of 32 channels.
 #include "common.h"
 #include "topk_regs.h"
 
