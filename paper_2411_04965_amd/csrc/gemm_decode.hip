@@ -177,7 +177,7 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
   }
 }
 
-// Up to 4 tokens, INT4 activations: eq. 7 inside the same launch.  Every block quantizes the
+// One token (the kernel takes up to 4), INT4 activations: eq. 7 inside the same launch.  Every block quantizes the
 // tokens itself (their rows are a few KB and come out of the cache; the statistics and the codes
 // take a few hundred instructions per thread), which saves the quantizer's launch: at these sizes a
 // launch costs as much as streaming the weights.  The arithmetic is that of the stand-alone
@@ -954,11 +954,14 @@ static int gr_run(const void* q, const float* scale, int M, int Kp, const void* 
   return S > 1 ? gd_reduce(S, M, N, A4 ? 10 : 6, scale, alpha, Y, ybf, acc_out, ws, s) : BL_OK;
 }
 
-// The fused INT4 linear is used for bfloat16 rows of up to 4 tokens when the one-tile-per-block
-// kernel would be (enough output tiles) and the rows are 16-byte aligned and at most 8192 channels long.
+// The fused INT4 linear is used for one bfloat16 token when the one-tile-per-block kernel would be
+// (enough output tiles) and the row is 16-byte aligned and at most 8192 channels long.  (The kernel
+// takes up to 4 tokens, but every block quantizes every token: measured per projection at 7B width,
+// HIP-graph replays, fused against two launches: 7.6 / 8.9 us at one token, 9.2 / 9.1 at two,
+// 12.0 / 9.1 at four.)
 bool bl_gemv_a4_fused_ok(int64_t M, int64_t N, int64_t K) {
   const int64_t Kp = bl_round_up(K, BL_KPAD);
-  return M <= 4 && gd_single_tile((int)M, (int)N) && K % 8 == 0 && Kp <= 8 * GD_THREADS * GF_NV;
+  return M == 1 && gd_single_tile((int)M, (int)N) && K % 8 == 0 && Kp <= 8 * GD_THREADS * GF_NV;
 }
 
 int bl_launch_gemv_a4_fused(const void* X, int64_t M, int64_t K, float eps, const void* Wp,

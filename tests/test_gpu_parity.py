@@ -302,10 +302,12 @@ def test_decode_odd_shapes(M):
         _check_linear(B.bitlinear_a8_sparse(dev(X, BF16), 700, pk, ak, N, EPS, B.BL_W_KMAJOR, F32, True), ref, F32)
 
 
-@pytest.mark.parametrize("M,N,K", [(2, 2064, 1500), (3, 4096, 2056), (4, 2050, 4096), (1, 2048, 256)])
+@pytest.mark.parametrize("M,N,K", [(1, 2064, 1504), (1, 4096, 2056), (1, 2050, 4096), (1, 2048, 256), (1, 2048, 8192),
+                                   (2, 2064, 1500), (4, 2050, 4096)])
 def test_decode_fused_int4(M, N, K):
-    """Up to 4 tokens with at least 128 output tiles: eq. 7 runs inside the GEMV launch.  Rows that
-    are 8- and 16-byte aligned, K with and without a ragged last tile, N ragged."""
+    """One token with at least 128 output tiles: eq. 7 runs inside the GEMV launch (K with and
+    without a ragged last tile, N ragged, the widest row it takes); two and four tokens, and a row
+    that is only 8-byte aligned, take the two-launch path."""
     say("decode fused int4 M=%d N=%d K=%d" % (M, N, K))
     X = S.heavy(M, K, S.seed_for(2, 500 + M))
     W = S.latent_weights(N, K, S.seed_for(2, 501 + N))
