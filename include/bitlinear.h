@@ -91,7 +91,9 @@ typedef enum {
   BL_ACT_TOPK_INT8_ABSMAX = 1, /* eq. 1 + eq. 3 */
   BL_ACT_FP4_E2M1_B32 = 2,     /* eq. 8-9 with one power-of-two scale per 32 channels */
   BL_ACT_INT4_ABSMEAN_MX6 = 3, /* eq. 7, levels stored as E3M2 codes for the block-float GEMM */
-  BL_ACT_FP4_E2M1_B32_MX = 4   /* eq. 8-9, codes and scales in the block order of the block-float GEMM */
+  BL_ACT_FP4_E2M1_B32_MX = 4,  /* eq. 8-9, codes and scales in the block order of the block-float GEMM */
+  BL_ACT_INT4_ABSMEAN2 = 5,    /* eq. 7 with beta = 2 mean|x| (ablation: inputs to the down projection) */
+  BL_ACT_INT4_ABSMAX = 6       /* 4-bit absmax, the form of eq. 3 with 7 in place of 127 (ablation) */
 } bl_act_mode;
 
 typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1, BL_W_MX4 = 2, BL_W_ROWS = 3 } bl_w_layout;
@@ -131,6 +133,9 @@ int pack_ternary(const void* W, bl_dtype w_dtype, int64_t N, int64_t K, float ep
  *   BL_ACT_INT4_ABSMEAN (eq. 7):  beta = mean|x| (float64 sum, rounded once);
  *       q = RoundClip(x * (sqrt7 / (beta + eps)), -8, 7);  scale_out[m] = beta / sqrt7.
  *   BL_ACT_INT4_ABSMEAN_MX6: the same quantizer, codes in the MX6 form (for BL_W_MX4 weights).
+ *   BL_ACT_INT4_ABSMEAN2 (Section 4.3): eq. 7 with beta = 2 mean|x|; BL_ACT_INT4_ABSMAX (Section 4.3):
+ *       gamma = max|x|; q = RoundClip(x * (7 / (gamma + eps)), -8, 7); scale_out[m] = gamma / 7.
+ *       Both write the INT4 nibble form; the linear layers take their output as BL_ACT_INT4_ABSMEAN's.
  *   BL_ACT_TOPK_INT8_ABSMAX (eq. 1, 3): mask = the `topk` largest |x| of the token
  *       (exactly topk entries; equal magnitudes: lower channel first; 1 <= topk <= K,
  *       topk = K is the dense INT8 quantizer); gamma = max|x|;

@@ -86,6 +86,28 @@ def quant_int4(X, eps=DEFAULT_EPS):
     return q, d
 
 
+def quant_int4_variant(X, eps=DEFAULT_EPS, kind="absmean2"):
+    """The two other INT4 quantizers of the ablations (Section 4.3), per token.
+
+    "absmean2": eq. 7 with beta = 2 mean|X| (used there for the inputs to the down projection);
+    "absmax":   the absmax form of eq. 3 at 4 bits, gamma/7 * RoundClip(7/(gamma+eps) * X, -8, 7),
+                gamma = max|X| (the paper names the quantizer without printing it).
+    Returns (q int8 [M, K] in [-8, 7], d float32 [M] = the dequantization scale)."""
+    X = np.asarray(X, dtype=F32)
+    if kind == "absmean2":
+        beta = (F32(2) * _mean_abs_f32(X, axis=1)).astype(F32)
+        s = (SQRT7 / (beta + F32(eps)).astype(F32)).astype(F32)
+        d = (beta / SQRT7).astype(F32)
+    elif kind == "absmax":
+        gamma = np.max(np.abs(X), axis=1).astype(F32)
+        s = (F32(7) / (gamma + F32(eps)).astype(F32)).astype(F32)
+        d = (gamma / F32(7)).astype(F32)
+    else:
+        raise ValueError(kind)
+    q = round_clip((X * s[:, None]).astype(F32), -8, 7).astype(np.int8)
+    return q, d
+
+
 def topk_mask(X, k_sel):
     """M = Top_k(|X|) per token  (eq. 1): exactly k_sel ones per row.
 

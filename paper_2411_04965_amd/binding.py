@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libbitlinear.so")
 BL_F32, BL_BF16 = 0, 1
 BL_ACT_INT4_ABSMEAN, BL_ACT_TOPK_INT8_ABSMAX, BL_ACT_FP4_E2M1_B32, BL_ACT_INT4_ABSMEAN_MX6 = 0, 1, 2, 3
 BL_ACT_FP4_E2M1_B32_MX = 4
+BL_ACT_INT4_ABSMEAN2, BL_ACT_INT4_ABSMAX = 5, 6
 BL_W_GEMM, BL_W_KMAJOR, BL_W_MX4, BL_W_ROWS = 0, 1, 2, 3
 BL_DECODE_MAX_M = 64
 DEFAULT_EPS = 1e-5

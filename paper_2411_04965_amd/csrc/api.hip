@@ -6,7 +6,10 @@ static inline size_t ws_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static bool valid_dtype(int d) { return d == BL_F32 || d == BL_BF16; }
 static bool valid_layout(int l) { return l >= BL_W_GEMM && l <= BL_W_ROWS; }
-static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_FP4_E2M1_B32_MX; }
+static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_INT4_ABSMAX; }
+static bool int4_nibble_mode(int m) {
+  return m == BL_ACT_INT4_ABSMEAN || m == BL_ACT_INT4_ABSMEAN2 || m == BL_ACT_INT4_ABSMAX;
+}
 static bool mx_mode(int m) { return m == BL_ACT_INT4_ABSMEAN_MX6 || m == BL_ACT_FP4_E2M1_B32_MX; }
 static bool fp4_mode(int m) { return m == BL_ACT_FP4_E2M1_B32 || m == BL_ACT_FP4_E2M1_B32_MX; }
 
@@ -70,7 +73,9 @@ extern "C" size_t quantize_act_bytes(bl_act_mode mode, int64_t M, int64_t K) {
   if (M < 1 || K < 1) return 0;
   const int64_t Kp = bl_round_up(K, BL_KPAD);
   switch (mode) {
-    case BL_ACT_INT4_ABSMEAN: return (size_t)(M * Kp / 2);
+    case BL_ACT_INT4_ABSMEAN:
+    case BL_ACT_INT4_ABSMEAN2:
+    case BL_ACT_INT4_ABSMAX: return (size_t)(M * Kp / 2);
     case BL_ACT_TOPK_INT8_ABSMAX: return (size_t)(M * Kp);
     case BL_ACT_FP4_E2M1_B32: return (size_t)(M * Kp / 2);
     case BL_ACT_INT4_ABSMEAN_MX6: return (size_t)(bl_round_up(M, 32) * Kp / 4 * 3);
@@ -117,6 +122,7 @@ extern "C" int quantize_act_glu(const void* G, const void* U, bl_dtype in_dtype,
 extern "C" int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K,
                           int8_t* codes_out, void* stream) {
   if (!q || !codes_out || !valid_mode(mode)) return BL_EINVAL;
+  if (int4_nibble_mode(mode)) mode = BL_ACT_INT4_ABSMEAN;
   int rc = check_sizes(M, 1, K);
   if (rc) return rc;
   return bl_launch_unpack_act(q, mode, M, K, codes_out, (hipStream_t)stream);
@@ -146,6 +152,7 @@ static int gemm_dispatch(const void* q, const void* scale, bl_act_mode mode, int
                          hipStream_t s) {
   // the block-float forms of activations and weights go together and with nothing else
   if (layout == BL_W_ROWS) return BL_EUNSUPPORTED;       // only the gate-first up projection reads rows
+  if (int4_nibble_mode(mode)) mode = BL_ACT_INT4_ABSMEAN;   // same codes, same rescale
   if (mx_mode(mode) != (layout == BL_W_MX4)) return BL_EINVAL;
   if (mode == BL_ACT_INT4_ABSMEAN_MX6)
     return bl_launch_gemm_a4_mx(q, (const float*)scale, M, K, W_packed, alpha, N, Y, y_dtype, acc_out, s);

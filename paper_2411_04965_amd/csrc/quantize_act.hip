@@ -52,10 +52,12 @@ __device__ __forceinline__ u32 qa_e3m2_of_level(int q) {
 // MX6: the same levels, written as E3M2 codes in the tile order of the block-float GEMM (blocks of
 // 32 tokens x 128 channels, 3072 bytes; see the format notes of the public header) instead of
 // packed nibbles.
+// stat: 0 = eq. 7 (beta = mean |x|), 1 = beta = 2 mean |x|, 2 = absmax with 7 levels (ablation
+// quantizers of Section 4.3)
 template <typename RawT, int VEC, bool MX6>
 __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
     const RawT* __restrict__ X, int K, int Kp, float eps, u32* __restrict__ q_out,
-    float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out) {
+    float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out, int stat) {
   extern __shared__ __align__(16) unsigned char qa_smem[];
   RawT* row = reinterpret_cast<RawT*>(qa_smem);
   __shared__ double red[QA_WAVES];
@@ -73,10 +75,29 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
   double tot = 0.0;
 #pragma unroll
   for (int w = 0; w < QA_WAVES; ++w) tot += red[w];
-  const float beta = (float)(tot / (double)K);
+  float beta = (float)(tot / (double)K);
   const float sqrt7 = 2.6457512f;            // float32(sqrt(7)) = 0x402953FD
-  const float s = sqrt7 / (beta + eps);
-  if (threadIdx.x == 0) scale_out[m] = beta / sqrt7;
+  float s, d;
+  if (stat == 2) {
+    // gamma = max |x| (bit patterns of non-negative floats order like integers)
+    __shared__ u32 redm[QA_WAVES];
+    u32 mx = 0;
+    for (int i = threadIdx.x; i < Kp; i += QA_THREADS) mx = max(mx, __float_as_uint(fabsf(qa_to_f32<RawT>(row[i]))));
+    mx = bl_wave_max_u32(mx);
+    if ((threadIdx.x & 63) == 0) redm[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = 0;
+#pragma unroll
+    for (int w = 0; w < QA_WAVES; ++w) mx = max(mx, redm[w]);
+    const float gamma = __uint_as_float(mx);
+    s = 7.0f / (gamma + eps);
+    d = gamma / 7.0f;
+  } else {
+    if (stat == 1) beta = 2.0f * beta;
+    s = sqrt7 / (beta + eps);
+    d = beta / sqrt7;
+  }
+  if (threadIdx.x == 0) scale_out[m] = d;
 
   int sum = 0;
   if (MX6) {
@@ -634,12 +655,14 @@ static int qa_run_row_kernels(const RawT* X, int64_t M, int K, int Kp, bl_act_mo
                               float eps, void* q, void* scale, int32_t* rowsum, int32_t* sel,
                               hipStream_t s) {
   const size_t smem = (size_t)Kp * sizeof(RawT);
-  if (mode == BL_ACT_INT4_ABSMEAN || mode == BL_ACT_INT4_ABSMEAN_MX6) {
-    auto kern = mode == BL_ACT_INT4_ABSMEAN ? quant_int4_kernel<RawT, VEC, false> : quant_int4_kernel<RawT, VEC, true>;
+  if (mode == BL_ACT_INT4_ABSMEAN || mode == BL_ACT_INT4_ABSMEAN_MX6 || mode == BL_ACT_INT4_ABSMEAN2 ||
+      mode == BL_ACT_INT4_ABSMAX) {
+    const int stat = mode == BL_ACT_INT4_ABSMEAN2 ? 1 : mode == BL_ACT_INT4_ABSMAX ? 2 : 0;
+    auto kern = mode == BL_ACT_INT4_ABSMEAN_MX6 ? quant_int4_kernel<RawT, VEC, true> : quant_int4_kernel<RawT, VEC, false>;
     if (smem > 48 * 1024 &&
         hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return BL_EHIP;
-    kern<<<(unsigned)M, QA_THREADS, smem, s>>>(X, K, Kp, eps, (u32*)q, (float*)scale, rowsum);
+    kern<<<(unsigned)M, QA_THREADS, smem, s>>>(X, K, Kp, eps, (u32*)q, (float*)scale, rowsum, stat);
   } else if (M <= 64) {
     auto kern = quant_topk_int8_kernel<RawT, VEC, 1024>;
     if (smem > 48 * 1024 &&

@@ -80,6 +80,30 @@ def test_quantize_int4(kind, M, K, dtype):
     assert np.array_equal(host(r["rowsum"]), q_ref.sum(1, dtype=np.int32))
 
 
+@pytest.mark.parametrize("mode,kind", [(B.BL_ACT_INT4_ABSMEAN2, "absmean2"), (B.BL_ACT_INT4_ABSMAX, "absmax")])
+@pytest.mark.parametrize("xkind,M,K,dtype", [("gauss", 16, 256, F32), ("glu", 33, 11008, BF16),
+                                             ("ties", 9, 1000, F32), ("heavy", 5, 301, BF16)])
+def test_quantize_int4_variants(mode, kind, xkind, M, K, dtype):
+    """The two other INT4 quantizers of the ablations (beta = 2 mean|x|; absmax with 7 levels)."""
+    say("quantize_act INT4 variant %s %s M=%d K=%d %s" % (kind, xkind, M, K, dtype))
+    x = _x(xkind, M, K, S.seed_for(0, 17 * M + K), dtype)
+    q_ref, d_ref = O.quant_int4_variant(x, EPS, kind)
+    r = B.quantize_act(dev(x, dtype), mode, 0, EPS, want_rowsum=True)
+    assert np.array_equal(host(r["scale"]), d_ref)
+    assert np.array_equal(decode_int4(host(r["q"]), M, K), q_ref)
+    assert np.array_equal(host(B.unpack_act(r["q"], mode, M, K)), q_ref)
+    assert np.array_equal(host(r["rowsum"]), q_ref.sum(1, dtype=np.int32))
+    # the linear layers take these codes as INT4 codes
+    N = 64
+    W = S.latent_weights(N, K, S.seed_for(0, 18))
+    T, alpha = O.ternarize(W, EPS)
+    p, a = pack(W)
+    Y, acc = B.bitlinear_gemm(r["q"], r["scale"], mode, M, K, p, a, N, y_dtype=F32, want_acc=True)
+    acc_ref = O.matmul_int(q_ref, T)
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(host(Y), O.rescale(acc_ref, d_ref, alpha, "f32"))
+
+
 @pytest.mark.parametrize("kind,M,K,topk,dtype", [
     ("gauss", 16, 512, 256, F32), ("heavy", 33, 4096, 2048, BF16), ("glu", 9, 5460, 2730, BF16),
     ("ties", 9, 1000, 500, F32), ("ties", 9, 1000, 1, BF16), ("ties", 9, 1000, 1000, BF16),

@@ -89,6 +89,65 @@ def test_int4_bruteforce_rows():
         assert d[m] == db
 
 
+# ------------------------------------------------------------------ Section 4.3: the other INT4 quantizers
+def _int4_variant_bruteforce(row, kind):
+    """The variant in exact rationals except for the float32 roundings the reading fixes."""
+    K = len(row)
+    if kind == "absmean2":
+        S = sum(abs(Fraction(float(v))) for v in row)
+        stat = f32(f32(2) * f32(float(S / K)))
+        num, den = O.SQRT7, O.SQRT7
+    else:
+        stat = f32(max(abs(float(v)) for v in row))
+        num, den = f32(7), f32(7)
+    s = f32(num / f32(stat + f32(EPS)))
+    out = []
+    for v in row:
+        p = f32(f32(v) * s)
+        out.append(int(min(max(round(Fraction(float(p))), -8), 7)))
+    return out, f32(stat / den)
+
+
+@pytest.mark.parametrize("kind", ["absmean2", "absmax"])
+def test_int4_variants(kind):
+    # hand-worked: |x| = 1, 1, 2, 2, 4, 4, 8, 8 -> mean 3.75, max 8
+    x = np.array([[1, -1, 2, -2, 4, -4, 8, -8]], dtype=F32)
+    q, d = O.quant_int4_variant(x, EPS, kind)
+    if kind == "absmean2":      # beta = 7.5, x * sqrt7 / 7.5 = .353, .706, 1.411, 2.822
+        assert q[0].tolist() == [0, 0, 1, -1, 1, -1, 3, -3]
+        assert d[0] == f32(f32(7.5) / O.SQRT7)
+    else:                       # x * 7 / 8.00001 = .875, 1.75, 3.4999956, 6.999991
+        assert q[0].tolist() == [1, -1, 2, -2, 3, -3, 7, -7]
+        assert d[0] == f32(f32(8) / f32(7))
+    rng = np.random.default_rng(21)
+    X = rng.standard_normal((10, 41)).astype(F32)
+    X[2] *= 30
+    X[4] = 0
+    X[5, :] = -0.5
+    q, d = O.quant_int4_variant(X, EPS, kind)
+    for m in range(X.shape[0]):
+        qb, db = _int4_variant_bruteforce(X[m], kind)
+        assert q[m].tolist() == qb and d[m] == db
+    assert q.min() >= -8 and q.max() <= 7
+    # power-of-two rescaling of a token changes nothing but the scale (eps = 0)
+    q1, d1 = O.quant_int4_variant(X[:4], 0.0, kind)
+    q2, d2 = O.quant_int4_variant(X[:4] * f32(8), 0.0, kind)
+    assert np.array_equal(q1, q2) and np.array_equal(d2, d1 * f32(8))
+    if kind == "absmax":        # the largest magnitude of a token gets code +-7, nothing clips
+        big = np.abs(X).argmax(axis=1)
+        rows = [m for m in range(X.shape[0]) if m != 4]
+        assert all(abs(int(q[m, big[m]])) == 7 for m in rows)
+        assert np.abs(q).max() == 7
+    else:                       # twice the beta of eq. 7: exactly twice its step
+        qa, da = O.quant_int4(X, EPS)
+        assert np.array_equal(d, da * f32(2))
+    # textbook uniform quantizer with step d: unclipped values land within half a step
+    deq = q.astype(np.float64) * d[:, None].astype(np.float64)
+    unclipped = (q > -8) & (q < 7)
+    half = 0.5 * np.repeat(d[:, None].astype(np.float64), X.shape[1], 1) * (1 + 1e-4) + 1e-5
+    assert np.all(np.abs(deq - X)[unclipped] <= half[unclipped])
+
+
 def test_int4_is_per_token_and_uniform_step():
     rng = np.random.default_rng(5)
     X = rng.standard_normal((6, 64)).astype(F32)
