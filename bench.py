@@ -13,7 +13,8 @@ dense-equivalent int8 TOPS (2*M*N*K per projection) over the whole step, quantiz
 included.  The roofline object covers the dominant kernel, the W1.58A4 prefill GEMM, timed
 with events on the launch stream inside the timed region.  Decode-shape weight bandwidth
 (packed-weight GB/s at 1/8/32/64 tokens) is reported in the same JSON line under "decode", and
-the FP4 activation variant against the INT4 path at 3B-like shapes under "fp4_variant".
+the FP4 activation variant against the INT4 path at 3B-like shapes under "fp4_variant"; one
+token through a whole FFN block, four calls against the gate-first form, under "decode_ffn_1token".
 """
 import argparse
 import json
@@ -205,7 +206,7 @@ def main():
         "metric": "W1.58A4 linear TOPS (prefill) & packed-weight GB/s (decode), 7B shapes",
         "value": round(value, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8+fp6xfp4",
         "data": "synthetic (seeded; N(0,1) + heavy-tailed outlier channels, bf16)",
         "config": {"workload": "7B prefill block: %d tokens x {qkv 4096->12288 A4, o 4096->4096 A8s, "
                                "gate/up 4096->11008 A4 (one shared quantized input), down 11008->4096 A8s}, "
@@ -216,11 +217,73 @@ def main():
     }
     if not args.no_decode:
         out["decode"] = decode_bench(B, S, torch, dev)
+        out["decode_ffn_1token"] = decode_ffn_bench(B, S, torch, dev)
     if not args.no_fp4:
         out["fp4_variant"] = fp4_compare(B, S, torch, dev)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
+
+
+def decode_ffn_bench(B, S, torch, dev, layers=8, replays=20):
+    """One token through the FFN's three linears and its glue at 7B width, from HIP-graph replays of
+    `layers` distinct weight sets: gate, up, ReLU^2 GLU, down as four calls against the gate-first
+    form (gate, then the up projection only where the gate is open with the GLU inside, then down)."""
+    bf16 = torch.bfloat16
+    X = torch.from_numpy(S.heavy(1, HIDDEN, S.seed_for(2, 900))).to(dev).to(bf16)
+    sets = []
+    for l in range(layers):
+        ws_ = []
+        for i, (N, K) in enumerate(((FFN, HIDDEN), (FFN, HIDDEN), (HIDDEN, FFN))):
+            w = torch.from_numpy(S.latent_weights(N, K, S.seed_for(2, 2000 + 10 * l + i))).to(dev)
+            ws_.append(B.pack_ternary(w, EPS, B.BL_W_GEMM))
+            if i == 1:
+                ws_.append(B.pack_ternary(w, EPS, B.BL_W_ROWS))
+            del w
+        sets.append(ws_)
+    ws4 = B.workspace(B.BL_ACT_INT4_ABSMEAN, 1, FFN, HIDDEN, dev)
+    ws8 = B.workspace(B.BL_ACT_TOPK_INT8_ABSMAX, 1, HIDDEN, FFN, dev)
+    G = torch.empty((1, FFN), dtype=torch.float32, device=dev)
+    U = torch.empty((1, FFN), dtype=torch.float32, device=dev)
+    Y = torch.empty((1, HIDDEN), dtype=bf16, device=dev)
+
+    def dense(l):
+        (pg, ag), (pu, au), _, (pd, ad) = sets[l]
+        B.bitlinear_a4(X, pg, ag, FFN, EPS, ws=ws4, out=G)
+        B.bitlinear_a4(X, pu, au, FFN, EPS, ws=ws4, out=U)
+        Hh = B.relu2_glu(G, U)
+        B.bitlinear_a8_sparse(Hh, FFN // 2, pd, ad, HIDDEN, EPS, ws=ws8, out=Y)
+
+    def gate_first(l):
+        (pg, ag), _, (pr, ar), (pd, ad) = sets[l]
+        B.bitlinear_a4(X, pg, ag, FFN, EPS, ws=ws4, out=G)
+        Hh = B.bitlinear_a4_up_gated(X, pr, ar, FFN, G, EPS)
+        B.bitlinear_a8_sparse(Hh, FFN // 2, pd, ad, HIDDEN, EPS, ws=ws8, out=Y)
+
+    res = {}
+    side = torch.cuda.Stream()
+    for name, fn in (("four_calls", dense), ("gate_first", gate_first)):
+        for l in range(layers):
+            fn(l)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for l in range(layers):
+                    fn(l)
+        g.replay()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(replays):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name + "_us"] = round(e0.elapsed_time(e1) / (replays * layers) * 1e3, 2)
+        del g
+    res["open_gate_fraction"] = round(float((G > 0).float().mean().item()), 3)
+    return res
 
 
 def fp4_compare(B, S, torch, dev, M=8192, hidden=3200, ffn=8640, iters=20):
