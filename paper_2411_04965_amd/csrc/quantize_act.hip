@@ -381,7 +381,7 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
   for (int i = 0; i < NC; ++i) {
     uint2 v = make_uint2(0u, 0u);
     const int ch = (c_begin + i) * 256 + lane * 4;
-    if (i < nc && ch < K) v = qa_load4<GLU>(x, x2, ch);       // K % 4 == 0 by dispatch
+    if (i < nc && ch < K) v = qa_token4<GLU>(x, x2, ch);       // K % 4 == 0 by dispatch
     raw[i][0] = v.x; raw[i][1] = v.y;
   }
   u32 kmax;

@@ -26,7 +26,7 @@ __device__ __forceinline__ int qa_wave_sum_dpp(int v) {
 // itself (`a`).  GLU = 1 / 2: the token is H = bf16(U * max(G, 0)^2) (eq. 5, float32 steps in that
 // order) of a gate row `a` and an up row `b`, bfloat16 / float32: the product never goes to memory.
 template <int GLU>
-__device__ __forceinline__ uint2 qa_load4(const void* a, const void* b, int ch) {
+__device__ __forceinline__ uint2 qa_token4(const void* a, const void* b, int ch) {
   if (GLU == 0) return *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a) + ch);
   float g[4], u[4];
   if (GLU == 1) {
@@ -107,7 +107,7 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
   for (int i = 0; i < CPW; ++i) {
     uint2 v = make_uint2(0u, 0u);
     const int ch = (c_begin + i) * 256 + lane * 4;
-    if (i < nc && ch < K) v = qa_load4<GLU>(x, x2, ch);      // K % 4 == 0 by dispatch
+    if (i < nc && ch < K) v = qa_token4<GLU>(x, x2, ch);      // K % 4 == 0 by dispatch
     raw[i][0] = v.x; raw[i][1] = v.y;
     pg[i][0] = v.x | QA_GUARD; pg[i][1] = v.y | QA_GUARD;
   }

@@ -379,6 +379,25 @@ def test_up_gated(M, N, K, gdt):
     assert not host(Hh)[:, closed].any()
 
 
+def test_maximum_width():
+    """The widest rows the library takes (BL_MAX_K channels): every quantizer and both INT4 GEMMs."""
+    K = 32768                                              # BL_MAX_K of the public header
+    say("maximum width K=%d" % K)
+    M, N = 40, 48
+    X = S.heavy(M, K, S.seed_for(0, 90))
+    W = S.latent_weights(N, K, S.seed_for(0, 91))
+    ref4 = O.bitlinear_a4(X, W, EPS, "f32")
+    for layout in (B.BL_W_GEMM, B.BL_W_MX4):
+        p, a = pack(W, layout)
+        _check_linear(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=F32, want_acc=True, layout=layout), ref4, F32)
+    p, a = pack(W)
+    ref8 = O.bitlinear_a8_sparse(X, W, K // 2, EPS, "f32")
+    _check_linear(B.bitlinear_a8_sparse(dev(X, BF16), K // 2, p, a, N, EPS, B.BL_W_GEMM, F32, True), ref8, F32)
+    codes_ref, e_ref = O.quant_fp4(X)
+    r = B.quantize_act(dev(X, BF16), B.BL_ACT_FP4_E2M1_B32)
+    assert np.array_equal(decode_fp4(host(r["q"]), M, K), codes_ref)
+
+
 # ------------------------------------------------------------------ full prefill size (config 3), sampled rows
 @pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (300, 520, 1000, BF16), (130, 2048, 5460, BF16),
                                          (257, 5460, 2048, BF16), (1100, 1100, 768, BF16),
