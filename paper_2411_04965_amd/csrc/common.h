@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/bitlinear.h"
 
 #define BL_KPAD 256   // K padding unit of every packed format
@@ -34,6 +36,30 @@ __device__ __forceinline__ double bl_wave_sum_f64(double v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
+}
+// The same sum with DPP moves instead of LDS permutes (a third of the latency); exact sums only,
+// the order of the additions differs.
+__device__ __forceinline__ double bl_wave_sum_f64_dpp(double v) {
+  // sum over the 64 lanes: 16-lane rows with DPP (two 32-bit moves per step), rows with readlane
+  auto step = [&](auto ctrl) {
+    constexpr int C = decltype(ctrl)::value;
+    const u32 lo = (u32)__double_as_longlong(v), hi = (u32)(__double_as_longlong(v) >> 32);
+    const u32 plo = (u32)__builtin_amdgcn_update_dpp(0, (int)lo, C, 0xF, 0xF, false);
+    const u32 phi = (u32)__builtin_amdgcn_update_dpp(0, (int)hi, C, 0xF, 0xF, false);
+    v += __longlong_as_double((long long)(((unsigned long long)phi << 32) | plo));
+  };
+  step(std::integral_constant<int, 0x121>{});    // row_ror:1
+  step(std::integral_constant<int, 0x122>{});    // row_ror:2
+  step(std::integral_constant<int, 0x124>{});    // row_ror:4
+  step(std::integral_constant<int, 0x128>{});    // row_ror:8
+  const u32 lo = (u32)__double_as_longlong(v), hi = (u32)(__double_as_longlong(v) >> 32);
+  double t = 0.0;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const u32 a = (u32)__builtin_amdgcn_readlane((int)lo, 16 * r), b = (u32)__builtin_amdgcn_readlane((int)hi, 16 * r);
+    t += __longlong_as_double((long long)(((unsigned long long)b << 32) | a));
+  }
+  return t;
 }
 __device__ __forceinline__ int bl_wave_sum_i32(int v) {
 #pragma unroll

@@ -184,28 +184,6 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_kernel(
 // quantizer (float64 sum of |x|, one rounding to float32, one float32 multiply per element), so
 // the codes are the same bit for bit.  Codes are kept as int8 in LDS, one row per token.
 #define GF_NV 4                                  // 16-byte pieces of a row per thread: K <= 8192
-__device__ __forceinline__ double gf_wave_sum_f64(double v) {
-  // sum over the 64 lanes: 16-lane rows with DPP (two 32-bit moves per step), rows with readlane
-  auto step = [&](auto ctrl) {
-    constexpr int C = decltype(ctrl)::value;
-    const u32 lo = (u32)__double_as_longlong(v), hi = (u32)(__double_as_longlong(v) >> 32);
-    const u32 plo = (u32)__builtin_amdgcn_update_dpp(0, (int)lo, C, 0xF, 0xF, false);
-    const u32 phi = (u32)__builtin_amdgcn_update_dpp(0, (int)hi, C, 0xF, 0xF, false);
-    v += __longlong_as_double((long long)(((unsigned long long)phi << 32) | plo));
-  };
-  step(std::integral_constant<int, 0x121>{});    // row_ror:1
-  step(std::integral_constant<int, 0x122>{});    // row_ror:2
-  step(std::integral_constant<int, 0x124>{});    // row_ror:4
-  step(std::integral_constant<int, 0x128>{});    // row_ror:8
-  const u32 lo = (u32)__double_as_longlong(v), hi = (u32)(__double_as_longlong(v) >> 32);
-  double t = 0.0;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const u32 a = (u32)__builtin_amdgcn_readlane((int)lo, 16 * r), b = (u32)__builtin_amdgcn_readlane((int)hi, 16 * r);
-    t += __longlong_as_double((long long)(((unsigned long long)b << 32) | a));
-  }
-  return t;
-}
 
 // eq. 7 for up to 4 bfloat16 token rows by one workgroup of 256 threads: int8 codes to `codes`
 // ([M][Kp], LDS), the dequantization scales beta / sqrt(7) to dq (the same in every thread).  The
@@ -239,7 +217,7 @@ __device__ __forceinline__ void gf_quantize_rows(const uint16_t* __restrict__ X,
           a += (double)fabsf(__uint_as_float(w4[e] & 0xFFFF0000u));
         }
       }
-      a = gf_wave_sum_f64(a);
+      a = bl_wave_sum_f64_dpp(a);
       if (lane == 0) red[m][wave] = a;
     }
   }

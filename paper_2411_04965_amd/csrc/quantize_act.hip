@@ -157,6 +157,132 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
   }
 }
 
+// The same quantizer for bfloat16 rows of up to 16384 channels without the trip through LDS: a
+// thread keeps its half units (16 channels = two 16-byte loads each; half units tid, tid + 256, ...)
+// in registers between the statistics and the coding; one barrier.  K % 8 == 0 by dispatch.
+template <bool MX6, int NV>
+__global__ __launch_bounds__(QA_THREADS) void quant_int4_regs_kernel(
+    const uint16_t* __restrict__ X, int K, int Kp, float eps, u32* __restrict__ q_out,
+    float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out, int stat) {
+  __shared__ double red[QA_WAVES];
+  __shared__ u32 redm[QA_WAVES];
+  __shared__ int redi[QA_WAVES];
+  const int64_t m = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint4* xv = reinterpret_cast<const uint4*>(X + m * (int64_t)K);
+  const int nv = K >> 3;                         // 16-byte pieces of the row
+  uint4 v[NV][2];
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int pc = 2 * (tid + QA_THREADS * j) + i;
+      v[j][i] = make_uint4(0u, 0u, 0u, 0u);
+      if (pc < nv) v[j][i] = xv[pc];
+    }
+  // statistics: float64 sum of |x| (exact for bfloat16 data), maximum of |x| as a bit pattern
+  double acc = 0.0;
+  u32 mx = 0;
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const u32 w4[4] = {v[j][i].x, v[j][i].y, v[j][i].z, v[j][i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const u32 lo = (w4[e] << 16) & 0x7FFFFFFFu, hi = w4[e] & 0x7FFF0000u;
+        acc += (double)__uint_as_float(lo);
+        acc += (double)__uint_as_float(hi);
+        mx = max(mx, max(lo, hi));
+      }
+    }
+  acc = bl_wave_sum_f64_dpp(acc);
+  if (stat == 2) mx = bl_wave_max_u32(mx);
+  if (lane == 0) { red[wave] = acc; redm[wave] = mx; }
+  __syncthreads();
+  double tot = 0.0;
+  u32 gmx = 0;
+#pragma unroll
+  for (int w = 0; w < QA_WAVES; ++w) { tot += red[w]; gmx = max(gmx, redm[w]); }
+  float beta = (float)(tot / (double)K);
+  const float sqrt7 = 2.6457512f;            // float32(sqrt(7)) = 0x402953FD
+  float s, d;
+  if (stat == 2) {
+    const float gamma = __uint_as_float(gmx);
+    s = 7.0f / (gamma + eps);
+    d = gamma / 7.0f;
+  } else {
+    if (stat == 1) beta = 2.0f * beta;
+    s = sqrt7 / (beta + eps);
+    d = beta / sqrt7;
+  }
+  if (tid == 0) scale_out[m] = d;
+
+  int sum = 0;
+  unsigned char* blk = reinterpret_cast<unsigned char*>(q_out) + (m >> 5) * (int64_t)(Kp / 128) * 3072;
+  const int r = (int)(m & 31);
+  u32* out = q_out + m * (int64_t)(Kp / 8);
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int h = tid + QA_THREADS * j;          // half unit: channels 16 h .. 16 h + 15
+    if (h < Kp / 16) {
+      int q[16];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const u32 w4[4] = {v[j][i].x, v[j][i].y, v[j][i].z, v[j][i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p0 = fminf(fmaxf(rintf(__uint_as_float(w4[e] << 16) * s), -8.0f), 7.0f);   // one float32 multiply
+          const float p1 = fminf(fmaxf(rintf(__uint_as_float(w4[e] & 0xFFFF0000u) * s), -8.0f), 7.0f);
+          q[8 * i + 2 * e] = (int)p0;
+          q[8 * i + 2 * e + 1] = (int)p1;
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 16; ++c) sum += q[c];
+      if (MX6) {
+        u32 w3[3] = {0u, 0u, 0u};
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+          const u32 code = qa_e3m2_of_level(q[c]);
+          const int bit = 6 * c;
+          w3[bit >> 5] |= code << (bit & 31);
+          if ((bit & 31) > 26) w3[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+        }
+        const int kb = h >> 3, u = (h >> 1) & 3;
+        unsigned char* b = blk + (int64_t)kb * 3072;
+        u32* pp = reinterpret_cast<u32*>(b + r * 64 + ((u ^ ((r >> 2) & 3)) << 4));
+        if ((h & 1) == 0) {                                   // stream bytes 0..11
+          pp[0] = w3[0]; pp[1] = w3[1]; pp[2] = w3[2];
+        } else {                                              // stream bytes 12..15 and 16..23
+          pp[3] = w3[0];
+          u32* qq = reinterpret_cast<u32*>(b + 2048 + r * 32 + ((u ^ ((r >> 3) & 3)) << 3));
+          qq[0] = w3[1]; qq[1] = w3[2];
+        }
+      } else {
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          u32 word = 0;
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            word |= (((u32)q[8 * g + b] & 15u) | (((u32)q[8 * g + 4 + b] & 15u) << 4)) << (8 * b);
+          out[2 * h + g] = word;
+        }
+      }
+    }
+  }
+  if (rowsum_out) {
+    sum = bl_wave_sum_i32(sum);
+    if (lane == 0) redi[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+      int t = 0;
+      for (int w = 0; w < QA_WAVES; ++w) t += redi[w];
+      rowsum_out[m] = t;
+    }
+  }
+}
+
 // ---------------------------------------------------------------- Top_k + INT8 absmax (eq. 1, 3)
 // Selection key = bit pattern of |x| (monotone for finite values, -0 equals +0).  The k-th
 // largest key tau is built bit by bit: a bit stays set if at least topk keys are >= the
@@ -735,6 +861,20 @@ int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K64, bl_ac
   if (dt == BL_BF16 && mode == BL_ACT_TOPK_INT8_ABSMAX && K % 4 == 0 && Kp <= 12288 &&
       sel_idx == nullptr)
     return qa_run_topk_regs<0>(X, nullptr, M, K, Kp, (int)topk, eps, q, scale, rowsum, s);
+  const bool int4_any = mode == BL_ACT_INT4_ABSMEAN || mode == BL_ACT_INT4_ABSMEAN_MX6 ||
+                        mode == BL_ACT_INT4_ABSMEAN2 || mode == BL_ACT_INT4_ABSMAX;
+  if (dt == BL_BF16 && int4_any && K % 8 == 0 && Kp <= 16384) {
+    // rows in registers, no LDS staging
+    const int stat = mode == BL_ACT_INT4_ABSMEAN2 ? 1 : mode == BL_ACT_INT4_ABSMAX ? 2 : 0;
+    const bool mx6 = mode == BL_ACT_INT4_ABSMEAN_MX6;
+    const int nvv = (Kp / 16 + QA_THREADS - 1) / QA_THREADS;      // half units per thread: 1 .. 4
+#define QA_I4(MX, NVV) quant_int4_regs_kernel<MX, NVV><<<(unsigned)M, QA_THREADS, 0, s>>>((const uint16_t*)X, K, Kp, eps, (u32*)q, (float*)scale, rowsum, stat)
+    if (mx6) { if (nvv <= 1) QA_I4(true, 1); else if (nvv <= 2) QA_I4(true, 2); else QA_I4(true, 4); }
+    else { if (nvv <= 1) QA_I4(false, 1); else if (nvv <= 2) QA_I4(false, 2); else QA_I4(false, 4); }
+#undef QA_I4
+    BL_HIP_CHECK_LAUNCH();
+    return BL_OK;
+  }
   if (dt == BL_BF16) {
     const uint16_t* x = (const uint16_t*)X;
     if (K % 8 == 0) return qa_run_row_kernels<uint16_t, 8>(x, M, K, Kp, mode, (int)topk, eps, q, scale, rowsum, sel_idx, s);
