@@ -142,6 +142,30 @@ def test_quantize_topk_int8_many_tokens(kind, M, K, topk):
     assert np.array_equal(host(r["rowsum"])[rows], q_ref.sum(1, dtype=np.int32))
 
 
+def test_quantize_topk_int8_seeded_sweep():
+    """40 seeded draws of (tokens, width, topk, input kind) over the register kernels' range: widths
+    that are multiples of 4 up to 12288, few and many tokens, topk from 1 to K, inputs with many
+    equal magnitudes (coarse grids, zeros) so that the threshold falls inside a run of ties."""
+    rng = np.random.default_rng(S.seed_for(0, 4242))
+    for it in range(40):
+        many = it % 4 == 3
+        M = int(rng.integers(2048, 2080)) if many else int(rng.integers(1, 70))
+        K = 4 * int(rng.integers(1, 1537 if many else 3073))
+        topk = int(rng.choice([1, K, max(1, K // 2), int(rng.integers(1, K + 1))]))
+        kind = ["ties", "glu", "heavy", "grid"][it % 4 if not many else int(rng.integers(0, 4))]
+        say("sweep %d: M=%d K=%d topk=%d %s" % (it, M, K, topk, kind))
+        if kind == "grid":          # a handful of distinct magnitudes: long runs of equal keys
+            x = (rng.integers(-3, 4, (M, K)) * 0.5).astype(np.float32)
+        else:
+            x = _x(kind, M, K, S.seed_for(0, 5000 + it), BF16)
+        rows = np.arange(M) if M < 70 else np.unique(rng.integers(0, M, 48))
+        q_ref, d_ref, _ = O.quant_topk_int8(x[rows], topk, EPS)
+        r = B.quantize_act(dev(x, BF16), B.BL_ACT_TOPK_INT8_ABSMAX, topk, EPS, want_rowsum=True)
+        assert np.array_equal(host(r["scale"])[rows], d_ref)
+        assert np.array_equal(decode_int8(host(r["q"]), M, K)[rows], q_ref)
+        assert np.array_equal(host(r["rowsum"])[rows], q_ref.sum(1, dtype=np.int32))
+
+
 @pytest.mark.parametrize("M,K,topk,dtype", [(9, 5460, 2730, F32), (2051, 5460, 2730, F32), (33, 11008, 5504, BF16),
                                             (2050, 4096, 2048, BF16), (5, 1000, 1, BF16), (7, 12288, 12288, F32)])
 def test_quantize_glu_topk_int8(M, K, topk, dtype):
@@ -377,6 +401,31 @@ def test_up_gated(M, N, K, gdt):
     closed = ~(g > 0).any(axis=0)
     assert closed.any() or N < 64                          # the case does skip rows
     assert not host(Hh)[:, closed].any()
+
+
+def test_linears_seeded_shape_sweep():
+    """16 seeded draws of (M, N, K) between 1 and ~700 / 900 / 3000: every linear on every weight
+    layout it takes, accumulators bit-exact (all kernel choices by token count, ragged everything)."""
+    rng = np.random.default_rng(S.seed_for(0, 777))
+    for it in range(16):
+        M = int(rng.choice([1, 2, 5, 16, 17, 40, 64, 65, int(rng.integers(66, 700))]))
+        N = int(rng.integers(1, 900)) if it % 3 else int(rng.choice([2048, 2064, 4096]))
+        K = int(rng.integers(1, 3000))
+        topk = int(rng.integers(1, K + 1))
+        say("shape sweep %d: M=%d N=%d K=%d topk=%d" % (it, M, N, K, topk))
+        X = S.heavy(M, K, S.seed_for(0, 6000 + it))
+        W = S.latent_weights(N, K, S.seed_for(0, 7000 + it))
+        ref4 = O.bitlinear_a4(X, W, EPS, "bf16")
+        ref8 = O.bitlinear_a8_sparse(X, W, topk, EPS, "bf16")
+        Xd = dev(X, BF16)
+        p, a = pack(W)
+        _check_linear(B.bitlinear_a4(Xd, p, a, N, EPS, y_dtype=BF16, want_acc=True), ref4, BF16)
+        _check_linear(B.bitlinear_a8_sparse(Xd, topk, p, a, N, EPS, B.BL_W_GEMM, BF16, True), ref8, BF16)
+        pm, am = pack(W, B.BL_W_MX4)
+        _check_linear(B.bitlinear_a4(Xd, pm, am, N, EPS, y_dtype=BF16, want_acc=True, layout=B.BL_W_MX4), ref4, BF16)
+        if M <= 8:
+            pk, ak = pack(W, B.BL_W_KMAJOR)
+            _check_linear(B.bitlinear_a8_sparse(Xd, topk, pk, ak, N, EPS, B.BL_W_KMAJOR, BF16, True), ref8, BF16)
 
 
 def test_maximum_width():
