@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-fp4", action="store_true")
+    ap.add_argument("--a4-weights", choices=["mx2", "mx4"], default="mx2",
+                    help="block-float weight form of the INT4 projections: 2-bit codes expanded in registers, or E2M1 nibbles")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for the HBM traffic counters)")
     return ap.parse_args()
@@ -104,12 +106,13 @@ def main():
         return torch.from_numpy(x).to(dev).to(bf16).contiguous()
 
     # ---- weights (packed once, offline step) and inputs, resident in HBM
+    A4L = B.BL_W_MX2 if args.a4_weights == "mx2" else B.BL_W_MX4
     projs = S.projections(HIDDEN, FFN)
     W = {}
     for i, (name, N, K, kind) in enumerate(projs):
         w = torch.from_numpy(S.latent_weights(N, K, S.seed_for(3, 20 + i))).to(dev)
         # INT4 projections: block-float layout (E2M1 nibbles) for the 6-bit x 4-bit matrix instruction
-        W[name] = B.pack_ternary(w, EPS, B.BL_W_MX4 if kind == "a4" else B.BL_W_GEMM)
+        W[name] = B.pack_ternary(w, EPS, A4L if kind == "a4" else B.BL_W_GEMM)
         del w
     x_hidden = to_dev(S.heavy(M, HIDDEN, S.seed_for(3, 1)))
     x_attn = to_dev(S.heavy(M, HIDDEN, S.seed_for(3, 3)))
@@ -122,7 +125,7 @@ def main():
         mode = B.BL_ACT_INT4_ABSMEAN_MX6 if kind == "a4" else B.BL_ACT_TOPK_INT8_ABSMAX
         L = B.lib()
         bufs[name] = dict(
-            mode=mode, layout=B.BL_W_MX4 if kind == "a4" else B.BL_W_GEMM,
+            mode=mode, layout=A4L if kind == "a4" else B.BL_W_GEMM,
             q=torch.empty(L.quantize_act_bytes(mode, M, K), dtype=torch.uint8, device=dev),
             scale=torch.empty(M, dtype=torch.float32, device=dev),
             Y=torch.empty((M, N), dtype=bf16, device=dev),
@@ -194,12 +197,14 @@ def main():
     a4_ops = sum(2.0 * M * N * K for _, N, K in a4)
     a4_ms = sum(per_kernel[n_]["gemm_ms"] for n_, _, _ in a4)
     achieved = a4_ops / (a4_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_a4_mx_kernel (qkv, gate, up): E3M2 x E2M1 block-float MFMA",
+    roofline = {"bound": "mfma", "kernel": "gemm_a4_mx_kernel (qkv, gate, up): E3M2 x E2M1 block-float MFMA, weights "
+                          + ("2-bit in HBM and LDS" if args.a4_weights == "mx2" else "E2M1 nibbles in HBM and LDS"),
                 "achieved": round(achieved, 1), "peak": FP6_FP4_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / FP6_FP4_PEAK_TOPS, 4),
                 "frac_of_int8_peak": round(achieved / INT8_PEAK_TOPS, 4),
-                "traffic": A4_GEMM_TRAFFIC_BYTES if M == 16384 else None,
-                "algorithmic_bytes": round(sum(M * K * 3 / 4 + N * K / 2 + 2 * M * N for _, N, K in a4) / len(a4)),
+                "traffic": A4_GEMM_TRAFFIC_BYTES if (M == 16384 and args.a4_weights == "mx2") else None,
+                "algorithmic_bytes": round(sum(M * K * 3 / 4 + N * K / (4 if args.a4_weights == "mx2" else 2) + 2 * M * N
+                                               for _, N, K in a4) / len(a4)),
                 "avg_launch_ms": round(a4_ms / len(a4), 4)}
 
     out = {
@@ -292,7 +297,7 @@ def fp4_compare(B, S, torch, dev, M=8192, hidden=3200, ffn=8640, iters=20):
     res = {"tokens": M}
     for name, N, K in (("qkv", 3 * hidden, hidden), ("gate", ffn, hidden)):
         w = torch.from_numpy(S.latent_weights(N, K, S.seed_for(4, 20 + len(name)))).to(dev)
-        p, a = B.pack_ternary(w, EPS, B.BL_W_MX4)
+        p, a = B.pack_ternary(w, EPS, B.BL_W_MX2)
         del w
         X = torch.from_numpy(S.heavy(M, K, S.seed_for(4, 21))).to(dev).to(torch.bfloat16)
         Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
@@ -300,13 +305,13 @@ def fp4_compare(B, S, torch, dev, M=8192, hidden=3200, ffn=8640, iters=20):
         for label, fp4, mode in (("fp4", True, B.BL_ACT_FP4_E2M1_B32_MX), ("int4", False, B.BL_ACT_INT4_ABSMEAN_MX6)):
             ws = B.workspace(mode, M, N, K, dev)
             for _ in range(3):
-                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=B.BL_W_MX4)
+                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=B.BL_W_MX2)
             torch.cuda.synchronize()
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(iters):
-                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=B.BL_W_MX4)
+                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=B.BL_W_MX2)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / iters

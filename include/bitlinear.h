@@ -42,6 +42,14 @@
  *               channel i of the unit in nibble i (low nibble of a byte first).  Used by the
  *               prefill GEMM of the INT4 path; twice the bytes of BL_W_GEMM.
  *
+ *   BL_W_MX2    the same blocks of 32 output channels x 128 input channels for the block-float GEMM,
+ *               with the weights kept as 2-bit codes (1024 bytes per block, block (nb, kb) at byte
+ *               (nb * Kp/128 + kb) * 1024) and expanded to E2M1 in registers.  Row r = n % 32 takes
+ *               32 bytes; its 8-byte piece p holds unit u = p ^ ((r / 8) % 4), i.e. channels
+ *               128*kb + 32*u ... + 31, as two 32-bit words of 16 channels each: nibble j (0..7) of a
+ *               word holds channels j and 8 + j of its 16, as (sign of j, sign of 8+j, magnitude of j,
+ *               magnitude of 8+j) from bit 3 down to bit 0, so that `w & 0xAAAAAAAA` and
+ *               `(w << 1) & 0xAAAAAAAA` are the E2M1 nibbles of channels 0..7 and 8..15.
  *   BL_W_ROWS   output-channel major: row n takes Kp/4 bytes at n * Kp/4; 32-bit word w of the
  *               row holds channels 16w ... 16w+15, channel 16w + f in bits 2f, 2f+1 (so byte b of
  *               the word holds channels 4b ... 4b+3).  A row can be fetched, or skipped, on its
@@ -96,7 +104,7 @@ typedef enum {
   BL_ACT_INT4_ABSMAX = 6       /* 4-bit absmax, the form of eq. 3 with 7 in place of 127 (ablation) */
 } bl_act_mode;
 
-typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1, BL_W_MX4 = 2, BL_W_ROWS = 3 } bl_w_layout;
+typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1, BL_W_MX4 = 2, BL_W_ROWS = 3, BL_W_MX2 = 4 } bl_w_layout;
 
 typedef enum {
   BL_OK = 0,

@@ -17,7 +17,7 @@ BL_F32, BL_BF16 = 0, 1
 BL_ACT_INT4_ABSMEAN, BL_ACT_TOPK_INT8_ABSMAX, BL_ACT_FP4_E2M1_B32, BL_ACT_INT4_ABSMEAN_MX6 = 0, 1, 2, 3
 BL_ACT_FP4_E2M1_B32_MX = 4
 BL_ACT_INT4_ABSMEAN2, BL_ACT_INT4_ABSMAX = 5, 6
-BL_W_GEMM, BL_W_KMAJOR, BL_W_MX4, BL_W_ROWS = 0, 1, 2, 3
+BL_W_GEMM, BL_W_KMAJOR, BL_W_MX4, BL_W_ROWS, BL_W_MX2 = 0, 1, 2, 3, 4
 BL_DECODE_MAX_M = 64
 DEFAULT_EPS = 1e-5
 
@@ -164,9 +164,9 @@ def bitlinear_a4(X, W_packed, alpha, N, eps=DEFAULT_EPS, act_fp4=False, y_dtype=
     _dev(X)
     M, K = X.shape
     if act_fp4:
-        mode = BL_ACT_FP4_E2M1_B32_MX if layout == BL_W_MX4 else BL_ACT_FP4_E2M1_B32
+        mode = BL_ACT_FP4_E2M1_B32_MX if layout in (BL_W_MX4, BL_W_MX2) else BL_ACT_FP4_E2M1_B32
     else:
-        mode = BL_ACT_INT4_ABSMEAN_MX6 if layout == BL_W_MX4 else BL_ACT_INT4_ABSMEAN
+        mode = BL_ACT_INT4_ABSMEAN_MX6 if layout in (BL_W_MX4, BL_W_MX2) else BL_ACT_INT4_ABSMEAN
     if ws is None:
         ws = workspace(mode, M, N, K, X.device)
     Y, acc = _out(M, N, y_dtype, X.device, want_acc) if out is None else (out, None)

@@ -5,7 +5,8 @@
 static inline size_t ws_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static bool valid_dtype(int d) { return d == BL_F32 || d == BL_BF16; }
-static bool valid_layout(int l) { return l >= BL_W_GEMM && l <= BL_W_ROWS; }
+static bool valid_layout(int l) { return l >= BL_W_GEMM && l <= BL_W_MX2; }
+static bool mx_layout(int l) { return l == BL_W_MX4 || l == BL_W_MX2; }
 static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_INT4_ABSMAX; }
 static bool int4_nibble_mode(int m) {
   return m == BL_ACT_INT4_ABSMEAN || m == BL_ACT_INT4_ABSMEAN2 || m == BL_ACT_INT4_ABSMAX;
@@ -42,6 +43,7 @@ extern "C" size_t pack_ternary_bytes(int64_t N, int64_t K, bl_w_layout layout) {
   if (layout == BL_W_GEMM) return (size_t)(bl_round_up(N, 16) * bl_round_up(K, BL_KPAD) / 4);
   if (layout == BL_W_KMAJOR) return (size_t)(bl_round_up(N, 512) / 4 * K);
   if (layout == BL_W_MX4) return (size_t)(bl_round_up(N, 32) * bl_round_up(K, BL_KPAD) / 2);
+  if (layout == BL_W_MX2) return (size_t)(bl_round_up(N, 32) * bl_round_up(K, BL_KPAD) / 4);
   if (layout == BL_W_ROWS) return (size_t)(N * bl_round_up(K, BL_KPAD) / 4);
   return 0;
 }
@@ -153,12 +155,14 @@ static int gemm_dispatch(const void* q, const void* scale, bl_act_mode mode, int
   // the block-float forms of activations and weights go together and with nothing else
   if (layout == BL_W_ROWS) return BL_EUNSUPPORTED;       // only the gate-first up projection reads rows
   if (int4_nibble_mode(mode)) mode = BL_ACT_INT4_ABSMEAN;   // same codes, same rescale
-  if (mx_mode(mode) != (layout == BL_W_MX4)) return BL_EINVAL;
+  if (mx_mode(mode) != mx_layout(layout)) return BL_EINVAL;
   if (mode == BL_ACT_INT4_ABSMEAN_MX6)
-    return bl_launch_gemm_a4_mx(q, (const float*)scale, M, K, W_packed, alpha, N, Y, y_dtype, acc_out, s);
+    return bl_launch_gemm_a4_mx(q, (const float*)scale, M, K, W_packed, layout == BL_W_MX2, alpha, N, Y, y_dtype,
+                                acc_out, s);
   if (mode == BL_ACT_FP4_E2M1_B32_MX) {
     if (acc_out) return BL_EINVAL;
-    return bl_launch_gemm_fp4_mx(q, (const uint8_t*)scale, M, K, W_packed, alpha, N, Y, y_dtype, s);
+    return bl_launch_gemm_fp4_mx(q, (const uint8_t*)scale, M, K, W_packed, layout == BL_W_MX2, alpha, N, Y,
+                                 y_dtype, s);
   }
   if (mode == BL_ACT_FP4_E2M1_B32) {
     if (layout != BL_W_GEMM || acc_out) return BL_EINVAL;
@@ -215,7 +219,7 @@ static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, 
   // reject what the second stage would reject, before the first kernel is enqueued
   if (mode == BL_ACT_FP4_E2M1_B32 && (layout != BL_W_GEMM || acc_out)) return BL_EINVAL;
   if (mode == BL_ACT_FP4_E2M1_B32_MX && acc_out) return BL_EINVAL;
-  if (mx_mode(mode) != (layout == BL_W_MX4)) return BL_EINVAL;
+  if (mx_mode(mode) != mx_layout(layout)) return BL_EINVAL;
   if (layout == BL_W_KMAJOR && (mode != BL_ACT_TOPK_INT8_ABSMAX || M > 8)) return BL_EUNSUPPORTED;
   if (layout == BL_W_ROWS) return BL_EUNSUPPORTED;
 
@@ -250,9 +254,9 @@ extern "C" int bitlinear_a4(const void* X, bl_dtype x_dtype, int64_t M, int64_t 
                             int32_t* acc_out, void* workspace, size_t workspace_bytes,
                             void* stream) {
   if (act_fp4 != 0 && act_fp4 != 1) return BL_EINVAL;
-  if (layout != BL_W_GEMM && layout != BL_W_MX4) return valid_layout(layout) ? BL_EUNSUPPORTED : BL_EINVAL;
-  const bl_act_mode int4_mode = layout == BL_W_MX4 ? BL_ACT_INT4_ABSMEAN_MX6 : BL_ACT_INT4_ABSMEAN;
-  const bl_act_mode fp4_mode_ = layout == BL_W_MX4 ? BL_ACT_FP4_E2M1_B32_MX : BL_ACT_FP4_E2M1_B32;
+  if (layout != BL_W_GEMM && !mx_layout(layout)) return valid_layout(layout) ? BL_EUNSUPPORTED : BL_EINVAL;
+  const bl_act_mode int4_mode = mx_layout(layout) ? BL_ACT_INT4_ABSMEAN_MX6 : BL_ACT_INT4_ABSMEAN;
+  const bl_act_mode fp4_mode_ = mx_layout(layout) ? BL_ACT_FP4_E2M1_B32_MX : BL_ACT_FP4_E2M1_B32;
   return linear_common(X, x_dtype, M, K, act_fp4 ? fp4_mode_ : int4_mode, 0,
                        W_packed, layout, alpha, N, eps, Y, y_dtype, acc_out, workspace,
                        workspace_bytes, stream);

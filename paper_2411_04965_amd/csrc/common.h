@@ -125,10 +125,10 @@ int bl_launch_gemv_sparse(const void* q, const float* scale, int64_t M, int64_t 
                           const void* Wk, const float* alpha, int64_t N, void* Y, bl_dtype ydt,
                           int32_t* acc_out, void* ws, hipStream_t s);
 size_t bl_gemv_sparse_ws_bytes(int64_t M, int64_t N, int64_t K);
-int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K, const void* Wp,
+int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K, const void* Wp, bool w2,
                          const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,
                          hipStream_t s);
-int bl_launch_gemm_fp4_mx(const void* q, const uint8_t* xscale, int64_t M, int64_t K, const void* Wp,
+int bl_launch_gemm_fp4_mx(const void* q, const uint8_t* xscale, int64_t M, int64_t K, const void* Wp, bool w2,
                           const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);
 int bl_launch_gemm_fp4(const void* q, const uint8_t* scale, int64_t M, int64_t K, const void* Wp,
                        const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);

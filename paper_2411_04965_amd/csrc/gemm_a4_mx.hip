@@ -69,7 +69,11 @@ __device__ __forceinline__ u32 gx_pack_bf16(float lo, float hi) {
 // scaled form with the block scales as the column operand's scale (`xsc`, 128 bytes per block in
 // block order; each lane holds exactly one 32-channel block of one token per instruction), no
 // per-token scale, float32 sums that are no longer integers.
-template <int OUT, bool ACC, bool FP4>
+// W2: the weights arrive as 2-bit codes (1 KB per block, BL_W_MX2) and are expanded to E2M1 nibbles
+// in registers behind the fragment read (3 vector instructions per 16 channels) instead of being
+// stored expanded: half the weight bytes from HBM, L2 and LDS, two instead of four pieces per
+// wave and step.
+template <int OUT, bool ACC, bool FP4, bool W2>
 __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale,
     const unsigned char* __restrict__ xsc, int M, int KB,
@@ -83,8 +87,9 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   const int n_tiles = MT * NTB;
   const int MB = (M + 31) >> 5, NB = (N + 31) >> 5;           // 32-row blocks of the operands
   constexpr int WM = 128, WN = 128, TM = 4, TN = 4;
-  constexpr int LA = FP4 ? 4 : 6, LB = 4;        // 1 KB pieces per wave and step: activations, weights
+  constexpr int LA = FP4 ? 4 : 6, LB = W2 ? 2 : 4;   // 1 KB pieces per wave and step: activations, weights
   constexpr int A_BLOCK = FP4 ? 2048 : GX_A_BLOCK;
+  constexpr int W_BLOCK = W2 ? 1024 : GX_W_BLOCK;
 
   // ---- global loads.  One cursor per operand names the (tile, K step) that is loaded next and
   // moves on along the block's stream of tiles by itself; weights run two steps ahead of the
@@ -102,7 +107,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     for (int i = 0; i < 2; ++i) {
       // row blocks past the end of an operand re-read its last block (their results are never stored)
       if (is_a) c.p[i] = A + (size_t)min((m0 >> 5) + 2 * wave + i, MB - 1) * KB * A_BLOCK;
-      else c.p[i] = Wp + (size_t)min((n0 >> 5) + 2 * wave + i, NB - 1) * KB * GX_W_BLOCK;
+      else c.p[i] = Wp + (size_t)min((n0 >> 5) + 2 * wave + i, NB - 1) * KB * W_BLOCK;
     }
   };
   // one step on; behind the block's last step the cursor stays where it is (loads that nobody uses)
@@ -113,7 +118,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     } else {
       ++c.kb;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) c.p[i] += is_a ? A_BLOCK : GX_W_BLOCK;
+      for (int i = 0; i < 2; ++i) c.p[i] += is_a ? A_BLOCK : W_BLOCK;
     }
   };
   // Two sets of staging registers, used by even and odd steps in turn: a register is refilled
@@ -127,8 +132,9 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   auto load_a = [&](const Cursor& c, int set, int j) {
     a_reg[set][j] = *reinterpret_cast<const v4i*>(c.p[j / PA] + (j % PA) * 1024 + lane16);
   };
+  constexpr int PB = LB / 2;                     // pieces per row block
   auto load_b = [&](const Cursor& c, int set, int j) {
-    b_reg[set][j] = *reinterpret_cast<const v4i*>(c.p[j / 2] + (j % 2) * 1024 + lane16);
+    b_reg[set][j] = *reinterpret_cast<const v4i*>(c.p[j / PB] + (j % PB) * 1024 + lane16);
   };
   auto store_a = [&](unsigned char* st, int set, int j) {
     const int rb = 2 * wave + j / PA, i = j % PA;
@@ -136,7 +142,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     *reinterpret_cast<v4i*>(dst + lane16) = a_reg[set][j];
   };
   auto store_b = [&](unsigned char* st, int set, int j) {
-    *reinterpret_cast<v4i*>(st + GX_W + (2 * wave + j / 2) * 2048 + (j % 2) * 1024 + lane16) = b_reg[set][j];
+    *reinterpret_cast<v4i*>(st + GX_W + (2 * wave + j / PB) * W_BLOCK + (j % PB) * 1024 + lane16) = b_reg[set][j];
   };
 
   // ---- FP4: block scales of the wave's four token blocks, one word (4 units) per lane and step,
@@ -177,7 +183,8 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     const int u = 2 * s + lh;
     xp_off[s] = (wm * WM + l32) * 64 + ((u ^ ((l32 >> 2) & 3)) << 4);
     xq_off[s] = GX_XQ + (wm * WM + l32) * 32 + ((u ^ ((l32 >> 3) & 3)) << 3);
-    w_off[s] = GX_W + (wn * WN + l32) * 64 + ((u ^ ((l32 >> 2) & 3)) << 4);
+    w_off[s] = W2 ? GX_W + (wn * WN + l32) * 32 + ((u ^ ((l32 >> 3) & 3)) << 3)
+                  : GX_W + (wn * WN + l32) * 64 + ((u ^ ((l32 >> 2) & 3)) << 4);
   }
   typedef typename std::conditional<FP4, v4i, v6i>::type XFrag;
   struct Frags {
@@ -194,7 +201,16 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     }
   };
   auto read_w = [&](const unsigned char* st, int s, int a) -> v4i {
-    return *reinterpret_cast<const v4i*>(st + w_off[s] + a * 2048);
+    if constexpr (W2) {
+      // two words of 16 two-bit codes (nibble j: sign and magnitude of channels j and 8 + j as bits
+      // s_j s_8+j m_j m_8+j) -> four words of E2M1 nibbles in channel order (s 0 m 0)
+      const v2i w = *reinterpret_cast<const v2i*>(st + w_off[s] + a * 1024);
+      const u32 w0 = (u32)w[0], w1 = (u32)w[1];
+      return (v4i){(int)(w0 & 0xAAAAAAAAu), (int)((w0 << 1) & 0xAAAAAAAAu),
+                   (int)(w1 & 0xAAAAAAAAu), (int)((w1 << 1) & 0xAAAAAAAAu)};
+    } else {
+      return *reinterpret_cast<const v4i*>(st + w_off[s] + a * 2048);
+    }
   };
 
   // The accumulators are pinned to AGPRs and updated in place.  (The host pass of the compiler
@@ -321,7 +337,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
           const int i = a * TM + b;              // one slot behind each MFMA
           if (i < 4) F[1].x[i] = read_x(st_own, 1, i);
           else if (i < 8) F[1].w[i - 4] = read_w(st_own, 1, i - 4);
-          else if (i % 2 == 0) {                 // slots 8, 10, 12, 14: weights of the next step
+          else if (i % 2 == 0 && (i - 8) / 2 < LB) {   // slots 8, 10, ...: weights of the next step
             store_b(st_other, PAR, (i - 8) / 2);
             load_b(cb, PAR, (i - 8) / 2);
           }
@@ -497,42 +513,46 @@ static int gx_num_cus() {
   return cus;
 }
 
-template <int OUT, bool ACC, bool FP4>
+template <int OUT, bool ACC, bool FP4, bool W2>
 static int gx_go(const void* q, const float* scale, const uint8_t* xsc, int M, int KB, const void* Wp,
                  const float* alpha, int N, void* Y, int y_bf16, int32_t* acc_out, int MT, int NTB,
                  hipStream_t s) {
-  if (hipFuncSetAttribute((const void*)gemm_a4_mx_kernel<OUT, ACC, FP4>,
+  if (hipFuncSetAttribute((const void*)gemm_a4_mx_kernel<OUT, ACC, FP4, W2>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, GX_LDS) != hipSuccess)
     return BL_EHIP;
   const int grid = min(MT * NTB, gx_num_cus());      // persistent blocks, one per CU (all of its LDS)
-  gemm_a4_mx_kernel<OUT, ACC, FP4><<<(unsigned)grid, GX_THREADS, GX_LDS, s>>>(
+  gemm_a4_mx_kernel<OUT, ACC, FP4, W2><<<(unsigned)grid, GX_THREADS, GX_LDS, s>>>(
       (const unsigned char*)q, scale, (const unsigned char*)xsc, M, KB, (const unsigned char*)Wp, alpha, N, Y,
       y_bf16, acc_out, MT, NTB);
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;
 }
 
-int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K, const void* Wp,
+int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K, const void* Wp, bool w2,
                          const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,
                          hipStream_t s) {
   const int KB = (int)(bl_round_up(K, BL_KPAD) / 128);
   const int MT = (int)((M + GX_BM - 1) / GX_BM), NTB = (int)((N + GX_BN - 1) / GX_BN);
   const int out = (ydt == BL_BF16 && (N & 7) == 0) ? 0 : ((N & 3) == 0 ? 1 : 2);
   const int yb = ydt == BL_BF16 ? 1 : 0;
-#define GX_CALL(OUT, ACC) gx_go<OUT, ACC, false>(q, scale, nullptr, (int)M, KB, Wp, alpha, (int)N, Y, yb, acc_out, MT, NTB, s)
+#define GX_CALL(OUT, ACC) \
+  (w2 ? gx_go<OUT, ACC, false, true>(q, scale, nullptr, (int)M, KB, Wp, alpha, (int)N, Y, yb, acc_out, MT, NTB, s) \
+      : gx_go<OUT, ACC, false, false>(q, scale, nullptr, (int)M, KB, Wp, alpha, (int)N, Y, yb, acc_out, MT, NTB, s))
   if (acc_out) return out == 0 ? GX_CALL(0, true) : out == 1 ? GX_CALL(1, true) : GX_CALL(2, true);
   return out == 0 ? GX_CALL(0, false) : out == 1 ? GX_CALL(1, false) : GX_CALL(2, false);
 #undef GX_CALL
 }
 
 // FP4 activations (E2M1 codes and E8M0 block scales in the MX form) x BL_W_MX4 weights.
-int bl_launch_gemm_fp4_mx(const void* q, const uint8_t* xscale, int64_t M, int64_t K, const void* Wp,
+int bl_launch_gemm_fp4_mx(const void* q, const uint8_t* xscale, int64_t M, int64_t K, const void* Wp, bool w2,
                           const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s) {
   const int KB = (int)(bl_round_up(K, BL_KPAD) / 128);
   const int MT = (int)((M + GX_BM - 1) / GX_BM), NTB = (int)((N + GX_BN - 1) / GX_BN);
   const int out = (ydt == BL_BF16 && (N & 7) == 0) ? 0 : ((N & 3) == 0 ? 1 : 2);
   const int yb = ydt == BL_BF16 ? 1 : 0;
-#define GX_CALL4(OUT) gx_go<OUT, false, true>(q, nullptr, xscale, (int)M, KB, Wp, alpha, (int)N, Y, yb, nullptr, MT, NTB, s)
+#define GX_CALL4(OUT) \
+  (w2 ? gx_go<OUT, false, true, true>(q, nullptr, xscale, (int)M, KB, Wp, alpha, (int)N, Y, yb, nullptr, MT, NTB, s) \
+      : gx_go<OUT, false, true, false>(q, nullptr, xscale, (int)M, KB, Wp, alpha, (int)N, Y, yb, nullptr, MT, NTB, s))
   return out == 0 ? GX_CALL4(0) : out == 1 ? GX_CALL4(1) : GX_CALL4(2);
 #undef GX_CALL4
 }

@@ -144,6 +144,45 @@ __global__ __launch_bounds__(PT_THREADS) void ternarize_pack_mx4_kernel(
   out[w] = word;
 }
 
+// One thread per 32-bit word of the 2-bit block-float GEMM layout: blocks of 32 outputs x 128 input
+// channels (1024 bytes); inside, row r = n % 32 takes 32 bytes, its 8-byte piece p holds the 32
+// channels of unit u = p ^ ((r / 8) % 4) as two words of 16 channels: nibble j of a word keeps
+// channels j and 8 + j as (sign j, sign 8+j, magnitude j, magnitude 8+j) from bit 3 down, so that
+// one mask, and one shift and mask, give their E2M1 nibbles (sign 0 magnitude 0).
+template <typename T>
+__global__ __launch_bounds__(PT_THREADS) void ternarize_pack_mx2_kernel(
+    const T* __restrict__ W, int64_t N, int64_t K, int64_t Kp, float eps,
+    const double* __restrict__ partial, int n_partial, u32* __restrict__ out,
+    float* __restrict__ alpha_out, int64_t n_words) {
+  __shared__ double red[PT_THREADS / BL_WAVE];
+  const float alpha = pt_alpha(partial, n_partial, N * K, red);
+  if (blockIdx.x == 0 && threadIdx.x == 0) alpha_out[0] = alpha;
+  const float t = alpha + eps;
+  const int64_t w = (int64_t)blockIdx.x * PT_THREADS + threadIdx.x;
+  if (w >= n_words) return;
+  const int64_t blk = w >> 8;               // 256 words per block
+  const int in = (int)(w & 255);
+  const int r = in >> 3, p = (in >> 1) & 3, h = in & 1;
+  const int64_t KB = Kp / 128;
+  const int64_t n = (blk / KB) * 32 + r;
+  const int64_t k0 = (blk % KB) * 128 + 32 * (p ^ ((r >> 3) & 3)) + 16 * h;
+  u32 word = 0;
+  if (n < N) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (k0 + j < K) {
+        const u32 c = pt_code(pt_load<T>(W, n * K + k0 + j), t);            // 00, 01, 11
+        word |= (((c & 2u) << 2) | ((c & 1u) << 1)) << (4 * j);
+      }
+      if (k0 + 8 + j < K) {
+        const u32 c = pt_code(pt_load<T>(W, n * K + k0 + 8 + j), t);
+        word |= (((c & 2u) << 1) | (c & 1u)) << (4 * j);
+      }
+    }
+  }
+  out[w] = word;
+}
+
 // One thread per 32-bit word of the output-channel-major layout: row n, channels 16 w .. 16 w + 15,
 // channel 16 w + f in bits 2 f, 2 f + 1.
 template <typename T>
@@ -182,7 +221,13 @@ __global__ __launch_bounds__(PT_THREADS) void unpack_ternary_kernel(const u32* _
     T[id] = (int8_t)(c == 0 ? 0 : ((c & 8u) ? -1 : 1));
     return;
   }
-  if (layout == BL_W_ROWS) {
+  if (layout == BL_W_MX2) {
+    const int r = (int)(n & 31), u = (int)((k >> 5) & 3), i = (int)(k & 31);
+    word = packed[((n >> 5) * (Kp / 128) + (k >> 7)) * 256 + r * 8 + ((u ^ ((r >> 3) & 3)) << 1) + (i >> 4)];
+    const u32 nib = (word >> (4 * (i & 7))) << ((i >> 3) & 1);       // channel's sign in bit 3, magnitude in bit 1
+    T[id] = (int8_t)((nib & 2u) ? ((nib & 8u) ? -1 : 1) : 0);
+    return;
+  } else if (layout == BL_W_ROWS) {
     word = packed[n * (Kp / 16) + (k >> 4)];
     f = (int)(k & 15);
   } else if (layout == BL_W_GEMM) {
@@ -224,6 +269,12 @@ static int pt_run(const T* W, int64_t N, int64_t K, float eps, bl_w_layout layou
     const int64_t n_words = Np * Kp / 8;
     const int64_t blocks = (n_words + PT_THREADS - 1) / PT_THREADS;
     ternarize_pack_mx4_kernel<T><<<(unsigned)blocks, PT_THREADS, 0, s>>>(
+        W, N, K, Kp, eps, partial, np, (u32*)out, alpha, n_words);
+  } else if (layout == BL_W_MX2) {
+    const int64_t Kp = bl_round_up(K, BL_KPAD), Np = bl_round_up(N, 32);
+    const int64_t n_words = Np * Kp / 16;
+    const int64_t blocks = (n_words + PT_THREADS - 1) / PT_THREADS;
+    ternarize_pack_mx2_kernel<T><<<(unsigned)blocks, PT_THREADS, 0, s>>>(
         W, N, K, Kp, eps, partial, np, (u32*)out, alpha, n_words);
   } else if (layout == BL_W_ROWS) {
     const int64_t Kp = bl_round_up(K, BL_KPAD);

@@ -84,6 +84,26 @@ def decode_w_mx4(packed, N, K):
     return full[:N, :K]
 
 
+def decode_w_mx2(packed, N, K):
+    """BL_W_MX2 bytes -> int8 [N, K]: 1 KB blocks of 32 outputs x 128 channels, 2-bit codes."""
+    Kp = (K + 255) // 256 * 256
+    Np = (N + 31) // 32 * 32
+    w = np.frombuffer(packed.tobytes(), dtype="<u4").reshape(Np // 32, Kp // 128, 32, 4, 2)
+    r = np.arange(32)
+    u = np.arange(4)
+    piece = u[None, :] ^ ((r[:, None] >> 3) & 3)                    # [r, u] -> piece that holds unit u
+    units = w[:, :, r[:, None], piece, :]                           # [nb, kb, r, u, 2 words]
+    j = np.arange(8, dtype=np.uint32)
+    nib = (units[..., None] >> (4 * j)) & 15                        # s_j s_8+j m_j m_8+j
+    lo = np.where(nib & 2, np.where(nib & 8, -1, 1), 0)             # channels 0..7 of the word's 16
+    hi = np.where(nib & 1, np.where(nib & 4, -1, 1), 0)             # channels 8..15
+    assert not ((nib & 8) & ~((nib & 2) << 2)).any() and not ((nib & 4) & ~((nib & 1) << 2)).any()   # no -0
+    T = np.concatenate([lo, hi], axis=-1).reshape(Np // 32, Kp // 128, 32, 4, 32).astype(np.int8)
+    full = np.transpose(T, (0, 2, 1, 3, 4)).reshape(Np, Kp)
+    assert not full[N:].any() and not full[:, K:].any()
+    return full[:N, :K]
+
+
 def decode_w_rows(packed, N, K):
     """BL_W_ROWS bytes -> int8 [N, K]: row n = Kp/4 bytes, channel k in bits 2 (k % 16) of word k / 16."""
     Kp = (K + 255) // 256 * 256

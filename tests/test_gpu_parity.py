@@ -10,7 +10,7 @@ from oracle import bitnet_a48 as O
 from paper_2411_04965_amd import binding as B
 from paper_2411_04965_amd import synth as S
 from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_fp4_mx, decode_int4, decode_int4_mx6,
-                            decode_int8, decode_w_gemm, decode_w_kmajor, decode_w_mx4, decode_w_rows, dev, host,
+                            decode_int8, decode_w_gemm, decode_w_kmajor, decode_w_mx2, decode_w_mx4, decode_w_rows, dev, host,
                             pack)
 
 pytestmark = pytest.mark.gpu
@@ -25,7 +25,7 @@ def say(msg):
 # ------------------------------------------------------------------ pack_ternary (eq. 2)
 @pytest.mark.parametrize("N,K,dtype", [(512, 256, F32), (256, 512, F32), (37, 100, F32),
                                        (1030, 5460, BF16), (2048, 5460, F32)])
-@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_KMAJOR, B.BL_W_MX4, B.BL_W_ROWS])
+@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_KMAJOR, B.BL_W_MX4, B.BL_W_ROWS, B.BL_W_MX2])
 def test_pack_ternary(N, K, dtype, layout):
     say("pack_ternary N=%d K=%d %s layout=%d" % (N, K, dtype, layout))
     W = S.latent_weights(N, K, seed=S.seed_for(0, N + K))
@@ -37,7 +37,7 @@ def test_pack_ternary(N, K, dtype, layout):
     T_lib = host(B.unpack_ternary(packed, N, K, layout))
     assert np.array_equal(T_lib, T_ref)
     dec = {B.BL_W_GEMM: decode_w_gemm, B.BL_W_KMAJOR: decode_w_kmajor, B.BL_W_MX4: decode_w_mx4,
-           B.BL_W_ROWS: decode_w_rows}[layout]
+           B.BL_W_ROWS: decode_w_rows, B.BL_W_MX2: decode_w_mx2}[layout]
     assert np.array_equal(dec(host(packed), N, K), T_ref)
 
 
@@ -305,6 +305,7 @@ def _decode_weights(name, N, K):
             packs[B.BL_W_KMAJOR] = pack(W, B.BL_W_KMAJOR)
         else:
             packs[B.BL_W_MX4] = pack(W, B.BL_W_MX4)
+            packs[B.BL_W_MX2] = pack(W, B.BL_W_MX2)
         _wcache[name] = (T, alpha, packs)
     return _wcache[name]
 
@@ -421,8 +422,9 @@ def test_linears_seeded_shape_sweep():
         p, a = pack(W)
         _check_linear(B.bitlinear_a4(Xd, p, a, N, EPS, y_dtype=BF16, want_acc=True), ref4, BF16)
         _check_linear(B.bitlinear_a8_sparse(Xd, topk, p, a, N, EPS, B.BL_W_GEMM, BF16, True), ref8, BF16)
-        pm, am = pack(W, B.BL_W_MX4)
-        _check_linear(B.bitlinear_a4(Xd, pm, am, N, EPS, y_dtype=BF16, want_acc=True, layout=B.BL_W_MX4), ref4, BF16)
+        for wl in (B.BL_W_MX4, B.BL_W_MX2):
+            pm, am = pack(W, wl)
+            _check_linear(B.bitlinear_a4(Xd, pm, am, N, EPS, y_dtype=BF16, want_acc=True, layout=wl), ref4, BF16)
         if M <= 8:
             pk, ak = pack(W, B.BL_W_KMAJOR)
             _check_linear(B.bitlinear_a8_sparse(Xd, topk, pk, ak, N, EPS, B.BL_W_KMAJOR, BF16, True), ref8, BF16)
@@ -436,7 +438,7 @@ def test_maximum_width():
     X = S.heavy(M, K, S.seed_for(0, 90))
     W = S.latent_weights(N, K, S.seed_for(0, 91))
     ref4 = O.bitlinear_a4(X, W, EPS, "f32")
-    for layout in (B.BL_W_GEMM, B.BL_W_MX4):
+    for layout in (B.BL_W_GEMM, B.BL_W_MX4, B.BL_W_MX2):
         p, a = pack(W, layout)
         _check_linear(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=F32, want_acc=True, layout=layout), ref4, F32)
     p, a = pack(W)
@@ -451,19 +453,20 @@ def test_maximum_width():
 @pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (300, 520, 1000, BF16), (130, 2048, 5460, BF16),
                                          (257, 5460, 2048, BF16), (1100, 1100, 768, BF16),
                                          (70, 1030, 300, BF16), (33, 257, 4096, F32), (600, 1500, 256, BF16)])
-def test_a4_block_float_gemm(M, N, K, dtype):
-    """The INT4 linear on the 6-bit x 4-bit matrix instruction (BL_W_MX4 weights): accumulators
+@pytest.mark.parametrize("wl", [B.BL_W_MX4, B.BL_W_MX2])
+def test_a4_block_float_gemm(M, N, K, dtype, wl):
+    """The INT4 linear on the 6-bit x 4-bit matrix instruction (BL_W_MX4 / BL_W_MX2 weights): accumulators
     bit-exact against the integer oracle, for several tiles, ragged M / N / K, every store path
     (N % 8 == 0, N % 4 == 0, odd N) and a single K block."""
     say("a4 block-float M=%d N=%d K=%d %s" % (M, N, K, dtype))
     X = S.heavy(M, K, S.seed_for(1, M + N))
     W = S.latent_weights(N, K, S.seed_for(1, K + N + 1))
-    p, a = pack(W, B.BL_W_MX4)
+    p, a = pack(W, wl)
     ref = O.bitlinear_a4(X, W, EPS, "bf16" if dtype == BF16 else "f32")
-    _check_linear(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=dtype, want_acc=True, layout=B.BL_W_MX4),
+    _check_linear(B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=dtype, want_acc=True, layout=wl),
                   ref, dtype)
     # the kernel variant without accumulator output (the one a caller normally runs)
-    Y = B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=dtype, layout=B.BL_W_MX4)
+    Y = B.bitlinear_a4(dev(X, BF16), p, a, N, EPS, y_dtype=dtype, layout=wl)
     assert np.array_equal(host(Y), ref["y"])
 
 
@@ -483,9 +486,10 @@ def test_config3_prefill_sampled_rows(name, N, K, kind):
         Y, acc = B.bitlinear_a4(Xd, p, a, N, EPS, y_dtype=BF16, want_acc=True)
         q, d = O.quant_int4(X[rows], EPS)
         # and on the block-float path, in the launch configuration the benchmark times
-        pm, am = packs[B.BL_W_MX4]
-        Ym = B.bitlinear_a4(Xd, pm, am, N, EPS, y_dtype=BF16, layout=B.BL_W_MX4)
-        assert torch.equal(Ym, Y)
+        for wl in (B.BL_W_MX2, B.BL_W_MX4):
+            pm, am = packs[wl]
+            Ym = B.bitlinear_a4(Xd, pm, am, N, EPS, y_dtype=BF16, layout=wl)
+            assert torch.equal(Ym, Y)
     else:
         Y, acc = B.bitlinear_a8_sparse(Xd, K // 2, p, a, N, EPS, B.BL_W_GEMM, BF16, True)
         q, d, _ = O.quant_topk_int8(X[rows], K // 2, EPS)
@@ -530,7 +534,7 @@ def _check_fp4(Y, ref, rows=None):
     assert np.all(err <= bound + 1e-30), "max err/bound %g" % (err / (bound + 1e-30)).max()
 
 
-@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_MX4])
+@pytest.mark.parametrize("layout", [B.BL_W_GEMM, B.BL_W_MX4, B.BL_W_MX2])
 @pytest.mark.parametrize("M,N,K,dtype", [(16, 512, 256, F32), (130, 200, 992, BF16), (300, 1100, 3200, BF16),
                                          (257, 1030, 288, BF16), (600, 257, 1504, BF16)])
 def test_fp4_linear(M, N, K, dtype, layout):
@@ -569,8 +573,8 @@ def test_config4_fp4_sampled_rows(name, N, K):
     _check_fp4(Y[torch.from_numpy(rows).cuda()], ref)
     # and on the prefill kernel (E2M1 weights in LDS tile order), in the launch configuration the
     # FP4 / INT4 comparison is timed in
-    pm, am = pack(W, B.BL_W_MX4)
-    Ym = B.bitlinear_a4(dev(X, BF16), pm, am, N, EPS, act_fp4=True, y_dtype=F32, layout=B.BL_W_MX4)
+    pm, am = pack(W, B.BL_W_MX2)
+    Ym = B.bitlinear_a4(dev(X, BF16), pm, am, N, EPS, act_fp4=True, y_dtype=F32, layout=B.BL_W_MX2)
     _check_fp4(Ym[torch.from_numpy(rows).cuda()], ref)
     # the INT4 path on identical inputs (the comparison the paper makes): both are reported
     # against the product of the raw activations with the same ternary weights; with
