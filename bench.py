@@ -35,8 +35,8 @@ HBM_PEAK_GBS = 8000.0
 # Bytes between L2 and the memory fabric per launch of the W1.58A4 prefill GEMM at the benchmark
 # shapes, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/gemm_7b_prefill_hbm_traffic.txt (calibrated against a 1 GiB device copy):
-# 677.6 MB fetched + 374.7 MB written.
-A4_GEMM_TRAFFIC_BYTES = 1052.3e6
+# 490.2 MB fetched + 374.7 MB written (2-bit weights; 677.6 MB fetched with E2M1 nibbles).
+A4_GEMM_TRAFFIC_BYTES = 864.9e6
 HIDDEN, FFN = 4096, 11008
 
 
