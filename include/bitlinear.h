@@ -140,7 +140,7 @@ int pack_ternary(const void* W, bl_dtype w_dtype, int64_t N, int64_t K, float ep
  * quantize_act: one token per row, statistics per token.
  *   BL_ACT_INT4_ABSMEAN (eq. 7):  beta = mean|x| (float64 sum, rounded once);
  *       q = RoundClip(x * (sqrt7 / (beta + eps)), -8, 7);  scale_out[m] = beta / sqrt7.
- *   BL_ACT_INT4_ABSMEAN_MX6: the same quantizer, codes in the MX6 form (for BL_W_MX4 weights).
+ *   BL_ACT_INT4_ABSMEAN_MX6: the same quantizer, codes in the MX6 form (for BL_W_MX4 / BL_W_MX2 weights).
  *   BL_ACT_INT4_ABSMEAN2 (Section 4.3): eq. 7 with beta = 2 mean|x|; BL_ACT_INT4_ABSMAX (Section 4.3):
  *       gamma = max|x|; q = RoundClip(x * (7 / (gamma + eps)), -8, 7); scale_out[m] = gamma / 7.
  *       Both write the INT4 nibble form; the linear layers take their output as BL_ACT_INT4_ABSMEAN's.
@@ -153,8 +153,8 @@ int pack_ternary(const void* W, bl_dtype w_dtype, int64_t N, int64_t K, float ep
  *       2^e with max|x| / 2^e <= 6 (e = 0 for an all-zero block, clamped to [-127, 127]);
  *       codes = x / 2^e rounded to the nearest E2M1 value, ties to the even code, zero
  *       always stored as +0; scale_out = E8M0 bytes (e + 127), [M][Kp/32]; eps unused.
- *   BL_ACT_FP4_E2M1_B32_MX: the same quantizer, codes and scales in the MX form (for BL_W_MX4
- *       weights); scale_out then takes round_up(M, 32) * Kp/32 bytes.
+ *   BL_ACT_FP4_E2M1_B32_MX: the same quantizer, codes and scales in the MX form (for BL_W_MX4 /
+ *       BL_W_MX2 weights); scale_out then takes round_up(M, 32) * Kp/32 bytes.
  *   X           device, [M, K] of x_dtype
  *   q_out       device, quantize_act_bytes(mode, M, K) bytes, fully overwritten
  *   scale_out   device, float32[M] (INT modes) or uint8[M * Kp/32] (FP4; MX form: M rounded up to 32)
@@ -176,12 +176,12 @@ int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, bl_act_m
  *   FP4 path: Y = alpha * sum over blocks 2^e * sum_k v_k * T[n, k], accumulated in
  *   float32 by the scaled FP4 matrix instruction (not bit-exact; acc_out must be NULL).
  *   X          device, [M, K] of x_dtype
- *   W_packed   device, output of pack_ternary for [N, K]; layout BL_W_GEMM, or BL_W_MX4
- *              (INT4 path only): then the activations are quantized to the MX6 form and the
+ *   W_packed   device, output of pack_ternary for [N, K]; layout BL_W_GEMM, or BL_W_MX4 / BL_W_MX2
+ *              (the block-float forms): then the activations are quantized to the MX6 form and the
  *              product runs on the 6-bit x 4-bit block-float matrix instruction at twice the
  *              INT8 rate; every product and every partial sum is an integer below 2^24, so the
  *              float32 accumulator equals the int32 one bit for bit.  Size the workspace with
- *              mode BL_ACT_INT4_ABSMEAN_MX6 in that case.  With act_fp4 = 1 and BL_W_MX4 the
+ *              mode BL_ACT_INT4_ABSMEAN_MX6 in that case.  With act_fp4 = 1 and a block-float form the
  *              activations go to the FP4 MX form and the product runs on the same instruction
  *              with the block scales as its scale operand (mode BL_ACT_FP4_E2M1_B32_MX).
  *   alpha      device, float32[1]
@@ -189,8 +189,9 @@ int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, bl_act_m
  *   acc_out    nullable; device int32[M, N], receives the integer accumulators
  *   workspace  device, >= bitlinear_workspace_bytes(mode, M, N, K) bytes; holds the
  *              packed activations and their scales between the two kernels
- * Kernel choice is by M: up to BL_DECODE_MAX_M tokens the weights are streamed once
- * by the skinny (decode) kernel, above that the tiled MFMA GEMM runs.
+ * Kernel choice (BL_W_GEMM) is by M: up to BL_DECODE_MAX_M tokens the weights are streamed once
+ * by a skinny (decode) kernel, with the quantizer inside the same launch for one token; above
+ * that the tiled MFMA GEMM runs.  The block-float forms always take the tiled GEMM.
  *
  * bitlinear_a8_sparse (eq. 1): Y = (Q_INT8(X) (.) Top_k(|X|)) . Q_w(W)^T, same
  * accumulation and rescale.  With layout BL_W_KMAJOR (decode, M <= BL_DECODE_MAX_M)
@@ -210,7 +211,7 @@ int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, i
 /* The matmul + rescale stage alone, on activations already quantized by quantize_act
  * (what the two calls above run after their quantize kernel).  q and scale are the
  * outputs of quantize_act in `mode`; BL_ACT_INT4_ABSMEAN_MX6 and BL_ACT_FP4_E2M1_B32_MX go with
- * BL_W_MX4 and with nothing else.  `workspace` must hold bitlinear_workspace_bytes(mode, M, N, K) bytes when
+ * BL_W_MX4 / BL_W_MX2 and with nothing else.  `workspace` must hold bitlinear_workspace_bytes(mode, M, N, K) bytes when
  * M <= BL_DECODE_MAX_M (partial sums of the split-K decode kernels) or the layout is
  * BL_W_KMAJOR; otherwise it may be NULL. */
 int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M, int64_t K,
