@@ -111,14 +111,16 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     }
   };
   // one step on; behind the block's last step the cursor stays where it is (loads that nobody uses)
+  // (the usual case without a taken branch: it sits between two MFMA sequences)
   auto advance = [&](Cursor& c, bool is_a) {
-    if (c.kb + 1 == KB) {
+    const bool last = c.kb + 1 == KB;
+    const int by = last ? 0 : (is_a ? A_BLOCK : W_BLOCK);
+    c.kb += last ? 0 : 1;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) c.p[i] += by;
+    if (__builtin_expect(last, 0)) {
       const int nt = c.tile + (int)gridDim.x;
       if (nt < n_tiles) point(c, nt, is_a);
-    } else {
-      ++c.kb;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) c.p[i] += is_a ? A_BLOCK : W_BLOCK;
     }
   };
   // Two sets of staging registers, used by even and odd steps in turn: a register is refilled
@@ -161,13 +163,14 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       c.p[b] = xsc + (size_t)min((m0 >> 5) + wm * 4 + b, MB - 1) * KB * 128 + l32 * 4;
   };
   auto advance_s = [&](SCursor& c) {
-    if (c.kb + 1 == KB) {
+    const bool last = c.kb + 1 == KB;
+    const int by = last ? 0 : 128;
+    c.kb += last ? 0 : 1;
+#pragma unroll
+    for (int b = 0; b < TM; ++b) c.p[b] += by;
+    if (__builtin_expect(last, 0)) {
       const int nt = c.tile + (int)gridDim.x;
       if (nt < n_tiles) point_s(c, nt);
-    } else {
-      ++c.kb;
-#pragma unroll
-      for (int b = 0; b < TM; ++b) c.p[b] += 128;
     }
   };
   u32 sc_reg[2][TM];
@@ -190,6 +193,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   struct Frags {
     XFrag x[TM];
     v4i w[TN];
+    v2i wr[TN];                                  // W2: the 2-bit codes as read, expanded a few slots later
   };
   auto read_x = [&](const unsigned char* st, int s, int b) -> XFrag {
     const v4i p = *reinterpret_cast<const v4i*>(st + xp_off[s] + b * 2048);
@@ -200,17 +204,28 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
       return (v6i){p[0], p[1], p[2], p[3], q[0], q[1]};
     }
   };
-  auto read_w = [&](const unsigned char* st, int s, int a) -> v4i {
-    if constexpr (W2) {
-      // two words of 16 two-bit codes (nibble j: sign and magnitude of channels j and 8 + j as bits
-      // s_j s_8+j m_j m_8+j) -> four words of E2M1 nibbles in channel order (s 0 m 0)
-      const v2i w = *reinterpret_cast<const v2i*>(st + w_off[s] + a * 1024);
-      const u32 w0 = (u32)w[0], w1 = (u32)w[1];
-      return (v4i){(int)(w0 & 0xAAAAAAAAu), (int)((w0 << 1) & 0xAAAAAAAAu),
-                   (int)(w1 & 0xAAAAAAAAu), (int)((w1 << 1) & 0xAAAAAAAAu)};
-    } else {
-      return *reinterpret_cast<const v4i*>(st + w_off[s] + a * 2048);
-    }
+  // two words of 16 two-bit codes (nibble j: sign and magnitude of channels j and 8 + j as bits
+  // s_j s_8+j m_j m_8+j) -> four words of E2M1 nibbles in channel order (s 0 m 0)
+  auto expand_w = [&](const v2i& w) -> v4i {
+    const u32 w0 = (u32)w[0], w1 = (u32)w[1];
+    return (v4i){(int)(w0 & 0xAAAAAAAAu), (int)((w0 << 1) & 0xAAAAAAAAu),
+                 (int)(w1 & 0xAAAAAAAAu), (int)((w1 << 1) & 0xAAAAAAAAu)};
+  };
+  // ... done in the slot where it is written: the empty statements keep the compiler from moving
+  // the arithmetic across the MFMAs around it in program order
+  auto expand_here = [&](Frags& f, int a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" : "+v"(f.wr[a]));            // not earlier ...
+#endif
+    f.w[a] = expand_w(f.wr[a]);
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" : "+v"(f.w[a]));             // ... and not later than here
+#endif
+  };
+  // W2: the read only (the expansion waits for the data, so it sits some MFMAs further down)
+  auto read_w = [&](Frags& f, const unsigned char* st, int s, int a) {
+    if constexpr (W2) f.wr[a] = *reinterpret_cast<const v2i*>(st + w_off[s] + a * 1024);
+    else f.w[a] = *reinterpret_cast<const v4i*>(st + w_off[s] + a * 2048);
   };
 
   // The accumulators are pinned to AGPRs and updated in place.  (The host pass of the compiler
@@ -291,8 +306,9 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     F[0].x[i] = read_x(gx_smem, 0, i);
-    F[0].w[i] = read_w(gx_smem, 0, i);
+    read_w(F[0], gx_smem, 0, i);
   }
+  if constexpr (W2) F[0].w[0] = expand_w(F[0].wr[0]);
 
   while (true) {
     const int next = tile + (int)gridDim.x;
@@ -336,10 +352,14 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
           }
           const int i = a * TM + b;              // one slot behind each MFMA
           if (i < 4) F[1].x[i] = read_x(st_own, 1, i);
-          else if (i < 8) F[1].w[i - 4] = read_w(st_own, 1, i - 4);
+          else if (i < 8) read_w(F[1], st_own, 1, i - 4);
           else if (i % 2 == 0 && (i - 8) / 2 < LB) {   // slots 8, 10, ...: weights of the next step
             store_b(st_other, PAR, (i - 8) / 2);
             load_b(cb, PAR, (i - 8) / 2);
+          }
+          if constexpr (W2) {                    // codes -> E2M1, one row of MFMAs ahead of its use
+            if (b == 1 && a + 1 < TN) expand_here(F[0], a + 1);
+            if (i == 14) expand_here(F[1], 0);
           }
         }
       }
@@ -354,10 +374,14 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
           else GX_MFMA(acc[a][b], F[1].w[a], F[1].x[b]);
           const int i = a * TM + b;
           if (i < 4) F[0].x[i] = read_x(st_other, 0, i);
-          else if (i < 8) F[0].w[i - 4] = read_w(st_other, 0, i - 4);
+          else if (i < 8) read_w(F[0], st_other, 0, i - 4);
           else if (i < 8 + LA) {                 // slots 8 ..: activations of the step after next
             store_a(st_own, PAR, i - 8);
             load_a(ca, PAR, i - 8);
+          }
+          if constexpr (W2) {
+            if (b == 1 && a + 1 < TN) expand_here(F[1], a + 1);
+            if (i == 14) expand_here(F[0], 0);
           }
         }
       }
