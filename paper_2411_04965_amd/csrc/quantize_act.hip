@@ -162,12 +162,19 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_kernel(
 // in registers between the statistics and the coding; one barrier.  K % 8 == 0 by dispatch.
 template <bool MX6, int NV>
 __global__ __launch_bounds__(QA_THREADS) void quant_int4_regs_kernel(
-    const uint16_t* __restrict__ X, int K, int Kp, float eps, u32* __restrict__ q_out,
+    const uint16_t* __restrict__ X, int64_t M, int K, int Kp, float eps, u32* __restrict__ q_out,
     float* __restrict__ scale_out, int32_t* __restrict__ rowsum_out, int stat) {
   __shared__ double red[QA_WAVES];
   __shared__ u32 redm[QA_WAVES];
   __shared__ int redi[QA_WAVES];
-  const int64_t m = blockIdx.x;
+  // Workgroups go to the eight XCDs in turn.  Tokens that share 128-byte lines of the blocked 6-bit
+  // output (neighbours within a block of 32) are given to one XCD, so that its L2 can put the lines
+  // together before they go to memory: workgroup 8 j + x works on token x * ceil(M / 8) + j.
+  int64_t m = blockIdx.x;
+  if (MX6) {
+    m = (int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (m >= M) return;                          // (whole workgroup, before any barrier)
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint4* xv = reinterpret_cast<const uint4*>(X + m * (int64_t)K);
   const int nv = K >> 3;                         // 16-byte pieces of the row
@@ -868,7 +875,8 @@ int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K64, bl_ac
     const int stat = mode == BL_ACT_INT4_ABSMEAN2 ? 1 : mode == BL_ACT_INT4_ABSMAX ? 2 : 0;
     const bool mx6 = mode == BL_ACT_INT4_ABSMEAN_MX6;
     const int nvv = (Kp / 16 + QA_THREADS - 1) / QA_THREADS;      // half units per thread: 1 .. 4
-#define QA_I4(MX, NVV) quant_int4_regs_kernel<MX, NVV><<<(unsigned)M, QA_THREADS, 0, s>>>((const uint16_t*)X, K, Kp, eps, (u32*)q, (float*)scale, rowsum, stat)
+    const unsigned grid = mx6 ? (unsigned)((M + 7) / 8 * 8) : (unsigned)M;   // MX6: a multiple of 8
+#define QA_I4(MX, NVV) quant_int4_regs_kernel<MX, NVV><<<grid, QA_THREADS, 0, s>>>((const uint16_t*)X, M, K, Kp, eps, (u32*)q, (float*)scale, rowsum, stat)
     if (mx6) { if (nvv <= 1) QA_I4(true, 1); else if (nvv <= 2) QA_I4(true, 2); else QA_I4(true, 4); }
     else { if (nvv <= 1) QA_I4(false, 1); else if (nvv <= 2) QA_I4(false, 2); else QA_I4(false, 4); }
 #undef QA_I4
