@@ -149,43 +149,61 @@ E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float64)
 FP4_BLOCK = 32
 
 
-def quant_fp4(X):
-    """FP4 (E2M1) MinMax quantizer (eq. 8-9) with one power-of-two scale per
-    block of 32 consecutive channels of a token.
+E1M2_GRID = np.arange(8, dtype=np.float64) / 4.0           # 0, 0.25, ..., 1.75
+
+
+def quant_fp4(X, fmt="e2m1"):
+    """FP4 MinMax quantizer (eq. 8-9) with one power-of-two scale per block of
+    32 consecutive channels of a token.  fmt = "e2m1" (E = 2, M = 1, the format
+    the paper adopts) or "e1m2" (E = 1, M = 2, the other arm of Section 4.3's
+    4-bit comparison).
 
     Reading of eq. 8-9 for power-of-two scales: the bias b is an integer per
     block, chosen as the largest one for which the block maximum does not clip,
-    i.e. the scale 2^e is the smallest power of two with max|x| / 2^e <= 6.
-    Within a block every value is rounded to the nearest E2M1 value (ties to
-    the even code).  A value that rounds to zero is stored as +0.
+    i.e. the scale 2^e is the smallest power of two with max|x| / 2^e <= top,
+    top = (2 - 2^-M) 2^(2^E - 2) = 6 for E2M1 and 1.75 for E1M2 (exponent bias 1
+    in both).  Within a block every value is rounded to the nearest value of the
+    format (ties to the even code).  A value that rounds to zero is stored as +0.
+    E1M2's values are the uniform grid j / 4, j = 0..7 (one subnormal and one
+    normal binade).
 
     Returns (codes uint8 [M, K] = sign<<3 | code3,  e int16 [M, K/32] block exponents;
     the E8M0 scale byte is e + 127)."""
+    assert fmt in ("e2m1", "e1m2")
     X = np.asarray(X, dtype=F32)
     M_, K = X.shape
     assert K % FP4_BLOCK == 0
     xb = X.reshape(M_, K // FP4_BLOCK, FP4_BLOCK).astype(np.float64)
     a = np.abs(xb).max(axis=2)                             # [M, K/32]
     mant, ex = np.frexp(a)                                 # a = mant * 2^ex, mant in [0.5, 1)
-    # a = (2 mant) * 2^(ex-1);  smallest e with a / 2^e <= 6 = 1.5 * 2^2
-    e = np.where(2.0 * mant <= 1.5, ex - 1 - 2, ex - 1 - 1)
+    if fmt == "e2m1":
+        # a = (2 mant) * 2^(ex-1);  smallest e with a / 2^e <= 6 = 1.5 * 2^2
+        e = np.where(2.0 * mant <= 1.5, ex - 1 - 2, ex - 1 - 1)
+    else:
+        # smallest e with a / 2^e <= 1.75 = 1.75 * 2^0
+        e = np.where(2.0 * mant <= 1.75, ex - 1, ex)
     e = np.where(a == 0.0, 0, e)
     e = np.clip(e, -127, 127).astype(np.int64)
     v = np.ldexp(xb, -e[:, :, None])                       # exact
     av = np.abs(v)
-    step = np.where(av < 2.0, 0.5, np.where(av < 4.0, 1.0, 2.0))
-    r = np.minimum(np.rint(av / step) * step, 6.0)         # RNE on the local step == ties to even code
-    code3 = np.searchsorted(E2M1_GRID, r).astype(np.uint8)
-    assert np.all(E2M1_GRID[code3] == r)
+    if fmt == "e2m1":
+        grid = E2M1_GRID
+        step = np.where(av < 2.0, 0.5, np.where(av < 4.0, 1.0, 2.0))
+        r = np.minimum(np.rint(av / step) * step, 6.0)     # RNE on the local step == ties to even code
+    else:
+        grid = E1M2_GRID
+        r = np.minimum(np.rint(av * 4.0) / 4.0, 1.75)      # one step everywhere
+    code3 = np.searchsorted(grid, r).astype(np.uint8)
+    assert np.all(grid[code3] == r)
     sign = ((v < 0) & (code3 != 0)).astype(np.uint8)
     codes = (sign << 3 | code3).reshape(M_, K)
     return codes, e.astype(np.int16)
 
 
-def fp4_dequant(codes, e):
+def fp4_dequant(codes, e, fmt="e2m1"):
     """float64 values encoded by quant_fp4's output."""
     M_, K = codes.shape
-    mag = E2M1_GRID[codes & 7]
+    mag = (E2M1_GRID if fmt == "e2m1" else E1M2_GRID)[codes & 7]
     val = np.where(codes & 8, -mag, mag).reshape(M_, K // FP4_BLOCK, FP4_BLOCK)
     return np.ldexp(val, e.astype(np.int64)[:, :, None]).reshape(M_, K)
 
@@ -221,6 +239,22 @@ def relu2_glu(g, u):
     r = np.maximum(g, F32(0))
     rr = (r * r).astype(F32)
     return bf16_round((u * rr).astype(F32))
+
+
+def swish_glu(g, u):
+    """Swish GLU combine  h = u (.) g sigmoid(g), the activation Section 4.3
+    compares squared ReLU with.  Evaluated in float64 from the float32 inputs
+    and rounded once, from float64, to bfloat16 (returned as float32 values): the
+    definition itself, so a float32 implementation may differ from it by one bfloat16 ulp
+    where its few-ulp float32 error straddles a rounding boundary."""
+    g = np.asarray(g, dtype=F32).astype(np.float64)
+    u = np.asarray(u, dtype=F32).astype(np.float64)
+    with np.errstate(over="ignore"):
+        h = u * (g / (1.0 + np.exp(-g)))
+    # nearest bfloat16 of the float64 value, ties to even: a power-of-two ulp makes h / ulp exact
+    _, ex = np.frexp(h)                                    # |h| in [2^(ex-1), 2^ex)
+    ulp = np.ldexp(1.0, np.maximum(ex - 1, -126) - 7)
+    return (np.rint(h / ulp) * ulp).astype(F32)
 
 
 # --------------------------------------------------------------------------

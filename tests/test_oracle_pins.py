@@ -429,6 +429,89 @@ def test_fp4_scale_choice_and_invariants():
         assert np.array_equal(ref, deq[r, blk * 32:(blk + 1) * 32])
 
 
+def test_fp4_e1m2_format():
+    """Section 4.3's other 4-bit float format (E = 1, M = 2) through the same eq. 8-9."""
+    # hand-worked block, maximum 1.75 -> scale 2^0, step 1/4: ties go to the even code
+    x = np.zeros((1, 32), F32)
+    x[0, :8] = [1.75, -0.3, 0.12, 0.13, 0.125, 0.375, -0.875, 1.7]
+    codes, e = O.quant_fp4(x, "e1m2")
+    assert e[0, 0] == 0
+    assert list(codes[0, :8]) == [7, 8 | 1, 0, 1, 0, 2, 8 | 4, 7]     # -0.875 * 4 = -3.5 -> 4 (even)
+    assert not codes[0, 8:].any()
+    # every bf16 magnitude in [2^-6, 1.75] with 1.75 in the block: nearest grid point by exact fractions
+    mags = [(1 + m / 128.0) * 2.0 ** ex for ex in range(-6, 1) for m in range(128)]
+    mags = [v for v in mags if v <= 1.75]
+    vals = np.array(mags + [-v for v in mags], dtype=F32)
+    vals = np.concatenate([vals, np.zeros((-len(vals)) % 31, F32)]).reshape(-1, 31)
+    X = np.concatenate([np.full((vals.shape[0], 1), 1.75, F32), vals], axis=1)
+    codes, e = O.quant_fp4(X, "e1m2")
+    assert np.all(e == 0)
+    for b in range(X.shape[0]):
+        for j in range(32):
+            a = Fraction(abs(float(X[b, j])))
+            want = min(range(8), key=lambda c: (abs(a - Fraction(c, 4)), c % 2))
+            assert (int(codes[b, j]) & 7) == want, (X[b, j], codes[b, j], want)
+            assert bool(codes[b, j] & 8) == (X[b, j] < 0 and want != 0)
+    # scale choice, accuracy, idempotence, and the printed formula with an integer bias (E = 1, M = 2)
+    rng = np.random.default_rng(21)
+    X = (rng.standard_normal((16, 128)) * np.exp(rng.uniform(-12, 12, (16, 1)))).astype(F32)
+    X[2, 64:96] = 0
+    codes, e = O.quant_fp4(X, "e1m2")
+    deq = O.fp4_dequant(codes, e, "e1m2")
+    a = np.abs(X.astype(np.float64)).reshape(16, 4, 32).max(2)
+    scaled = a / np.exp2(e.astype(np.float64))
+    nz = a > 0
+    assert np.all((scaled[nz] > 0.875) & (scaled[nz] <= 1.75))      # never clips, never wastes a binade
+    assert np.all(e[~nz] == 0) and not codes[2, 64:96].any()
+    err = np.abs(deq - X).reshape(16, 4, 32)
+    assert np.all(err <= np.exp2(e.astype(np.float64))[:, :, None] * 0.125)   # half a step of 1/4
+    c2, e2 = O.quant_fp4(deq.astype(F32), "e1m2")
+    assert np.array_equal(O.fp4_dequant(c2, e2, "e1m2"), deq)
+    Eb, Mb = 1, 2
+    for (r, blk) in ((0, 0), (5, 2), (9, 3)):
+        x = X[r, blk * 32:(blk + 1) * 32].astype(np.float64)
+        b = math.floor(math.log2((2 - 2.0 ** -Mb) / np.abs(x).max()) + 2 ** Eb - 1)
+        assert e[r, blk] == 1 - b
+        with np.errstate(divide="ignore"):
+            p = np.maximum(np.floor(np.log2(np.abs(x))) + b, 1)
+        step = np.exp2(p - Mb - b)
+        assert np.array_equal(step * np.rint(x / step), deq[r, blk * 32:(blk + 1) * 32])
+    # the two formats differ where they should: E2M1 reaches 6 with coarse steps, E1M2 is uniform
+    d21 = O.fp4_dequant(*O.quant_fp4(X), "e2m1")
+    assert not np.array_equal(d21, deq)
+
+
+def test_swish_glu():
+    """h = u g sigmoid(g): closed forms and identities of the textbook function."""
+    g = np.array([0.0, 1.0, -1.0, 30.0, -30.0, 200.0, -200.0], F32)
+    h = O.swish_glu(g, np.ones_like(g)).astype(np.float64)
+    want = [0.0, 1 / (1 + math.exp(-1.0)), -1 / (1 + math.exp(1.0)), 30.0, -30.0 * math.exp(-30.0), 200.0, 0.0]
+    for got, w in zip(h, want):
+        assert abs(got - w) <= 2.0 ** -8 * abs(w)                  # one bf16 rounding
+    assert h[6] == 0.0 and not np.isnan(h).any()                   # exp overflow handled
+    # swish(x) - swish(-x) = x, checked before the final rounding by taking u as a power of two
+    rng = np.random.default_rng(22)
+    x = rng.uniform(-8, 8, 4096).astype(F32)
+    hp = O.swish_glu(x, np.ones_like(x)).astype(np.float64)
+    hm = O.swish_glu(-x, np.ones_like(x)).astype(np.float64)
+    assert np.all(np.abs((hp - hm) - x) <= 2.0 ** -7 * np.maximum(np.abs(hp), np.abs(hm)) + 1e-30)
+    # minimum of the function: -0.27846 at x = -1.27846 (root of 1 + e^-x (1 + ... ) = 0)
+    xs = np.linspace(-3, 0, 30001).astype(F32)
+    hs = O.swish_glu(xs, np.ones_like(xs))
+    # (bfloat16 resolution flattens the bottom: the location is only good to a few hundredths)
+    assert abs(float(xs[hs.argmin()]) + 1.27846) < 0.1 and abs(float(hs.min()) + 0.27846) < 2e-3
+    # linear in u, results are bfloat16 values, ties to even from float64
+    u = rng.standard_normal(4096).astype(F32)
+    h2 = O.swish_glu(x, u)
+    assert np.array_equal(O.bf16_round(h2), h2)
+    ref = u.astype(np.float64) * (x.astype(np.float64) / (1 + np.exp(-x.astype(np.float64))))
+    assert np.all(np.abs(h2 - ref) <= 2.0 ** -8 * np.abs(ref) * (1 + 1e-9) + 1e-40)
+    # a value exactly between two bfloat16 neighbours goes to the even one: 1 + 2^-8 with sigmoid = 1
+    big = np.array([64.0], F32)                                    # sigmoid(64) == 1.0 in float64
+    hb = O.swish_glu(big, np.array([(1 + 2.0 ** -8) / 64.0], F32))
+    assert hb[0] == 1.0
+
+
 def test_bitlinear_fp4_against_dense():
     rng = np.random.default_rng(15)
     X = rng.standard_normal((5, 64)).astype(F32)
