@@ -101,7 +101,8 @@ typedef enum {
   BL_ACT_INT4_ABSMEAN_MX6 = 3, /* eq. 7, levels stored as E3M2 codes for the block-float GEMM */
   BL_ACT_FP4_E2M1_B32_MX = 4,  /* eq. 8-9, codes and scales in the block order of the block-float GEMM */
   BL_ACT_INT4_ABSMEAN2 = 5,    /* eq. 7 with beta = 2 mean|x| (ablation: inputs to the down projection) */
-  BL_ACT_INT4_ABSMAX = 6       /* 4-bit absmax, the form of eq. 3 with 7 in place of 127 (ablation) */
+  BL_ACT_INT4_ABSMAX = 6,      /* 4-bit absmax, the form of eq. 3 with 7 in place of 127 (ablation) */
+  BL_ACT_FP4_E1M2_B32 = 7      /* eq. 8-9 with E = 1, M = 2 (ablation); quantizer and unpack_act only */
 } bl_act_mode;
 
 typedef enum { BL_W_GEMM = 0, BL_W_KMAJOR = 1, BL_W_MX4 = 2, BL_W_ROWS = 3, BL_W_MX2 = 4 } bl_w_layout;
@@ -155,6 +156,13 @@ int pack_ternary(const void* W, bl_dtype w_dtype, int64_t N, int64_t K, float ep
  *       always stored as +0; scale_out = E8M0 bytes (e + 127), [M][Kp/32]; eps unused.
  *   BL_ACT_FP4_E2M1_B32_MX: the same quantizer, codes and scales in the MX form (for BL_W_MX4 /
  *       BL_W_MX2 weights); scale_out then takes round_up(M, 32) * Kp/32 bytes.
+ *   BL_ACT_FP4_E1M2_B32 (Section 4.3, the other 4-bit float format of the comparison): eq. 8-9
+ *       with E = 1, M = 2, whose values are the uniform grid j / 4, j = 0..7: per block of 32
+ *       channels the smallest 2^e with max|x| / 2^e <= 1.75, code j = x / 2^e * 4 rounded half
+ *       to even, nibble = sign << 3 | j (zero as +0).  Same containers and sizes as
+ *       BL_ACT_FP4_E2M1_B32.  No matrix instruction takes this format as an operand: the linear
+ *       entry points and bitlinear_gemm return BL_EUNSUPPORTED for it; quantize_act and
+ *       unpack_act (which returns the nibbles) serve it.
  *   X           device, [M, K] of x_dtype
  *   q_out       device, quantize_act_bytes(mode, M, K) bytes, fully overwritten
  *   scale_out   device, float32[M] (INT modes) or uint8[M * Kp/32] (FP4; MX form: M rounded up to 32)
@@ -238,6 +246,14 @@ int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const void* W_row
 /* ReLU^2 GLU combine (eq. 5): H = bf16(U * max(G, 0)^2), float32 steps in that order.
  * G, U device [M, N] of in_dtype; H device [M, N] bfloat16. */
 int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,
+              void* H, void* stream);
+
+/* Swish GLU combine (Section 4.3, the activation squared ReLU is compared with):
+ * H = bf16(U * (G * sigmoid(G))), sigmoid(g) = 1 / (1 + exp(-g)) in float32, one bfloat16 rounding;
+ * within one bfloat16 ulp of the exactly evaluated function (results below 2^-100 in magnitude:
+ * within 2^-100; exp(-g) overflows float32 for g < -88.7 and H is then 0).  Arguments and errors as
+ * relu2_glu. */
+int swish_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,
               void* H, void* stream);
 
 /* eq. 5 followed by eq. 1 / eq. 3 in one pass over G and U: the tokens that are quantized are the

@@ -17,6 +17,7 @@ BL_F32, BL_BF16 = 0, 1
 BL_ACT_INT4_ABSMEAN, BL_ACT_TOPK_INT8_ABSMAX, BL_ACT_FP4_E2M1_B32, BL_ACT_INT4_ABSMEAN_MX6 = 0, 1, 2, 3
 BL_ACT_FP4_E2M1_B32_MX = 4
 BL_ACT_INT4_ABSMEAN2, BL_ACT_INT4_ABSMAX = 5, 6
+BL_ACT_FP4_E1M2_B32 = 7
 BL_W_GEMM, BL_W_KMAJOR, BL_W_MX4, BL_W_ROWS, BL_W_MX2 = 0, 1, 2, 3, 4
 BL_DECODE_MAX_M = 64
 DEFAULT_EPS = 1e-5
@@ -40,6 +41,7 @@ _SIGNATURES = {
     "bitlinear_gemm": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _int, _vp, _i64, _vp, _int, _vp,
                               _vp, _sz, _vp]),
     "relu2_glu": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _vp]),
+    "swish_glu": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _vp]),
     "quantize_act_glu": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
     "bitlinear_a4_up_gated": (_int, [_vp, _i64, _i64, _vp, _vp, _i64, _f32, _vp, _int, _vp, _vp]),
     "unpack_ternary": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
@@ -129,7 +131,7 @@ def quantize_act(X, mode, topk=0, eps=DEFAULT_EPS, want_rowsum=False, want_sel=F
     M, K = X.shape
     L = lib()
     q = torch.empty(L.quantize_act_bytes(mode, M, K), dtype=torch.uint8, device=X.device)
-    if mode == BL_ACT_FP4_E2M1_B32:
+    if mode in (BL_ACT_FP4_E2M1_B32, BL_ACT_FP4_E1M2_B32):
         scale = torch.empty(M * (L.bl_padded_k(K) // 32), dtype=torch.uint8, device=X.device)
     elif mode == BL_ACT_FP4_E2M1_B32_MX:
         scale = torch.empty((M + 31) // 32 * 32 * (L.bl_padded_k(K) // 32), dtype=torch.uint8, device=X.device)
@@ -230,4 +232,12 @@ def relu2_glu(G, U):
     M, N = G.shape
     H = torch.empty((M, N), dtype=torch.bfloat16, device=G.device)
     _check("relu2_glu", lib().relu2_glu(_ptr(G), _ptr(U), _dt(G), M, N, _ptr(H), _stream()))
+    return H
+
+
+def swish_glu(G, U):
+    _dev(G), _dev(U)
+    M, N = G.shape
+    H = torch.empty((M, N), dtype=torch.bfloat16, device=G.device)
+    _check("swish_glu", lib().swish_glu(_ptr(G), _ptr(U), _dt(G), M, N, _ptr(H), _stream()))
     return H

@@ -7,12 +7,14 @@ static inline size_t ws_align(size_t x) { return (x + 255) & ~(size_t)255; }
 static bool valid_dtype(int d) { return d == BL_F32 || d == BL_BF16; }
 static bool valid_layout(int l) { return l >= BL_W_GEMM && l <= BL_W_MX2; }
 static bool mx_layout(int l) { return l == BL_W_MX4 || l == BL_W_MX2; }
-static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_INT4_ABSMAX; }
+static bool valid_mode(int m) { return m >= BL_ACT_INT4_ABSMEAN && m <= BL_ACT_FP4_E1M2_B32; }
 static bool int4_nibble_mode(int m) {
   return m == BL_ACT_INT4_ABSMEAN || m == BL_ACT_INT4_ABSMEAN2 || m == BL_ACT_INT4_ABSMAX;
 }
 static bool mx_mode(int m) { return m == BL_ACT_INT4_ABSMEAN_MX6 || m == BL_ACT_FP4_E2M1_B32_MX; }
-static bool fp4_mode(int m) { return m == BL_ACT_FP4_E2M1_B32 || m == BL_ACT_FP4_E2M1_B32_MX; }
+static bool fp4_mode(int m) {
+  return m == BL_ACT_FP4_E2M1_B32 || m == BL_ACT_FP4_E2M1_B32_MX || m == BL_ACT_FP4_E1M2_B32;
+}
 
 static int check_sizes(int64_t M, int64_t N, int64_t K) {
   if (M < 1 || N < 1 || K < 1) return BL_EINVAL;
@@ -79,7 +81,8 @@ extern "C" size_t quantize_act_bytes(bl_act_mode mode, int64_t M, int64_t K) {
     case BL_ACT_INT4_ABSMEAN2:
     case BL_ACT_INT4_ABSMAX: return (size_t)(M * Kp / 2);
     case BL_ACT_TOPK_INT8_ABSMAX: return (size_t)(M * Kp);
-    case BL_ACT_FP4_E2M1_B32: return (size_t)(M * Kp / 2);
+    case BL_ACT_FP4_E2M1_B32:
+    case BL_ACT_FP4_E1M2_B32: return (size_t)(M * Kp / 2);
     case BL_ACT_INT4_ABSMEAN_MX6: return (size_t)(bl_round_up(M, 32) * Kp / 4 * 3);
     case BL_ACT_FP4_E2M1_B32_MX: return (size_t)(bl_round_up(M, 32) * Kp / 2);
     default: return 0;
@@ -87,7 +90,8 @@ extern "C" size_t quantize_act_bytes(bl_act_mode mode, int64_t M, int64_t K) {
 }
 
 static size_t act_scale_bytes(bl_act_mode mode, int64_t M, int64_t K) {
-  if (mode == BL_ACT_FP4_E2M1_B32) return (size_t)(M * (bl_round_up(K, BL_KPAD) / 32));
+  if (mode == BL_ACT_FP4_E2M1_B32 || mode == BL_ACT_FP4_E1M2_B32)
+    return (size_t)(M * (bl_round_up(K, BL_KPAD) / 32));
   if (mode == BL_ACT_FP4_E2M1_B32_MX) return (size_t)(bl_round_up(M, 32) * (bl_round_up(K, BL_KPAD) / 32));
   return (size_t)M * sizeof(float);
 }
@@ -154,6 +158,7 @@ static int gemm_dispatch(const void* q, const void* scale, bl_act_mode mode, int
                          hipStream_t s) {
   // the block-float forms of activations and weights go together and with nothing else
   if (layout == BL_W_ROWS) return BL_EUNSUPPORTED;       // only the gate-first up projection reads rows
+  if (mode == BL_ACT_FP4_E1M2_B32) return BL_EUNSUPPORTED;   // a quantizer format only: no MFMA operand type
   if (int4_nibble_mode(mode)) mode = BL_ACT_INT4_ABSMEAN;   // same codes, same rescale
   if (mx_mode(mode) != mx_layout(layout)) return BL_EINVAL;
   if (mode == BL_ACT_INT4_ABSMEAN_MX6)
@@ -300,6 +305,40 @@ __global__ __launch_bounds__(256) void relu2_glu_kernel(const RawT* __restrict__
   const float r = fmaxf(g, 0.0f);
   const float rr = r * r;
   H[i] = bl_f32_to_bf16_rne(u * rr);
+}
+
+// Swish GLU (Section 4.3): h = u * (g * sigmoid(g)), float32 steps, one bfloat16 rounding
+template <typename RawT>
+__global__ __launch_bounds__(256) void swish_glu_kernel(const RawT* __restrict__ G,
+                                                        const RawT* __restrict__ U, int64_t n,
+                                                        uint16_t* __restrict__ H) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float g, u;
+  if (sizeof(RawT) == 2) {
+    g = bl_bf16_to_f32((uint16_t)G[i]);
+    u = bl_bf16_to_f32((uint16_t)U[i]);
+  } else {
+    g = __uint_as_float((u32)G[i]);
+    u = __uint_as_float((u32)U[i]);
+  }
+  const float sg = 1.0f / (1.0f + expf(-g));               // expf(-g) = inf for g < -88.7: sg = 0, h = -0
+  const float sw = g * sg;
+  H[i] = bl_f32_to_bf16_rne(u * sw);
+}
+
+extern "C" int swish_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,
+                         void* H, void* stream) {
+  if (!G || !U || !H || !valid_dtype(in_dtype)) return BL_EINVAL;
+  if (M < 1 || N < 1 || M > ((int64_t)1 << 40) / N) return BL_ESHAPE;
+  const int64_t n = M * N;
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  if (in_dtype == BL_BF16)
+    swish_glu_kernel<uint16_t><<<blocks, 256, 0, (hipStream_t)stream>>>((const uint16_t*)G, (const uint16_t*)U, n, (uint16_t*)H);
+  else
+    swish_glu_kernel<u32><<<blocks, 256, 0, (hipStream_t)stream>>>((const u32*)G, (const u32*)U, n, (uint16_t*)H);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
 }
 
 extern "C" int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,

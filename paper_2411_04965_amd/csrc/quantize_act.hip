@@ -640,7 +640,9 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
 // One thread per block of 32 channels.
 // MX: codes and scales in the block order of the block-float GEMM (32 tokens x 128 channels per
 // block, channels of a unit in natural nibble order) instead of token-major.
-template <typename RawT, bool MX>
+// E1M2 = false: E2M1 (top value 6); true: E1M2 (the uniform grid j / 4, top value 1.75; row-major
+// nibbles only)
+template <typename RawT, bool MX, bool E1M2 = false>
 __global__ __launch_bounds__(QA_THREADS) void quant_fp4_kernel(
     const RawT* __restrict__ X, int64_t M, int K, int Kp, u32* __restrict__ q_out,
     uint8_t* __restrict__ scale_out) {
@@ -675,13 +677,14 @@ __global__ __launch_bounds__(QA_THREADS) void quant_fp4_kernel(
       a = fmaxf(a, fabsf(v[j]));
     }
   }
-  // smallest e with a / 2^e <= 6 = 1.5 * 2^2
+  // smallest e with a / 2^e <= 6 = 1.5 * 2^2 (E1M2: <= 1.75 = 1.75 * 2^0)
   int e = 0;
   if (a != 0.0f) {
     const u32 ab = __float_as_uint(a);
     const int be = (int)(ab >> 23);                       // biased exponent (0 for subnormals)
     const u32 mant = ab & 0x7FFFFFu;
-    e = (be - 127) - ((mant <= 0x400000u) ? 2 : 1);
+    if (E1M2) e = (be - 127) + ((mant <= 0x600000u) ? 0 : 1);
+    else e = (be - 127) - ((mant <= 0x400000u) ? 2 : 1);
     if (be == 0) e = -127;                                // subnormal maximum: below the clamp
     e = max(-127, min(127, e));
   }
@@ -695,6 +698,11 @@ __global__ __launch_bounds__(QA_THREADS) void quant_fp4_kernel(
   for (int j = 0; j < 32; ++j) {
     const float sv = ldexpf(v[j], -e);                    // exact
     const float av = fabsf(sv);
+    if (E1M2) {                                           // one step of 1/4 everywhere, av <= 1.75
+      const int code = min((int)rintf(av * 4.0f), 7);
+      nib[j] = (u32)code | ((sv < 0.0f && code != 0) ? 8u : 0u);
+      continue;
+    }
     float r;
     if (av < 2.0f) r = rintf(av * 2.0f) * 0.5f;
     else if (av < 4.0f) r = rintf(av);
@@ -851,11 +859,14 @@ int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K64, bl_ac
                        int64_t topk, float eps, void* q, void* scale, int32_t* rowsum,
                        int32_t* sel_idx, hipStream_t s) {
   const int K = (int)K64, Kp = (int)bl_round_up(K64, BL_KPAD);
-  if (mode == BL_ACT_FP4_E2M1_B32 || mode == BL_ACT_FP4_E2M1_B32_MX) {
+  if (mode == BL_ACT_FP4_E2M1_B32 || mode == BL_ACT_FP4_E2M1_B32_MX || mode == BL_ACT_FP4_E1M2_B32) {
     const int64_t n = M * (Kp / 32);
     const unsigned blocks = (unsigned)((n + QA_THREADS - 1) / QA_THREADS);
     const bool mx = mode == BL_ACT_FP4_E2M1_B32_MX;
-    if (dt == BL_BF16) {
+    if (mode == BL_ACT_FP4_E1M2_B32) {
+      if (dt == BL_BF16) quant_fp4_kernel<uint16_t, false, true><<<blocks, QA_THREADS, 0, s>>>((const uint16_t*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
+      else quant_fp4_kernel<u32, false, true><<<blocks, QA_THREADS, 0, s>>>((const u32*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
+    } else if (dt == BL_BF16) {
       if (mx) quant_fp4_kernel<uint16_t, true><<<blocks, QA_THREADS, 0, s>>>((const uint16_t*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
       else quant_fp4_kernel<uint16_t, false><<<blocks, QA_THREADS, 0, s>>>((const uint16_t*)X, M, K, Kp, (u32*)q, (uint8_t*)scale);
     } else {

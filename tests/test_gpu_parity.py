@@ -215,6 +215,59 @@ def test_quantize_fp4(kind, M, K, dtype):
     assert np.array_equal(lib_codes, codes_ref)
 
 
+@pytest.mark.parametrize("kind,M,K,dtype", [("gauss", 16, 256, F32), ("heavy", 20, 3200, BF16),
+                                            ("glu", 6, 8640, BF16), ("ties", 9, 992, F32)])
+def test_quantize_fp4_e1m2(kind, M, K, dtype):
+    """Section 4.3's E1M2 arm of eq. 8-9: codes and block exponents bit for bit; the linear entry
+    points refuse the format (no matrix instruction takes it)."""
+    say("quantize_act FP4 E1M2 %s M=%d K=%d %s" % (kind, M, K, dtype))
+    x = _x(kind, M, K, S.seed_for(4, 50 + M + K), dtype)
+    x[M - 1, :32] *= 1e-30                                # tiny block
+    x[0, 32:64] = 0                                       # empty block
+    x[1, 64:96] = np.linspace(-1.75, 1.75, 32)            # the top value and ties at multiples of 1/8
+    if dtype == BF16:
+        x = S.snap_bf16(x)
+    codes_ref, e_ref = O.quant_fp4(x, "e1m2")
+    r = B.quantize_act(dev(x, dtype), B.BL_ACT_FP4_E1M2_B32)
+    Kp = B.padded_k(K)
+    sc = host(r["scale"]).reshape(M, Kp // 32)
+    assert np.array_equal(sc[:, :K // 32].astype(np.int16) - 127, e_ref)
+    assert np.all(sc[:, K // 32:] == 127)
+    assert np.array_equal(decode_fp4(host(r["q"]), M, K), codes_ref)
+    lib_codes = host(B.unpack_act(r["q"], B.BL_ACT_FP4_E1M2_B32, M, K)).view(np.uint8)
+    assert np.array_equal(lib_codes, codes_ref)
+    W = S.latent_weights(32, K, S.seed_for(4, 51))
+    pw, aw = pack(W)
+    Y = torch.empty((M, 32), dtype=torch.float32, device="cuda")
+    rc = B.lib().bitlinear_gemm(r["q"].data_ptr(), r["scale"].data_ptr(), B.BL_ACT_FP4_E1M2_B32, M, K,
+                                pw.data_ptr(), B.BL_W_GEMM, aw.data_ptr(), 32, Y.data_ptr(), B.BL_F32,
+                                None, None, 0, None)
+    assert rc == -6, rc                                   # BL_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("M,N,dtype", [(7, 300, F32), (33, 5460, BF16), (1, 1, F32), (64, 11008, BF16)])
+def test_swish_glu(M, N, dtype):
+    """Section 4.3's Swish GLU against the exactly evaluated function: at most one bfloat16 ulp off
+    (2^-100 absolute for results smaller than that), and that only where the float32 chain's error
+    straddles a rounding boundary (rare)."""
+    say("swish_glu M=%d N=%d %s" % (M, N, dtype))
+    g = S.heavy(M, N, S.seed_for(6, M + N))
+    u = S.heavy(M, N, S.seed_for(6, M + N + 1))
+    g.flat[:4] = [0.0, -200.0, 200.0, -1.27846][:g.size if g.size < 4 else 4]
+    if dtype == BF16:
+        g, u = S.snap_bf16(g), S.snap_bf16(u)
+    else:
+        g, u = g.astype(np.float32), u.astype(np.float32)
+    h_ref = O.swish_glu(g, u)
+    Hh = host(B.swish_glu(dev(g, dtype), dev(u, dtype))).astype(np.float32)
+    assert not np.isnan(Hh).any()
+    ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(h_ref), 2.0 ** -126))) - 7)
+    diff = np.abs(Hh.astype(np.float64) - h_ref.astype(np.float64))
+    # (below g = -88.7 float32 exp(-g) overflows and the result is 0 instead of about 1e-40)
+    assert np.all(diff <= np.maximum(ulp, 2.0 ** -100)), float((diff / ulp).max())
+    assert (diff > 0).mean() <= 0.002, float((diff > 0).mean())
+
+
 # ------------------------------------------------------------------ whole linears
 def _check_linear(res, ref, y_dtype):
     Y, acc = res
