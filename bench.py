@@ -297,25 +297,30 @@ def fp4_compare(B, S, torch, dev, M=8192, hidden=3200, ffn=8640, iters=20):
     res = {"tokens": M}
     for name, N, K in (("qkv", 3 * hidden, hidden), ("gate", ffn, hidden)):
         w = torch.from_numpy(S.latent_weights(N, K, S.seed_for(4, 20 + len(name)))).to(dev)
-        p, a = B.pack_ternary(w, EPS, B.BL_W_MX2)
+        # each path with the weight form it runs fastest on (measured): 2-bit codes for INT4, E2M1
+        # nibbles for FP4, whose scaled MFMA leaves less room for the expansion arithmetic
+        packed = {lay: B.pack_ternary(w, EPS, lay) for lay in (B.BL_W_MX2, B.BL_W_MX4)}
         del w
         X = torch.from_numpy(S.heavy(M, K, S.seed_for(4, 21))).to(dev).to(torch.bfloat16)
         Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         row = {}
-        for label, fp4, mode in (("fp4", True, B.BL_ACT_FP4_E2M1_B32_MX), ("int4", False, B.BL_ACT_INT4_ABSMEAN_MX6)):
+        for label, fp4, mode, lay in (("fp4", True, B.BL_ACT_FP4_E2M1_B32_MX, B.BL_W_MX4),
+                                      ("int4", False, B.BL_ACT_INT4_ABSMEAN_MX6, B.BL_W_MX2)):
+            p, a = packed[lay]
             ws = B.workspace(mode, M, N, K, dev)
             for _ in range(3):
-                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=B.BL_W_MX2)
+                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=lay)
             torch.cuda.synchronize()
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(iters):
-                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=B.BL_W_MX2)
+                B.bitlinear_a4(X, p, a, N, EPS, act_fp4=fp4, ws=ws, out=Y, layout=lay)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / iters
-            row[label] = {"ms": round(ms, 4), "tops": round(2.0 * M * N * K / ms / 1e9, 1)}
+            row[label] = {"ms": round(ms, 4), "tops": round(2.0 * M * N * K / ms / 1e9, 1),
+                          "weights": "mx4" if lay == B.BL_W_MX4 else "mx2"}
         res[name] = row
     return res
 

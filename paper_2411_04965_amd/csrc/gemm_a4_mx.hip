@@ -213,14 +213,18 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   };
   // ... done in the slot where it is written: the empty statements keep the compiler from moving
   // the arithmetic across the MFMAs around it in program order
-  auto expand_here = [&](Frags& f, int a) {
+  // (half h = word h of the codes -> words 2 h and 2 h + 1 of the fragment: three instructions)
+  auto expand_here = [&](Frags& f, int a, int h) {
+    u32 c = (u32)f.wr[a][h];
 #if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("" : "+v"(f.wr[a]));            // not earlier ...
+    asm volatile("" : "+v"(c));                  // not earlier ...
 #endif
-    f.w[a] = expand_w(f.wr[a]);
+    u32 lo = c & 0xAAAAAAAAu, hi = (c << 1) & 0xAAAAAAAAu;
 #if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("" : "+v"(f.w[a]));             // ... and not later than here
+    asm volatile("" : "+v"(lo), "+v"(hi));       // ... and not later than here
 #endif
+    f.w[a][2 * h] = (int)lo;
+    f.w[a][2 * h + 1] = (int)hi;
   };
   // W2: the read only (the expansion waits for the data, so it sits some MFMAs further down)
   auto read_w = [&](Frags& f, const unsigned char* st, int s, int a) {
@@ -358,8 +362,8 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
             load_b(cb, PAR, (i - 8) / 2);
           }
           if constexpr (W2) {                    // codes -> E2M1, one row of MFMAs ahead of its use
-            if (b == 1 && a + 1 < TN) expand_here(F[0], a + 1);
-            if (i == 14) expand_here(F[1], 0);
+            if ((b == 1 || b == 2) && a + 1 < TN) expand_here(F[0], a + 1, b - 1);
+            if (i == 13 || i == 14) expand_here(F[1], 0, i - 13);
           }
         }
       }
@@ -380,8 +384,8 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
             load_a(ca, PAR, i - 8);
           }
           if constexpr (W2) {
-            if (b == 1 && a + 1 < TN) expand_here(F[1], a + 1);
-            if (i == 14) expand_here(F[0], 0);
+            if ((b == 1 || b == 2) && a + 1 < TN) expand_here(F[1], a + 1, b - 1);
+            if (i == 13 || i == 14) expand_here(F[0], 0, i - 13);
           }
         }
       }
