@@ -388,6 +388,59 @@ def test_config2_decode(name, N, K, kind, M):
         _check_linear(res, ref, BF16)
 
 
+@pytest.mark.parametrize("M", [1, 8, 32])
+def test_decode_graph_replays(M):
+    """The decode linears inside a captured graph, as the benchmark times them: every replay gives
+    the oracle's bits, with other work on the same buffers and synchronisations between replays
+    (the kernels keep partial sums and counters in the workspace, so a replay must not depend on
+    what the one before left there)."""
+    say("decode graph replays M=%d" % M)
+    cases = []
+    for name, N, K, kind in (("gate", 1024, 2048, "a4"), ("down", 2048, 2816, "a8")):
+        W = S.latent_weights(N, K, S.seed_for(2, 900 + N))
+        T, alpha = O.ternarize(W, EPS)
+        X = S.heavy(M, K, S.seed_for(2, 901 + M)) if kind == "a4" else S.glu_like(M, K, S.seed_for(2, 902 + M))
+        if kind == "a4":
+            q, d = O.quant_int4(X, EPS)
+            mode = B.BL_ACT_INT4_ABSMEAN
+        else:
+            q, d, _ = O.quant_topk_int8(X, K // 2, EPS)
+            mode = B.BL_ACT_TOPK_INT8_ABSMAX
+        y_ref = O.rescale(O.matmul_int(q, T), d, alpha, "bf16")
+        p, a = pack(W)
+        Xd = dev(X, BF16)
+        ws = B.workspace(mode, M, N, K, "cuda")
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        cases.append((kind, N, K, p, a, Xd, ws, Y, y_ref))
+
+    def run():
+        for kind, N, K, p, a, Xd, ws, Y, _ in cases:
+            if kind == "a4":
+                B.bitlinear_a4(Xd, p, a, N, EPS, ws=ws, out=Y)
+            else:
+                B.bitlinear_a8_sparse(Xd, K // 2, p, a, N, EPS, ws=ws, out=Y)
+
+    run()
+    torch.cuda.synchronize()
+    for c in cases:
+        assert np.array_equal(host(c[7]), c[8])
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            run()
+    for rep in range(4):
+        for c in cases:                                    # eager work between the replays: outputs and
+            c[7].fill_(float(rep + 1))                     # workspaces overwritten with other values
+            c[6].fill_(0x5A + rep)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for c in cases:
+            assert np.array_equal(host(c[7]), c[8]), "replay %d differs" % rep
+    del g
+
+
 @pytest.mark.parametrize("M", [3, 17, 48])
 def test_decode_odd_shapes(M):
     say("decode odd shapes M=%d" % M)
