@@ -525,3 +525,47 @@ def test_bitlinear_fp4_against_dense():
             assert abs(r["y"][m, n] - float(r["alpha"]) * s) <= 1e-12 * (1 + abs(s))
     for v in np.unique(deq / np.exp2(r["e"].astype(np.float64)).repeat(32, 1)):
         assert v in GRID15
+
+
+# ------------------------------------------------------------------ symmetries of the whole layers
+def test_layer_symmetries():
+    """What the equations imply whatever the arithmetic details: tokens are independent, sign flips and
+    power-of-two gains pass through exactly (with eps = 0), output channels permute with the rows of W."""
+    rng = np.random.default_rng(31)
+    X = O.bf16_round(rng.standard_normal((6, 96)).astype(F32))
+    X[:, 5] *= 17.0
+    W = (0.02 * rng.standard_normal((10, 96))).astype(F32)
+    base4 = O.bitlinear_a4(X, W, 0.0)
+    base8 = O.bitlinear_a8_sparse(X, W, 48, 0.0)
+    # tokens are independent: any permutation or subset of rows gives the same rows
+    perm = rng.permutation(6)
+    assert np.array_equal(O.bitlinear_a4(X[perm], W, 0.0)["y"], base4["y"][perm])
+    assert np.array_equal(O.bitlinear_a8_sparse(X[perm[:3]], W, 48, 0.0)["y"], base8["y"][perm[:3]])
+    # x -> -x: codes and outputs change sign, scales and the Top_k mask stay (|x| decides both)
+    n4 = O.bitlinear_a4(-X, W, 0.0)
+    n8 = O.bitlinear_a8_sparse(-X, W, 48, 0.0)
+    assert np.array_equal(n4["d"], base4["d"]) and np.array_equal(n8["mask"], base8["mask"])
+    # (the INT4 grid -8..7 is not symmetric: where a value clips, one side reads -8 and the other +7;
+    # nothing else differs)
+    diff = n4["q"] != -base4["q"]
+    assert np.all(np.minimum(base4["q"], n4["q"])[diff] == -8) and np.all(np.maximum(base4["q"], n4["q"])[diff] == 7)
+    assert diff.sum() > 0                                  # the outlier channel does clip
+    assert np.array_equal(n8["q"], -base8["q"]) and np.array_equal(n8["y"], -base8["y"])
+    # x -> 2^k x with eps = 0: same codes, scale and output times 2^k exactly
+    for k in (-3, 5):
+        g = np.ldexp(X, k).astype(F32)
+        s4 = O.bitlinear_a4(g, W, 0.0)
+        s8 = O.bitlinear_a8_sparse(g, W, 48, 0.0)
+        assert np.array_equal(s4["q"], base4["q"]) and np.array_equal(s8["q"], base8["q"])
+        assert np.array_equal(s4["d"], np.ldexp(base4["d"], k))
+        assert np.array_equal(s4["y"], np.ldexp(base4["y"], k)) and np.array_equal(s8["y"], np.ldexp(base8["y"], k))
+    # W -> -W: ternary codes and outputs change sign, alpha stays; rows of W permute the output channels
+    m4 = O.bitlinear_a4(X, -W, 0.0)
+    assert np.array_equal(m4["T"], -base4["T"]) and m4["alpha"] == base4["alpha"]
+    assert np.array_equal(m4["y"], -base4["y"])
+    pn = rng.permutation(10)
+    assert np.array_equal(O.bitlinear_a4(X, W[pn], 0.0)["y"], base4["y"][:, pn])
+    # channels permute together in X and W: the integer sums do not change, and alpha, d neither
+    pk = rng.permutation(96)
+    p4 = O.bitlinear_a4(X[:, pk], W[:, pk], 0.0)
+    assert np.array_equal(p4["acc"], base4["acc"]) and np.array_equal(p4["y"], base4["y"])
