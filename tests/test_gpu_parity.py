@@ -608,6 +608,36 @@ def test_config3_prefill_sampled_rows(name, N, K, kind):
 
 
 # ------------------------------------------------------------------ error paths (no kernel runs)
+@pytest.mark.parametrize("name,N,K,kind", [("qkv", 12288, 4096, "a4"), ("down", 4096, 11008, "a8s")])
+def test_config3_full_size_properties(name, N, K, kind):
+    """M = 16384 in the benchmark's launch configuration, every output checked through properties the
+    equations imply at any size: a permutation of the tokens permutes the output rows bit for bit
+    (every row meets every tile position), and a power-of-two gain on the input with eps = 0 comes
+    out as the same gain on the output, exactly."""
+    say("config 3 full-size properties %s" % name)
+    M = 16384
+    T, alpha, packs = _decode_weights(name, N, K)
+    wl = B.BL_W_MX2 if kind == "a4" else B.BL_W_GEMM
+    p, a = packs[wl]
+    X = S.heavy(M, K, S.seed_for(3, 1)) if kind == "a4" else S.glu_like(M, K, S.seed_for(3, 2))
+    Xd = dev(X, BF16)
+
+    def run(x, eps):
+        if kind == "a4":
+            return B.bitlinear_a4(x, p, a, N, eps, y_dtype=BF16, layout=wl)
+        return B.bitlinear_a8_sparse(x, K // 2, p, a, N, eps, wl, BF16, False)
+
+    Y = run(Xd, EPS)
+    perm = torch.from_numpy(np.random.default_rng(S.seed_for(3, 11)).permutation(M)).cuda()
+    Yp = run(Xd[perm].contiguous(), EPS)
+    assert torch.equal(Yp, Y[perm])
+    del Yp
+    Y0 = run(Xd, 0.0)
+    Y4 = run((Xd.float() * 4.0).to(torch.bfloat16), 0.0)
+    assert torch.equal(Y4.float(), Y0.float() * 4.0)
+    assert torch.isfinite(Y0.float()).all() and float(Y0.float().abs().max()) > 0
+
+
 def test_argument_errors():
     say("argument errors")
     X = dev(np.zeros((4, 64), np.float32))
