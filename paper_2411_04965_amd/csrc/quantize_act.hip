@@ -49,6 +49,15 @@ __device__ __forceinline__ u32 qa_e3m2_of_level(int q) {
   return ((u32)(lut >> (6 * a)) & 63u) | (q < 0 ? 32u : 0u);
 }
 
+// The same code from the level as a float (an integer value in [-8, 7]): its exponent field minus
+// 124 and its top two mantissa bits are the five magnitude bits (the low five bits of bits >> 21,
+// with bit 4 flipped), the sign moves from bit 31 to bit 5, and zero of either sign is code 0.
+__device__ __forceinline__ u32 qa_e3m2_of_levelf(float p) {
+  const u32 b = __float_as_uint(p);
+  const u32 c = (((b >> 21) & 31u) ^ 16u) | ((b >> 26) & 32u);
+  return (b << 1) != 0u ? c : 0u;
+}
+
 // MX6: the same levels, written as E3M2 codes in the tile order of the block-float GEMM (blocks of
 // 32 tokens x 128 channels, 3072 bytes; see the format notes of the public header) instead of
 // packed nibbles.
@@ -190,21 +199,30 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_regs_kernel(
   // statistics: float64 sum of |x| (exact for bfloat16 data), maximum of |x| as a bit pattern
   double acc = 0.0;
   u32 mx = 0;
+  if (stat == 2) {                               // (uniform) only the maximum is needed
 #pragma unroll
-  for (int j = 0; j < NV; ++j)
+    for (int j = 0; j < NV; ++j)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const u32 w4[4] = {v[j][i].x, v[j][i].y, v[j][i].z, v[j][i].w};
+      for (int i = 0; i < 2; ++i) {
+        const u32 w4[4] = {v[j][i].x, v[j][i].y, v[j][i].z, v[j][i].w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const u32 lo = (w4[e] << 16) & 0x7FFFFFFFu, hi = w4[e] & 0x7FFF0000u;
-        acc += (double)__uint_as_float(lo);
-        acc += (double)__uint_as_float(hi);
-        mx = max(mx, max(lo, hi));
+        for (int e = 0; e < 4; ++e) mx = max(mx, max((w4[e] << 16) & 0x7FFFFFFFu, w4[e] & 0x7FFF0000u));
       }
-    }
-  acc = bl_wave_sum_f64_dpp(acc);
-  if (stat == 2) mx = bl_wave_max_u32(mx);
+    mx = bl_wave_max_u32(mx);
+  } else {                                       // only the sum
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const u32 w4[4] = {v[j][i].x, v[j][i].y, v[j][i].z, v[j][i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc += (double)fabsf(__uint_as_float(w4[e] << 16));
+          acc += (double)fabsf(__uint_as_float(w4[e] & 0xFFFF0000u));
+        }
+      }
+    acc = bl_wave_sum_f64_dpp(acc);
+  }
   if (lane == 0) { red[wave] = acc; redm[wave] = mx; }
   __syncthreads();
   double tot = 0.0;
@@ -233,25 +251,29 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_regs_kernel(
   for (int j = 0; j < NV; ++j) {
     const int h = tid + QA_THREADS * j;          // half unit: channels 16 h .. 16 h + 15
     if (h < Kp / 16) {
-      int q[16];
+      float pf[16];                              // the levels, as floats
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const u32 w4[4] = {v[j][i].x, v[j][i].y, v[j][i].z, v[j][i].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float p0 = fminf(fmaxf(rintf(__uint_as_float(w4[e] << 16) * s), -8.0f), 7.0f);   // one float32 multiply
-          const float p1 = fminf(fmaxf(rintf(__uint_as_float(w4[e] & 0xFFFF0000u) * s), -8.0f), 7.0f);
-          q[8 * i + 2 * e] = (int)p0;
-          q[8 * i + 2 * e + 1] = (int)p1;
+          pf[8 * i + 2 * e] = fminf(fmaxf(rintf(__uint_as_float(w4[e] << 16) * s), -8.0f), 7.0f);   // one float32 multiply
+          pf[8 * i + 2 * e + 1] = fminf(fmaxf(rintf(__uint_as_float(w4[e] & 0xFFFF0000u) * s), -8.0f), 7.0f);
         }
       }
+      int q[16];
+      if (!MX6 || rowsum_out) {                  // (uniform: the 6-bit codes come from the floats)
 #pragma unroll
-      for (int c = 0; c < 16; ++c) sum += q[c];
+        for (int c = 0; c < 16; ++c) {
+          q[c] = (int)pf[c];
+          sum += q[c];
+        }
+      }
       if (MX6) {
         u32 w3[3] = {0u, 0u, 0u};
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
-          const u32 code = qa_e3m2_of_level(q[c]);
+          const u32 code = qa_e3m2_of_levelf(pf[c]);
           const int bit = 6 * c;
           w3[bit >> 5] |= code << (bit & 31);
           if ((bit & 31) > 26) w3[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
