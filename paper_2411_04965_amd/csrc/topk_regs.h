@@ -101,13 +101,15 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
   const int nc = c_end - c_begin;                         // chunks of this wave; the rest hold key 0
 
   // one pass over the row: 4 consecutive channels (8 bytes) per lane and chunk, zero beyond K
+  // (one address per lane, the chunks at constant distances from it)
   u32 raw[CPW][2], pg[CPW][2];
   u32 km2 = QA_GUARD;
+  const int ch0 = c_begin * 256 + lane * 4;
+  const int left = K - ch0;                               // channels from this lane's first one on
 #pragma unroll
   for (int i = 0; i < CPW; ++i) {
     uint2 v = make_uint2(0u, 0u);
-    const int ch = (c_begin + i) * 256 + lane * 4;
-    if (i < nc && ch < K) v = qa_token4<GLU>(x, x2, ch);      // K % 4 == 0 by dispatch
+    if (i < nc && i * 256 < left) v = qa_token4<GLU>(x, x2, ch0 + i * 256);   // K % 4 == 0 by dispatch
     raw[i][0] = v.x; raw[i][1] = v.y;
     pg[i][0] = v.x | QA_GUARD; pg[i][1] = v.y | QA_GUARD;
   }
@@ -204,10 +206,10 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
   const u32 tk = eq_all ? t0 : t1;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   int sum = 0;
+  u32* out0 = out + c_begin * 64 + lane;
 #pragma unroll
   for (int i = 0; i < CPW; ++i) {
     if (i < nc) {                                         // wave-uniform
-      const int c = c_begin + i;
       // kept keys as guard-bit flags: key >= tau where the wave keeps all its keys equal to tau,
       // key > tau where it keeps none of them
       u32 k0 = (pg[i][0] - tk) & QA_GUARD, k1 = (pg[i][1] - tk) & QA_GUARD;
@@ -245,7 +247,7 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
       const u32 keep4 = (__builtin_amdgcn_perm(k1, k0, 0x07050301u) >> 7) * 255u;
       const u32 word = (w01 | w23) & keep4;
       sum = __builtin_amdgcn_sdot4((int)word, 0x01010101, sum, false);
-      out[c * 64 + lane] = word;
+      out0[i * 64] = word;
     }
   }
   if (rowsum_out) {
