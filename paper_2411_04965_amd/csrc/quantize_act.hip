@@ -532,11 +532,12 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
   const size_t row = (size_t)m * K * (GLU == 2 ? 4 : 2);
   const unsigned char* x = reinterpret_cast<const unsigned char*>(X) + row;
   const unsigned char* x2 = GLU ? reinterpret_cast<const unsigned char*>(X2) + row : nullptr;
+  const int ch0 = c_begin * 256 + lane * 4;               // (one address per lane, chunks at constant distances)
+  const int left = K - ch0;
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
     uint2 v = make_uint2(0u, 0u);
-    const int ch = (c_begin + i) * 256 + lane * 4;
-    if (i < nc && ch < K) v = qa_token4<GLU>(x, x2, ch);       // K % 4 == 0 by dispatch
+    if (i < nc && i * 256 < left) v = qa_token4<GLU>(x, x2, ch0 + i * 256);   // K % 4 == 0 by dispatch
     raw[i][0] = v.x; raw[i][1] = v.y;
   }
   u32 kmax;
@@ -615,7 +616,7 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
   const u32 tk = eq_all ? t0 : t1;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   int sum = 0;
-  u32* out = q_out + m * (int64_t)(Kp / 4);
+  u32* out0 = q_out + m * (int64_t)(Kp / 4) + c_begin * 64 + lane;
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
     if (i < nc) {                                         // wave-uniform
@@ -649,7 +650,7 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
       const u32 keep4 = (__builtin_amdgcn_perm(k1, k0, 0x07050301u) >> 7) * 255u;
       const u32 word = (w01 | w23) & keep4;
       sum = __builtin_amdgcn_sdot4((int)word, 0x01010101, sum, false);
-      out[(c_begin + i) * 64 + lane] = word;
+      out0[i * 64] = word;
     }
   }
   if (rowsum_out) {
