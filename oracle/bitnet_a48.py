@@ -144,6 +144,30 @@ def quant_topk_int8(X, k_sel, eps=DEFAULT_EPS):
     return np.where(mask, q, np.int8(0)).astype(np.int8), d, mask
 
 
+def quant_heads(X, bits, eps=DEFAULT_EPS):
+    """Low-bit attention states (Section 4.2, "Low-bit Attention"; Table 3): every head vector of a
+    token (post-RoPE query, key or value) is quantized on its own with the absmax function, to
+    `bits` = 4 or 3 bits, and stored as an unsigned integer.
+
+    Reading (the paper gives one sentence and no formula): the absmax form of eq. 3 with
+    Q_b = 2^(bits-1) - 1 levels on each side,
+        q = RoundClip(Q_b / (gamma + eps) * x, -Q_b, Q_b),  gamma = max|x| over the head,
+    stored with the offset 2^(bits-1):  code = q + 2^(bits-1), in [1, 2^bits - 1];
+    the value it stands for is (code - 2^(bits-1)) * gamma / Q_b.  (Which tokens get which width -
+    the paper keeps the first token's heads at 4 bits in the 3-bit cache - is the caller's choice.)
+
+    X [T, H, D] -> (codes uint8 [T, H, D], d float32 [T, H] = gamma / Q_b)."""
+    assert bits in (3, 4)
+    X = np.asarray(X, dtype=F32)
+    Qb = F32(2 ** (bits - 1) - 1)
+    gamma = np.abs(X).max(axis=2).astype(F32)
+    s = (Qb / (gamma + F32(eps)).astype(F32)).astype(F32)
+    q = round_clip((X * s[:, :, None]).astype(F32), -float(Qb), float(Qb)).astype(np.int16)
+    codes = (q + 2 ** (bits - 1)).astype(np.uint8)
+    d = (gamma / Qb).astype(F32)
+    return codes, d
+
+
 # E2M1 magnitudes by 3-bit code (1 sign, 2 exponent, 1 mantissa bit).
 E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float64)
 FP4_BLOCK = 32

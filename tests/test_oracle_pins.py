@@ -527,6 +527,65 @@ def test_bitlinear_fp4_against_dense():
         assert v in GRID15
 
 
+# ------------------------------------------------------------------ Section 4.2: low-bit attention states
+@pytest.mark.parametrize("bits", [4, 3])
+def test_quant_heads(bits):
+    Qb = 2 ** (bits - 1) - 1
+    off = 2 ** (bits - 1)
+    # hand-worked head, gamma = 7 (eps = 0): 4 bits -> q = x exactly; 3 bits -> q = rint(3 x / 7)
+    x = np.array([[[7.0, -7.0, 3.5, -3.5, 1.0, 0.0, -0.4, 5.9]]], F32)
+    codes, d = O.quant_heads(x, bits, 0.0)
+    if bits == 4:
+        assert codes[0, 0].tolist() == [15, 1, 12, 4, 9, 8, 8, 14]      # 3.5 -> 4 (even), -3.5 -> -4, 5.9 -> 6
+        assert d[0, 0] == f32(1.0)
+    else:
+        assert codes[0, 0].tolist() == [7, 1, 6, 2, 4, 4, 4, 7]         # 1.5 -> 2 (even), 3/7 -> 0, 2.53 -> 3
+        assert d[0, 0] == f32(f32(7) / f32(3))
+    # brute force in exact rationals except for the float32 roundings the reading fixes
+    rng = np.random.default_rng(41)
+    X = rng.standard_normal((5, 3, 24)).astype(F32)
+    X[1, 0] *= 40
+    X[2, 1] = 0
+    X[3, 2, :] = -0.75
+    codes, d = O.quant_heads(X, bits, EPS)
+    for t in range(5):
+        for h in range(3):
+            row = X[t, h]
+            gamma = f32(max(abs(float(v)) for v in row))
+            s = f32(f32(Qb) / f32(gamma + f32(EPS)))
+            want = [int(min(max(round(Fraction(float(f32(f32(v) * s)))), -Qb), Qb)) + off for v in row]
+            assert codes[t, h].tolist() == want and d[t, h] == f32(gamma / f32(Qb))
+    # unsigned codes in [1, 2^bits - 1]; the largest magnitude of a head sits at an end of the range;
+    # an all-zero head is all `off` with scale 0; heads do not influence one another
+    assert codes.min() >= 1 and codes.max() <= 2 * off - 1
+    big = np.abs(X).reshape(15, 24).argmax(1)
+    cc = codes.reshape(15, 24)
+    for i in range(15):
+        if i != 2 * 3 + 1:
+            assert cc[i, big[i]] in (1, 2 * off - 1)
+    assert np.all(codes[2, 1] == off) and d[2, 1] == 0
+    X2 = X.copy()
+    X2[0, 0] *= 9
+    c2, d2 = O.quant_heads(X2, bits, EPS)
+    keep = np.ones((5, 3), bool)
+    keep[0, 0] = False
+    assert np.array_equal(c2[keep], codes[keep]) and np.array_equal(d2[keep], d[keep])
+    # uniform quantizer with step d: within half a step; x -> -x mirrors the codes; 2^k gains pass (eps = 0)
+    deq = (codes.astype(np.float64) - off) * d[:, :, None].astype(np.float64)
+    assert np.all(np.abs(deq - X) <= 0.5 * d[:, :, None] * (1 + 1e-4) + 1e-5)
+    cn, dn = O.quant_heads(-X, bits, EPS)
+    assert np.array_equal(cn.astype(int), 2 * off - codes.astype(int)) and np.array_equal(dn, d)
+    Xnz = X[[0, 1, 3, 4]]                                  # (eps = 0 needs gamma > 0)
+    c0, d0 = O.quant_heads(Xnz, bits, 0.0)
+    c8, d8 = O.quant_heads(Xnz * f32(8), bits, 0.0)
+    assert np.array_equal(c0, c8) and np.array_equal(d8, d0 * f32(8))
+    # 4 bits: the same integers as the INT4 absmax quantizer of the ablations (7 levels) on the same row
+    if bits == 4:
+        q7, d7 = O.quant_int4_variant(X.reshape(15, 24), EPS, "absmax")
+        assert np.array_equal(codes.reshape(15, 24).astype(int) - 8, q7.astype(int))
+        assert np.array_equal(d.reshape(15), d7)
+
+
 # ------------------------------------------------------------------ symmetries of the whole layers
 def test_layer_symmetries():
     """What the equations imply whatever the arithmetic details: tokens are independent, sign flips and
