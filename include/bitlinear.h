@@ -243,6 +243,26 @@ int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const void* W_row
                           const float* alpha, int64_t N, float eps, const void* G,
                           bl_dtype g_dtype, void* H, void* stream);
 
+/* Low-bit attention states (Section 4.2, "Low-bit Attention"; Table 3): each head vector of a token
+ * (post-RoPE query, key or value) is quantized on its own with the absmax function to `bits` = 4 or
+ * 3 bits and stored as an unsigned integer.  The paper gives one sentence and no formula; the form
+ * taken is eq. 3's with Q_b = 2^(bits-1) - 1 levels on each side:
+ *     gamma = max|x| over the head;  q = RoundClip(x * (Q_b / (gamma + eps)), -Q_b, Q_b);
+ *     code = q + 2^(bits-1), in [1, 2^bits - 1];  scale_out = gamma / Q_b
+ * (the value a code stands for is (code - 2^(bits-1)) * scale).  The paper's 3-bit cache keeps the
+ * first token's heads at 4 bits: call once for that token with bits = 4 and once for the others.
+ *   X          device, [T, H, D] of x_dtype, 16-byte aligned, D % 8 == 0, D <= BL_MAX_K
+ *   q_out      device, quantize_heads_bytes(bits, T, H, D) = T * H * D * bits / 8 bytes, 16-byte
+ *              aligned: per head D * bits / 8 bytes, heads in [T, H] order; code j of a head in
+ *              bits bits*j .. bits*j + bits-1 of the head's little-endian bit stream (4 bits: two
+ *              codes per byte, the even channel in the low nibble; 3 bits: eight codes in three bytes)
+ *   scale_out  device, float32 [T, H]
+ * Errors: BL_EINVAL (null pointer, bits, eps < 0, sizes < 1), BL_ESHAPE (D % 8 != 0 or too large),
+ * BL_EALIGN. */
+size_t quantize_heads_bytes(int bits, int64_t T, int64_t H, int64_t D);
+int quantize_heads(const void* X, bl_dtype x_dtype, int64_t T, int64_t H, int64_t D, int bits, float eps,
+                   void* q_out, float* scale_out, void* stream);
+
 /* ReLU^2 GLU combine (eq. 5): H = bf16(U * max(G, 0)^2), float32 steps in that order.
  * G, U device [M, N] of in_dtype; H device [M, N] bfloat16. */
 int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,

@@ -42,6 +42,8 @@ _SIGNATURES = {
                               _vp, _sz, _vp]),
     "relu2_glu": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _vp]),
     "swish_glu": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _vp]),
+    "quantize_heads_bytes": (_sz, [_int, _i64, _i64, _i64]),
+    "quantize_heads": (_int, [_vp, _int, _i64, _i64, _i64, _int, _f32, _vp, _vp, _vp]),
     "quantize_act_glu": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
     "bitlinear_a4_up_gated": (_int, [_vp, _i64, _i64, _vp, _vp, _i64, _f32, _vp, _int, _vp, _vp]),
     "unpack_ternary": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
@@ -233,6 +235,17 @@ def relu2_glu(G, U):
     H = torch.empty((M, N), dtype=torch.bfloat16, device=G.device)
     _check("relu2_glu", lib().relu2_glu(_ptr(G), _ptr(U), _dt(G), M, N, _ptr(H), _stream()))
     return H
+
+
+def quantize_heads(X, bits, eps=DEFAULT_EPS):
+    """X [T, H, D] -> (packed codes uint8 [T * H * D * bits / 8], scale float32 [T, H])."""
+    _dev(X)
+    T, H, D = X.shape
+    L = lib()
+    q = torch.empty(L.quantize_heads_bytes(bits, T, H, D), dtype=torch.uint8, device=X.device)
+    scale = torch.empty((T, H), dtype=torch.float32, device=X.device)
+    _check("quantize_heads", L.quantize_heads(_ptr(X), _dt(X), T, H, D, bits, eps, _ptr(q), _ptr(scale), _stream()))
+    return q, scale
 
 
 def swish_glu(G, U):

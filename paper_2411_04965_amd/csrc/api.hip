@@ -134,6 +134,24 @@ extern "C" int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K,
   return bl_launch_unpack_act(q, mode, M, K, codes_out, (hipStream_t)stream);
 }
 
+// ---------------------------------------------------------------- attention states (Section 4.2)
+extern "C" size_t quantize_heads_bytes(int bits, int64_t T, int64_t H, int64_t D) {
+  if ((bits != 3 && bits != 4) || T < 1 || H < 1 || D < 8 || D % 8 != 0) return 0;
+  return (size_t)(T * H * (D / 8) * bits);
+}
+
+extern "C" int quantize_heads(const void* X, bl_dtype x_dtype, int64_t T, int64_t H, int64_t D, int bits,
+                              float eps, void* q_out, float* scale_out, void* stream) {
+  if (!X || !q_out || !scale_out) return BL_EINVAL;
+  if (!valid_dtype(x_dtype) || (bits != 3 && bits != 4) || !(eps >= 0.0f)) return BL_EINVAL;
+  if (T < 1 || H < 1 || D < 1) return BL_EINVAL;
+  if (D % 8 != 0 || D > BL_MAX_K) return BL_ESHAPE;
+  const int64_t lim = (int64_t)1 << 40;
+  if (T > lim / H || T * H > lim / D) return BL_ESHAPE;
+  if (!bl_aligned16(X) || !bl_aligned16(q_out)) return BL_EALIGN;
+  return bl_launch_quantize_heads(X, x_dtype, T * H, D, bits, eps, q_out, scale_out, (hipStream_t)stream);
+}
+
 // ---------------------------------------------------------------- linear layers
 // Workspace layout: [codes | scales | stage-2 scratch], each part 256-byte aligned.
 static size_t stage2_ws_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K) {

@@ -104,6 +104,8 @@ int bl_launch_quantize(const void* X, bl_dtype dt, int64_t M, int64_t K, bl_act_
                        int32_t* sel_idx, hipStream_t s);
 int bl_launch_unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K, int8_t* codes,
                          hipStream_t s);
+int bl_launch_quantize_heads(const void* X, bl_dtype dt, int64_t n_heads, int64_t D, int bits, float eps,
+                             void* q, float* scale, hipStream_t s);
 int bl_launch_gemm_prefill(const void* q, const float* scale, bl_act_mode mode, int64_t M,
                            int64_t K, const void* Wp, const float* alpha, int64_t N, void* Y,
                            bl_dtype ydt, int32_t* acc_out, hipStream_t s);

@@ -191,3 +191,11 @@ def assert_close_rel(y_gpu, y_ref, tol=REL_TOL):
 
 def pack(W, layout=B.BL_W_GEMM, dtype=torch.float32):
     return B.pack_ternary(dev(W, dtype), EPS, layout)
+
+
+def decode_heads(q, T, H, D, bits):
+    """Packed head codes (little-endian bit stream per head, `bits` bits per code) -> uint8 [T, H, D]."""
+    b = np.frombuffer(q.tobytes(), dtype=np.uint8).reshape(T * H, D * bits // 8)
+    bitsarr = np.unpackbits(b, axis=1, bitorder="little").reshape(T * H, D, bits)
+    w = (1 << np.arange(bits)).astype(np.uint8)
+    return (bitsarr * w).sum(axis=2).astype(np.uint8).reshape(T, H, D)

@@ -9,7 +9,7 @@ import torch
 from oracle import bitnet_a48 as O
 from paper_2411_04965_amd import binding as B
 from paper_2411_04965_amd import synth as S
-from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_fp4_mx, decode_int4, decode_int4_mx6,
+from tests.gpu_util import (EPS, assert_close_rel, decode_fp4, decode_heads, decode_fp4_mx, decode_int4, decode_int4_mx6,
                             decode_int8, decode_w_gemm, decode_w_kmajor, decode_w_mx2, decode_w_mx4, decode_w_rows, dev, host,
                             pack)
 
@@ -266,6 +266,27 @@ def test_swish_glu(M, N, dtype):
     # (below g = -88.7 float32 exp(-g) overflows and the result is 0 instead of about 1e-40)
     assert np.all(diff <= np.maximum(ulp, 2.0 ** -100)), float((diff / ulp).max())
     assert (diff > 0).mean() <= 0.002, float((diff > 0).mean())
+
+
+@pytest.mark.parametrize("T,H,D,dtype", [(5, 3, 128, BF16), (33, 32, 128, BF16), (7, 4, 64, F32), (9, 2, 96, BF16),
+                                         (6, 5, 80, BF16), (3, 2, 256, F32), (4, 1, 8, BF16), (2048, 32, 128, BF16)])
+@pytest.mark.parametrize("bits", [4, 3])
+def test_quantize_heads(T, H, D, dtype, bits):
+    """Section 4.2's per-head absmax quantizer of the attention states (4 and 3 bits, unsigned codes):
+    codes and scales bit for bit against the oracle, both kernels (a head per 16 lanes; a head per
+    wave), head widths that fill and do not fill the 16 lanes, an all-zero head."""
+    say("quantize_heads T=%d H=%d D=%d %s bits=%d" % (T, H, D, dtype, bits))
+    x = S.heavy(T * H, D, S.seed_for(7, T + H + D)).reshape(T, H, D)
+    x[0, 0] = 0
+    x[T - 1, H - 1, :4] = [3.5, -3.5, 1.5, -0.5]          # ties after scaling when the maximum is 7 or 3
+    x[T - 1, H - 1, 4] = 7.0 if bits == 4 else 3.0
+    x[T - 1, H - 1, 5:] = 0
+    x = S.snap_bf16(x) if dtype == BF16 else x.astype(np.float32)
+    codes_ref, d_ref = O.quant_heads(x, bits, EPS)
+    q, d = B.quantize_heads(dev(x, dtype), bits, EPS)
+    assert q.numel() == T * H * D * bits // 8
+    assert np.array_equal(host(d), d_ref)
+    assert np.array_equal(decode_heads(host(q), T, H, D, bits), codes_ref)
 
 
 # ------------------------------------------------------------------ whole linears
