@@ -14,7 +14,8 @@ included.  The roofline object covers the dominant kernel, the W1.58A4 prefill G
 with events on the launch stream inside the timed region.  Decode-shape weight bandwidth
 (packed-weight GB/s at 1/8/32/64 tokens) is reported in the same JSON line under "decode", and
 the FP4 activation variant against the INT4 path at 3B-like shapes under "fp4_variant"; one
-token through a whole FFN block, four calls against the gate-first form, under "decode_ffn_1token".
+token through a whole FFN block, four calls against the gate-first form, under "decode_ffn_1token";
+the per-head quantizer of the attention states (Section 4.2) at 7B width under "attention_states".
 """
 import argparse
 import json
@@ -225,6 +226,7 @@ def main():
         out["decode_ffn_1token"] = decode_ffn_bench(B, S, torch, dev)
     if not args.no_fp4:
         out["fp4_variant"] = fp4_compare(B, S, torch, dev)
+    out["attention_states"] = heads_bench(B, S, torch, dev, M)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
@@ -288,6 +290,33 @@ def decode_ffn_bench(B, S, torch, dev, layers=8, replays=20):
         res[name + "_us"] = round(e0.elapsed_time(e1) / (replays * layers) * 1e3, 2)
         del g
     res["open_gate_fraction"] = round(float((G > 0).float().mean().item()), 3)
+    return res
+
+
+def heads_bench(B, S, torch, dev, T, H=32, D=128, iters=20):
+    """Per-head absmax quantizer of the attention states (Section 4.2) on one projection's worth of
+    heads at 7B width: T tokens x 32 heads x 128 channels of bfloat16, to 4 and to 3 bits.  GB/s over
+    the algorithmic bytes (2 D in, D bits / 8 + 4 out per head).  The calls rotate over four input
+    tensors (0.5 GB together) so that none of them is still in the 256 MB memory-side cache when
+    its turn comes again."""
+    Xs = [torch.from_numpy(S.heavy(T, H * D, S.seed_for(5, 1 + i))).to(dev).to(torch.bfloat16).reshape(T, H, D)
+          for i in range(4)]
+    res = {"tokens": T, "heads": H, "head_dim": D}
+    for bits in (4, 3):
+        for i in range(4):
+            B.quantize_heads(Xs[i], bits, EPS)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            B.quantize_heads(Xs[i % 4], bits, EPS)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        nbytes = T * H * (2 * D + D * bits // 8 + 4)
+        res["bits%d" % bits] = {"ms": round(ms, 4), "gbs": round(nbytes / ms / 1e6, 1),
+                                "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 3)}
     return res
 
 
