@@ -676,6 +676,15 @@ def test_argument_errors():
         Xu = torch.zeros(4 * 64 + 4, device="cuda")[1:257].view(4, 64)      # 4-byte offset
         B.bitlinear_a4(Xu, p, a, 32)
     assert e.value.status == -3
+    Hd = dev(np.zeros((2, 3, 64), np.float32))
+    with pytest.raises(B.BitlinearError) as e:
+        B.quantize_heads(Hd, 5)                                             # 3 or 4 bits only
+    assert e.value.status == -1
+    L = B.lib()
+    qb = torch.empty(64, dtype=torch.uint8, device="cuda")
+    sb = torch.empty(8, dtype=torch.float32, device="cuda")
+    assert L.quantize_heads(Hd.data_ptr(), B.BL_F32, 2, 3, 12, 4, 1e-5, qb.data_ptr(), sb.data_ptr(), None) == -2   # D % 8
+    assert L.quantize_heads_bytes(4, 2, 3, 12) == 0 and L.quantize_heads_bytes(3, 2, 3, 64) == 2 * 3 * 24
 
 
 # ------------------------------------------------------------------ FP4 variant (config 4)
