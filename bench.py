@@ -33,12 +33,22 @@ EPS = 1e-5
 INT8_PEAK_TOPS = 5033.0      # MI355X dense int8 MFMA
 FP6_FP4_PEAK_TOPS = 10066.0  # MI355X dense fp6 / fp4 MFMA (the INT4 GEMM runs on E3M2 x E2M1 operands)
 HBM_PEAK_GBS = 8000.0
-# Bytes between L2 and the memory fabric per launch of the W1.58A4 prefill GEMM at the benchmark
-# shapes, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/gemm_7b_prefill_hbm_traffic.txt (calibrated against a 1 GiB device copy):
-# 490.2 MB fetched + 374.7 MB written (2-bit weights; 677.6 MB fetched with E2M1 nibbles).
-A4_GEMM_TRAFFIC_BYTES = 864.9e6
 HIDDEN, FFN = 4096, 11008
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemm_7b_prefill_hbm_traffic.txt")
+
+
+def measured_traffic_bytes():
+    """Bytes between L2 and the memory fabric per launch of the W1.58A4 prefill GEMM at the
+    benchmark's shapes, as the rocprofv3 FETCH_SIZE / WRITE_SIZE runs measured them (counters cannot
+    be read from inside this process): the line `roofline_traffic_bytes_per_launch: <bytes>` of the
+    committed summary of those runs, or None if the summary is absent."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("roofline_traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def parse():
@@ -48,6 +58,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true",
+                    help="skip the timed prefill step (profiling the decode sweep alone); the line then has value 0")
+    ap.add_argument("--decode-tokens", type=int, nargs="*", default=[1, 8, 32, 64])
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-fp4", action="store_true")
     ap.add_argument("--a4-weights", choices=["mx2", "mx4"], default="mx2",
@@ -134,16 +147,19 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     L = B.lib()
 
+    # events of the timed steps exist before the timed region: recording one is all that is left in it
+    n_timed = 0 if args.no_prefill else args.steps
+    pool = [[tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in projs] for _ in range(n_timed)]
     gemm_events = {name: [] for name, *_ in projs}
     quant_events = {name: [] for name, *_ in projs}
 
-    def step(record):
-        for name, N, K, kind in projs:
+    def step(record, it=0):
+        for pi, (name, N, K, kind) in enumerate(projs):
             b = bufs[name]
             X = inputs[name]
             topk = K // 2 if kind == "a8s" else 0
             if record:
-                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                e0, e1, e2 = pool[it][pi]
                 e0.record()
             if name == "up":
                 # gate and up read the same tensor: it is quantized once (by "gate") and used twice
@@ -172,12 +188,21 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.no_prefill:
+        out = {"metric": "W1.58A4 linear TOPS (prefill) & packed-weight GB/s (decode), 7B shapes", "value": 0.0,
+               "unit": "TOPS", "n_gpus": 1, "steps": 0, "warmup": 0, "ms_per_step": 0.0, "higher_is_better": True,
+               "scaling": "weak", "vs_baseline": None, "dtype": "int8+fp6xfp4", "data": "synthetic",
+               "config": {"workload": "decode sweep only (--no-prefill): not a benchmark result"}}
+        out["decode"] = decode_bench(B, S, torch, dev, tokens=tuple(args.decode_tokens))
+        print(json.dumps(out))
+        return
+
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(True)
+    for it in range(args.steps):
+        step(True, it)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -203,9 +228,12 @@ def main():
                 "achieved": round(achieved, 1), "peak": FP6_FP4_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / FP6_FP4_PEAK_TOPS, 4),
                 "frac_of_int8_peak": round(achieved / INT8_PEAK_TOPS, 4),
-                "traffic": A4_GEMM_TRAFFIC_BYTES if (M == 16384 and args.a4_weights == "mx2") else None,
-                "algorithmic_bytes": round(sum(M * K * 3 / 4 + N * K / (4 if args.a4_weights == "mx2" else 2) + 2 * M * N
-                                               for _, N, K in a4) / len(a4)),
+                "traffic": measured_traffic_bytes() if (M == 16384 and args.a4_weights == "mx2") else None,
+                # what the method itself has to move per launch: 4-bit codes, 2-bit weights, bf16 outputs
+                "algorithmic_bytes": round(sum(M * K / 2 + N * K / 4 + 2 * M * N for _, N, K in a4) / len(a4)),
+                # what this kernel's formats move: the INT4 levels travel as 6-bit E3M2 codes
+                "format_bytes": round(sum(M * K * 3 / 4 + N * K / (4 if args.a4_weights == "mx2" else 2) + 2 * M * N
+                                          for _, N, K in a4) / len(a4)),
                 "avg_launch_ms": round(a4_ms / len(a4), 4)}
 
     out = {
@@ -222,7 +250,7 @@ def main():
         "kernels": per_kernel,
     }
     if not args.no_decode:
-        out["decode"] = decode_bench(B, S, torch, dev)
+        out["decode"] = decode_bench(B, S, torch, dev, tokens=tuple(args.decode_tokens))
         out["decode_ffn_1token"] = decode_ffn_bench(B, S, torch, dev)
     if not args.no_fp4:
         out["fp4_variant"] = fp4_compare(B, S, torch, dev)
@@ -359,63 +387,130 @@ def bl_code_bytes(kind, K):
     return Kp * 3 // 4 if kind == "a4" else Kp      # 6-bit codes / int8
 
 
-def decode_bench(B, S, torch, dev, layers=8, replays=20):
-    """Packed-weight bandwidth at decode shapes.  `layers` distinct weight sets per projection
-    (more than the 256 MB last-level cache holds in total) are run back to back from one HIP
-    graph per projection, so launch overhead of the Python binding is not in the timing."""
-    res = {}
+def _graph_time_us(torch, fn, n_calls, replays, side):
+    """Capture `n_calls` invocations fn(0) .. fn(n_calls - 1) in one HIP graph on `side` and time
+    `replays` replays with events on the current stream: microseconds per invocation."""
+    for i in range(n_calls):
+        fn(i)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for i in range(n_calls):
+                fn(i)
+    g.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (replays * n_calls)
+    del g
+    return us
+
+
+DECODE_LAYERS = 32            # distinct layers of the sweep: 32 x 50.6 MB = 1.6 GB of packed weights
+DECODE_MIN_SET_BYTES = 640e6  # per-projection timing cycles at least this many bytes of distinct weights
+
+
+def decode_bench(B, S, torch, dev, tokens=(1, 8, 32, 64), replays=5):
+    """Packed-weight bandwidth at decode shapes, with the weights coming from HBM.
+
+    Weights: DECODE_LAYERS distinct layers (five projections each, 1.6 GB in all), drawn on the
+    device from a seeded generator and packed once.  Per token count:
+      * `layer_sweep`: one HIP graph walks all five projections of all layers in model order, so
+        every weight byte read is one of 1.6 GB read since its last use (the memory-side cache
+        holds 256 MB);
+      * per projection: a graph over enough distinct weight sets of that one shape that a replay
+        touches at least DECODE_MIN_SET_BYTES (the o projection gets extra sets for that);
+      * for the two top-K + INT8 projections at 1 and 8 tokens also the row-skipping path
+        (BL_W_KMAJOR): microseconds, GB/s over the bytes it has to read (the rows of the channels
+        kept by at least one token) and dense-equivalent GB/s (all N*K/4 bytes over the same time).
+    `launch_floor_us` is the same graph timing of the library's empty kernel."""
     bf16 = torch.bfloat16
     projs = S.projections(HIDDEN, FFN)
-    packed = {}
-    for i, (name, N, K, kind) in enumerate(projs):
-        sets = []
-        for l in range(layers):
-            w = torch.from_numpy(S.latent_weights(N, K, S.seed_for(2, 1000 + 10 * l + i))).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(S.seed_for(2, 4000))
+
+    def n_sets(nbytes):
+        return max(DECODE_LAYERS, int(-(-DECODE_MIN_SET_BYTES // nbytes)))
+
+    packed, packed_k = {}, {}
+    for name, N, K, kind in projs:
+        sets, sets_k = [], []
+        for l in range(n_sets(N * K / 4)):
+            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
             sets.append(B.pack_ternary(w, EPS, B.BL_W_GEMM))
+            if kind == "a8s":
+                sets_k.append(B.pack_ternary(w, EPS, B.BL_W_KMAJOR))
             del w
         packed[name] = sets
+        packed_k[name] = sets_k
     side = torch.cuda.Stream()
-    for M in (1, 8, 32, 64):
+    res = {"layers": DECODE_LAYERS,
+           "weights_resident_mb": round(sum(p.numel() for v in list(packed.values()) + list(packed_k.values())
+                                            for p, _ in v) / 1e6, 1),
+           "launch_floor_us": round(_graph_time_us(torch, lambda i: B.noop(), 160, 20, side), 3)}
+    for M in tokens:
         row = {}
-        tot_bytes, tot_ms = 0.0, 0.0
+        X, ws, Y = {}, {}, {}
         for name, N, K, kind in projs:
-            X = torch.from_numpy(S.glu_like(M, K, S.seed_for(2, 200 + M)) if name == "down"
-                                 else S.heavy(M, K, S.seed_for(2, 100 + M))).to(dev).to(bf16)
+            X[name] = torch.from_numpy(S.glu_like(M, K, S.seed_for(2, 200 + M)) if name == "down"
+                                       else S.heavy(M, K, S.seed_for(2, 100 + M))).to(dev).to(bf16)
             mode = B.BL_ACT_INT4_ABSMEAN if kind == "a4" else B.BL_ACT_TOPK_INT8_ABSMAX
-            ws = B.workspace(mode, M, N, K, dev)
-            Y = torch.empty((M, N), dtype=bf16, device=dev)
+            ws[name] = B.workspace(mode, M, N, K, dev)
+            Y[name] = torch.empty((M, N), dtype=bf16, device=dev)
 
-            def run(l):
-                p, a = packed[name][l % layers]
-                if kind == "a4":
-                    B.bitlinear_a4(X, p, a, N, EPS, ws=ws, out=Y)
-                else:
-                    B.bitlinear_a8_sparse(X, K // 2, p, a, N, EPS, ws=ws, out=Y)
-            for l in range(layers):
-                run(l)
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.stream(side):
-                with torch.cuda.graph(g, stream=side):
-                    for l in range(layers):
-                        run(l)
-            g.replay()
-            torch.cuda.synchronize()
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(replays):
-                g.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / (replays * layers)
+        def run(name, N, K, kind, l, kmajor=False):
+            if kind == "a4":
+                p, a = packed[name][l]
+                B.bitlinear_a4(X[name], p, a, N, EPS, ws=ws[name], out=Y[name])
+            elif kmajor:
+                p, a = packed_k[name][l]
+                B.bitlinear_a8_sparse(X[name], K // 2, p, a, N, EPS, layout=B.BL_W_KMAJOR, ws=ws[name], out=Y[name])
+            else:
+                p, a = packed[name][l]
+                B.bitlinear_a8_sparse(X[name], K // 2, p, a, N, EPS, ws=ws[name], out=Y[name])
+
+        for name, N, K, kind in projs:
+            n = len(packed[name])
+            us = _graph_time_us(torch, lambda l: run(name, N, K, kind, l), n, replays, side)
             wbytes = N * K / 4
-            row[name] = {"us": round(ms * 1e3, 2), "weight_gbs": round(wbytes / ms / 1e6, 1)}
-            tot_bytes += wbytes
-            tot_ms += ms
-            del g
-        row["layer_weight_gbs"] = round(tot_bytes / tot_ms / 1e6, 1)
-        row["frac_hbm_peak"] = round(tot_bytes / tot_ms / 1e6 / HBM_PEAK_GBS, 4)
+            row[name] = {"us": round(us, 2), "weight_gbs": round(wbytes / us / 1e3, 1),
+                         "frac_hbm_peak": round(wbytes / us / 1e3 / HBM_PEAK_GBS, 4), "weight_sets": n}
+            if kind == "a8s" and M <= 8:
+                qd = B.quantize_act(X[name], B.BL_ACT_TOPK_INT8_ABSMAX, topk=K // 2, eps=EPS)
+                codes = B.unpack_act(qd["q"], B.BL_ACT_TOPK_INT8_ABSMAX, M, K)
+                union = int((codes != 0).any(dim=0).sum().item())
+                us_k = _graph_time_us(torch, lambda l: run(name, N, K, kind, l, True), n, replays, side)
+                need = union * N / 4
+                row[name]["row_skipping"] = {
+                    "us": round(us_k, 2), "channels_read": union, "channels": K,
+                    "required_gbs": round(need / us_k / 1e3, 1),
+                    "frac_hbm_peak": round(need / us_k / 1e3 / HBM_PEAK_GBS, 4),
+                    "dense_equivalent_gbs": round(wbytes / us_k / 1e3, 1)}
+
+        def layer(i):
+            for name, N, K, kind in projs:
+                run(name, N, K, kind, i)
+        us_layer = _graph_time_us(torch, layer, DECODE_LAYERS, replays, side)
+        lbytes = sum(N * K / 4 for _, N, K, _ in projs)
+        row["layer_sweep"] = {"us_per_layer": round(us_layer, 2), "weight_gbs": round(lbytes / us_layer / 1e3, 1),
+                              "frac_hbm_peak": round(lbytes / us_layer / 1e3 / HBM_PEAK_GBS, 4)}
+        if M <= 8:
+            def layer_k(i):
+                for name, N, K, kind in projs:
+                    run(name, N, K, kind, i, kmajor=(kind == "a8s"))
+            us_lk = _graph_time_us(torch, layer_k, DECODE_LAYERS, replays, side)
+            need = sum((row[name]["row_skipping"]["channels_read"] * N / 4) if kind == "a8s" else N * K / 4
+                       for name, N, K, kind in projs)
+            row["layer_sweep_row_skipping"] = {
+                "us_per_layer": round(us_lk, 2), "required_gbs": round(need / us_lk / 1e3, 1),
+                "frac_hbm_peak": round(need / us_lk / 1e3 / HBM_PEAK_GBS, 4),
+                "dense_equivalent_gbs": round(lbytes / us_lk / 1e3, 1)}
         res["M%d" % M] = row
     return res
 

@@ -10,12 +10,18 @@
  *   - The caller owns every buffer.  The library never allocates, frees or
  *     synchronises; every kernel is enqueued on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and the call returns at once.
- *   - Data pointers must be 16-byte aligned; rows are dense (no strides).
+ *   - Data pointers must be 16-byte aligned (per-token float32 scales, E8M0 block scales and
+ *     alpha: 4 bytes; G and H of bitlinear_a4_up_gated: their element size); rows are dense
+ *     (no strides).
  *   - Inputs must be finite.  NaN/Inf give unspecified codes, never a trap.
  *   - Return value: BL_OK (0) or a negative bl_status.  Arguments are validated
- *     before anything is launched; on error nothing has been enqueued.
+ *     before anything is launched; on an argument error nothing has been enqueued.  The one
+ *     exception is BL_EHIP (the driver refused a launch or a kernel attribute): a call that
+ *     runs several kernels may by then have enqueued the earlier ones.
  *   - eps is the epsilon of eq. 2, 3 and 7 (the paper gives no value; 1e-5 is used
- *     by the tests and the benchmark).
+ *     by the tests and the benchmark).  eps = 0 is accepted, but an all-zero token (or weight
+ *     matrix) then scales by 1 / 0: its codes are unspecified and a linear layer's outputs
+ *     for that token may be NaN.  With eps > 0 an all-zero token gives zero codes and outputs.
  *
  * Packed formats (all little-endian; Kp = bl_padded_k(K) = K rounded up to 256,
  * Np = N rounded up to 16; padding codes are zero):
@@ -202,10 +208,12 @@ int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, bl_act_m
  * that the tiled MFMA GEMM runs.  The block-float forms always take the tiled GEMM.
  *
  * bitlinear_a8_sparse (eq. 1): Y = (Q_INT8(X) (.) Top_k(|X|)) . Q_w(W)^T, same
- * accumulation and rescale.  With layout BL_W_KMAJOR (decode, M <= BL_DECODE_MAX_M)
- * only the weight rows of channels with a non-zero code in at least one token are read.
+ * accumulation and rescale.  With layout BL_W_KMAJOR (decode, M <= BL_SPARSE_MAX_M; more tokens:
+ * BL_EUNSUPPORTED, their union of kept channels is nearly every channel) only the weight rows of
+ * channels with a non-zero code in at least one token are read.
  */
 #define BL_DECODE_MAX_M 64
+#define BL_SPARSE_MAX_M 8
 size_t bitlinear_workspace_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K);
 int bitlinear_a4(const void* X, bl_dtype x_dtype, int64_t M, int64_t K,
                  const void* W_packed, bl_w_layout layout, const float* alpha, int64_t N,
@@ -233,7 +241,7 @@ int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M
  * X with the up weights -- but row n of the weights is read, and U[., n] computed, only if
  * G[m, n] > 0 for some token m; elsewhere H = +0.  U is kept in float32 (never rounded to
  * bfloat16) before the product, float32 steps in the order of relu2_glu.
- *   X        device, [M, K] bfloat16, M <= 4, K % 8 == 0, K <= 8192 and M * K <= 16384
+ *   X        device, [M, K] bfloat16, M <= 4, K % 8 == 0, K <= 8192 and M * bl_padded_k(K) <= 16384
  *   W_rows   device, output of pack_ternary in layout BL_W_ROWS for [N, K]
  *   alpha    device, float32[1]
  *   G        device, [M, N] of g_dtype
@@ -294,6 +302,10 @@ int unpack_ternary(const void* packed, int64_t N, int64_t K, bl_w_layout layout,
                    int8_t* T_out, void* stream);
 int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K, int8_t* codes_out,
                void* stream);
+
+/* Enqueue an empty kernel (one wave that does nothing) on `stream`: what a launch costs on its own,
+ * the floor under every figure measured per launch at decode sizes. */
+int bl_noop(void* stream);
 
 /* Human-readable name of a status code (host pointer to a static string). */
 const char* bl_status_string(int status);

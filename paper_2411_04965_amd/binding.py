@@ -48,6 +48,7 @@ _SIGNATURES = {
     "bitlinear_a4_up_gated": (_int, [_vp, _i64, _i64, _vp, _vp, _i64, _f32, _vp, _int, _vp, _vp]),
     "unpack_ternary": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
     "unpack_act": (_int, [_vp, _int, _i64, _i64, _vp, _vp]),
+    "bl_noop": (_int, [_vp]),
     "bl_status_string": (ctypes.c_char_p, [_int]),
 }
 
@@ -101,6 +102,11 @@ def _dev(t):
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("contiguous device tensor expected")
     return t
+
+
+def noop():
+    """Enqueue the library's empty kernel on the current stream (launch-floor measurements)."""
+    _check("bl_noop", lib().bl_noop(_stream()))
 
 
 def padded_k(K):

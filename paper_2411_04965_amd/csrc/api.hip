@@ -26,6 +26,32 @@ static int check_sizes(int64_t M, int64_t N, int64_t K) {
 
 extern "C" int64_t bl_padded_k(int64_t K) { return bl_round_up(K, BL_KPAD); }
 
+// Every elementwise launcher runs 256 threads per workgroup, one element (or block of 32) each.
+static bool elementwise_grid_ok(int64_t n) { return bl_grid_ok((n + 255) / 256); }
+
+int bl_num_cus() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  std::atomic<int>& slot = cached[dev & 63];
+  int cus = slot.load(std::memory_order_relaxed);
+  if (cus == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 256;
+    cus = v;
+    slot.store(cus, std::memory_order_relaxed);
+  }
+  return cus;
+}
+
+__global__ void bl_noop_kernel() {}
+
+extern "C" int bl_noop(void* stream) {
+  bl_noop_kernel<<<1, 64, 0, (hipStream_t)stream>>>();
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}
+
 extern "C" const char* bl_status_string(int status) {
   switch (status) {
     case BL_OK: return "ok";
@@ -69,6 +95,7 @@ extern "C" int unpack_ternary(const void* packed, int64_t N, int64_t K, bl_w_lay
   if (!packed || !T_out || !valid_layout(layout)) return BL_EINVAL;
   int rc = check_sizes(1, N, K);
   if (rc) return rc;
+  if (!elementwise_grid_ok(N * K)) return BL_ESHAPE;
   return bl_launch_unpack_ternary(packed, N, K, layout, T_out, (hipStream_t)stream);
 }
 
@@ -107,6 +134,7 @@ extern "C" int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t 
   if (mode == BL_ACT_TOPK_INT8_ABSMAX && (topk < 1 || topk > K)) return BL_EINVAL;
   if (mode != BL_ACT_TOPK_INT8_ABSMAX && sel_idx_out) return BL_EINVAL;
   if (fp4_mode(mode) && rowsum_out) return BL_EINVAL;
+  if (fp4_mode(mode) && !elementwise_grid_ok(M * (bl_round_up(K, BL_KPAD) / 32))) return BL_ESHAPE;
   if (!bl_aligned16(X) || !bl_aligned16(q_out)) return BL_EALIGN;
   return bl_launch_quantize(X, x_dtype, M, K, mode, topk, eps, q_out, scale_out, rowsum_out,
                             sel_idx_out, (hipStream_t)stream);
@@ -131,6 +159,7 @@ extern "C" int unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K,
   if (int4_nibble_mode(mode)) mode = BL_ACT_INT4_ABSMEAN;
   int rc = check_sizes(M, 1, K);
   if (rc) return rc;
+  if (!elementwise_grid_ok(M * K)) return BL_ESHAPE;
   return bl_launch_unpack_act(q, mode, M, K, codes_out, (hipStream_t)stream);
 }
 
@@ -148,6 +177,8 @@ extern "C" int quantize_heads(const void* X, bl_dtype x_dtype, int64_t T, int64_
   if (D % 8 != 0 || D > BL_MAX_K) return BL_ESHAPE;
   const int64_t lim = (int64_t)1 << 40;
   if (T > lim / H || T * H > lim / D) return BL_ESHAPE;
+  // the kernels take 4 or 16 heads per workgroup: bound the grid by the smaller
+  if (!bl_grid_ok((T * H + 3) / 4)) return BL_ESHAPE;
   if (!bl_aligned16(X) || !bl_aligned16(q_out)) return BL_EALIGN;
   return bl_launch_quantize_heads(X, x_dtype, T * H, D, bits, eps, q_out, scale_out, (hipStream_t)stream);
 }
@@ -157,7 +188,7 @@ extern "C" int quantize_heads(const void* X, bl_dtype x_dtype, int64_t T, int64_
 static size_t stage2_ws_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K) {
   if (fp4_mode(mode) || mx_mode(mode) || M > BL_DECODE_MAX_M) return 0;
   size_t a = bl_gemm_decode_ws_bytes(M, N, K);
-  if (mode == BL_ACT_TOPK_INT8_ABSMAX && M <= 8) {
+  if (mode == BL_ACT_TOPK_INT8_ABSMAX && M <= BL_SPARSE_MAX_M) {
     const size_t b = bl_gemv_sparse_ws_bytes(M, N, K);
     if (b > a) a = b;
   }
@@ -193,7 +224,7 @@ static int gemm_dispatch(const void* q, const void* scale, bl_act_mode mode, int
   }
   if (layout == BL_W_KMAJOR) {
     if (mode != BL_ACT_TOPK_INT8_ABSMAX) return BL_EUNSUPPORTED;
-    if (M > 8) return BL_EUNSUPPORTED;
+    if (M > BL_SPARSE_MAX_M) return BL_EUNSUPPORTED;
     if (!ws || ws_bytes < bl_gemv_sparse_ws_bytes(M, N, K)) return BL_EWORKSPACE;
     return bl_launch_gemv_sparse(q, (const float*)scale, M, K, W_packed, alpha, N, Y, y_dtype,
                                  acc_out, ws, s);
@@ -220,6 +251,8 @@ extern "C" int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode
   if (!bl_aligned16(q) || !bl_aligned16(W_packed) || !bl_aligned16(Y) ||
       (acc_out && !bl_aligned16(acc_out)) || (workspace && !bl_aligned16(workspace)))
     return BL_EALIGN;
+  // scales: float32 per token, or E8M0 block scales that the FP4 GEMMs fetch four at a time
+  if (reinterpret_cast<uintptr_t>(scale) & 3) return BL_EALIGN;
   return gemm_dispatch(q, scale, mode, M, K, W_packed, layout, alpha, N, Y, y_dtype, acc_out,
                        workspace, workspace_bytes, (hipStream_t)stream);
 }
@@ -243,7 +276,7 @@ static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, 
   if (mode == BL_ACT_FP4_E2M1_B32 && (layout != BL_W_GEMM || acc_out)) return BL_EINVAL;
   if (mode == BL_ACT_FP4_E2M1_B32_MX && acc_out) return BL_EINVAL;
   if (mx_mode(mode) != mx_layout(layout)) return BL_EINVAL;
-  if (layout == BL_W_KMAJOR && (mode != BL_ACT_TOPK_INT8_ABSMAX || M > 8)) return BL_EUNSUPPORTED;
+  if (layout == BL_W_KMAJOR && (mode != BL_ACT_TOPK_INT8_ABSMAX || M > BL_SPARSE_MAX_M)) return BL_EUNSUPPORTED;
   if (layout == BL_W_ROWS) return BL_EUNSUPPORTED;
 
   // a few tokens: quantizer and product in one launch
@@ -302,6 +335,9 @@ extern "C" int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const 
   int rc = check_sizes(M, N, K);
   if (rc) return rc;
   if (!bl_aligned16(X) || !bl_aligned16(W_rows)) return BL_EALIGN;
+  // G and H are read and written one element at a time: natural alignment is all they need
+  if ((reinterpret_cast<uintptr_t>(G) & (g_dtype == BL_F32 ? 3 : 1)) || (reinterpret_cast<uintptr_t>(H) & 1))
+    return BL_EALIGN;
   return bl_launch_up_gated(X, M, K, eps, W_rows, alpha, N, G, g_dtype, H, (hipStream_t)stream);
 }
 
@@ -350,6 +386,7 @@ extern "C" int swish_glu(const void* G, const void* U, bl_dtype in_dtype, int64_
   if (!G || !U || !H || !valid_dtype(in_dtype)) return BL_EINVAL;
   if (M < 1 || N < 1 || M > ((int64_t)1 << 40) / N) return BL_ESHAPE;
   const int64_t n = M * N;
+  if (!elementwise_grid_ok(n)) return BL_ESHAPE;
   const unsigned blocks = (unsigned)((n + 255) / 256);
   if (in_dtype == BL_BF16)
     swish_glu_kernel<uint16_t><<<blocks, 256, 0, (hipStream_t)stream>>>((const uint16_t*)G, (const uint16_t*)U, n, (uint16_t*)H);
@@ -364,6 +401,7 @@ extern "C" int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_
   if (!G || !U || !H || !valid_dtype(in_dtype)) return BL_EINVAL;
   if (M < 1 || N < 1 || M > ((int64_t)1 << 40) / N) return BL_ESHAPE;
   const int64_t n = M * N;
+  if (!elementwise_grid_ok(n)) return BL_ESHAPE;
   const unsigned blocks = (unsigned)((n + 255) / 256);
   if (in_dtype == BL_BF16)
     relu2_glu_kernel<uint16_t><<<blocks, 256, 0, (hipStream_t)stream>>>((const uint16_t*)G, (const uint16_t*)U, n, (uint16_t*)H);

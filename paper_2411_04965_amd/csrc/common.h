@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "../../include/bitlinear.h"
@@ -17,6 +18,28 @@
 
 static inline int64_t bl_round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 static inline bool bl_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+// A one-dimensional grid holds at most 2^31 - 1 workgroups.
+static inline bool bl_grid_ok(int64_t blocks) { return blocks >= 1 && blocks <= (int64_t)0x7FFFFFFF; }
+
+// Compute units of the current device (cached per device; 256 if the query fails).
+int bl_num_cus();
+
+// Raise a kernel's dynamic LDS limit to `BYTES`, once per device and call site (a driver call,
+// kept off the launch path after the first time).  Expands to a statement that returns BL_EHIP
+// from the enclosing function when the driver refuses.
+#define BL_SET_MAX_LDS_ONCE(KERN, BYTES)                                                          \
+  do {                                                                                            \
+    static std::atomic<unsigned long long> bl_done_{0};                                           \
+    int bl_dev_ = 0;                                                                              \
+    if (hipGetDevice(&bl_dev_) != hipSuccess) return BL_EHIP;                                     \
+    const unsigned long long bl_bit_ = 1ull << (bl_dev_ & 63);                                    \
+    if (!(bl_done_.load(std::memory_order_acquire) & bl_bit_)) {                                  \
+      if (hipFuncSetAttribute((const void*)(KERN), hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                              (int)(BYTES)) != hipSuccess)                                        \
+        return BL_EHIP;                                                                           \
+      bl_done_.fetch_or(bl_bit_, std::memory_order_release);                                      \
+    }                                                                                             \
+  } while (0)
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -134,5 +157,3 @@ int bl_launch_gemm_fp4_mx(const void* q, const uint8_t* xscale, int64_t M, int64
                           const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);
 int bl_launch_gemm_fp4(const void* q, const uint8_t* scale, int64_t M, int64_t K, const void* Wp,
                        const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);
-int bl_launch_relu2_glu(const void* G, const void* U, bl_dtype dt, int64_t n, void* H,
-                        hipStream_t s);

@@ -530,25 +530,12 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
 #undef GX_MFMA0
 }
 
-static int gx_num_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  }
-  return cus;
-}
-
 template <int OUT, bool ACC, bool FP4, bool W2>
 static int gx_go(const void* q, const float* scale, const uint8_t* xsc, int M, int KB, const void* Wp,
                  const float* alpha, int N, void* Y, int y_bf16, int32_t* acc_out, int MT, int NTB,
                  hipStream_t s) {
-  if (hipFuncSetAttribute((const void*)gemm_a4_mx_kernel<OUT, ACC, FP4, W2>,
-                          hipFuncAttributeMaxDynamicSharedMemorySize, GX_LDS) != hipSuccess)
-    return BL_EHIP;
-  const int grid = min(MT * NTB, gx_num_cus());      // persistent blocks, one per CU (all of its LDS)
+  BL_SET_MAX_LDS_ONCE((gemm_a4_mx_kernel<OUT, ACC, FP4, W2>), GX_LDS);
+  const int grid = min(MT * NTB, bl_num_cus());      // persistent blocks, one per CU (all of its LDS)
   gemm_a4_mx_kernel<OUT, ACC, FP4, W2><<<(unsigned)grid, GX_THREADS, GX_LDS, s>>>(
       (const unsigned char*)q, scale, (const unsigned char*)xsc, M, KB, (const unsigned char*)Wp, alpha, N, Y,
       y_bf16, acc_out, MT, NTB);

@@ -638,6 +638,7 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_rows_kernel(
 #define GR_WAVES 16
 #define GR_G 3
 #define GR_X_BYTES 131072                        // LDS for the codes (pitch = row bytes + 16)
+#define GR_LDS_MAX (160 * 1024)                  // the LDS of a compute unit
 template <int MT, bool A4>
 __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
@@ -837,16 +838,6 @@ __global__ __launch_bounds__(GD_THREADS) void decode_reduce_kernel(
 // chip: one 16-output tile per block, no split of K, one launch.  Up to 16 tokens and few outputs:
 // 64 outputs per block and K split until the grid is large.  More tokens: codes resident in LDS.
 static bool gd_single_tile(int M, int N) { return M <= 16 && (N + 15) / 16 >= 128; }
-static int gd_num_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  }
-  return cus;
-}
 // resident kernel: tiles of K per slice so that 16 * MT rows of codes fit
 static int gr_slice_tiles(int MT, bool a4) { return GR_X_BYTES / (MT * 16) / (a4 ? 128 : 256); }
 static int gd_pick_split(int M, int N, int KT, bool a4) {
@@ -912,8 +903,10 @@ static int gr_run(const void* q, const float* scale, int M, int Kp, const void* 
   const int L = (KT + S - 1) / S;                        // tiles of the longest slice
   // output tiles per block: as few as still give at most one block per CU (one block takes most
   // of a CU's LDS), at most one per wave
+  // (64 tokens: at most 12, so that the partial tiles and the sums fit the LDS together)
+  const int nwt_max = MT == 4 ? 12 : GR_WAVES;
   int NWT = 1;
-  while (NWT < GR_WAVES && ((NT16 + NWT - 1) / NWT) * S > gd_num_cus()) ++NWT;
+  while (NWT < nwt_max && ((NT16 + NWT - 1) / NWT) * S > bl_num_cus()) ++NWT;
   const int NBn = (NT16 + NWT - 1) / NWT;
   const int NG = (NWT + GR_G - 1) / GR_G;                // groups of output tiles, one per wave
   // parts of the slice per group: every part gets at least one tile; at most 8 working waves (two
@@ -922,8 +915,10 @@ static int gr_run(const void* q, const float* scale, int M, int Kp, const void* 
   const size_t smem = max((size_t)MT * 16 * ((size_t)L * (A4 ? 128 : 256) + 16),
                           (size_t)NG * KS * GR_G * MT * 1024 + (size_t)MT * 16 * (NWT * 16 + 4) * sizeof(int32_t));
   auto kern = gemm_decode_resident_kernel<MT, A4>;
-  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-    return BL_EHIP;
+  // (the limit is raised once, to the most a launch can ask for: the codes' space plus row padding, or
+  // eight waves' partial tiles plus the block's sums)
+  BL_SET_MAX_LDS_ONCE((gemm_decode_resident_kernel<MT, A4>), GR_LDS_MAX);
+  if (smem > GR_LDS_MAX) return BL_ESHAPE;
   const int ybf = ydt == BL_BF16 ? 1 : 0;
   kern<<<(unsigned)(NBn * S), GR_THREADS, smem, s>>>((const unsigned char*)q, scale, M, Kp,
                                                      (const unsigned char*)Wp, alpha, N, Y, ybf,
@@ -962,7 +957,7 @@ int bl_launch_up_gated(const void* X, int64_t M, int64_t K, float eps, const voi
   const int nch = (Kp + 4095) / 4096;            // 1 KB chunks of a weight row: 1 or 2
   const int mv = M <= 1 ? 1 : M <= 2 ? 2 : 4;
   // outputs per block: about two blocks per CU, at most one output per thread
-  int npb = (int)((N + 2 * gd_num_cus() - 1) / (2 * gd_num_cus()));
+  int npb = (int)((N + 2 * bl_num_cus() - 1) / (2 * bl_num_cus()));
   npb = max(16, min(GD_THREADS, npb));
   const unsigned grid = (unsigned)((N + npb - 1) / npb);
   const size_t smem = (size_t)M * Kp;

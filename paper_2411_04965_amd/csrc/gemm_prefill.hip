@@ -534,42 +534,31 @@ __global__ __launch_bounds__(GP_THREADS, 1) void gemm_prefill_kernel(
 #undef GP_MFMA
 }
 
-static int gp_num_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  }
-  return cus;
+template <int BM, int BN, bool A4, int OUT, bool ACC>
+static int gp_go(const void* q, const float* scale, int M, int Kp, const void* Wp, const float* alpha, int N,
+                 void* Y, int y_bf16, int32_t* acc_out, int MT, int NTB, hipStream_t s) {
+  constexpr int smem = GpSmem<BM, BN>::total;
+  BL_SET_MAX_LDS_ONCE((gemm_prefill_kernel<BM, BN, A4, OUT, ACC>), smem);
+  // persistent blocks: one per CU for the large tile (128 KB of LDS, 512 registers per lane)
+  const int per_cu = (BM == 256) ? 1 : 2;
+  const int grid = min(MT * NTB, bl_num_cus() * per_cu);
+  gemm_prefill_kernel<BM, BN, A4, OUT, ACC><<<(unsigned)grid, GP_THREADS, smem, s>>>(
+      (const unsigned char*)q, scale, M, Kp, (const unsigned char*)Wp, alpha, N, Y, y_bf16, acc_out, MT, NTB);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
 }
 
 template <int BM, int BN, bool A4>
 static int gp_launch(const void* q, const float* scale, int M, int Kp, const void* Wp,
                      const float* alpha, int N, void* Y, bl_dtype ydt, int32_t* acc_out,
                      hipStream_t s) {
-  constexpr int smem = GpSmem<BM, BN>::total;
   const int MT = (M + BM - 1) / BM, NTB = (N + BN - 1) / BN;
   const int out = (ydt == BL_BF16 && (N & 7) == 0) ? 0 : ((N & 3) == 0 ? 1 : 2);
-  void (*kern)(const unsigned char*, const float*, int, int, const unsigned char*, const float*, int,
-               void*, int, int32_t*, int, int);
-  if (acc_out)
-    kern = out == 0 ? gemm_prefill_kernel<BM, BN, A4, 0, true>
-         : out == 1 ? gemm_prefill_kernel<BM, BN, A4, 1, true> : gemm_prefill_kernel<BM, BN, A4, 2, true>;
-  else
-    kern = out == 0 ? gemm_prefill_kernel<BM, BN, A4, 0, false>
-         : out == 1 ? gemm_prefill_kernel<BM, BN, A4, 1, false> : gemm_prefill_kernel<BM, BN, A4, 2, false>;
-  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-    return BL_EHIP;
-  // persistent blocks: one per CU for the large tile (128 KB of LDS, 512 registers per lane)
-  const int per_cu = (BM == 256) ? 1 : 2;
-  const int grid = min(MT * NTB, gp_num_cus() * per_cu);
-  kern<<<(unsigned)grid, GP_THREADS, smem, s>>>(
-      (const unsigned char*)q, scale, M, Kp, (const unsigned char*)Wp, alpha, N, Y,
-      ydt == BL_BF16 ? 1 : 0, acc_out, MT, NTB);
-  BL_HIP_CHECK_LAUNCH();
-  return BL_OK;
+  const int yb = ydt == BL_BF16 ? 1 : 0;
+#define GP_CALL(OUT, ACC) gp_go<BM, BN, A4, OUT, ACC>(q, scale, M, Kp, Wp, alpha, N, Y, yb, acc_out, MT, NTB, s)
+  if (acc_out) return out == 0 ? GP_CALL(0, true) : out == 1 ? GP_CALL(1, true) : GP_CALL(2, true);
+  return out == 0 ? GP_CALL(0, false) : out == 1 ? GP_CALL(1, false) : GP_CALL(2, false);
+#undef GP_CALL
 }
 
 int bl_launch_gemm_prefill(const void* q, const float* scale, bl_act_mode mode, int64_t M,

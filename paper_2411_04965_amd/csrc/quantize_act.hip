@@ -822,23 +822,23 @@ static int qa_run_row_kernels(const RawT* X, int64_t M, int K, int Kp, bl_act_mo
   if (mode == BL_ACT_INT4_ABSMEAN || mode == BL_ACT_INT4_ABSMEAN_MX6 || mode == BL_ACT_INT4_ABSMEAN2 ||
       mode == BL_ACT_INT4_ABSMAX) {
     const int stat = mode == BL_ACT_INT4_ABSMEAN2 ? 1 : mode == BL_ACT_INT4_ABSMAX ? 2 : 0;
-    auto kern = mode == BL_ACT_INT4_ABSMEAN_MX6 ? quant_int4_kernel<RawT, VEC, true> : quant_int4_kernel<RawT, VEC, false>;
-    if (smem > 48 * 1024 &&
-        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-      return BL_EHIP;
-    kern<<<(unsigned)M, QA_THREADS, smem, s>>>(X, K, Kp, eps, (u32*)q, (float*)scale, rowsum, stat);
+    // (the limit is raised once, to the widest row the library accepts)
+    constexpr int max_smem = BL_MAX_K * (int)sizeof(RawT);
+    if (mode == BL_ACT_INT4_ABSMEAN_MX6) {
+      BL_SET_MAX_LDS_ONCE((quant_int4_kernel<RawT, VEC, true>), max_smem);
+      quant_int4_kernel<RawT, VEC, true><<<(unsigned)M, QA_THREADS, smem, s>>>(X, K, Kp, eps, (u32*)q, (float*)scale, rowsum, stat);
+    } else {
+      BL_SET_MAX_LDS_ONCE((quant_int4_kernel<RawT, VEC, false>), max_smem);
+      quant_int4_kernel<RawT, VEC, false><<<(unsigned)M, QA_THREADS, smem, s>>>(X, K, Kp, eps, (u32*)q, (float*)scale, rowsum, stat);
+    }
   } else if (M <= 64) {
-    auto kern = quant_topk_int8_kernel<RawT, VEC, 1024>;
-    if (smem > 48 * 1024 &&
-        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-      return BL_EHIP;
-    kern<<<(unsigned)M, 1024, smem, s>>>(X, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum, sel);
+    constexpr int max_smem = BL_MAX_K * (int)sizeof(RawT);
+    BL_SET_MAX_LDS_ONCE((quant_topk_int8_kernel<RawT, VEC, 1024>), max_smem);
+    quant_topk_int8_kernel<RawT, VEC, 1024><<<(unsigned)M, 1024, smem, s>>>(X, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum, sel);
   } else {
-    auto kern = quant_topk_int8_kernel<RawT, VEC, QA_THREADS>;
-    if (smem > 48 * 1024 &&
-        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-      return BL_EHIP;
-    kern<<<(unsigned)M, QA_THREADS, smem, s>>>(X, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum, sel);
+    constexpr int max_smem = BL_MAX_K * (int)sizeof(RawT);
+    BL_SET_MAX_LDS_ONCE((quant_topk_int8_kernel<RawT, VEC, QA_THREADS>), max_smem);
+    quant_topk_int8_kernel<RawT, VEC, QA_THREADS><<<(unsigned)M, QA_THREADS, smem, s>>>(X, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum, sel);
   }
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;

@@ -63,15 +63,18 @@ def heavy(M: int, K: int, seed: int, frac: float = 0.005, scale: float = 10.0) -
     return snap_bf16(x)
 
 
-def glu_like(M: int, K: int, seed: int) -> np.ndarray:
-    """bf16-valued stand-in for a down-projection input: u * relu(g)^2.
+def glu_like(M: int, K: int, seed: int, keep: float = 0.45) -> np.ndarray:
+    """bf16-valued stand-in for a down-projection input, drawn directly (no gating arithmetic).
 
-    At least half of the entries are exact zeros and the rest is heavy tailed,
-    like the output of a squared-ReLU gated unit."""
-    u = heavy(M, K, seed)
-    g = heavy(M, K, seed + 500)
-    r = np.maximum(g, np.float32(0))
-    return snap_bf16(u * (r * r))
+    Each entry is zero with probability 1 - keep (more than half of a row in expectation),
+    otherwise a `heavy` value times an independent chi-square(1) magnitude: sharply peaked
+    at zero with a long tail and a few outlier channels, like the state behind a gated
+    unit."""
+    x = heavy(M, K, seed)
+    rng = np.random.default_rng(seed + 500)
+    mag = rng.gamma(0.5, 2.0, size=(M, K)).astype(np.float32)
+    mask = rng.random((M, K)) < keep
+    return snap_bf16(np.where(mask, x * mag, np.float32(0)).astype(np.float32))
 
 
 def latent_weights(N: int, K: int, seed: int, std: float = 0.02) -> np.ndarray:
