@@ -421,9 +421,10 @@ def decode_bench(B, S, torch, dev, tokens=(1, 8, 32, 64), replays=5):
 
     Weights: DECODE_LAYERS distinct layers (five projections each, 1.6 GB in all), drawn on the
     device from a seeded generator and packed once.  Per token count:
-      * `layer_sweep`: one HIP graph walks all five projections of all layers in model order, so
-        every weight byte read is one of 1.6 GB read since its last use (the memory-side cache
-        holds 256 MB);
+      * `layer_sweep`: one HIP graph walks the projections of all layers in model order (qkv, o, the
+        gate and up projection with their GLU behind one entry point, down), so every weight byte
+        read is one of 1.6 GB read since its last use (the memory-side cache holds 256 MB);
+        `layer_sweep_five_calls` is the same walk with gate and up as two calls;
       * per projection: a graph over enough distinct weight sets of that one shape that a replay
         touches at least DECODE_MIN_SET_BYTES (the o projection gets extra sets for that);
       * for the two top-K + INT8 projections at 1 and 8 tokens also the row-skipping path
@@ -493,13 +494,39 @@ def decode_bench(B, S, torch, dev, tokens=(1, 8, 32, 64), replays=5):
                     "frac_hbm_peak": round(need / us_k / 1e3 / HBM_PEAK_GBS, 4),
                     "dense_equivalent_gbs": round(wbytes / us_k / 1e3, 1)}
 
+        # gate and up projection behind one entry point (one quantized input; one launch for up to 8
+        # tokens), writing H = bf16(U * max(G, 0)^2) only
+        Hbuf = {"H": torch.empty((M, FFN), dtype=bf16, device=dev)}
+        ws_gu = torch.empty(max(B.lib().bitlinear_gate_up_workspace_bytes(M, FFN, HIDDEN, B.BL_W_GEMM), 16),
+                            dtype=torch.uint8, device=dev)
+
+        def gate_up(l):
+            (pg, ag), (pu, au) = packed["gate"][l], packed["up"][l]
+            B.bitlinear_a4_gate_up(X["gate"], pg, ag, pu, au, FFN, EPS, want=("H",), ws=ws_gu, out=Hbuf)
+        n = len(packed["gate"])
+        us = _graph_time_us(torch, gate_up, n, replays, side)
+        wbytes = 2 * FFN * HIDDEN / 4
+        row["gate_up_glu"] = {"us": round(us, 2), "weight_gbs": round(wbytes / us / 1e3, 1),
+                              "frac_hbm_peak": round(wbytes / us / 1e3 / HBM_PEAK_GBS, 4), "weight_sets": n}
+
+        lbytes = sum(N * K / 4 for _, N, K, _ in projs)
+
         def layer(i):
             for name, N, K, kind in projs:
                 run(name, N, K, kind, i)
         us_layer = _graph_time_us(torch, layer, DECODE_LAYERS, replays, side)
-        lbytes = sum(N * K / 4 for _, N, K, _ in projs)
+        row["layer_sweep_five_calls"] = {"us_per_layer": round(us_layer, 2), "weight_gbs": round(lbytes / us_layer / 1e3, 1),
+                                         "frac_hbm_peak": round(lbytes / us_layer / 1e3 / HBM_PEAK_GBS, 4)}
+
+        def layer_fused(i):
+            run("qkv", 3 * HIDDEN, HIDDEN, "a4", i)
+            run("o", HIDDEN, HIDDEN, "a8s", i)
+            gate_up(i)
+            run("down", HIDDEN, FFN, "a8s", i)
+        us_layer = _graph_time_us(torch, layer_fused, DECODE_LAYERS, replays, side)
         row["layer_sweep"] = {"us_per_layer": round(us_layer, 2), "weight_gbs": round(lbytes / us_layer / 1e3, 1),
-                              "frac_hbm_peak": round(lbytes / us_layer / 1e3 / HBM_PEAK_GBS, 4)}
+                              "frac_hbm_peak": round(lbytes / us_layer / 1e3 / HBM_PEAK_GBS, 4),
+                              "calls": "qkv, o, gate+up+GLU, down"}
         if M <= 8:
             def layer_k(i):
                 for name, N, K, kind in projs:

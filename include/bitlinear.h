@@ -204,8 +204,9 @@ int quantize_act(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, bl_act_m
  *   workspace  device, >= bitlinear_workspace_bytes(mode, M, N, K) bytes; holds the
  *              packed activations and their scales between the two kernels
  * Kernel choice (BL_W_GEMM) is by M: up to BL_DECODE_MAX_M tokens the weights are streamed once
- * by a skinny (decode) kernel, with the quantizer inside the same launch for one token; above
- * that the tiled MFMA GEMM runs.  The block-float forms always take the tiled GEMM.
+ * by a skinny (decode) kernel, with the quantizer inside the same launch for up to 8 bfloat16
+ * tokens (INT4) or one (Top_k + INT8); above that the tiled MFMA GEMM runs.  The block-float forms
+ * always take the tiled GEMM.
  *
  * bitlinear_a8_sparse (eq. 1): Y = (Q_INT8(X) (.) Top_k(|X|)) . Q_w(W)^T, same
  * accumulation and rescale.  With layout BL_W_KMAJOR (decode, M <= BL_SPARSE_MAX_M; more tokens:
@@ -234,6 +235,26 @@ int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M
                    const void* W_packed, bl_w_layout layout, const float* alpha, int64_t N,
                    void* Y, bl_dtype y_dtype, int32_t* acc_out,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Gate and up projection of an FFN block on ONE quantized input, and their ReLU^2 GLU combine
+ * (eq. 5 with eq. 6 and eq. 7): the token is quantized once (INT4 absmean),
+ *     G = Q(X) . Q_w(W_gate)^T,  U = Q(X) . Q_w(W_up)^T   (accumulate and rescale as bitlinear_a4),
+ *     H = bf16(U * max(G, 0)^2)  from the float32 G and U, float32 steps in that order, one rounding.
+ * Any of G, U, H may be NULL (not all three): only the others are written.  G and U are the same
+ * numbers bitlinear_a4 returns for each matrix, H the same as relu2_glu of their float32 forms.
+ *   X          device, [M, K] of x_dtype
+ *   W_gate, W_up  device, outputs of pack_ternary for [N, K] in `layout` (BL_W_GEMM, BL_W_MX4 or BL_W_MX2)
+ *   G, U       device, [M, N] of gu_dtype, nullable;   H  device, [M, N] bfloat16, nullable
+ *   workspace  device, >= bitlinear_gate_up_workspace_bytes(M, N, K, layout) bytes (packed activations,
+ *              scales, decode partial sums, and float32 G and U where H is wanted without them)
+ * Up to 8 bfloat16 tokens with BL_W_GEMM weights (K % 8 == 0, K <= 8192) run as one launch that
+ * streams both matrices once and uses no workspace (it may then be NULL); other shapes run the
+ * quantizer, the two products and the combine as separate kernels. */
+size_t bitlinear_gate_up_workspace_bytes(int64_t M, int64_t N, int64_t K, bl_w_layout layout);
+int bitlinear_a4_gate_up(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, const void* W_gate,
+                         const float* alpha_gate, const void* W_up, const float* alpha_up,
+                         bl_w_layout layout, int64_t N, float eps, void* G, void* U, bl_dtype gu_dtype,
+                         void* H, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Gate-first up projection of the FFN for a few tokens (Section 2.1's observation that the up
  * projection is only needed where the gate is open, eq. 5): with G = the gate projection's

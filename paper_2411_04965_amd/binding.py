@@ -45,6 +45,9 @@ _SIGNATURES = {
     "quantize_heads_bytes": (_sz, [_int, _i64, _i64, _i64]),
     "quantize_heads": (_int, [_vp, _int, _i64, _i64, _i64, _int, _f32, _vp, _vp, _vp]),
     "quantize_act_glu": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
+    "bitlinear_gate_up_workspace_bytes": (_sz, [_i64, _i64, _i64, _int]),
+    "bitlinear_a4_gate_up": (_int, [_vp, _int, _i64, _i64, _vp, _vp, _vp, _vp, _int, _i64, _f32, _vp, _vp, _int,
+                                    _vp, _vp, _sz, _vp]),
     "bitlinear_a4_up_gated": (_int, [_vp, _i64, _i64, _vp, _vp, _i64, _f32, _vp, _int, _vp, _vp]),
     "unpack_ternary": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
     "unpack_act": (_int, [_vp, _int, _i64, _i64, _vp, _vp]),
@@ -222,6 +225,27 @@ def quantize_act_glu(G, U, topk, eps=DEFAULT_EPS, want_rowsum=False):
     _check("quantize_act_glu", L.quantize_act_glu(_ptr(G), _ptr(U), _dt(G), M, K, topk, eps, _ptr(q),
                                                   _ptr(scale), _ptr(rowsum), _stream()))
     return dict(q=q, scale=scale, rowsum=rowsum)
+
+
+def bitlinear_a4_gate_up(X, W_gate, alpha_gate, W_up, alpha_up, N, eps=DEFAULT_EPS, layout=BL_W_GEMM,
+                         want=("G", "U", "H"), gu_dtype=torch.float32, ws=None, out=None):
+    """Gate and up projection on one quantized input.  Returns a dict with the tensors named in
+    `want` (G, U of gu_dtype; H = bf16(U * max(G, 0)^2)); `out` may bring preallocated ones."""
+    _dev(X)
+    M, K = X.shape
+    out = dict(out or {})
+    for k in want:
+        if k not in out:
+            out[k] = torch.empty((M, N), dtype=torch.bfloat16 if k == "H" else gu_dtype, device=X.device)
+    if ws is None:
+        ws = torch.empty(max(lib().bitlinear_gate_up_workspace_bytes(M, N, K, layout), 16), dtype=torch.uint8,
+                         device=X.device)
+    G, U, H = out.get("G"), out.get("U"), out.get("H")
+    gdt = _dt(G) if G is not None else (_dt(U) if U is not None else BL_F32)
+    _check("bitlinear_a4_gate_up", lib().bitlinear_a4_gate_up(
+        _ptr(X), _dt(X), M, K, _ptr(W_gate), _ptr(alpha_gate), _ptr(W_up), _ptr(alpha_up), layout, N, eps,
+        _ptr(G), _ptr(U), gdt, _ptr(H), _ptr(ws), ws.numel(), _stream()))
+    return out
 
 
 def bitlinear_a4_up_gated(X, W_rows, alpha, N, G, eps=DEFAULT_EPS):

@@ -183,6 +183,46 @@ extern "C" int quantize_heads(const void* X, bl_dtype x_dtype, int64_t T, int64_
   return bl_launch_quantize_heads(X, x_dtype, T * H, D, bits, eps, q_out, scale_out, (hipStream_t)stream);
 }
 
+// ---------------------------------------------------------------- ReLU^2 GLU (eq. 5)
+template <typename RawT>
+__global__ __launch_bounds__(256) void relu2_glu_kernel(const RawT* __restrict__ G,
+                                                        const RawT* __restrict__ U, int64_t n,
+                                                        uint16_t* __restrict__ H) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float g, u;
+  if (sizeof(RawT) == 2) {
+    g = bl_bf16_to_f32((uint16_t)G[i]);
+    u = bl_bf16_to_f32((uint16_t)U[i]);
+  } else {
+    g = __uint_as_float((u32)G[i]);
+    u = __uint_as_float((u32)U[i]);
+  }
+  const float r = fmaxf(g, 0.0f);
+  const float rr = r * r;
+  H[i] = bl_f32_to_bf16_rne(u * rr);
+}
+
+// Swish GLU (Section 4.3): h = u * (g * sigmoid(g)), float32 steps, one bfloat16 rounding
+template <typename RawT>
+__global__ __launch_bounds__(256) void swish_glu_kernel(const RawT* __restrict__ G,
+                                                        const RawT* __restrict__ U, int64_t n,
+                                                        uint16_t* __restrict__ H) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float g, u;
+  if (sizeof(RawT) == 2) {
+    g = bl_bf16_to_f32((uint16_t)G[i]);
+    u = bl_bf16_to_f32((uint16_t)U[i]);
+  } else {
+    g = __uint_as_float((u32)G[i]);
+    u = __uint_as_float((u32)U[i]);
+  }
+  const float sg = 1.0f / (1.0f + expf(-g));               // expf(-g) = inf for g < -88.7: sg = 0, h = -0
+  const float sw = g * sg;
+  H[i] = bl_f32_to_bf16_rne(u * sw);
+}
+
 // ---------------------------------------------------------------- linear layers
 // Workspace layout: [codes | scales | stage-2 scratch], each part 256-byte aligned.
 static size_t stage2_ws_bytes(bl_act_mode mode, int64_t M, int64_t N, int64_t K) {
@@ -281,9 +321,9 @@ static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, 
 
   // a few tokens: quantizer and product in one launch
   if (mode == BL_ACT_INT4_ABSMEAN && layout == BL_W_GEMM && x_dtype == BL_BF16 &&
-      bl_gemv_a4_fused_ok(M, N, K))
-    return bl_launch_gemv_a4_fused(X, M, K, eps, W_packed, alpha, N, Y, y_dtype, acc_out,
-                                   (hipStream_t)stream);
+      bl_gemv_stream_ok(M, N, K, true))
+    return bl_launch_gemv_stream_a4(X, M, K, eps, W_packed, alpha, N, Y, y_dtype, acc_out,
+                                    (hipStream_t)stream);
 
   if (mode == BL_ACT_TOPK_INT8_ABSMAX && layout == BL_W_GEMM && x_dtype == BL_BF16 &&
       bl_gemv_a8_fused_ok(M, N, K))
@@ -327,6 +367,74 @@ extern "C" int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, i
                        N, eps, Y, y_dtype, acc_out, workspace, workspace_bytes, stream);
 }
 
+// ---------------------------------------------------------------- gate and up projection on one quantized input
+extern "C" size_t bitlinear_gate_up_workspace_bytes(int64_t M, int64_t N, int64_t K, bl_w_layout layout) {
+  if (M < 1 || N < 1 || K < 1) return 0;
+  const bl_act_mode mode = mx_layout(layout) ? BL_ACT_INT4_ABSMEAN_MX6 : BL_ACT_INT4_ABSMEAN;
+  return bitlinear_workspace_bytes(mode, M, N, K) + 2 * ws_align((size_t)M * N * sizeof(float));
+}
+
+extern "C" int bitlinear_a4_gate_up(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, const void* W_gate,
+                                    const float* alpha_gate, const void* W_up, const float* alpha_up,
+                                    bl_w_layout layout, int64_t N, float eps, void* G, void* U, bl_dtype gu_dtype,
+                                    void* H, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!X || !W_gate || !alpha_gate || !W_up || !alpha_up || (!G && !U && !H)) return BL_EINVAL;
+  if (!valid_dtype(x_dtype) || !valid_dtype(gu_dtype) || !valid_layout(layout) || !(eps >= 0.0f)) return BL_EINVAL;
+  if (layout != BL_W_GEMM && !mx_layout(layout)) return BL_EUNSUPPORTED;
+  int rc = check_sizes(M, N, K);
+  if (rc) return rc;
+  if (!bl_aligned16(X) || !bl_aligned16(W_gate) || !bl_aligned16(W_up) || (G && !bl_aligned16(G)) ||
+      (U && !bl_aligned16(U)) || (H && !bl_aligned16(H)))
+    return BL_EALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  // a few tokens: quantizer, both products and the combine in one launch, no workspace
+  if (layout == BL_W_GEMM && x_dtype == BL_BF16 && bl_gemv_stream_pair_ok(M, N, K, H != nullptr))
+    return bl_launch_gemv_stream_gate_up(X, M, K, eps, W_gate, alpha_gate, W_up, alpha_up, N, G, U, gu_dtype, H, s);
+
+  // composed: quantize once, two products, then the combine on float32 G and U
+  const bl_act_mode mode = mx_layout(layout) ? BL_ACT_INT4_ABSMEAN_MX6 : BL_ACT_INT4_ABSMEAN;
+  const size_t base = bitlinear_workspace_bytes(mode, M, N, K);
+  if (!workspace || workspace_bytes < base) return BL_EWORKSPACE;
+  if (!bl_aligned16(workspace)) return BL_EALIGN;
+  if (H && !elementwise_grid_ok(M * N)) return BL_ESHAPE;
+  unsigned char* p = (unsigned char*)workspace;
+  void* codes = p;
+  p += ws_align(quantize_act_bytes(mode, M, K));
+  void* scales = p;
+  p += ws_align(act_scale_bytes(mode, M, K));
+  void* ws2 = p;
+  const size_t ws2_bytes = ws_align(stage2_ws_bytes(mode, M, N, K));
+  p += ws2_bytes;
+  // when H is wanted the products are kept in float32 (eq. 5 combines them before any rounding)
+  const bool need_f32 = H != nullptr && gu_dtype != BL_F32;
+  void* Gt = G;
+  void* Ut = U;
+  bl_dtype tdt = gu_dtype;
+  if (H && (!G || need_f32)) { Gt = p; p += ws_align((size_t)M * N * sizeof(float)); tdt = BL_F32; }
+  if (H && (!U || need_f32)) { Ut = p; p += ws_align((size_t)M * N * sizeof(float)); tdt = BL_F32; }
+  if ((size_t)(p - (unsigned char*)workspace) > workspace_bytes) return BL_EWORKSPACE;
+  rc = bl_launch_quantize(X, x_dtype, M, K, mode, 0, eps, codes, scales, nullptr, nullptr, s);
+  if (rc) return rc;
+  if (H && need_f32) {
+    // float32 copies for the combine, and the caller's own G / U in its dtype
+    rc = gemm_dispatch(codes, scales, mode, M, K, W_gate, layout, alpha_gate, N, Gt, BL_F32, nullptr, ws2, ws2_bytes, s);
+    if (rc) return rc;
+    rc = gemm_dispatch(codes, scales, mode, M, K, W_up, layout, alpha_up, N, Ut, BL_F32, nullptr, ws2, ws2_bytes, s);
+    if (rc) return rc;
+    if (G) { rc = gemm_dispatch(codes, scales, mode, M, K, W_gate, layout, alpha_gate, N, G, gu_dtype, nullptr, ws2, ws2_bytes, s); if (rc) return rc; }
+    if (U) { rc = gemm_dispatch(codes, scales, mode, M, K, W_up, layout, alpha_up, N, U, gu_dtype, nullptr, ws2, ws2_bytes, s); if (rc) return rc; }
+  } else {
+    if (Gt) { rc = gemm_dispatch(codes, scales, mode, M, K, W_gate, layout, alpha_gate, N, Gt, tdt, nullptr, ws2, ws2_bytes, s); if (rc) return rc; }
+    if (Ut) { rc = gemm_dispatch(codes, scales, mode, M, K, W_up, layout, alpha_up, N, Ut, tdt, nullptr, ws2, ws2_bytes, s); if (rc) return rc; }
+  }
+  if (H) {
+    const int64_t n = M * N;
+    relu2_glu_kernel<u32><<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const u32*)Gt, (const u32*)Ut, n, (uint16_t*)H);
+    BL_HIP_CHECK_LAUNCH();
+  }
+  return BL_OK;
+}
+
 extern "C" int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const void* W_rows,
                                      const float* alpha, int64_t N, float eps, const void* G,
                                      bl_dtype g_dtype, void* H, void* stream) {
@@ -339,46 +447,6 @@ extern "C" int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const 
   if ((reinterpret_cast<uintptr_t>(G) & (g_dtype == BL_F32 ? 3 : 1)) || (reinterpret_cast<uintptr_t>(H) & 1))
     return BL_EALIGN;
   return bl_launch_up_gated(X, M, K, eps, W_rows, alpha, N, G, g_dtype, H, (hipStream_t)stream);
-}
-
-// ---------------------------------------------------------------- ReLU^2 GLU (eq. 5)
-template <typename RawT>
-__global__ __launch_bounds__(256) void relu2_glu_kernel(const RawT* __restrict__ G,
-                                                        const RawT* __restrict__ U, int64_t n,
-                                                        uint16_t* __restrict__ H) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  float g, u;
-  if (sizeof(RawT) == 2) {
-    g = bl_bf16_to_f32((uint16_t)G[i]);
-    u = bl_bf16_to_f32((uint16_t)U[i]);
-  } else {
-    g = __uint_as_float((u32)G[i]);
-    u = __uint_as_float((u32)U[i]);
-  }
-  const float r = fmaxf(g, 0.0f);
-  const float rr = r * r;
-  H[i] = bl_f32_to_bf16_rne(u * rr);
-}
-
-// Swish GLU (Section 4.3): h = u * (g * sigmoid(g)), float32 steps, one bfloat16 rounding
-template <typename RawT>
-__global__ __launch_bounds__(256) void swish_glu_kernel(const RawT* __restrict__ G,
-                                                        const RawT* __restrict__ U, int64_t n,
-                                                        uint16_t* __restrict__ H) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  float g, u;
-  if (sizeof(RawT) == 2) {
-    g = bl_bf16_to_f32((uint16_t)G[i]);
-    u = bl_bf16_to_f32((uint16_t)U[i]);
-  } else {
-    g = __uint_as_float((u32)G[i]);
-    u = __uint_as_float((u32)U[i]);
-  }
-  const float sg = 1.0f / (1.0f + expf(-g));               // expf(-g) = inf for g < -88.7: sg = 0, h = -0
-  const float sw = g * sg;
-  H[i] = bl_f32_to_bf16_rne(u * sw);
 }
 
 extern "C" int swish_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,

@@ -146,6 +146,16 @@ int bl_launch_gemv_a8_fused(const void* X, int64_t K, int64_t topk, float eps, c
 int bl_launch_gemv_a4_fused(const void* X, int64_t M, int64_t K, float eps, const void* Wp,
                             const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,
                             hipStream_t s);
+// one persistent launch for up to 16 tokens (gemv_stream.hip)
+bool bl_gemv_stream_ok(int64_t M, int64_t N, int64_t K, bool quant_inside);
+bool bl_gemv_stream_pair_ok(int64_t M, int64_t N, int64_t K, bool glu);
+int bl_launch_gemv_stream(const void* q, const float* scale, bool a4, int64_t M, int64_t K, const void* Wp,
+                          const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out, hipStream_t s);
+int bl_launch_gemv_stream_a4(const void* X, int64_t M, int64_t K, float eps, const void* Wp, const float* alpha,
+                             int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out, hipStream_t s);
+int bl_launch_gemv_stream_gate_up(const void* X, int64_t M, int64_t K, float eps, const void* Wg, const float* ag,
+                                  const void* Wu, const float* au, int64_t N, void* G, void* U, bl_dtype ydt,
+                                  void* H, hipStream_t s);
 int bl_launch_gemv_sparse(const void* q, const float* scale, int64_t M, int64_t K,
                           const void* Wk, const float* alpha, int64_t N, void* Y, bl_dtype ydt,
                           int32_t* acc_out, void* ws, hipStream_t s);

@@ -1008,6 +1008,9 @@ int bl_launch_gemm_decode(const void* q, const float* scale, bl_act_mode mode, i
                           bl_dtype ydt, int32_t* acc_out, void* ws, hipStream_t s) {
   const int Kp = (int)bl_round_up(K, BL_KPAD);
   const bool a4 = mode == BL_ACT_INT4_ABSMEAN;
+  // up to 16 tokens whose codes fit the LDS: the persistent one-launch kernel
+  if (bl_gemv_stream_ok(M, N, K, false))
+    return bl_launch_gemv_stream(q, scale, a4, M, K, Wp, alpha, N, Y, ydt, acc_out, s);
 #define GD_ARGS q, scale, (int)M, Kp, Wp, alpha, (int)N, Y, ydt, acc_out, ws, s
   if (gd_single_tile((int)M, (int)N)) return a4 ? gd_run<1, true, true>(GD_ARGS) : gd_run<1, false, true>(GD_ARGS);
   if (M <= 16) return a4 ? gd_run<1, true, false>(GD_ARGS) : gd_run<1, false, false>(GD_ARGS);
