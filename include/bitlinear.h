@@ -120,7 +120,8 @@ typedef enum {
   BL_EALIGN = -3,       /* a pointer is not 16-byte aligned */
   BL_EWORKSPACE = -4,   /* workspace missing or too small */
   BL_EHIP = -5,         /* a HIP call failed (launch error) */
-  BL_EUNSUPPORTED = -6  /* valid request that this build does not implement */
+  BL_EUNSUPPORTED = -6, /* valid request that this build does not implement */
+  BL_ESCRATCH = -7      /* bitlinear_a8_sparse_static: the request needs more than BL_STATIC_SCRATCH_BYTES */
 } bl_status;
 
 /* Largest sizes accepted: M, N, K >= 1, K <= BL_MAX_K, M*N and N*K below 2^40. */
@@ -224,6 +225,23 @@ int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, i
                         const void* W_packed, bl_w_layout layout, const float* alpha,
                         int64_t N, float eps, void* Y, bl_dtype y_dtype, int32_t* acc_out,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* bitlinear_a8_sparse for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as bitlinear_a8_sparse, without `workspace`: the packed activations, their scales and
+ * the integer partial sums of the decode kernels live in a buffer of BL_STATIC_SCRATCH_BYTES inside the
+ * library's device image (one per GPU, held until the process ends).  The call allocates and frees
+ * nothing and calls no allocating routine.
+ *   Limits: M <= BL_DECODE_MAX_M and bitlinear_workspace_bytes(BL_ACT_TOPK_INT8_ABSMAX, M, N, K) <=
+ *           BL_STATIC_SCRATCH_BYTES, otherwise BL_ESCRATCH (nothing enqueued).
+ *   Every call on a GPU uses that GPU's one buffer, which keeps the last call's contents (nothing in
+ *   it needs clearing: each call writes what it reads): calls that overlap in time on one GPU (two
+ *   streams, two threads) race; calls on one stream are ordered and safe. */
+#define BL_STATIC_SCRATCH_BYTES (8 << 20)
+int bitlinear_a8_sparse_static(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, int64_t topk,
+                               const void* W_packed, bl_w_layout layout, const float* alpha,
+                               int64_t N, float eps, void* Y, bl_dtype y_dtype, int32_t* acc_out,
+                               void* stream);
 
 /* The matmul + rescale stage alone, on activations already quantized by quantize_act
  * (what the two calls above run after their quantize kernel).  q and scale are the

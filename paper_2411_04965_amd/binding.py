@@ -38,6 +38,8 @@ _SIGNATURES = {
                             _vp, _vp, _sz, _vp]),
     "bitlinear_a8_sparse": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _int, _vp, _i64, _f32, _vp,
                                    _int, _vp, _vp, _sz, _vp]),
+    "bitlinear_a8_sparse_static": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _int, _vp, _i64, _f32, _vp,
+                                          _int, _vp, _vp]),
     "bitlinear_gemm": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _int, _vp, _i64, _vp, _int, _vp,
                               _vp, _sz, _vp]),
     "relu2_glu": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _vp]),
@@ -200,6 +202,16 @@ def bitlinear_a8_sparse(X, topk, W_packed, alpha, N, eps=DEFAULT_EPS, layout=BL_
         _ptr(X), _dt(X), M, K, topk, _ptr(W_packed), layout, _ptr(alpha), N, eps, _ptr(Y),
         _dt(Y), _ptr(acc), _ptr(ws), ws.numel(), _stream()))
     return (Y, acc) if want_acc else Y
+
+
+def bitlinear_a8_sparse_static(X, topk, W_packed, alpha, N, out, eps=DEFAULT_EPS, layout=BL_W_GEMM, acc=None):
+    """bitlinear_a8_sparse on the library's static scratch: the caller brings the output (and the
+    accumulator buffer if wanted); nothing is allocated here or in the library."""
+    M, K = X.shape
+    _check("bitlinear_a8_sparse_static", lib().bitlinear_a8_sparse_static(
+        _ptr(X), _dt(X), M, K, topk, _ptr(W_packed), layout, _ptr(alpha), N, eps, _ptr(out), _dt(out),
+        _ptr(acc), _stream()))
+    return out
 
 
 def bitlinear_gemm(q, scale, mode, M, K, W_packed, alpha, N, layout=BL_W_GEMM,

@@ -2,6 +2,8 @@
 // the contract of every entry point.
 #include "common.h"
 
+#include <mutex>
+
 static inline size_t ws_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static bool valid_dtype(int d) { return d == BL_F32 || d == BL_BF16; }
@@ -61,6 +63,7 @@ extern "C" const char* bl_status_string(int status) {
     case BL_EWORKSPACE: return "workspace missing or too small";
     case BL_EHIP: return "HIP launch failed";
     case BL_EUNSUPPORTED: return "not implemented for these arguments";
+    case BL_ESCRATCH: return "request needs more scratch memory than the library's static buffer holds";
     default: return "unknown status";
   }
 }
@@ -365,6 +368,44 @@ extern "C" int bitlinear_a8_sparse(const void* X, bl_dtype x_dtype, int64_t M, i
                                    size_t workspace_bytes, void* stream) {
   return linear_common(X, x_dtype, M, K, BL_ACT_TOPK_INT8_ABSMAX, topk, W_packed, layout, alpha,
                        N, eps, Y, y_dtype, acc_out, workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------- the entry point that allocates nothing
+// Scratch memory of bitlinear_a8_sparse_static: lives in the library's device image, one copy per
+// GPU, from load to process end.  The name below is a host-side stand-in: device code and HIP calls
+// get the array's address on the current device from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[BL_STATIC_SCRATCH_BYTES];
+
+static int static_scratch_ptr(void** out) {
+  static std::mutex mu;
+  static void* ptrs[64] = {nullptr};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BL_EHIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BL_EHIP;
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return BL_OK;
+}
+
+extern "C" int bitlinear_a8_sparse_static(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, int64_t topk,
+                                          const void* W_packed, bl_w_layout layout, const float* alpha,
+                                          int64_t N, float eps, void* Y, bl_dtype y_dtype, int32_t* acc_out,
+                                          void* stream) {
+  if (M < 1 || N < 1 || K < 1) return BL_EINVAL;
+  if (M > BL_DECODE_MAX_M) return BL_ESCRATCH;
+  const size_t need = bitlinear_workspace_bytes(BL_ACT_TOPK_INT8_ABSMAX, M, N, K);
+  if (need > (size_t)BL_STATIC_SCRATCH_BYTES) return BL_ESCRATCH;
+  void* ws = nullptr;
+  const int rc = static_scratch_ptr(&ws);
+  if (rc) return rc;
+  // (nothing in the scratch has to start at zero: codes, scales and every partial sum that is read
+  // are written by this call's own kernels first)
+  return linear_common(X, x_dtype, M, K, BL_ACT_TOPK_INT8_ABSMAX, topk, W_packed, layout, alpha, N, eps, Y,
+                       y_dtype, acc_out, ws, (size_t)BL_STATIC_SCRATCH_BYTES, stream);
 }
 
 // ---------------------------------------------------------------- gate and up projection on one quantized input
