@@ -329,9 +329,9 @@ static int linear_common(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, 
                                     (hipStream_t)stream);
 
   if (mode == BL_ACT_TOPK_INT8_ABSMAX && layout == BL_W_GEMM && x_dtype == BL_BF16 &&
-      bl_gemv_a8_fused_ok(M, N, K))
-    return bl_launch_gemv_a8_fused(X, K, topk, eps, W_packed, alpha, N, Y, y_dtype, acc_out,
-                                   (hipStream_t)stream);
+      bl_gemv_stream_topk_ok(M, N, K))
+    return bl_launch_gemv_stream_topk(X, K, topk, eps, W_packed, alpha, N, Y, y_dtype, acc_out,
+                                      (hipStream_t)stream);
 
   unsigned char* p = (unsigned char*)workspace;
   void* codes = p;

@@ -153,6 +153,9 @@ int bl_launch_gemv_stream(const void* q, const float* scale, bool a4, int64_t M,
                           const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out, hipStream_t s);
 int bl_launch_gemv_stream_a4(const void* X, int64_t M, int64_t K, float eps, const void* Wp, const float* alpha,
                              int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out, hipStream_t s);
+bool bl_gemv_stream_topk_ok(int64_t M, int64_t N, int64_t K);
+int bl_launch_gemv_stream_topk(const void* X, int64_t K, int64_t topk, float eps, const void* Wp, const float* alpha,
+                               int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out, hipStream_t s);
 int bl_launch_gemv_stream_gate_up(const void* X, int64_t M, int64_t K, float eps, const void* Wg, const float* ag,
                                   const void* Wu, const float* au, int64_t N, void* G, void* U, bl_dtype ydt,
                                   void* H, hipStream_t s);

@@ -22,6 +22,7 @@
 // Integer sums are exact, so the split of K over waves changes nothing: accumulators and outputs
 // equal those of the quantizer followed by any other exact kernel.
 #include "common.h"
+#include "topk_regs.h"
 
 #define GV_THREADS 512
 #define GV_WAVES 8
@@ -190,23 +191,26 @@ __device__ __forceinline__ void gv_quantize_rows(const uint4 (&xr)[QM][GV_NV], i
 // QM = 0: codes and scales come from the stand-alone quantizer; QM > 0: `src` is the bfloat16 input
 // and eq. 7 runs here for up to QM tokens.  GLU: the two matrices are gate and up, the workgroup owns
 // the same outputs of both and stores H (eq. 5); their own outputs are stored too where Y is given.
+// TK > 0: `src` is ONE bfloat16 token and eq. 1 + eq. 3 run here (Top_k of `topk` channels, INT8 absmax;
+// TK = 4 or 8 chunks of 256 channels per wave; A4 = false, QM = 0).
 // UNR: weight tiles a wave requests per round (all of its share at the shapes the launcher picks it for).
 // Work: `upb` units (output tiles; GLU: gate/up tile pairs) per workgroup, one more for the first
 // `urem` workgroups.  A workgroup's tiles form at most two contiguous runs in memory (one per
 // matrix); its entries (output tiles) are numbered run 0 first.
-template <bool A4, int QM, bool GLU, int UNR>
+template <bool A4, int QM, bool GLU, int UNR, int TK>
 __global__ __launch_bounds__(GV_THREADS) void gemv_stream_kernel(
     const void* __restrict__ src, const float* __restrict__ scale, int M, int K, int Kp, float eps,
-    GvMat m0, GvMat m1, uint16_t* __restrict__ H, int y_bf16, int upb, int urem) {
+    GvMat m0, GvMat m1, uint16_t* __restrict__ H, int y_bf16, int upb, int urem, int topk) {
   extern __shared__ __align__(16) unsigned char gv_smem[];
   __shared__ float sh_dq[16], sh_sq[16];
+  __shared__ __align__(16) u32 sh_tk[TK > 0 ? 80 : 4];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // every argument is fetched now, in one round trip to the argument segment (left alone the compiler
   // fetches each where it is first used, and each fetch then stalls the requests below)
   asm volatile("" ::"s"(src), "s"(scale), "s"(M), "s"(K), "s"(Kp), "s"(eps), "s"(m0.W), "s"(m0.alpha), "s"(m0.Y),
                "s"(m0.acc), "s"(m0.N), "s"(m0.NT), "s"(m1.W), "s"(m1.alpha), "s"(m1.Y), "s"(m1.acc), "s"(m1.N),
-               "s"(m1.NT), "s"(H), "s"(y_bf16), "s"(upb), "s"(urem));
+               "s"(m1.NT), "s"(H), "s"(y_bf16), "s"(upb), "s"(urem), "s"(topk));
   const int KT = Kp >> 8;
 
   // ---- requests first.  Tokens (or their codes), then round 0 of the weights: loads come back in the
@@ -216,11 +220,26 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_stream_kernel(
   // flight and wait for each one alone.
   constexpr int QMR = QM > 0 ? QM : 1;
   uint4 xr[QMR][GV_NV];
-  constexpr int NCP = QM > 0 ? 1 : GV_NCP;                             // code pieces (16 bytes) per thread
+  constexpr int NCP = (QM > 0 || TK > 0) ? 1 : GV_NCP;                 // code pieces (16 bytes) per thread
   uint4 cr[NCP];
   const int code_ppr = A4 ? (Kp >> 5) : (Kp >> 4);                     // pieces per token row
   const int n_code_pieces = M * code_ppr;
-  if (QM > 0) {
+  // (TK) this wave's chunks of 256 channels of the token: 4 consecutive channels per lane and chunk
+  constexpr int TKR = TK > 0 ? TK : 4;
+  u32 traw[TKR][2];
+  const int tk_per_wave = ((Kp >> 8) + GV_WAVES - 1) / GV_WAVES;
+  const int tk_begin = min(wave * tk_per_wave, Kp >> 8);
+  const int tk_nc = min(tk_begin + tk_per_wave, Kp >> 8) - tk_begin;
+  if (TK > 0) {
+    const int ch0 = tk_begin * 256 + lane * 4;
+#pragma unroll
+    for (int i = 0; i < TKR; ++i) {
+      uint2 v = make_uint2(0u, 0u);
+      if (i < tk_nc && ch0 + i * 256 < K) v = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(src) + ch0 + i * 256);
+      traw[i][0] = v.x;
+      traw[i][1] = v.y;
+    }
+  } else if (QM > 0) {
     const int nv = K >> 3;
 #pragma unroll
     for (int m = 0; m < QMR; ++m)
@@ -271,7 +290,9 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_stream_kernel(
     for (int i = tid; i < NE * GV_WAVES * 64; i += GV_THREADS) red[i] = (v4i){0, 0, 0, 0};
 
   // ---- the tokens' codes
-  if (QM > 0) {
+  if constexpr (TK > 0) {
+    qa_topk_row_regs8<TKR>(traw, tk_nc, tk_begin, topk, eps, reinterpret_cast<u32*>(codes), sh_dq, sh_tk);
+  } else if (QM > 0) {
     const int ne_max = (upb + (urem > 0 ? 1 : 0)) * (GLU ? 2 : 1);    // the launch's LDS holds this many entries
     double* part = reinterpret_cast<double*>(gv_smem + (size_t)M * pitch + (size_t)ne_max * GV_WAVES * 1024);
     gv_quantize_rows<QMR>(xr, M, K, Kp, eps, codes, pitch, sh_dq, sh_sq, part);
@@ -361,7 +382,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_stream_kernel(
   constexpr int SHIFT = (A4 && QM == 0) ? 10 : 6;                      // weights carry 64 T, nibble codes 16 q
   const int m = li;
   if (m >= M) return;
-  const float d = QM > 0 ? sh_dq[m] : scale[m];
+  const float d = (QM > 0 || TK > 0) ? sh_dq[m] : scale[m];
   auto entry_sum = [&](int e, int (&iv)[4]) {
     v4i sum = (v4i){0, 0, 0, 0};
 #pragma unroll
@@ -451,13 +472,13 @@ bool bl_gemv_stream_pair_ok(int64_t M, int64_t N, int64_t K, bool glu) {
   return glu ? gv_plan(M, Kp, (N + 15) / 16, 2, true, grid, smem) : gv_plan(M, Kp, 2 * ((N + 15) / 16), 1, true, grid, smem);
 }
 
-template <bool A4, int QM, bool GLU, int UNR>
+template <bool A4, int QM, bool GLU, int UNR, int TK = 0>
 static int gv_go2(const void* src, const float* scale, int M, int K, int Kp, float eps, const GvMat& m0,
-                  const GvMat& m1, uint16_t* H, int ybf, int grid, size_t smem, hipStream_t s) {
-  BL_SET_MAX_LDS_ONCE((gemv_stream_kernel<A4, QM, GLU, UNR>), GV_LDS_MAX);
+                  const GvMat& m1, uint16_t* H, int ybf, int grid, size_t smem, hipStream_t s, int topk = 0) {
+  BL_SET_MAX_LDS_ONCE((gemv_stream_kernel<A4, QM, GLU, UNR, TK>), GV_LDS_MAX);
   const int64_t units = GLU ? m0.NT : (int64_t)m0.NT + m1.NT;
-  gemv_stream_kernel<A4, QM, GLU, UNR><<<(unsigned)grid, GV_THREADS, smem, s>>>(
-      src, scale, M, K, Kp, eps, m0, m1, H, ybf, (int)(units / grid), (int)(units % grid));
+  gemv_stream_kernel<A4, QM, GLU, UNR, TK><<<(unsigned)grid, GV_THREADS, smem, s>>>(
+      src, scale, M, K, Kp, eps, m0, m1, H, ybf, (int)(units / grid), (int)(units % grid), topk);
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;
 }
@@ -527,4 +548,33 @@ int bl_launch_gemv_stream_gate_up(const void* X, int64_t M, int64_t K, float eps
   const int ybf = ydt == BL_BF16 ? 1 : 0;
   if (glu) return gv_quant_dispatch<true>(X, (int)M, (int)K, Kp, eps, m0, m1, (uint16_t*)H, ybf, grid, smem, s);
   return gv_quant_dispatch<false>(X, (int)M, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s);
+}
+
+// One bfloat16 token, Top_k + INT8 (eq. 1, eq. 3) inside, one matrix.
+bool bl_gemv_stream_topk_ok(int64_t M, int64_t N, int64_t K) {
+  int grid;
+  size_t smem;
+  const int64_t Kp = bl_round_up(K, BL_KPAD);
+  return M == 1 && K % 4 == 0 && Kp <= 16384 && gv_plan(1, Kp, (N + 15) / 16, 1, false, grid, smem);
+}
+
+int bl_launch_gemv_stream_topk(const void* X, int64_t K, int64_t topk, float eps, const void* Wp, const float* alpha,
+                               int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out, hipStream_t s) {
+  if (!bl_gemv_stream_topk_ok(1, N, K)) return BL_EUNSUPPORTED;
+  const int Kp = (int)bl_round_up(K, BL_KPAD);
+  int grid;
+  size_t smem;
+  gv_plan(1, Kp, (N + 15) / 16, 1, false, grid, smem);
+  const GvMat m0 = {(const unsigned char*)Wp, alpha, Y, acc_out, (int)N, (int)((N + 15) / 16)};
+  const GvMat m1 = {nullptr, nullptr, nullptr, nullptr, 0, 0};
+  const int ybf = ydt == BL_BF16 ? 1 : 0;
+  const int64_t ne = (m0.NT + grid - 1) / grid;
+  const int64_t per_wave = (ne * (Kp >> 8) + GV_WAVES - 1) / GV_WAVES;
+  const bool small = (Kp >> 8) <= 4 * GV_WAVES;            // at most 4 chunks of 256 channels per wave
+#define GV_TK(UNRV)                                                                                                \
+  (small ? gv_go2<false, 0, false, UNRV, 4>(X, nullptr, 1, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s, (int)topk) \
+         : gv_go2<false, 0, false, UNRV, 8>(X, nullptr, 1, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s, (int)topk))
+  if (per_wave <= 6) return GV_TK(6);
+  return GV_TK(GV_UNR);
+#undef GV_TK
 }

@@ -510,6 +510,33 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_regs_kernel(
                              q_out + m * (int64_t)(Kp / 4), scale_out + m, rowsum_out ? rowsum_out + m : nullptr);
 }
 
+// Few tokens (decode): what counts is how long one token takes, not how many run at once.  Eight
+// waves per token, 11-bit keys and three bits of the threshold per pass (topk_regs.h); codes and
+// scales only (the codes are those of the kernels above bit for bit).
+template <int CPW>
+__global__ __launch_bounds__(512) void quant_topk_int8_regs8_kernel(
+    const uint16_t* __restrict__ X, int K, int Kp, int topk, float eps, u32* __restrict__ q_out,
+    float* __restrict__ scale_out) {
+  __shared__ __align__(16) u32 sh[80];
+  const int64_t m = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n_chunks = Kp >> 8;
+  const int per_wave = (n_chunks + 7) / 8;
+  const int c_begin = min(wave * per_wave, n_chunks);
+  const int nc = min(c_begin + per_wave, n_chunks) - c_begin;
+  const uint16_t* x = X + m * (int64_t)K;
+  u32 raw[CPW][2];
+  const int ch0 = c_begin * 256 + lane * 4;
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) {
+    uint2 v = make_uint2(0u, 0u);
+    if (i < nc && ch0 + i * 256 < K) v = *reinterpret_cast<const uint2*>(x + ch0 + i * 256);   // K % 4 == 0 by dispatch
+    raw[i][0] = v.x;
+    raw[i][1] = v.y;
+  }
+  qa_topk_row_regs8<CPW>(raw, nc, c_begin, topk, eps, q_out + m * (int64_t)(Kp / 4), scale_out + m, sh);
+}
+
 // The same selection with one wave per token, for many tokens of moderate width: the fixed cost of a
 // pass (wave sum, compare, branch) is paid once per token instead of four times, and there is no LDS
 // traffic and no barrier at all.  A lane holds up to 4 * NB chunks' worth of keys (NB blocks of 16
@@ -852,7 +879,13 @@ static int qa_run_topk_regs(const void* x, const void* x2, int64_t M, int K, int
   // many tokens of up to 6144 channels: one wave per token (measured at 16384 tokens: 0.051 against
   // 0.075 ms at 4096 channels, 0.077 against 0.110 ms at 5460; from 8 register blocks on it loses)
   const int nb = (Kp / 256 + 3) / 4;
-  if (M >= 2048 && nb <= 6) {
+  if (GLU == 0 && rowsum == nullptr && M <= 256) {
+    // (K % 4 == 0 and Kp <= 12288 by dispatch: at most 6 chunks of 256 channels per wave)
+    if (Kp <= 8192)
+      quant_topk_int8_regs8_kernel<4><<<(unsigned)M, 512, 0, s>>>((const uint16_t*)x, K, Kp, topk, eps, (u32*)q, (float*)scale);
+    else
+      quant_topk_int8_regs8_kernel<8><<<(unsigned)M, 512, 0, s>>>((const uint16_t*)x, K, Kp, topk, eps, (u32*)q, (float*)scale);
+  } else if (M >= 2048 && nb <= 6) {
     const unsigned grid = (unsigned)((M + QA_WAVES - 1) / QA_WAVES);
     if (nb <= 4)
       quant_topk_int8_wave_kernel<4, GLU><<<grid, QA_THREADS, 0, s>>>(x, x2, M, K, Kp, topk, eps, (u32*)q, (float*)scale, rowsum);

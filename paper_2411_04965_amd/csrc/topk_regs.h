@@ -83,6 +83,65 @@ __device__ __forceinline__ void qa_bit_transpose16(u32 (&w)[8]) {
   }
 }
 
+// Codes of one wave's chunks once tau is known.  Of the keys equal to tau the first r in channel
+// order are kept (eq_base = keys equal to tau in earlier waves, eq_here = in this wave): for a whole
+// wave that is all of them, none of them, or (for one wave of the token) a prefix found with
+// ballots.  raw / pg: the wave's chunks as loaded / with the guard bits set; out0: this lane's word
+// of the wave's first chunk (chunk i at out0[64 i]); sum: the sum of the lane's codes is added to it.
+template <int CPW>
+__device__ __forceinline__ void qa_code_chunks(const u32 (&raw)[CPW][2], const u32 (&pg)[CPW][2], int nc, u32 tau,
+                                               int r, int eq_base, int eq_here, float s, u32* out0, int& sum) {
+  const int lane = threadIdx.x & 63;
+  const bool eq_all = eq_base + eq_here <= r;
+  const bool eq_none = eq_base >= r;
+  const u32 t1 = (tau + 1u) * 0x10001u, t0 = tau * 0x10001u;
+  const u32 tk = eq_all ? t0 : t1;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) {
+    if (i < nc) {                                         // wave-uniform
+      // kept keys as guard-bit flags: key >= tau where the wave keeps all its keys equal to tau,
+      // key > tau where it keeps none of them
+      u32 k0 = (pg[i][0] - tk) & QA_GUARD, k1 = (pg[i][1] - tk) & QA_GUARD;
+      if (!eq_all && !eq_none) {                          // the wave that holds the r-th equal key
+        const u32 e0 = ((pg[i][0] - t0) & QA_GUARD) ^ k0, e1 = ((pg[i][1] - t0) & QA_GUARD) ^ k1;
+        const bool eqf[4] = {(e0 & 0x8000u) != 0, (e0 >> 31) != 0, (e1 & 0x8000u) != 0, (e1 >> 31) != 0};
+        uint64_t beq[4], any_eq = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { beq[j] = __ballot(eqf[j]); any_eq |= beq[j]; }
+        if (any_eq) {
+          int rank = eq_base, in_chunk = 0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            rank += __popcll(beq[j] & lt_mask);
+            in_chunk += __popcll(beq[j]);
+          }
+          if (eqf[0]) { if (rank < r) k0 |= 0x8000u; ++rank; }
+          if (eqf[1]) { if (rank < r) k0 |= 0x80000000u; ++rank; }
+          if (eqf[2]) { if (rank < r) k1 |= 0x8000u; ++rank; }
+          if (eqf[3]) { if (rank < r) k1 |= 0x80000000u; ++rank; }
+          eq_base += in_chunk;
+        }
+      }
+      // codes: |x * s| <= 127 for every finite row, so RoundClip is the rounding alone, taken
+      // from the low byte of (x * s) + 1.5 * 2^23 (round to nearest even at integer spacing)
+      const float xs[4] = {__uint_as_float(raw[i][0] << 16), __uint_as_float(raw[i][0] & 0xFFFF0000u),
+                           __uint_as_float(raw[i][1] << 16), __uint_as_float(raw[i][1] & 0xFFFF0000u)};
+      u32 rb[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) rb[j] = __float_as_uint(xs[j] * s + 12582912.0f);
+      const u32 w01 = __builtin_amdgcn_perm(rb[1], rb[0], 0x0c0c0400u);   // bytes: rb0.b0, rb1.b0, 0, 0
+      const u32 w23 = __builtin_amdgcn_perm(rb[3], rb[2], 0x04000c0cu);   // bytes: 0, 0, rb2.b0, rb3.b0
+      // the four flags (bits 15 and 31 of k0, k1) as a byte mask: bytes 1 and 3 of each word hold
+      // 0x80 or 0; shifted down that is 1 or 0 per byte, times 255 it is the mask
+      const u32 keep4 = (__builtin_amdgcn_perm(k1, k0, 0x07050301u) >> 7) * 255u;
+      const u32 word = (w01 | w23) & keep4;
+      sum = __builtin_amdgcn_sdot4((int)word, 0x01010101, sum, false);
+      out0[i * 64] = word;
+    }
+  }
+}
+
 // Body for one token and one workgroup of 4 waves: row x of K channels -> Kp / 4 code words at
 // `out`, the dequantization scale at `scale_out` (both may point into LDS), the sum of the codes at
 // `rowsum_out` if not null.  Every thread of the workgroup must call it (it has barriers).
@@ -198,58 +257,8 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
     if (w < wave) eq_base += (int)eqs[w];
   eq_base = __builtin_amdgcn_readfirstlane(eq_base);
   const int eq_here = __builtin_amdgcn_readfirstlane((int)sh_c[wave]);
-  // Of the keys equal to tau the first r in channel order are kept.  For a whole wave that is
-  // all of them, none of them, or (for one wave of the token) a prefix found with ballots.
-  const bool eq_all = eq_base + eq_here <= r;
-  const bool eq_none = eq_base >= r;
-  const u32 t1 = (tau + 1u) * 0x10001u, t0 = tau * 0x10001u;
-  const u32 tk = eq_all ? t0 : t1;
-  const uint64_t lt_mask = (1ull << lane) - 1ull;
   int sum = 0;
-  u32* out0 = out + c_begin * 64 + lane;
-#pragma unroll
-  for (int i = 0; i < CPW; ++i) {
-    if (i < nc) {                                         // wave-uniform
-      // kept keys as guard-bit flags: key >= tau where the wave keeps all its keys equal to tau,
-      // key > tau where it keeps none of them
-      u32 k0 = (pg[i][0] - tk) & QA_GUARD, k1 = (pg[i][1] - tk) & QA_GUARD;
-      if (!eq_all && !eq_none) {                          // the wave that holds the r-th equal key
-        const u32 e0 = ((pg[i][0] - t0) & QA_GUARD) ^ k0, e1 = ((pg[i][1] - t0) & QA_GUARD) ^ k1;
-        const bool eqf[4] = {(e0 & 0x8000u) != 0, (e0 >> 31) != 0, (e1 & 0x8000u) != 0, (e1 >> 31) != 0};
-        uint64_t beq[4], any_eq = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { beq[j] = __ballot(eqf[j]); any_eq |= beq[j]; }
-        if (any_eq) {
-          int rank = eq_base, in_chunk = 0;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            rank += __popcll(beq[j] & lt_mask);
-            in_chunk += __popcll(beq[j]);
-          }
-          if (eqf[0]) { if (rank < r) k0 |= 0x8000u; ++rank; }
-          if (eqf[1]) { if (rank < r) k0 |= 0x80000000u; ++rank; }
-          if (eqf[2]) { if (rank < r) k1 |= 0x8000u; ++rank; }
-          if (eqf[3]) { if (rank < r) k1 |= 0x80000000u; ++rank; }
-          eq_base += in_chunk;
-        }
-      }
-      // codes: |x * s| <= 127 for every finite row, so RoundClip is the rounding alone, taken
-      // from the low byte of (x * s) + 1.5 * 2^23 (round to nearest even at integer spacing)
-      const float xs[4] = {__uint_as_float(raw[i][0] << 16), __uint_as_float(raw[i][0] & 0xFFFF0000u),
-                           __uint_as_float(raw[i][1] << 16), __uint_as_float(raw[i][1] & 0xFFFF0000u)};
-      u32 rb[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) rb[j] = __float_as_uint(xs[j] * s + 12582912.0f);
-      const u32 w01 = __builtin_amdgcn_perm(rb[1], rb[0], 0x0c0c0400u);   // bytes: rb0.b0, rb1.b0, 0, 0
-      const u32 w23 = __builtin_amdgcn_perm(rb[3], rb[2], 0x04000c0cu);   // bytes: 0, 0, rb2.b0, rb3.b0
-      // the four flags (bits 15 and 31 of k0, k1) as a byte mask: bytes 1 and 3 of each word hold
-      // 0x80 or 0; shifted down that is 1 or 0 per byte, times 255 it is the mask
-      const u32 keep4 = (__builtin_amdgcn_perm(k1, k0, 0x07050301u) >> 7) * 255u;
-      const u32 word = (w01 | w23) & keep4;
-      sum = __builtin_amdgcn_sdot4((int)word, 0x01010101, sum, false);
-      out0[i * 64] = word;
-    }
-  }
+  qa_code_chunks<CPW>(raw, pg, nc, tau, r, eq_base, eq_here, s, out + c_begin * 64 + lane, sum);
   if (rowsum_out) {
     sum = qa_wave_sum_dpp(sum);
     __syncthreads();
@@ -260,4 +269,182 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
       rowsum_out[0] = (int32_t)(t.x + t.y + t.z + t.w);
     }
   }
+}
+
+// ---------------------------------------------------------------- one token, 8 waves, 3 bits of tau per pass
+// The same selection for a workgroup of 8 waves that has one token to quantize and little time (the
+// decode kernel that streams a weight matrix past one token), and that needs the token's CODES only
+// (no mask, no index list).  What costs there is not the counting but the chain of dependent steps --
+// count, add up over the workgroup, decide, next bits -- so:
+//   * Keys are cut to 11 bits.  A channel below gamma / 256 has code 0 whether Top_k keeps it or not
+//     (|x| s < 127 / 256 rounds to 0), so the keys at or below C = key(gamma) - 8 binades are
+//     collapsed into one lowest class: key' = max(key, C) - C, at most 1024.  If the topk-th largest
+//     key' is positive the selection among the keys above C is the exact one, ties included; if it
+//     is 0 every key above C is kept, and what happens inside the lowest class changes no code.
+//   * A pass settles three bits of tau' at once: the still-undecided keys are split by their next
+//     three bits into eight classes (bit planes: fourteen ANDs), the class sizes are packed two to a
+//     word, added over the wave with DPP (row rotations, then the row broadcasts into the last row)
+//     and left in LDS by the wave's last lane; after one barrier lane l takes wave l % 8's words,
+//     three more DPP steps give every lane the workgroup's sums, and the decision is scalar
+//     arithmetic.  Four passes (bits 10..8, 7..5, 4..2, 1..0).
+//   * The last pass's per-wave class sizes are also the per-wave counts of keys equal to tau that the
+//     tie rule (lower channel first; waves own contiguous channel ranges) needs: no further exchange.
+//   raw     this wave's chunks of 256 channels as loaded by the caller (chunk i of the wave = chunk
+//           c_begin + i of the token; 4 consecutive channels per lane; zero beyond K and beyond nc)
+//   sh      80 words of LDS scratch (16-byte aligned)
+// Chunks are dealt to the waves in contiguous ranges of per_wave = ceil(n_chunks / 8), so channel
+// order is (wave, chunk, lane, j) order as in the 4-wave body.  Every thread of the workgroup must
+// call it (it has barriers); the caller adds the barrier that publishes the codes.
+__device__ __forceinline__ u32 qa_sum8_dpp(u32 x) {       // sum over each aligned group of 8 lanes, in all of them
+  int v = (int)x;
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);      // quad_perm [2,3,0,1]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x124, 0xF, 0xF, false);     // row_ror:4 (lanes hold every value twice per row)
+  return (u32)v;
+}
+__device__ __forceinline__ u32 qa_max8_dpp(u32 x) {
+  u32 v = x;
+  v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));
+  v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));
+  v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xF, 0xF, false));
+  return v;
+}
+
+template <int CPW>
+__device__ __forceinline__ void qa_topk_row_regs8(const u32 (&raw)[CPW][2], int nc, int c_begin, int topk, float eps,
+                                                  u32* out, float* scale_out, u32* sh) {
+  static_assert(CPW == 4 || CPW == 8, "16 or 32 keys per lane");
+  constexpr int NBK = CPW / 4;
+  typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  u32* sh_max = sh;              // [8]
+  u32* sh_cnt = sh + 16;         // [2][8 waves][4] class sizes of a pass per wave (slots alternate)
+
+  u32 pg[CPW][2];
+  u32 km2 = QA_GUARD;
+  {
+    us2 km = __builtin_bit_cast(us2, km2);
+#pragma unroll
+    for (int i = 0; i < CPW; ++i)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        pg[i][h] = raw[i][h] | QA_GUARD;
+        km = __builtin_elementwise_max(km, __builtin_bit_cast(us2, pg[i][h]));   // v_pk_max_u16
+      }
+    km2 = __builtin_bit_cast(u32, km);
+  }
+  u32 kmax = max(km2 & 0x7FFFu, (km2 >> 16) & 0x7FFFu);
+  kmax = bl_wave_max_u32(kmax);
+  if (lane == 0) sh_max[wave] = kmax;
+  __syncthreads();
+  kmax = (u32)__builtin_amdgcn_readfirstlane((int)qa_max8_dpp(sh_max[lane & 7]));
+  const float gamma = __uint_as_float(kmax << 16);
+  const float s = 127.0f / (gamma + eps);
+  if (tid == 0) scale_out[0] = gamma / 127.0f;
+
+  // 11-bit keys and their bit planes: plane(bit) has key r of the lane in bit r
+  const u32 C = kmax > 1024u ? kmax - 1024u : 0u;
+  const us2 C2 = __builtin_bit_cast(us2, C * 0x10001u);
+  u32 pl[NBK][8];
+#pragma unroll
+  for (int B = 0; B < NBK; ++B) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const us2 k = __builtin_bit_cast(us2, raw[4 * B + (i >> 1)][i & 1] & 0x7FFF7FFFu);
+      pl[B][i] = __builtin_bit_cast(u32, (us2)(__builtin_elementwise_max(k, C2) - C2));
+    }
+    qa_bit_transpose16(pl[B]);
+  }
+  auto plane = [&](int bit) -> u32 {
+    if (bit < 0) return 0u;
+    if (NBK == 1) return (bit & 1) ? pl[0][bit >> 1] >> 16 : pl[0][bit >> 1] & 0xFFFFu;
+    return __builtin_amdgcn_perm(pl[NBK - 1][bit >> 1], pl[0][bit >> 1], (bit & 1) ? 0x07060302u : 0x05040100u);
+  };
+  // keys of chunks this wave does not have stay out: they would count as members of the lowest class
+  u32 act = nc >= 8 ? ~0u : ((1u << (4 * nc)) - 1u);
+  if (NBK == 1) act &= 0xFFFFu;
+  u32 tau = 0;                                            // tau' (11 bits)
+  int above = 0;
+  int d = 0;
+  uint4 q = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int b0 = 8 - 3 * p;                             // the pass settles bits b0 + 2, b0 + 1, b0 (b0 = -1: two bits)
+    const u32 P2 = plane(b0 + 2), P1 = plane(b0 + 1), P0 = plane(b0);
+    // classes by the three bits: m[c] = undecided keys whose bits spell c
+    u32 m[8];
+    {
+      const u32 hi = act & P2, lo = act ^ hi;
+      const u32 h1 = hi & P1, h0 = hi ^ h1, l1 = lo & P1, l0 = lo ^ l1;
+      m[7] = h1 & P0; m[6] = h1 ^ m[7];
+      m[5] = h0 & P0; m[4] = h0 ^ m[5];
+      m[3] = l1 & P0; m[2] = l1 ^ m[3];
+      m[1] = l0 & P0; m[0] = l0 ^ m[1];
+    }
+    // class sizes, two to a word (a token has at most 16384 keys: no carry between the halves)
+    u32 w[4];
+    w[0] = (u32)__popc(m[1]) | ((u32)__popc(m[2]) << 16);
+    w[1] = (u32)__popc(m[3]) | ((u32)__popc(m[4]) << 16);
+    w[2] = (u32)__popc(m[5]) | ((u32)__popc(m[6]) << 16);
+    w[3] = (u32)__popc(m[7]) | ((u32)__popc(m[0]) << 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int v = (int)w[j];
+      v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+      v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
+      v += __builtin_amdgcn_update_dpp(0, v, 0x124, 0xF, 0xF, false);   // row_ror:4
+      v += __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, false);   // row_ror:8
+      v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+      v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+      w[j] = (u32)v;                                      // (the wave's sum, in the lanes of the last row)
+    }
+    u32* slot = sh_cnt + (p & 1) * 32;                    // (one barrier per pass: slots alternate)
+    if (lane == 63) *reinterpret_cast<uint4*>(slot + 4 * wave) = make_uint4(w[0], w[1], w[2], w[3]);
+    __syncthreads();
+    q = *reinterpret_cast<const uint4*>(slot + 4 * (lane & 7));         // lane l: the sizes in wave l % 8
+    const u32 t0 = (u32)__builtin_amdgcn_readfirstlane((int)qa_sum8_dpp(q.x));
+    const u32 t1 = (u32)__builtin_amdgcn_readfirstlane((int)qa_sum8_dpp(q.y));
+    const u32 t2 = (u32)__builtin_amdgcn_readfirstlane((int)qa_sum8_dpp(q.z));
+    const u32 t3 = (u32)__builtin_amdgcn_readfirstlane((int)qa_sum8_dpp(q.w));
+    // cum[c] = undecided keys of class c or higher; the topk-th largest key is in the highest class
+    // c with above + cum[c] >= topk (class 0 if none).  Scalar arithmetic from here.
+    const int need = topk - above;
+    int cum[9];
+    cum[8] = 0;
+    cum[7] = (int)(t3 & 0xFFFFu);
+    cum[6] = cum[7] + (int)(t2 >> 16);
+    cum[5] = cum[6] + (int)(t2 & 0xFFFFu);
+    cum[4] = cum[5] + (int)(t1 >> 16);
+    cum[3] = cum[4] + (int)(t1 & 0xFFFFu);
+    cum[2] = cum[3] + (int)(t0 >> 16);
+    cum[1] = cum[2] + (int)(t0 & 0xFFFFu);
+    d = 0;
+#pragma unroll
+    for (int c = 1; c < 8; ++c) d += cum[c] >= need ? 1 : 0;
+    int add = cum[1];
+#pragma unroll
+    for (int c = 1; c < 8; ++c)
+      if (d == c) add = cum[c + 1];
+    above += add;
+    // the class's members: keys whose three bits spell d
+    act &= (P2 ^ ((d & 4) ? 0u : ~0u)) & (P1 ^ ((d & 2) ? 0u : ~0u)) & (P0 ^ ((d & 1) ? 0u : ~0u));
+    tau |= b0 >= 0 ? (u32)d << b0 : (u32)d >> 1;
+  }
+
+  // Keys equal to tau per wave = the sizes of class d of the last pass, which lane l still holds for
+  // wave l % 8.  tau' = 0: the lowest class is dropped as a whole (its codes are 0 either way).
+  const u32 qw = d == 0 ? q.w : d <= 2 ? q.x : d <= 4 ? q.y : d <= 6 ? q.z : q.w;
+  const u32 e = ((d == 0 || ((d - 1) & 1)) ? qw >> 16 : qw) & 0xFFFFu;
+  const int r = topk - above;
+  int eq_base = 0, eq_here = 0;                           // keys equal to tau in earlier waves, in this one
+#pragma unroll
+  for (int ww = 0; ww < 8; ++ww) {
+    const int ev = __builtin_amdgcn_readlane((int)e, ww);
+    if (ww < wave) eq_base += ev;
+    if (ww == wave) eq_here = ev;
+  }
+  const bool low = tau == 0;
+  int sum = 0;
+  qa_code_chunks<CPW>(raw, pg, nc, tau + C, r, low ? r : eq_base, eq_here, s, out + c_begin * 64 + lane, sum);
 }

@@ -563,7 +563,8 @@ def test_gate_up(M, N, K, layout):
 
 @pytest.mark.parametrize("kind,N,K,topk", [("heavy", 2050, 1500, 700), ("glu", 2048, 5460, 2730),
                                            ("glu", 4096, 8640, 4320), ("ties", 2064, 1000, 500),
-                                           ("ties", 2048, 4096, 1)])
+                                           ("ties", 2048, 4096, 1), ("heavy", 300, 16384, 8192),
+                                           ("ties", 2064, 9000, 3), ("glu", 16, 256, 100), ("heavy", 4096, 4096, 4096)])
 def test_decode_fused_topk_int8(kind, N, K, topk):
     """One token with at least 128 output tiles: eq. 1 + eq. 3 run inside the GEMV launch, for every
     register-block count of the selection, ragged K and N, ties at the threshold."""
