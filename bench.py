@@ -65,6 +65,8 @@ def parse():
     ap.add_argument("--no-fp4", action="store_true")
     ap.add_argument("--a4-weights", choices=["mx2", "mx4"], default="mx2",
                     help="block-float weight form of the INT4 projections: 2-bit codes expanded in registers, or E2M1 nibbles")
+    ap.add_argument("--ffn", choices=["fused", "separate"], default="fused",
+                    help="gate and up projection as one GEMM with the ReLU^2 GLU in its epilogue (H written), or as two GEMMs (G and U written)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for the HBM traffic counters)")
     return ap.parse_args()
@@ -146,21 +148,41 @@ def main():
             ws=B.workspace(mode, M, N, K, dev))
     stream = torch.cuda.current_stream().cuda_stream
     L = B.lib()
+    fused = args.ffn == "fused"
+    H_ffn = torch.empty((M, FFN), dtype=bf16, device=dev)
+    ws_gu = torch.empty(max(L.bitlinear_gate_up_workspace_bytes(M, FFN, HIDDEN, A4L), 16), dtype=torch.uint8, device=dev)
+    # the step's launches: with the fused FFN front, gate and up are one entry (N = both widths)
+    launches = ([("qkv", 3 * HIDDEN, HIDDEN, "a4"), ("o", HIDDEN, HIDDEN, "a8s"), ("gate_up", 2 * FFN, HIDDEN, "a4"),
+                 ("down", HIDDEN, FFN, "a8s")] if fused else projs)
 
     # events of the timed steps exist before the timed region: recording one is all that is left in it
     n_timed = 0 if args.no_prefill else args.steps
-    pool = [[tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in projs] for _ in range(n_timed)]
-    gemm_events = {name: [] for name, *_ in projs}
-    quant_events = {name: [] for name, *_ in projs}
+    pool = [[tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in launches] for _ in range(n_timed)]
+    gemm_events = {name: [] for name, *_ in launches}
+    quant_events = {name: [] for name, *_ in launches}
 
     def step(record, it=0):
-        for pi, (name, N, K, kind) in enumerate(projs):
-            b = bufs[name]
-            X = inputs[name]
+        for pi, (name, N, K, kind) in enumerate(launches):
+            b = bufs["gate" if name == "gate_up" else name]
+            X = inputs["gate" if name == "gate_up" else name]
             topk = K // 2 if kind == "a8s" else 0
             if record:
                 e0, e1, e2 = pool[it][pi]
                 e0.record()
+            if name == "gate_up":
+                # eq. 7 once, then one GEMM over both weight matrices whose epilogue applies eq. 5: H only
+                rc = L.quantize_act(X.data_ptr(), B.BL_BF16, M, K, b["mode"], 0, EPS,
+                                    b["q"].data_ptr(), b["scale"].data_ptr(), None, None, stream)
+                assert rc == 0, rc
+                if record:
+                    e1.record()
+                rc = B.gemm_a4_glu_prequantized(L, b["q"], b["scale"], M, K, W["gate"], W["up"], A4L, FFN, H_ffn, stream)
+                assert rc == 0, rc
+                if record:
+                    e2.record()
+                    quant_events[name].append((e0, e1))
+                    gemm_events[name].append((e1, e2))
+                continue
             if name == "up":
                 # gate and up read the same tensor: it is quantized once (by "gate") and used twice
                 b = dict(b, q=bufs["gate"]["q"], scale=bufs["gate"]["scale"])
@@ -210,7 +232,7 @@ def main():
     value = ops_per_step / (ms_per_step * 1e-3) / 1e12
 
     per_kernel = {}
-    for name, N, K, kind in projs:
+    for name, N, K, kind in launches:
         g = float(np.mean([a.elapsed_time(b) for a, b in gemm_events[name]]))
         qd = float(np.mean([a.elapsed_time(b) for a, b in quant_events[name]]))
         in_b = M * K * 2
@@ -218,22 +240,26 @@ def main():
         per_kernel[name] = {"gemm_ms": round(g, 4), "gemm_tops": round(2.0 * M * N * K / g / 1e9, 1),
                             "quant_ms": round(qd, 4),
                             "quant_gbs": None if name == "up" else round((in_b + out_b) / qd / 1e6, 1)}
-    # dominant kernel: the W1.58A4 prefill GEMM (qkv, gate, up launches)
-    a4 = [(n_, N, K) for n_, N, K, kind in projs if kind == "a4"]
+    # dominant kernel: the W1.58A4 prefill GEMM (qkv, gate, up launches; gate and up as one launch
+    # with the GLU epilogue when fused)
+    a4 = [(n_, N, K) for n_, N, K, kind in launches if kind == "a4"]
     a4_ops = sum(2.0 * M * N * K for _, N, K in a4)
     a4_ms = sum(per_kernel[n_]["gemm_ms"] for n_, _, _ in a4)
     achieved = a4_ops / (a4_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_a4_mx_kernel (qkv, gate, up): E3M2 x E2M1 block-float MFMA, weights "
+    def out_bytes(n_, N):                       # bf16 outputs: H alone for the fused gate/up launch
+        return 2 * M * (N // 2 if n_ == "gate_up" else N)
+    roofline = {"bound": "mfma", "kernel": "gemm_a4_mx_kernel (%s): E3M2 x E2M1 block-float MFMA, weights "
+                          % ("qkv; gate + up with the GLU epilogue" if fused else "qkv, gate, up")
                           + ("2-bit in HBM and LDS" if args.a4_weights == "mx2" else "E2M1 nibbles in HBM and LDS"),
                 "achieved": round(achieved, 1), "peak": FP6_FP4_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / FP6_FP4_PEAK_TOPS, 4),
                 "frac_of_int8_peak": round(achieved / INT8_PEAK_TOPS, 4),
                 "traffic": measured_traffic_bytes() if (M == 16384 and args.a4_weights == "mx2") else None,
                 # what the method itself has to move per launch: 4-bit codes, 2-bit weights, bf16 outputs
-                "algorithmic_bytes": round(sum(M * K / 2 + N * K / 4 + 2 * M * N for _, N, K in a4) / len(a4)),
+                "algorithmic_bytes": round(sum(M * K / 2 + N * K / 4 + out_bytes(n_, N) for n_, N, K in a4) / len(a4)),
                 # what this kernel's formats move: the INT4 levels travel as 6-bit E3M2 codes
-                "format_bytes": round(sum(M * K * 3 / 4 + N * K / (4 if args.a4_weights == "mx2" else 2) + 2 * M * N
-                                          for _, N, K in a4) / len(a4)),
+                "format_bytes": round(sum(M * K * 3 / 4 + N * K / (4 if args.a4_weights == "mx2" else 2) + out_bytes(n_, N)
+                                          for n_, N, K in a4) / len(a4)),
                 "avg_launch_ms": round(a4_ms / len(a4), 4)}
 
     out = {
@@ -243,12 +269,13 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "int8+fp6xfp4",
         "data": "synthetic (seeded; N(0,1) + heavy-tailed outlier channels, bf16)",
         "config": {"workload": "7B prefill block: %d tokens x {qkv 4096->12288 A4, o 4096->4096 A8s, "
-                               "gate/up 4096->11008 A4 (one shared quantized input), down 11008->4096 A8s}, "
-                               "quantize + GEMM" % M,
-                   "tokens": M},
+                               "gate/up 4096->11008 A4 (one shared quantized input%s), down 11008->4096 A8s}, "
+                               "quantize + GEMM" % (M, "; one GEMM, ReLU^2 GLU in its epilogue, H written" if fused else ""),
+                   "tokens": M, "ffn_front": args.ffn},
         "roofline": roofline,
         "kernels": per_kernel,
     }
+    out["ffn_front"] = ffn_front_bench(B, L, torch, M, x_hidden, bufs["gate"], W, A4L, H_ffn, stream)
     if not args.no_decode:
         out["decode"] = decode_bench(B, S, torch, dev, tokens=tuple(args.decode_tokens))
         out["decode_ffn_1token"] = decode_ffn_bench(B, S, torch, dev)
@@ -258,6 +285,54 @@ def main():
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
+
+
+def ffn_front_bench(B, L, torch, M, X, b, W, A4L, H, stream, iters=20):
+    """From the input of an FFN block to the quantized input of its down projection, two ways on the same
+    buffers: (a) gate GEMM, up GEMM (G and U written as bfloat16), then the Top_k + INT8 quantizer
+    that forms eq. 5 while it loads G and U; (b) one GEMM over both weight matrices with eq. 5 in its
+    epilogue (H written), then the Top_k + INT8 quantizer on H.  The INT4 quantizer of the input is
+    common to both and left out."""
+    dev = X.device
+    G = torch.empty((M, FFN), dtype=torch.bfloat16, device=dev)
+    U = torch.empty((M, FFN), dtype=torch.bfloat16, device=dev)
+    q8 = torch.empty(L.quantize_act_bytes(B.BL_ACT_TOPK_INT8_ABSMAX, M, FFN), dtype=torch.uint8, device=dev)
+    s8 = torch.empty(M, dtype=torch.float32, device=dev)
+    rc = L.quantize_act(X.data_ptr(), B.BL_BF16, M, HIDDEN, b["mode"], 0, EPS, b["q"].data_ptr(),
+                        b["scale"].data_ptr(), None, None, stream)
+    assert rc == 0
+
+    def three():
+        for name, Y in (("gate", G), ("up", U)):
+            rc = L.bitlinear_gemm(b["q"].data_ptr(), b["scale"].data_ptr(), b["mode"], M, HIDDEN, W[name][0].data_ptr(),
+                                  A4L, W[name][1].data_ptr(), FFN, Y.data_ptr(), B.BL_BF16, None, None, 0, stream)
+            assert rc == 0, rc
+        rc = L.quantize_act_glu(G.data_ptr(), U.data_ptr(), B.BL_BF16, M, FFN, FFN // 2, EPS, q8.data_ptr(),
+                                s8.data_ptr(), None, stream)
+        assert rc == 0, rc
+
+    def fused():
+        rc = B.gemm_a4_glu_prequantized(L, b["q"], b["scale"], M, HIDDEN, W["gate"], W["up"], A4L, FFN, H, stream)
+        assert rc == 0, rc
+        rc = L.quantize_act(H.data_ptr(), B.BL_BF16, M, FFN, B.BL_ACT_TOPK_INT8_ABSMAX, FFN // 2, EPS, q8.data_ptr(),
+                            s8.data_ptr(), None, None, stream)
+        assert rc == 0, rc
+
+    res = {}
+    for label, fn in (("two_gemms_then_glu_quantizer_ms", three), ("glu_gemm_then_quantizer_ms", fused)):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[label] = round(e0.elapsed_time(e1) / iters, 4)
+    res["bytes_written_and_reread_between"] = {"two_gemms": 2 * 2 * M * FFN * 2, "glu_gemm": 2 * M * FFN * 2}
+    return res
 
 
 def decode_ffn_bench(B, S, torch, dev, layers=8, replays=20):

@@ -266,13 +266,23 @@ int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M
  *   workspace  device, >= bitlinear_gate_up_workspace_bytes(M, N, K, layout) bytes (packed activations,
  *              scales, decode partial sums, and float32 G and U where H is wanted without them)
  * Up to 8 bfloat16 tokens with BL_W_GEMM weights (K % 8 == 0, K <= 8192) run as one launch that
- * streams both matrices once and uses no workspace (it may then be NULL); other shapes run the
- * quantizer, the two products and the combine as separate kernels. */
+ * streams both matrices once and uses no workspace (it may then be NULL).  With block-float weights
+ * (BL_W_MX4 / BL_W_MX2) and only H asked for, the quantizer is followed by one GEMM over both
+ * matrices whose epilogue applies eq. 5 to its accumulators: G and U never reach memory.  Other
+ * cases run the quantizer, the two products and the combine as separate kernels. */
 size_t bitlinear_gate_up_workspace_bytes(int64_t M, int64_t N, int64_t K, bl_w_layout layout);
 int bitlinear_a4_gate_up(const void* X, bl_dtype x_dtype, int64_t M, int64_t K, const void* W_gate,
                          const float* alpha_gate, const void* W_up, const float* alpha_up,
                          bl_w_layout layout, int64_t N, float eps, void* G, void* U, bl_dtype gu_dtype,
                          void* H, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The product stage of bitlinear_a4_gate_up alone, on activations already quantized by quantize_act in
+ * mode BL_ACT_INT4_ABSMEAN_MX6: one GEMM over both weight matrices (BL_W_MX4 or BL_W_MX2, [N, K] each)
+ * whose epilogue writes H = bf16(U * max(G, 0)^2) (eq. 5 on the rescaled float32 accumulators); G and U
+ * are not written.  H device [M, N] bfloat16.  Other layouts: BL_EUNSUPPORTED. */
+int bitlinear_gemm_glu(const void* q, const float* scale, int64_t M, int64_t K, const void* W_gate,
+                       const float* alpha_gate, const void* W_up, const float* alpha_up,
+                       bl_w_layout layout, int64_t N, void* H, void* stream);
 
 /* Gate-first up projection of the FFN for a few tokens (Section 2.1's observation that the up
  * projection is only needed where the gate is open, eq. 5): with G = the gate projection's

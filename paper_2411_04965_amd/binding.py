@@ -50,6 +50,7 @@ _SIGNATURES = {
     "bitlinear_gate_up_workspace_bytes": (_sz, [_i64, _i64, _i64, _int]),
     "bitlinear_a4_gate_up": (_int, [_vp, _int, _i64, _i64, _vp, _vp, _vp, _vp, _int, _i64, _f32, _vp, _vp, _int,
                                     _vp, _vp, _sz, _vp]),
+    "bitlinear_gemm_glu": (_int, [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _int, _i64, _vp, _vp]),
     "bitlinear_a4_up_gated": (_int, [_vp, _i64, _i64, _vp, _vp, _i64, _f32, _vp, _int, _vp, _vp]),
     "unpack_ternary": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
     "unpack_act": (_int, [_vp, _int, _i64, _i64, _vp, _vp]),
@@ -258,6 +259,12 @@ def bitlinear_a4_gate_up(X, W_gate, alpha_gate, W_up, alpha_up, N, eps=DEFAULT_E
         _ptr(X), _dt(X), M, K, _ptr(W_gate), _ptr(alpha_gate), _ptr(W_up), _ptr(alpha_up), layout, N, eps,
         _ptr(G), _ptr(U), gdt, _ptr(H), _ptr(ws), ws.numel(), _stream()))
     return out
+
+
+def gemm_a4_glu_prequantized(L, q, scale, M, K, Wg, Wu, layout, N, H, stream):
+    """Raw call of bitlinear_gemm_glu on preallocated buffers (Wg, Wu = (packed, alpha) pairs); returns the status."""
+    return L.bitlinear_gemm_glu(q.data_ptr(), scale.data_ptr(), M, K, Wg[0].data_ptr(), Wg[1].data_ptr(),
+                                Wu[0].data_ptr(), Wu[1].data_ptr(), layout, N, H.data_ptr(), stream)
 
 
 def bitlinear_a4_up_gated(X, W_rows, alpha, N, G, eps=DEFAULT_EPS):

@@ -446,6 +446,13 @@ extern "C" int bitlinear_a4_gate_up(const void* X, bl_dtype x_dtype, int64_t M, 
   void* ws2 = p;
   const size_t ws2_bytes = ws_align(stage2_ws_bytes(mode, M, N, K));
   p += ws2_bytes;
+  // block-float weights and only H wanted: one GEMM over both matrices with eq. 5 in its epilogue
+  if (mx_layout(layout) && H && !G && !U) {
+    rc = bl_launch_quantize(X, x_dtype, M, K, mode, 0, eps, codes, scales, nullptr, nullptr, s);
+    if (rc) return rc;
+    return bl_launch_gemm_a4_mx_glu(codes, (const float*)scales, M, K, W_gate, alpha_gate, W_up, alpha_up,
+                                    layout == BL_W_MX2, N, H, s);
+  }
   // when H is wanted the products are kept in float32 (eq. 5 combines them before any rounding)
   const bool need_f32 = H != nullptr && gu_dtype != BL_F32;
   void* Gt = G;
@@ -474,6 +481,20 @@ extern "C" int bitlinear_a4_gate_up(const void* X, bl_dtype x_dtype, int64_t M, 
     BL_HIP_CHECK_LAUNCH();
   }
   return BL_OK;
+}
+
+extern "C" int bitlinear_gemm_glu(const void* q, const float* scale, int64_t M, int64_t K, const void* W_gate,
+                                  const float* alpha_gate, const void* W_up, const float* alpha_up,
+                                  bl_w_layout layout, int64_t N, void* H, void* stream) {
+  if (!q || !scale || !W_gate || !alpha_gate || !W_up || !alpha_up || !H) return BL_EINVAL;
+  if (!valid_layout(layout)) return BL_EINVAL;
+  if (!mx_layout(layout)) return BL_EUNSUPPORTED;
+  int rc = check_sizes(M, N, K);
+  if (rc) return rc;
+  if (!bl_aligned16(q) || !bl_aligned16(W_gate) || !bl_aligned16(W_up) || !bl_aligned16(H)) return BL_EALIGN;
+  if (reinterpret_cast<uintptr_t>(scale) & 3) return BL_EALIGN;
+  return bl_launch_gemm_a4_mx_glu(q, scale, M, K, W_gate, alpha_gate, W_up, alpha_up, layout == BL_W_MX2, N, H,
+                                  (hipStream_t)stream);
 }
 
 extern "C" int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const void* W_rows,

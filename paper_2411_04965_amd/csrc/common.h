@@ -166,6 +166,8 @@ size_t bl_gemv_sparse_ws_bytes(int64_t M, int64_t N, int64_t K);
 int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K, const void* Wp, bool w2,
                          const float* alpha, int64_t N, void* Y, bl_dtype ydt, int32_t* acc_out,
                          hipStream_t s);
+int bl_launch_gemm_a4_mx_glu(const void* q, const float* scale, int64_t M, int64_t K, const void* Wg, const float* ag,
+                             const void* Wu, const float* au, bool w2, int64_t N, void* H, hipStream_t s);
 int bl_launch_gemm_fp4_mx(const void* q, const uint8_t* xscale, int64_t M, int64_t K, const void* Wp, bool w2,
                           const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);
 int bl_launch_gemm_fp4(const void* q, const uint8_t* scale, int64_t M, int64_t K, const void* Wp,

@@ -73,12 +73,20 @@ __device__ __forceinline__ u32 gx_pack_bf16(float lo, float hi) {
 // in registers behind the fragment read (3 vector instructions per 16 channels) instead of being
 // stored expanded: half the weight bytes from HBM, L2 and LDS, two instead of four pieces per
 // wave and step.
-template <int OUT, bool ACC, bool FP4, bool W2>
+// GLU: gate and up projection of an FFN in one pass with eq. 5 in the epilogue.  Wp / Wp2 are the gate
+// and the up weights ([N, K] each); a 256-column tile is 128 outputs of both: weight rows 64 w .. 64 w + 63
+// of the tile (the rows wave w stages) are gate outputs for even w and up outputs for odd w, of the
+// same 64 outputs, so the wave that owns columns 128 wn .. holds G in its column tiles 0, 1 and U of
+// the same outputs in its column tiles 2, 3.  The epilogue forms H = bf16(U * max(G, 0)^2) from the
+// rescaled float32 values (the order of relu2_glu) and writes H[M, N] only; G and U never leave
+// the registers.
+template <int OUT, bool ACC, bool FP4, bool W2, bool GLU = false>
 __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale,
     const unsigned char* __restrict__ xsc, int M, int KB,
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N, void* __restrict__ Y,
-    int y_bf16, int32_t* __restrict__ acc_out, int MT, int NTB) {
+    int y_bf16, int32_t* __restrict__ acc_out, int MT, int NTB,
+    const unsigned char* __restrict__ Wp2 = nullptr, const float* __restrict__ alpha2_p = nullptr) {
   extern __shared__ __align__(16) unsigned char gx_smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -107,6 +115,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     for (int i = 0; i < 2; ++i) {
       // row blocks past the end of an operand re-read its last block (their results are never stored)
       if (is_a) c.p[i] = A + (size_t)min((m0 >> 5) + 2 * wave + i, MB - 1) * KB * A_BLOCK;
+      else if (GLU) c.p[i] = ((wave & 1) ? Wp2 : Wp) + (size_t)min((n0 >> 6) + 2 * (wave >> 1) + i, NB - 1) * KB * W_BLOCK;
       else c.p[i] = Wp + (size_t)min((n0 >> 5) + 2 * wave + i, NB - 1) * KB * W_BLOCK;
     }
   };
@@ -317,7 +326,7 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
   while (true) {
     const int next = tile + (int)gridDim.x;
     const bool has_next = next < n_tiles;
-    const bool interior = (m0 + GX_BM <= M) && (n0 + GX_BN <= N);
+    const bool interior = (m0 + GX_BM <= M) && (GLU ? (n0 >> 1) + GX_BN / 2 <= N : n0 + GX_BN <= N);
     v16f acc[TN][TM];
     // Per-token scales of this tile, fetched now: a global load inside the epilogue would have
     // to wait for the stores issued before it (loads and stores share one counter).
@@ -416,6 +425,78 @@ __global__ __launch_bounds__(GX_THREADS, 1) void gemm_a4_mx_kernel(
     // ---- epilogue.  acc[a][b][r] is output n = 32 a + 8 (r / 4) + 4 lh + r % 4 of token
     // m = 32 b + l32 (relative to the wave tile).  bf16 rows leave through an LDS transpose
     // (its own space behind the stages) so that every store instruction writes whole lines.
+    if constexpr (GLU) {
+      // acc[a][b] (a = 0, 1) is G and acc[a + 2][b] is U of output n = n0 / 2 + 64 wn + 32 a + 8 (r / 4) +
+      // 4 lh + r % 4, token m = 32 b + l32 of the wave tile
+      const float alpha2 = alpha2_p[0];
+      const int nw = (n0 >> 1) + wn * (WN / 2);                // first H column of this wave
+      if (OUT == 0) {
+        constexpr int TB_ROW = WN + 32;                      // 64 bfloat16 per token + padding
+        unsigned char* tbuf = gx_smem + GX_TB + wave * (32 * (WN * 2 + 32));
+        constexpr int LANES_PER_ROW = WN / 16;               // 8 lanes cover one token's 128 bytes
+        constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+        constexpr int NPASS = 32 / ROWS_PER_PASS;
+        const int rr = lane / LANES_PER_ROW, cc = lane % LANES_PER_ROW;
+        uint16_t* ywave = (uint16_t*)Y + (size_t)(m0 + wm * WM) * N + nw;
+        const u32 lane_off = (u32)rr * (u32)N + cc * 8;
+        const int m_left = M - (m0 + wm * WM) - rr, n_left = N - nw - cc * 8;
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+          const float d = dsc[b];
+#pragma unroll
+          for (int a = 0; a < TN / 2; ++a) {
+            asm volatile("" : "+a"(acc[a][b]));
+            asm volatile("" : "+a"(acc[a + 2][b]));
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              float hv[4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const float g = (acc[a][b][4 * q4 + r] * d) * alpha;
+                const float u = (acc[a + 2][b][4 * q4 + r] * d) * alpha2;
+                const float rl = fmaxf(g, 0.0f);
+                const float rr2 = rl * rl;
+                hv[r] = u * rr2;
+              }
+              uint2 p;
+              p.x = gx_pack_bf16(hv[0], hv[1]);
+              p.y = gx_pack_bf16(hv[2], hv[3]);
+              *reinterpret_cast<uint2*>(tbuf + l32 * TB_ROW + (a * 32 + 8 * q4 + 4 * lh) * 2) = p;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+#pragma unroll
+          for (int i = 0; i < NPASS; ++i) {
+            const int row = b * 32 + i * ROWS_PER_PASS;
+            const v4i v = *reinterpret_cast<const v4i*>(tbuf + (rr + i * ROWS_PER_PASS) * TB_ROW + cc * 16);
+            if (interior || (row < m_left && 0 < n_left)) *reinterpret_cast<v4i*>(ywave + (size_t)row * N + lane_off) = v;
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+          const int m = m0 + wm * WM + b * 32 + l32;
+          const float d = dsc[b];
+#pragma unroll
+          for (int a = 0; a < TN / 2; ++a) {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const int n = nw + a * 32 + 8 * q4 + 4 * lh;
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const float g = (acc[a][b][4 * q4 + r] * d) * alpha;
+                const float u = (acc[a + 2][b][4 * q4 + r] * d) * alpha2;
+                const float rl = fmaxf(g, 0.0f);
+                const float rr2 = rl * rl;
+                if (m < M && n + r < N) ((uint16_t*)Y)[(size_t)m * N + n + r] = bl_f32_to_bf16_rne(u * rr2);
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
+    } else
     if (OUT == 0) {
       constexpr int TB_ROW = WN * 2 + 32;
       unsigned char* tbuf = gx_smem + GX_TB + wave * (32 * TB_ROW);
@@ -556,6 +637,31 @@ int bl_launch_gemm_a4_mx(const void* q, const float* scale, int64_t M, int64_t K
   if (acc_out) return out == 0 ? GX_CALL(0, true) : out == 1 ? GX_CALL(1, true) : GX_CALL(2, true);
   return out == 0 ? GX_CALL(0, false) : out == 1 ? GX_CALL(1, false) : GX_CALL(2, false);
 #undef GX_CALL
+}
+
+// Gate and up projection with the ReLU^2 GLU in the epilogue: H[M, N] bfloat16 from INT4 activations in the
+// MX6 form and two weight matrices [N, K] in the same block-float layout.
+template <int OUT, bool W2>
+static int gx_go_glu(const void* q, const float* scale, int M, int KB, const void* Wg, const float* ag, const void* Wu,
+                     const float* au, int N, void* H, int MT, int NTB, hipStream_t s) {
+  BL_SET_MAX_LDS_ONCE((gemm_a4_mx_kernel<OUT, false, false, W2, true>), GX_LDS);
+  const int grid = min(MT * NTB, bl_num_cus());
+  gemm_a4_mx_kernel<OUT, false, false, W2, true><<<(unsigned)grid, GX_THREADS, GX_LDS, s>>>(
+      (const unsigned char*)q, scale, nullptr, M, KB, (const unsigned char*)Wg, ag, N, H, 1, nullptr, MT, NTB,
+      (const unsigned char*)Wu, au);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}
+
+int bl_launch_gemm_a4_mx_glu(const void* q, const float* scale, int64_t M, int64_t K, const void* Wg, const float* ag,
+                             const void* Wu, const float* au, bool w2, int64_t N, void* H, hipStream_t s) {
+  const int KB = (int)(bl_round_up(K, BL_KPAD) / 128);
+  const int MT = (int)((M + GX_BM - 1) / GX_BM), NTB = (int)((N + GX_BN / 2 - 1) / (GX_BN / 2));
+  const bool rows = (N & 7) == 0;
+  if (w2) return rows ? gx_go_glu<0, true>(q, scale, (int)M, KB, Wg, ag, Wu, au, (int)N, H, MT, NTB, s)
+                      : gx_go_glu<2, true>(q, scale, (int)M, KB, Wg, ag, Wu, au, (int)N, H, MT, NTB, s);
+  return rows ? gx_go_glu<0, false>(q, scale, (int)M, KB, Wg, ag, Wu, au, (int)N, H, MT, NTB, s)
+              : gx_go_glu<2, false>(q, scale, (int)M, KB, Wg, ag, Wu, au, (int)N, H, MT, NTB, s);
 }
 
 // FP4 activations (E2M1 codes and E8M0 block scales in the MX form) x BL_W_MX4 weights.

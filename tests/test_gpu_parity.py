@@ -534,7 +534,9 @@ def test_decode_stream_codes_from_quantizer(M, N, K, kind):
                                           (8, 5460, 2048, B.BL_W_GEMM), (3, 37, 256, B.BL_W_GEMM),
                                           (2, 2050, 1000, B.BL_W_GEMM), (8, 16400, 512, B.BL_W_GEMM),
                                           (20, 1040, 2048, B.BL_W_GEMM), (130, 520, 1000, B.BL_W_MX2),
-                                          (70, 300, 512, B.BL_W_GEMM)])
+                                          (70, 300, 512, B.BL_W_GEMM), (300, 5460, 2048, B.BL_W_MX2),
+                                          (257, 330, 1504, B.BL_W_MX4), (513, 333, 256, B.BL_W_MX2),
+                                          (2048, 5460, 2048, B.BL_W_MX2)])
 def test_gate_up(M, N, K, layout):
     """Gate and up projection on one quantized input (eq. 5-7): G, U and H = bf16(U * max(G, 0)^2)
     against the oracle's two linears and its GLU, bit for bit -- the one-launch form for up to 8
@@ -697,6 +699,27 @@ def test_config3_prefill_sampled_rows(name, N, K, kind):
     y_ref = O.rescale(acc_ref, d, alpha, "bf16")
     assert_close_rel(host(Y[idx]), y_ref)
     assert np.array_equal(host(Y[idx]), y_ref)
+
+
+def test_config3_gate_up_glu_sampled_rows():
+    """The FFN's gate and up projection as one GEMM with eq. 5 in its epilogue, at M = 16384 in the launch
+    configuration the benchmark times: H on 128 sampled token rows against the oracle's two linears and
+    its GLU, bit for bit."""
+    say("config 3 gate/up GEMM with the GLU epilogue")
+    M, N, K = 16384, 11008, 4096
+    Tg, ag_ref, packs_g = _decode_weights("gate", N, K)
+    Tu, au_ref, packs_u = _decode_weights("up", N, K)
+    X = S.heavy(M, K, S.seed_for(3, 1))
+    rows = np.random.default_rng(S.seed_for(3, 9)).choice(M, 128, replace=False)
+    rows[:2] = (0, M - 1)
+    q, d = O.quant_int4(X[rows], EPS)
+    g = O.rescale(O.matmul_int(q, Tg), d, ag_ref, "f32")
+    u = O.rescale(O.matmul_int(q, Tu), d, au_ref, "f32")
+    h_ref = O.relu2_glu(g, u)
+    pg, ag = packs_g[B.BL_W_MX2]
+    pu, au = packs_u[B.BL_W_MX2]
+    r = B.bitlinear_a4_gate_up(dev(X, BF16), pg, ag, pu, au, N, EPS, B.BL_W_MX2, want=("H",))
+    assert np.array_equal(host(r["H"][torch.from_numpy(rows).cuda()]), h_ref)
 
 
 @pytest.mark.parametrize("name,N,K,kind", [("qkv", 12288, 4096, "a4"), ("down", 4096, 11008, "a8s")])
