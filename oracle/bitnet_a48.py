@@ -168,6 +168,65 @@ def quant_heads(X, bits, eps=DEFAULT_EPS):
     return codes, d
 
 
+def dequant_heads(codes, d, bits):
+    """Value a low-bit attention code stands for (Section 4.2; the reading of quant_heads):
+    (code - 2^(bits-1)) * d, one float32 multiply.  codes uint8 [T, H, D], d float32 [T, H]."""
+    assert bits in (3, 4)
+    q = codes.astype(np.int16) - 2 ** (bits - 1)
+    return (q.astype(F32) * np.asarray(d, dtype=F32)[:, :, None]).astype(F32)
+
+
+def _pack_bits_le(codes, bits):
+    """One head's codes -> bytes of its little-endian bit stream (code j in bits bits*j ...)."""
+    acc = 0
+    for j, c in enumerate(int(v) for v in codes):
+        acc |= c << (bits * j)
+    n = (len(codes) * bits + 7) // 8
+    return [(acc >> (8 * i)) & 255 for i in range(n)]
+
+
+def kv_cache_pack(X, eps=DEFAULT_EPS):
+    """The 3-bit key / value cache of Table 3 ("4-bit Q, 3-bit KV": "the heads of the bos token"
+    stay at 4 bits, Section 4.2): token 0 of the sequence is quantized per head to 4 bits, every later
+    token to 3 bits, all with quant_heads.  Byte layout (this build's; the paper defines none):
+    token 0 takes H * D / 2 bytes, every later token H * 3 D / 8 bytes, tokens in order, heads in
+    order inside a token, a head's codes as a little-endian bit stream (code j in bits bits*j ...).
+
+    X [T, H, D] (D % 8 == 0) -> (bytes uint8 [H*D/2 + (T-1)*H*3D/8], d float32 [T, H])."""
+    X = np.asarray(X, dtype=F32)
+    T, H, D = X.shape
+    assert D % 8 == 0
+    out = []
+    d = np.zeros((T, H), dtype=F32)
+    for t in range(T):
+        bits = 4 if t == 0 else 3
+        c, dt = quant_heads(X[t:t + 1], bits, eps)
+        d[t] = dt[0]
+        for h in range(H):
+            out.extend(_pack_bits_le(c[0, h], bits))
+    return np.array(out, dtype=np.uint8), d
+
+
+def kv_cache_unpack(raw, d, T, H, D):
+    """Inverse of kv_cache_pack's layout followed by dequant_heads: float32 values [T, H, D]."""
+    raw = [int(v) for v in np.asarray(raw, dtype=np.uint8)]
+    out = np.zeros((T, H, D), dtype=F32)
+    pos = 0
+    for t in range(T):
+        bits = 4 if t == 0 else 3
+        nb = D * bits // 8
+        codes = np.zeros((1, H, D), dtype=np.uint8)
+        for h in range(H):
+            acc = 0
+            for i in range(nb):
+                acc |= raw[pos + i] << (8 * i)
+            pos += nb
+            for j in range(D):
+                codes[0, h, j] = (acc >> (bits * j)) & (2 ** bits - 1)
+        out[t] = dequant_heads(codes, d[t:t + 1], bits)[0]
+    return out
+
+
 # E2M1 magnitudes by 3-bit code (1 sign, 2 exponent, 1 mantissa bit).
 E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float64)
 FP4_BLOCK = 32

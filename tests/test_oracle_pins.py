@@ -586,6 +586,54 @@ def test_quant_heads(bits):
         assert np.array_equal(d.reshape(15), d7)
 
 
+def test_kv_cache_mixed_width():
+    """Table 3's 3-bit key / value cache with the first token's heads at 4 bits: the hand-worked
+    two-token example (literal bytes), a bit-by-bit decode of the layout in plain Python, exact-rational
+    dequantization, and the properties of a uniform quantizer."""
+    g = GOLD["kv_cache"]
+    x = np.array(g["x"], F32)
+    raw, d = O.kv_cache_pack(x, 0.0)
+    assert raw.tolist() == g["bytes"] and d.reshape(-1).tolist() == g["scales"]
+    assert O.quant_heads(x[:1], 4, 0.0)[0][0, 0].tolist() == g["codes_token0"]
+    assert O.quant_heads(x[1:], 3, 0.0)[0][0, 0].tolist() == g["codes_token1"]
+    assert np.array_equal(O.kv_cache_unpack(raw, d, 2, 1, 8), np.array(g["values"], F32))
+    # seeded tokens: sizes, every code recovered bit by bit from the documented layout, values as
+    # exact rationals (code - offset) * d rounded once to float32
+    rng = np.random.default_rng(61)
+    T, H, D = 5, 3, 24
+    X = rng.standard_normal((T, H, D)).astype(F32)
+    X[2, 1] *= 30
+    X[3, 0] = 0
+    raw, d = O.kv_cache_pack(X, EPS)
+    assert raw.size == H * D // 2 + (T - 1) * H * 3 * D // 8 and d.shape == (T, H)
+    bits_all = "".join(format(int(b), "08b")[::-1] for b in raw)          # bit i of the stream at index i
+    pos = 0
+    vals = O.kv_cache_unpack(raw, d, T, H, D)
+    for t in range(T):
+        bits = 4 if t == 0 else 3
+        codes, dt = O.quant_heads(X[t:t + 1], bits, EPS)
+        assert np.array_equal(dt[0], d[t])
+        for h in range(H):
+            for j in range(D):
+                code = int(bits_all[pos:pos + bits][::-1], 2)
+                pos += bits
+                assert code == int(codes[0, h, j])
+                want = f32(float(Fraction(code - 2 ** (bits - 1)) * Fraction(float(d[t, h]))))
+                assert vals[t, h, j] == want
+    assert pos == 8 * raw.size
+    # within half a step of the input (plus the eps shrink), zero head -> zeros, sign symmetry
+    assert np.all(np.abs(vals - X) <= 0.5 * d[:, :, None] * (1 + 1e-4) + 1e-5)
+    assert not vals[3, 0].any()
+    rawn, dn = O.kv_cache_pack(-X, EPS)
+    assert np.array_equal(O.kv_cache_unpack(rawn, dn, T, H, D), -vals)
+    # dequant_heads alone: the uniform-width form
+    for bits in (4, 3):
+        c, dd = O.quant_heads(X, bits, EPS)
+        v = O.dequant_heads(c, dd, bits)
+        off = 2 ** (bits - 1)
+        assert np.array_equal(v, ((c.astype(np.float64) - off) * dd[:, :, None].astype(np.float64)).astype(F32))
+
+
 def test_up_projection_sparsity_composition():
     """The gate-first up projection needs a multiply only where the input code and the gate are both
     non-zero; the paper's 7B figures (12.0 % zero codes, 67.5 % closed gates) compose to its 71.4 %.
