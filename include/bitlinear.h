@@ -307,7 +307,7 @@ int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const void* W_row
  *     gamma = max|x| over the head;  q = RoundClip(x * (Q_b / (gamma + eps)), -Q_b, Q_b);
  *     code = q + 2^(bits-1), in [1, 2^bits - 1];  scale_out = gamma / Q_b
  * (the value a code stands for is (code - 2^(bits-1)) * scale).  The paper's 3-bit cache keeps the
- * first token's heads at 4 bits: call once for that token with bits = 4 and once for the others.
+ * first token's heads at 4 bits: kv_cache_append below writes that mixed-width form.
  *   X          device, [T, H, D] of x_dtype, 16-byte aligned, D % 8 == 0, D <= BL_MAX_K
  *   q_out      device, quantize_heads_bytes(bits, T, H, D) = T * H * D * bits / 8 bytes, 16-byte
  *              aligned: per head D * bits / 8 bytes, heads in [T, H] order; code j of a head in
@@ -319,6 +319,31 @@ int bitlinear_a4_up_gated(const void* X, int64_t M, int64_t K, const void* W_row
 size_t quantize_heads_bytes(int bits, int64_t T, int64_t H, int64_t D);
 int quantize_heads(const void* X, bl_dtype x_dtype, int64_t T, int64_t H, int64_t D, int bits, float eps,
                    void* q_out, float* scale_out, void* stream);
+
+/* The value a code of quantize_heads stands for: out = (code - 2^(bits-1)) * scale, one float32
+ * multiply (and one rounding to bfloat16 if out_dtype is BL_BF16).
+ *   q, scale   the outputs of quantize_heads for [T, H, D] at `bits`
+ *   out        device, [T, H, D] of out_dtype, 16-byte aligned */
+int dequantize_heads(const void* q, const float* scale, int64_t T, int64_t H, int64_t D, int bits,
+                     void* out, bl_dtype out_dtype, void* stream);
+
+/* Key / value cache of one sequence at 3 bits with the first token's heads at 4 bits (Table 3: "4-bit Q,
+ * 3-bit KV", the heads of the bos token kept at 4 bits; Section 4.2).  The paper defines no storage
+ * format; this one is: the token at position 0 takes H * D / 2 bytes (4-bit codes), every later token
+ * H * 3 D / 8 bytes (3-bit codes), tokens in order of position, heads in order inside a token, a head's
+ * codes as quantize_heads writes them; the token at position p > 0 starts at byte
+ * H * D / 2 + (p - 1) * H * 3 D / 8.  Scales: float32 [positions, H].  D % 32 == 0.
+ *   kv_cache_bytes(T, H, D)   bytes of the codes of T positions
+ *   kv_cache_append           quantizes X [T, H, D] (the tokens at positions pos0 .. pos0 + T - 1) into
+ *                             `cache` and scales[pos0 ..]: position 0 at 4 bits, the others at 3
+ *   kv_cache_read             out [T, H, D] = the values of positions pos0 .. pos0 + T - 1 (dequantize_heads'
+ *                             arithmetic)
+ * cache, X, out 16-byte aligned.  Errors: BL_EINVAL, BL_ESHAPE (D % 32 != 0, sizes), BL_EALIGN. */
+size_t kv_cache_bytes(int64_t T, int64_t H, int64_t D);
+int kv_cache_append(const void* X, bl_dtype x_dtype, int64_t T, int64_t H, int64_t D, int64_t pos0,
+                    float eps, void* cache, float* scales, void* stream);
+int kv_cache_read(const void* cache, const float* scales, int64_t pos0, int64_t T, int64_t H, int64_t D,
+                  void* out, bl_dtype out_dtype, void* stream);
 
 /* ReLU^2 GLU combine (eq. 5): H = bf16(U * max(G, 0)^2), float32 steps in that order.
  * G, U device [M, N] of in_dtype; H device [M, N] bfloat16. */

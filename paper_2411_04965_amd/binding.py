@@ -46,6 +46,10 @@ _SIGNATURES = {
     "swish_glu": (_int, [_vp, _vp, _int, _i64, _i64, _vp, _vp]),
     "quantize_heads_bytes": (_sz, [_int, _i64, _i64, _i64]),
     "quantize_heads": (_int, [_vp, _int, _i64, _i64, _i64, _int, _f32, _vp, _vp, _vp]),
+    "dequantize_heads": (_int, [_vp, _vp, _i64, _i64, _i64, _int, _vp, _int, _vp]),
+    "kv_cache_bytes": (_sz, [_i64, _i64, _i64]),
+    "kv_cache_append": (_int, [_vp, _int, _i64, _i64, _i64, _i64, _f32, _vp, _vp, _vp]),
+    "kv_cache_read": (_int, [_vp, _vp, _i64, _i64, _i64, _i64, _vp, _int, _vp]),
     "quantize_act_glu": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _f32, _vp, _vp, _vp, _vp]),
     "bitlinear_gate_up_workspace_bytes": (_sz, [_i64, _i64, _i64, _int]),
     "bitlinear_a4_gate_up": (_int, [_vp, _int, _i64, _i64, _vp, _vp, _vp, _vp, _int, _i64, _f32, _vp, _vp, _int,
@@ -295,6 +299,30 @@ def quantize_heads(X, bits, eps=DEFAULT_EPS):
     scale = torch.empty((T, H), dtype=torch.float32, device=X.device)
     _check("quantize_heads", L.quantize_heads(_ptr(X), _dt(X), T, H, D, bits, eps, _ptr(q), _ptr(scale), _stream()))
     return q, scale
+
+
+def dequantize_heads(q, scale, T, H, D, bits, out_dtype=torch.float32):
+    out = torch.empty((T, H, D), dtype=out_dtype, device=q.device)
+    _check("dequantize_heads", lib().dequantize_heads(_ptr(q), _ptr(scale), T, H, D, bits, _ptr(out), _dt(out), _stream()))
+    return out
+
+
+def kv_cache_new(T_max, H, D, device):
+    """Empty mixed-width key / value cache for T_max positions: (codes uint8, scales float32 [T_max, H])."""
+    return (torch.zeros(lib().kv_cache_bytes(T_max, H, D), dtype=torch.uint8, device=device),
+            torch.zeros((T_max, H), dtype=torch.float32, device=device))
+
+
+def kv_cache_append(X, pos0, cache, scales, eps=DEFAULT_EPS):
+    _dev(X)
+    T, H, D = X.shape
+    _check("kv_cache_append", lib().kv_cache_append(_ptr(X), _dt(X), T, H, D, pos0, eps, _ptr(cache), _ptr(scales), _stream()))
+
+
+def kv_cache_read(cache, scales, pos0, T, H, D, out_dtype=torch.float32):
+    out = torch.empty((T, H, D), dtype=out_dtype, device=cache.device)
+    _check("kv_cache_read", lib().kv_cache_read(_ptr(cache), _ptr(scales), pos0, T, H, D, _ptr(out), _dt(out), _stream()))
+    return out
 
 
 def swish_glu(G, U):

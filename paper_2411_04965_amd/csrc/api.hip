@@ -186,6 +186,83 @@ extern "C" int quantize_heads(const void* X, bl_dtype x_dtype, int64_t T, int64_
   return bl_launch_quantize_heads(X, x_dtype, T * H, D, bits, eps, q_out, scale_out, (hipStream_t)stream);
 }
 
+extern "C" int dequantize_heads(const void* q, const float* scale, int64_t T, int64_t H, int64_t D, int bits,
+                                void* out, bl_dtype out_dtype, void* stream) {
+  if (!q || !scale || !out) return BL_EINVAL;
+  if (!valid_dtype(out_dtype) || (bits != 3 && bits != 4)) return BL_EINVAL;
+  if (T < 1 || H < 1 || D < 1) return BL_EINVAL;
+  if (D % 8 != 0 || D > BL_MAX_K) return BL_ESHAPE;
+  const int64_t lim = (int64_t)1 << 40;
+  if (T > lim / H || T * H > lim / D) return BL_ESHAPE;
+  if (!bl_aligned16(out)) return BL_EALIGN;
+  return bl_launch_dequantize_heads(q, scale, T * H, D, bits, out, out_dtype, (hipStream_t)stream);
+}
+
+// The 3-bit key / value cache with the first token's heads at 4 bits (Table 3): byte offset of the
+// token at sequence position `pos`.
+static int64_t kv_token_offset(int64_t pos, int64_t H, int64_t D) {
+  return pos == 0 ? 0 : H * (D / 2) + (pos - 1) * H * (3 * D / 8);
+}
+
+extern "C" size_t kv_cache_bytes(int64_t T, int64_t H, int64_t D) {
+  if (T < 1 || H < 1 || D < 8 || D % 8 != 0) return 0;
+  return (size_t)kv_token_offset(T, H, D);
+}
+
+static int kv_check(int64_t T, int64_t H, int64_t D, int64_t pos0) {
+  if (T < 1 || H < 1 || D < 1 || pos0 < 0) return BL_EINVAL;
+  // D % 32: every token's codes then start on a 4-byte boundary, which the quantizer's stores need
+  if (D % 32 != 0 || D > BL_MAX_K) return BL_ESHAPE;
+  const int64_t lim = (int64_t)1 << 40;
+  if (pos0 > lim - T || (pos0 + T) > lim / H || (pos0 + T) * H > lim / D) return BL_ESHAPE;
+  if (!bl_grid_ok((T * H + 3) / 4)) return BL_ESHAPE;
+  return BL_OK;
+}
+
+extern "C" int kv_cache_append(const void* X, bl_dtype x_dtype, int64_t T, int64_t H, int64_t D, int64_t pos0,
+                               float eps, void* cache, float* scales, void* stream) {
+  if (!X || !cache || !scales) return BL_EINVAL;
+  if (!valid_dtype(x_dtype) || !(eps >= 0.0f)) return BL_EINVAL;
+  int rc = kv_check(T, H, D, pos0);
+  if (rc) return rc;
+  if (!bl_aligned16(X) || !bl_aligned16(cache)) return BL_EALIGN;
+  const size_t esz = x_dtype == BL_BF16 ? 2 : 4;
+  const unsigned char* x = (const unsigned char*)X;
+  unsigned char* c = (unsigned char*)cache;
+  int64_t t = 0;
+  if (pos0 == 0) {                                         // the sequence's first token: 4 bits
+    rc = bl_launch_quantize_heads(x, x_dtype, H, D, 4, eps, c, scales, (hipStream_t)stream);
+    if (rc) return rc;
+    t = 1;
+  }
+  if (t < T)
+    rc = bl_launch_quantize_heads(x + (size_t)t * H * D * esz, x_dtype, (T - t) * H, D, 3, eps,
+                                  c + kv_token_offset(pos0 + t, H, D), scales + (pos0 + t) * H, (hipStream_t)stream);
+  return rc;
+}
+
+extern "C" int kv_cache_read(const void* cache, const float* scales, int64_t pos0, int64_t T, int64_t H, int64_t D,
+                             void* out, bl_dtype out_dtype, void* stream) {
+  if (!cache || !scales || !out) return BL_EINVAL;
+  if (!valid_dtype(out_dtype)) return BL_EINVAL;
+  int rc = kv_check(T, H, D, pos0);
+  if (rc) return rc;
+  if (!bl_aligned16(out)) return BL_EALIGN;
+  const size_t esz = out_dtype == BL_BF16 ? 2 : 4;
+  const unsigned char* c = (const unsigned char*)cache;
+  unsigned char* o = (unsigned char*)out;
+  int64_t t = 0;
+  if (pos0 == 0) {
+    rc = bl_launch_dequantize_heads(c, scales, H, D, 4, o, out_dtype, (hipStream_t)stream);
+    if (rc) return rc;
+    t = 1;
+  }
+  if (t < T)
+    rc = bl_launch_dequantize_heads(c + kv_token_offset(pos0 + t, H, D), scales + (pos0 + t) * H, (T - t) * H, D, 3,
+                                    o + (size_t)t * H * D * esz, out_dtype, (hipStream_t)stream);
+  return rc;
+}
+
 // ---------------------------------------------------------------- ReLU^2 GLU (eq. 5)
 template <typename RawT>
 __global__ __launch_bounds__(256) void relu2_glu_kernel(const RawT* __restrict__ G,

@@ -129,6 +129,8 @@ int bl_launch_unpack_act(const void* q, bl_act_mode mode, int64_t M, int64_t K, 
                          hipStream_t s);
 int bl_launch_quantize_heads(const void* X, bl_dtype dt, int64_t n_heads, int64_t D, int bits, float eps,
                              void* q, float* scale, hipStream_t s);
+int bl_launch_dequantize_heads(const void* q, const float* scale, int64_t n_heads, int64_t D, int bits, void* out,
+                               bl_dtype odt, hipStream_t s);
 int bl_launch_gemm_prefill(const void* q, const float* scale, bl_act_mode mode, int64_t M,
                            int64_t K, const void* Wp, const float* alpha, int64_t N, void* Y,
                            bl_dtype ydt, int32_t* acc_out, hipStream_t s);

@@ -140,3 +140,48 @@ int bl_launch_quantize_heads(const void* X, bl_dtype dt, int64_t n_heads, int64_
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;
 }
+
+// ---------------------------------------------------------------- reading the codes back
+// value = (code - 2^(bits-1)) * scale, one float32 multiply (bfloat16 outputs: one rounding more).
+// One thread per group of 8 channels: BITS bytes in, 8 values out.
+template <typename OutT, int BITS>
+__global__ __launch_bounds__(QH_THREADS) void dequant_heads_kernel(
+    const unsigned char* __restrict__ q, const float* __restrict__ scale, int64_t n_groups, int gph,
+    OutT* __restrict__ out) {
+  const int64_t g = (int64_t)blockIdx.x * QH_THREADS + threadIdx.x;
+  if (g >= n_groups) return;
+  const float d = scale[g / gph];                          // gph = groups of 8 channels per head
+  const unsigned char* p = q + g * BITS;
+  u32 v = 0;
+#pragma unroll
+  for (int b = 0; b < BITS; ++b) v |= (u32)p[b] << (8 * b);
+  constexpr int OFF = 1 << (BITS - 1);
+  float x[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) x[j] = (float)((int)((v >> (BITS * j)) & ((1u << BITS) - 1u)) - OFF) * d;
+  if (sizeof(OutT) == 2) {
+    uint4 w;
+    w.x = (u32)bl_f32_to_bf16_rne(x[0]) | ((u32)bl_f32_to_bf16_rne(x[1]) << 16);
+    w.y = (u32)bl_f32_to_bf16_rne(x[2]) | ((u32)bl_f32_to_bf16_rne(x[3]) << 16);
+    w.z = (u32)bl_f32_to_bf16_rne(x[4]) | ((u32)bl_f32_to_bf16_rne(x[5]) << 16);
+    w.w = (u32)bl_f32_to_bf16_rne(x[6]) | ((u32)bl_f32_to_bf16_rne(x[7]) << 16);
+    reinterpret_cast<uint4*>(out)[g] = w;
+  } else {
+    reinterpret_cast<float4*>(out)[2 * g] = make_float4(x[0], x[1], x[2], x[3]);
+    reinterpret_cast<float4*>(out)[2 * g + 1] = make_float4(x[4], x[5], x[6], x[7]);
+  }
+}
+
+int bl_launch_dequantize_heads(const void* q, const float* scale, int64_t n_heads, int64_t D, int bits, void* out,
+                               bl_dtype odt, hipStream_t s) {
+  const int64_t n_groups = n_heads * (D / 8);
+  const int64_t blocks = (n_groups + QH_THREADS - 1) / QH_THREADS;
+  if (!bl_grid_ok(blocks)) return BL_ESHAPE;
+  const int gph = (int)(D / 8);
+#define QH_DQ(T, B) dequant_heads_kernel<T, B><<<(unsigned)blocks, QH_THREADS, 0, s>>>((const unsigned char*)q, scale, n_groups, gph, (T*)out)
+  if (odt == BL_BF16) { if (bits == 4) QH_DQ(uint16_t, 4); else QH_DQ(uint16_t, 3); }
+  else { if (bits == 4) QH_DQ(float, 4); else QH_DQ(float, 3); }
+#undef QH_DQ
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}

@@ -290,6 +290,48 @@ def test_quantize_heads(T, H, D, dtype, bits):
 
 
 # ------------------------------------------------------------------ whole linears
+@pytest.mark.parametrize("T,H,D", [(5, 3, 128), (33, 32, 128), (9, 2, 96), (3, 2, 256)])
+@pytest.mark.parametrize("bits", [4, 3])
+def test_dequantize_heads(T, H, D, bits):
+    """Codes of the per-head quantizer read back: (code - 2^(bits-1)) * scale, bit for bit the oracle's."""
+    say("dequantize heads T=%d H=%d D=%d bits=%d" % (T, H, D, bits))
+    X = S.heavy(T, H * D, S.seed_for(5, 40 + T)).reshape(T, H, D)
+    codes, d = O.quant_heads(X, bits, EPS)
+    want = O.dequant_heads(codes, d, bits)
+    q, sc = B.quantize_heads(dev(X, BF16), bits, EPS)
+    assert np.array_equal(host(B.dequantize_heads(q, sc, T, H, D, bits, F32)), want)
+    assert np.array_equal(host(B.dequantize_heads(q, sc, T, H, D, bits, BF16)), O.bf16_round(want))
+
+
+@pytest.mark.parametrize("T,H,D,dtype", [(7, 3, 128, BF16), (40, 32, 128, BF16), (5, 2, 64, F32), (1, 4, 96, BF16)])
+def test_kv_cache_mixed_width(T, H, D, dtype):
+    """Table 3's key / value cache (first token at 4 bits, later tokens at 3): a prefill append of the first
+    tokens and one-token appends after it give the oracle's bytes and scales; whole and partial reads give
+    its values."""
+    say("kv cache T=%d H=%d D=%d" % (T, H, D))
+    X = S.heavy(T, H * D, S.seed_for(5, 60 + T)).reshape(T, H, D) if dtype == BF16 else \
+        S.gauss_outlier(T, H * D, 4, 20.0, S.seed_for(5, 61 + T)).reshape(T, H, D)
+    raw, d = O.kv_cache_pack(X, EPS)
+    vals = O.kv_cache_unpack(raw, d, T, H, D)
+    assert B.lib().kv_cache_bytes(T, H, D) == raw.size
+    cache, scales = B.kv_cache_new(T, H, D, "cuda")
+    Xd = dev(X.reshape(T, H * D), dtype).reshape(T, H, D)
+    t_pre = max(1, T // 2)
+    B.kv_cache_append(Xd[:t_pre].contiguous(), 0, cache, scales, EPS)
+    for t in range(t_pre, T):
+        B.kv_cache_append(Xd[t:t + 1].contiguous(), t, cache, scales, EPS)
+    assert np.array_equal(cache.cpu().numpy(), raw)
+    assert np.array_equal(host(scales), d)
+    assert np.array_equal(host(B.kv_cache_read(cache, scales, 0, T, H, D, F32)), vals)
+    assert np.array_equal(host(B.kv_cache_read(cache, scales, 0, T, H, D, BF16)), O.bf16_round(vals))
+    if T > 2:
+        assert np.array_equal(host(B.kv_cache_read(cache, scales, 1, T - 2, H, D, F32)), vals[1:T - 1])
+    L = B.lib()
+    assert L.kv_cache_bytes(4, 2, 12) == 0
+    assert L.kv_cache_append(Xd.data_ptr(), B.BL_BF16, 1, 2, 48, 0, EPS, cache.data_ptr(), scales.data_ptr(), None) == -2  # D % 32
+    assert L.kv_cache_read(cache.data_ptr(), scales.data_ptr(), -1, 1, H, D, Xd.data_ptr(), B.BL_BF16, None) == -1
+
+
 def _check_linear(res, ref, y_dtype):
     Y, acc = res
     assert np.array_equal(host(acc), ref["acc"]), "int32 accumulators differ"
