@@ -251,33 +251,46 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_regs_kernel(
   for (int j = 0; j < NV; ++j) {
     const int h = tid + QA_THREADS * j;          // half unit: channels 16 h .. 16 h + 15
     if (h < Kp / 16) {
-      float pf[16];                              // the levels, as floats
+      // The 16 levels as int8 bytes, four to a word.  RoundClip as round(clamp(v)) (the bounds are
+      // integers, so this equals clamp(round(v))): one float32 multiply, the clamp, and the rounding as the
+      // float32 addition of 1.5 * 2^23 (round to nearest even at integer spacing), whose low byte is the level.
+      u32 lv[4];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const u32 w4[4] = {v[j][i].x, v[j][i].y, v[j][i].z, v[j][i].w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          pf[8 * i + 2 * e] = fminf(fmaxf(rintf(__uint_as_float(w4[e] << 16) * s), -8.0f), 7.0f);   // one float32 multiply
-          pf[8 * i + 2 * e + 1] = fminf(fmaxf(rintf(__uint_as_float(w4[e] & 0xFFFF0000u) * s), -8.0f), 7.0f);
+        for (int e = 0; e < 4; e += 2) {
+          u32 rb[4];
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const float v0 = __uint_as_float(w4[e + t] << 16) * s;
+            const float v1 = __uint_as_float(w4[e + t] & 0xFFFF0000u) * s;
+            rb[2 * t] = __float_as_uint(__builtin_amdgcn_fmed3f(v0, -8.0f, 7.0f) + 12582912.0f);
+            rb[2 * t + 1] = __float_as_uint(__builtin_amdgcn_fmed3f(v1, -8.0f, 7.0f) + 12582912.0f);
+          }
+          lv[2 * i + (e >> 1)] = __builtin_amdgcn_perm(rb[1], rb[0], 0x0c0c0400u) | __builtin_amdgcn_perm(rb[3], rb[2], 0x04000c0cu);
         }
       }
-      int q[16];
-      if (!MX6 || rowsum_out) {                  // (uniform: the 6-bit codes come from the floats)
+      if (rowsum_out) {
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-          q[c] = (int)pf[c];
-          sum += q[c];
-        }
+        for (int c = 0; c < 4; ++c) sum = __builtin_amdgcn_sdot4((int)lv[c], 0x01010101, sum, false);
       }
       if (MX6) {
-        u32 w3[3] = {0u, 0u, 0u};
+        // E3M2 codes of four levels at once from two 8-entry byte tables (v_perm as the lookup): levels
+        // 0 .. 7 -> 00 0C 10 12 14 15 16 17; levels -8 .. -1, by their low three bits -> 38 37 36 35 34 32 30 2C
+        u32 t24[4];
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-          const u32 code = qa_e3m2_of_levelf(pf[c]);
-          const int bit = 6 * c;
-          w3[bit >> 5] |= code << (bit & 31);
-          if ((bit & 31) > 26) w3[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+        for (int c = 0; c < 4; ++c) {
+          const u32 sel = lv[c] & 0x07070707u;
+          const u32 pos = __builtin_amdgcn_perm(0x17161514u, 0x12100C00u, sel);
+          const u32 neg = __builtin_amdgcn_perm(0x2C303234u, 0x35363738u, sel);
+          const u32 nm = ((lv[c] >> 7) & 0x01010101u) * 255u;           // bytes of negative levels
+          const u32 cd = (neg & nm) | (pos & ~nm);
+          // four 6-bit codes in four bytes -> 24 bits
+          const u32 pr = ((cd >> 2) & 0x0FC00FC0u) | (cd & 0x003F003Fu);
+          t24[c] = (pr & 0xFFFu) | ((pr >> 4) & 0xFFF000u);
         }
+        const u32 w3[3] = {t24[0] | (t24[1] << 24), (t24[1] >> 8) | (t24[2] << 16), (t24[2] >> 16) | (t24[3] << 8)};
         const int kb = h >> 3, u = (h >> 1) & 3;
         unsigned char* b = blk + (int64_t)kb * 3072;
         u32* pp = reinterpret_cast<u32*>(b + r * 64 + ((u ^ ((r >> 2) & 3)) << 4));
@@ -289,14 +302,10 @@ __global__ __launch_bounds__(QA_THREADS) void quant_int4_regs_kernel(
           qq[0] = w3[1]; qq[1] = w3[2];
         }
       } else {
+        // nibble form: byte b of a word = level b | level 4 + b << 4
 #pragma unroll
-        for (int g = 0; g < 2; ++g) {
-          u32 word = 0;
-#pragma unroll
-          for (int b = 0; b < 4; ++b)
-            word |= (((u32)q[8 * g + b] & 15u) | (((u32)q[8 * g + 4 + b] & 15u) << 4)) << (8 * b);
-          out[2 * h + g] = word;
-        }
+        for (int g = 0; g < 2; ++g)
+          out[2 * h + g] = (lv[2 * g] & 0x0F0F0F0Fu) | ((lv[2 * g + 1] << 4) & 0xF0F0F0F0u);
       }
     }
   }
