@@ -187,6 +187,14 @@ __device__ __forceinline__ void gv_quantize_rows(const uint4 (&xr)[QM][GV_NV], i
   }
 }
 
+// Word t4 of a lane's 16 bytes of a weight tile as the A operand of one MFMA step: the four 2-bit codes
+// of each byte become four int8 values 64 T (code 00 -> 0, 01 -> 64, 11 -> -64).
+__device__ __forceinline__ v4i gv_unpack(const uint4& wc, int t4) {
+  const u32 w = t4 == 0 ? wc.x : t4 == 1 ? wc.y : t4 == 2 ? wc.z : wc.w;
+  return (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u), (int)((w << 2) & 0xC0C0C0C0u),
+               (int)(w & 0xC0C0C0C0u)};
+}
+
 // A4: the activations are INT4 levels (codes from memory: nibbles, kept in LDS as 16 q; made here: q).
 // QM = 0: codes and scales come from the stand-alone quantizer; QM > 0: `src` is the bfloat16 input
 // and eq. 7 runs here for up to QM tokens.  GLU: the two matrices are gate and up, the workgroup owns
@@ -197,7 +205,10 @@ __device__ __forceinline__ void gv_quantize_rows(const uint4 (&xr)[QM][GV_NV], i
 // Work: `upb` units (output tiles; GLU: gate/up tile pairs) per workgroup, one more for the first
 // `urem` workgroups.  A workgroup's tiles form at most two contiguous runs in memory (one per
 // matrix); its entries (output tiles) are numbered run 0 first.
-template <bool A4, int QM, bool GLU, int UNR, int TK>
+// JT > 0: the rows have exactly 8 JT tiles of 256 channels and a wave's whole share is one round, so
+// that tile u of a wave is K tile wave + 8 (u mod JT) of entry u / JT: entry changes, LDS addresses and
+// the stores of the parts are fixed when the kernel is compiled.  JT = 0: any row length, any share.
+template <bool A4, int QM, bool GLU, int UNR, int TK, int JT>
 __global__ __launch_bounds__(GV_THREADS) void gemv_stream_kernel(
     const void* __restrict__ src, const float* __restrict__ scale, int M, int K, int Kp, float eps,
     GvMat m0, GvMat m1, uint16_t* __restrict__ H, int y_bf16, int upb, int urem, int topk) {
@@ -325,6 +336,21 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_stream_kernel(
       }
     }
   }
+  // (compile-time schedule) the first tiles are expanded to int8 before the barrier: a wave that waits
+  // there for the other waves' codes would otherwise do this work after it, on the critical path
+  constexpr int NPRE = JT > 0 ? (UNR < 6 ? UNR : 6) : 1;
+  v4i wpre[NPRE][4];
+  if constexpr (JT > 0) {
+#pragma unroll
+    for (int u = 0; u < NPRE; ++u)
+      if (u / JT < NE) {                                               // wave-uniform
+#pragma unroll
+        for (int t4 = 0; t4 < 4; ++t4) {
+          wpre[u][t4] = gv_unpack(wr[u], t4);
+          asm volatile("" : "+v"(wpre[u][t4]));
+        }
+      }
+  }
   __syncthreads();
 
   // ---- the products.  Lane (li, lg) holds token li, and of a tile's 256 channels the 64 of group
@@ -343,39 +369,65 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_stream_kernel(
 #pragma unroll
     for (int t4 = 0; t4 < 4; ++t4) x[t4] = *reinterpret_cast<const v4i*>(xrow + kt * 256 + t4 * 16);
   };
-  v4i xn[4];
-  read_x(min(kt_c, KT - 1), xn);                                       // (lanes of token columns past M read token M - 1
-                                                                       //  again: their output columns are never stored)
-  for (int i0 = wave; i0 < T; i0 += GV_WAVES * UNR) {
-    if (i0 != wave) issue_round(i0);                                   // (later rounds: more tiles than 8 UNR per workgroup)
+  if constexpr (JT > 0) {
+    // a wave meets only JT different K tiles: their token fragments stay in registers
+    v4i xs[JT][4];
+#pragma unroll
+    for (int j = 0; j < JT; ++j) read_x(wave + GV_WAVES * j, xs[j]);
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-      if (i0 + GV_WAVES * u < T) {                                     // wave-uniform
-        if (e_c != cur_e) {
-          flush();
-          cur_e = e_c;
+      const int e = u / JT, j = u % JT;                                // (compile-time after unrolling)
+      if (e < NE) {                                                    // wave-uniform
+        if (j == 0) {
           acc0 = (v4i){0, 0, 0, 0};
           acc1 = (v4i){0, 0, 0, 0};
         }
-        v4i xo[4];
-#pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) xo[t4] = xn[t4];
-        kt_c += GV_WAVES;
-        while (kt_c >= KT) { kt_c -= KT; ++e_c; }
-        read_x(kt_c, xn);                                              // (past the last tile: a row inside the codes' space)
-        const uint4 wc = wr[u];
 #pragma unroll
         for (int t4 = 0; t4 < 4; ++t4) {
-          const u32 w = t4 == 0 ? wc.x : t4 == 1 ? wc.y : t4 == 2 ? wc.z : wc.w;
-          const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
-                               (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
-          if (t4 & 1) acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo[t4], acc1, 0, 0, 0);
-          else acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo[t4], acc0, 0, 0, 0);
+          v4i wo;
+          if (u < NPRE) wo = wpre[u < NPRE ? u : 0][t4];
+          else wo = gv_unpack(wr[u], t4);
+          if (t4 & 1) acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xs[j][t4], acc1, 0, 0, 0);
+          else acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xs[j][t4], acc0, 0, 0, 0);
+        }
+        if (j == JT - 1) red[(e * GV_WAVES + wave) * 64 + lane] = acc0 + acc1;
+      }
+    }
+  } else {
+    v4i xn[4];
+    read_x(min(kt_c, KT - 1), xn);                                       // (lanes of token columns past M read token M - 1
+                                                                         //  again: their output columns are never stored)
+    for (int i0 = wave; i0 < T; i0 += GV_WAVES * UNR) {
+      if (i0 != wave) issue_round(i0);                                   // (later rounds: more tiles than 8 UNR per workgroup)
+  #pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        if (i0 + GV_WAVES * u < T) {                                     // wave-uniform
+          if (e_c != cur_e) {
+            flush();
+            cur_e = e_c;
+            acc0 = (v4i){0, 0, 0, 0};
+            acc1 = (v4i){0, 0, 0, 0};
+          }
+          v4i xo[4];
+  #pragma unroll
+          for (int t4 = 0; t4 < 4; ++t4) xo[t4] = xn[t4];
+          kt_c += GV_WAVES;
+          while (kt_c >= KT) { kt_c -= KT; ++e_c; }
+          read_x(kt_c, xn);                                              // (past the last tile: a row inside the codes' space)
+          const uint4 wc = wr[u];
+  #pragma unroll
+          for (int t4 = 0; t4 < 4; ++t4) {
+            const u32 w = t4 == 0 ? wc.x : t4 == 1 ? wc.y : t4 == 2 ? wc.z : wc.w;
+            const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
+                                 (int)((w << 2) & 0xC0C0C0C0u), (int)(w & 0xC0C0C0C0u)};
+            if (t4 & 1) acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo[t4], acc1, 0, 0, 0);
+            else acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(wo, xo[t4], acc0, 0, 0, 0);
+          }
         }
       }
     }
+    flush();
   }
-  flush();
   __syncthreads();
 
   // ---- add the waves' parts, rescale, store: wave w finishes entry w (GLU: the pair w, n0 + w)
@@ -472,12 +524,12 @@ bool bl_gemv_stream_pair_ok(int64_t M, int64_t N, int64_t K, bool glu) {
   return glu ? gv_plan(M, Kp, (N + 15) / 16, 2, true, grid, smem) : gv_plan(M, Kp, 2 * ((N + 15) / 16), 1, true, grid, smem);
 }
 
-template <bool A4, int QM, bool GLU, int UNR, int TK = 0>
+template <bool A4, int QM, bool GLU, int UNR, int TK = 0, int JT = 0>
 static int gv_go2(const void* src, const float* scale, int M, int K, int Kp, float eps, const GvMat& m0,
                   const GvMat& m1, uint16_t* H, int ybf, int grid, size_t smem, hipStream_t s, int topk = 0) {
-  BL_SET_MAX_LDS_ONCE((gemv_stream_kernel<A4, QM, GLU, UNR, TK>), GV_LDS_MAX);
+  BL_SET_MAX_LDS_ONCE((gemv_stream_kernel<A4, QM, GLU, UNR, TK, JT>), GV_LDS_MAX);
   const int64_t units = GLU ? m0.NT : (int64_t)m0.NT + m1.NT;
-  gemv_stream_kernel<A4, QM, GLU, UNR, TK><<<(unsigned)grid, GV_THREADS, smem, s>>>(
+  gemv_stream_kernel<A4, QM, GLU, UNR, TK, JT><<<(unsigned)grid, GV_THREADS, smem, s>>>(
       src, scale, M, K, Kp, eps, m0, m1, H, ybf, (int)(units / grid), (int)(units % grid), topk);
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;
@@ -491,6 +543,10 @@ static int gv_go(const void* src, const float* scale, int M, int K, int Kp, floa
   const int64_t units = GLU ? m0.NT : (int64_t)m0.NT + m1.NT;
   const int64_t ne = ((units + grid - 1) / grid) * (GLU ? 2 : 1);
   const int64_t per_wave = (ne * (Kp >> 8) + GV_WAVES - 1) / GV_WAVES;
+  if ((Kp >> 8) == 16 && per_wave <= GV_UNR) {                         // 4096 channels: the compile-time schedule
+    if (per_wave <= 6) return gv_go2<A4, QM, GLU, 6, 0, 2>(src, scale, M, K, Kp, eps, m0, m1, H, ybf, grid, smem, s);
+    return gv_go2<A4, QM, GLU, GV_UNR, 0, 2>(src, scale, M, K, Kp, eps, m0, m1, H, ybf, grid, smem, s);
+  }
   if (per_wave <= 6) return gv_go2<A4, QM, GLU, 6>(src, scale, M, K, Kp, eps, m0, m1, H, ybf, grid, smem, s);
   return gv_go2<A4, QM, GLU, GV_UNR>(src, scale, M, K, Kp, eps, m0, m1, H, ybf, grid, smem, s);
 }
@@ -572,8 +628,10 @@ int bl_launch_gemv_stream_topk(const void* X, int64_t K, int64_t topk, float eps
   const int64_t per_wave = (ne * (Kp >> 8) + GV_WAVES - 1) / GV_WAVES;
   const bool small = (Kp >> 8) <= 4 * GV_WAVES;            // at most 4 chunks of 256 channels per wave
 #define GV_TK(UNRV)                                                                                                \
-  (small ? gv_go2<false, 0, false, UNRV, 4>(X, nullptr, 1, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s, (int)topk) \
-         : gv_go2<false, 0, false, UNRV, 8>(X, nullptr, 1, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s, (int)topk))
+  ((Kp >> 8) == 16 && per_wave <= UNRV                                                                             \
+       ? gv_go2<false, 0, false, UNRV, 4, 2>(X, nullptr, 1, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s, (int)topk) \
+   : small ? gv_go2<false, 0, false, UNRV, 4>(X, nullptr, 1, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s, (int)topk) \
+           : gv_go2<false, 0, false, UNRV, 8>(X, nullptr, 1, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s, (int)topk))
   if (per_wave <= 6) return GV_TK(6);
   return GV_TK(GV_UNR);
 #undef GV_TK
