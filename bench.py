@@ -63,6 +63,10 @@ def parse():
     ap.add_argument("--decode-tokens", type=int, nargs="*", default=[1, 8, 32, 64])
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-fp4", action="store_true")
+    ap.add_argument("--no-probe", action="store_true", help="skip the operand-data probe of the qkv GEMM")
+    ap.add_argument("--probe-only", action="store_true",
+                    help="run only the operand-data probe (for a counter run: its launches are then the only "
+                         "block-float GEMM launches of the process, 23 per operand setting, in order)")
     ap.add_argument("--a4-weights", choices=["mx2", "mx4"], default="mx2",
                     help="block-float weight form of the INT4 projections: 2-bit codes expanded in registers, or E2M1 nibbles")
     ap.add_argument("--ffn", choices=["fused", "separate"], default="fused",
@@ -210,6 +214,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.probe_only:
+        b = bufs["qkv"]
+        rc = L.quantize_act(x_hidden.data_ptr(), B.BL_BF16, M, HIDDEN, b["mode"], 0, EPS, b["q"].data_ptr(),
+                            b["scale"].data_ptr(), None, None, stream)
+        assert rc == 0, rc
+        print(json.dumps({"operand_data_probe": operand_data_probe(B, L, torch, M, b, W["qkv"], A4L, stream)}))
+        return
+
     if args.no_prefill:
         out = {"metric": "W1.58A4 linear TOPS (prefill) & packed-weight GB/s (decode), 7B shapes", "value": 0.0,
                "unit": "TOPS", "n_gpus": 1, "steps": 0, "warmup": 0, "ms_per_step": 0.0, "higher_is_better": True,
@@ -276,6 +288,8 @@ def main():
         "kernels": per_kernel,
     }
     out["ffn_front"] = ffn_front_bench(B, L, torch, M, x_hidden, bufs["gate"], W, A4L, H_ffn, stream)
+    if not args.no_probe:
+        out["operand_data_probe"] = operand_data_probe(B, L, torch, M, bufs["qkv"], W["qkv"], A4L, stream)
     if not args.no_decode:
         out["decode"] = decode_bench(B, S, torch, dev, tokens=tuple(args.decode_tokens))
         out["decode_ffn_1token"] = decode_ffn_bench(B, S, torch, dev)
@@ -332,6 +346,45 @@ def ffn_front_bench(B, L, torch, M, X, b, W, A4L, H, stream, iters=20):
         torch.cuda.synchronize()
         res[label] = round(e0.elapsed_time(e1) / iters, 4)
     res["bytes_written_and_reread_between"] = {"two_gemms": 2 * 2 * M * FFN * 2, "glu_gemm": 2 * M * FFN * 2}
+    return res
+
+
+def operand_data_probe(B, L, torch, M, b, Wq, A4L, stream, iters=20):
+    """The qkv GEMM of the step timed on its real operands, then with the activation codes zeroed, then with
+    the weights zeroed too.  The kernel executes the same instructions on the same addresses in all three
+    (no branch depends on a code or a weight), so a shorter time can only come from a higher clock: the
+    matrix units draw less power when their operands do not toggle."""
+    N, K = 3 * HIDDEN, HIDDEN
+    q0 = b["q"].clone()
+    w0 = Wq[0].clone()
+    Y = b["Y"]
+
+    def run(q, w):
+        rc = L.bitlinear_gemm(q.data_ptr(), b["scale"].data_ptr(), b["mode"], M, K, w.data_ptr(), A4L,
+                              Wq[1].data_ptr(), N, Y.data_ptr(), B.BL_BF16, None, b["ws"].data_ptr(),
+                              b["ws"].numel(), stream)
+        assert rc == 0, rc
+
+    res = {}
+    for label, zq, zw in (("real_operands_ms", False, False), ("zero_codes_ms", True, False),
+                          ("zero_codes_zero_weights_ms", True, True)):
+        if zq:
+            q0.zero_()
+        if zw:
+            w0.zero_()
+        for _ in range(3):
+            run(q0, w0)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            run(q0, w0)
+        e1.record()
+        torch.cuda.synchronize()
+        res[label] = round(e0.elapsed_time(e1) / iters, 4)
+    res["tops_real"] = round(2.0 * M * N * K / res["real_operands_ms"] / 1e9, 1)
+    res["tops_zero"] = round(2.0 * M * N * K / res["zero_codes_zero_weights_ms"] / 1e9, 1)
     return res
 
 

@@ -376,3 +376,28 @@ def ffn_block(X, W_gate, W_up, W_down, k_sel, eps=DEFAULT_EPS):
     h = relu2_glu(g["y"], u["y"])
     dn = bitlinear_a8_sparse(h, W_down, k_sel, eps, "bf16")
     return dict(gate=g, up=u, h=h, down=dn)
+
+
+# --------------------------------------------------------------------------
+# training: straight-through backward of a quantized linear
+# --------------------------------------------------------------------------
+def ste_backward(dY, q, d, T, alpha):
+    """Gradients of Y = Q(X) . Q_w(W)^T under the straight-through estimator
+    (Section 2.2, "Gradient approximation"): the quantizers of the activations
+    and of the weights and the Top_k mask are passed over in the backward pass,
+    i.e. dL/dX := dL/dQ(X) and dL/dW := dL/dQ_w(W).  With the dequantized
+    operands  Xq = d_m * q[m, k]  (masked entries are zeros of q)  and
+    Wq = alpha * T[n, k]  the layer is the plain product Y = Xq . Wq^T, hence
+
+        dX[m, k] = sum_n dY[m, n] * Wq[n, k]         (does not depend on X or on the mask)
+        dW[n, k] = sum_m dY[m, n] * Xq[m, k]         (the gradient for the latent weight)
+
+    Everything in float64 (the paper fixes no precision for the backward pass
+    beyond "mixed precision training")."""
+    dY = np.asarray(dY, dtype=np.float64)
+    Xq = np.asarray(d, dtype=np.float64)[:, None] * np.asarray(q, dtype=np.float64)
+    Wq = np.float64(alpha) * np.asarray(T, dtype=np.float64)
+    dX = dY @ Wq
+    dW = dY.T @ Xq
+    return dX, dW
+

@@ -697,3 +697,60 @@ def test_layer_symmetries():
     pk = rng.permutation(96)
     p4 = O.bitlinear_a4(X[:, pk], W[:, pk], 0.0)
     assert np.array_equal(p4["acc"], base4["acc"]) and np.array_equal(p4["y"], base4["y"])
+
+
+def test_ste_backward():
+    """Section 2.2's straight-through backward of a quantized linear: the hand-worked example, central
+    differences of the forward pass in its dequantized operands (the forward is linear in each, so the
+    differences are exact up to rounding), torch's autograd of the same dense product, and what the
+    estimator means: dX does not depend on the activations or on the Top_k mask, dW is zero in the
+    columns of channels no token kept."""
+    g = GOLD["ste_backward"]
+    dX, dW = O.ste_backward(np.array(g["dY"]), np.array(g["q"]), np.array(g["d"]), np.array(g["T"]), g["alpha"])
+    assert dX.tolist() == g["dX"] and dW.tolist() == g["dW"]
+
+    rng = np.random.default_rng(77)
+    M, K, N = 5, 12, 7
+    X = (rng.standard_normal((M, K)) * 3).astype(F32)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(F32)
+    lay = O.bitlinear_a8_sparse(X, W, K // 2, EPS)
+    q, d, T, alpha = lay["q"], lay["d"], lay["T"], lay["alpha"]
+    R = rng.standard_normal((M, N))                                     # dL/dY of the loss L = sum(Y * R)
+    dX, dW = O.ste_backward(R, q, d, T, alpha)
+    Xq = d.astype(np.float64)[:, None] * q.astype(np.float64)
+    Wq = np.float64(alpha) * T.astype(np.float64)
+
+    def loss(xq, wq):                                                   # the forward pass, element by element
+        tot = 0.0
+        for m in range(M):
+            for n in range(N):
+                tot += R[m, n] * sum(xq[m, k] * wq[n, k] for k in range(K))
+        return tot
+
+    h = 0.5
+    for (m, k) in ((0, 0), (2, 5), (4, 11)):
+        e = np.zeros_like(Xq)
+        e[m, k] = h
+        assert abs((loss(Xq + e, Wq) - loss(Xq - e, Wq)) / (2 * h) - dX[m, k]) < 1e-9
+    for (n, k) in ((0, 3), (3, 0), (6, 11)):
+        e = np.zeros_like(Wq)
+        e[n, k] = h
+        assert abs((loss(Xq, Wq + e) - loss(Xq, Wq - e)) / (2 * h) - dW[n, k]) < 1e-9
+
+    xt = torch.tensor(Xq, requires_grad=True)
+    wt = torch.tensor(Wq, requires_grad=True)
+    (xt @ wt.T * torch.tensor(R)).sum().backward()
+    assert np.allclose(xt.grad.numpy(), dX, rtol=1e-12, atol=1e-12)
+    assert np.allclose(wt.grad.numpy(), dW, rtol=1e-12, atol=1e-12)
+
+    # the estimator passes over Top_k and the quantizer: another token matrix changes dW only
+    lay2 = O.bitlinear_a8_sparse(X[::-1].copy() * F32(1.7), W, 2, EPS)
+    dX2, dW2 = O.ste_backward(R, lay2["q"], lay2["d"], T, alpha)
+    assert np.array_equal(dX2, dX) and not np.array_equal(dW2, dW)
+    dead = ~lay2["mask"].any(axis=0)                                    # channels no token kept
+    assert dead.any() and not dW2[:, dead].any()
+    assert dX[:, ~lay["mask"].all(axis=0)].any()                        # masked entries still get a gradient
+    # shapes, and linearity in dY
+    assert dX.shape == (M, K) and dW.shape == (N, K)
+    a, b = O.ste_backward(2.0 * R, q, d, T, alpha)
+    assert np.array_equal(a, 2.0 * dX) and np.array_equal(b, 2.0 * dW)
