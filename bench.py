@@ -33,6 +33,7 @@ EPS = 1e-5
 INT8_PEAK_TOPS = 5033.0      # MI355X dense int8 MFMA
 FP6_FP4_PEAK_TOPS = 10066.0  # MI355X dense fp6 / fp4 MFMA (the INT4 GEMM runs on E3M2 x E2M1 operands)
 HBM_PEAK_GBS = 8000.0
+BF16_PEAK_TFLOPS = 2516.0    # MI355X dense bfloat16 MFMA (the gradient GEMMs of the backward pass)
 HIDDEN, FFN = 4096, 11008
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemm_7b_prefill_hbm_traffic.txt")
 
@@ -296,6 +297,7 @@ def main():
     if not args.no_fp4:
         out["fp4_variant"] = fp4_compare(B, S, torch, dev)
     out["attention_states"] = heads_bench(B, S, torch, dev, M)
+    out["ste_backward"] = ste_backward_bench(B, S, torch, dev, M)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
@@ -385,6 +387,38 @@ def operand_data_probe(B, L, torch, M, b, Wq, A4L, stream, iters=20):
         res[label] = round(e0.elapsed_time(e1) / iters, 4)
     res["tops_real"] = round(2.0 * M * N * K / res["real_operands_ms"] / 1e9, 1)
     res["tops_zero"] = round(2.0 * M * N * K / res["zero_codes_zero_weights_ms"] / 1e9, 1)
+    return res
+
+
+def ste_backward_bench(B, S, torch, dev, M, iters=5):
+    """Straight-through backward (Section 2.2) of the qkv projection at the step's token count: the two
+    gradient GEMMs on bfloat16 operands with their operand preparation (weights expanded from 2 bits,
+    dY scaled and transposed, codes transposed), timed apart."""
+    N, K = 3 * HIDDEN, HIDDEN
+    L = B.lib()
+    w = torch.from_numpy(S.latent_weights(N, K, S.seed_for(3, 70))).to(dev)
+    pk, ak = B.pack_ternary(w, EPS, B.BL_W_KMAJOR)
+    del w
+    X = torch.from_numpy(S.heavy(M, K, S.seed_for(3, 71))).to(dev).to(torch.bfloat16)
+    qa = B.quantize_act(X, B.BL_ACT_INT4_ABSMEAN, 0, EPS)
+    dY = (torch.randn((M, N), device=dev) * 0.01).to(torch.bfloat16)
+    ws = torch.empty(L.bitlinear_backward_workspace_bytes(M, N, K), dtype=torch.uint8, device=dev)
+    res = {"shape": "dY %d x %d, K = %d" % (M, N, K)}
+    for label, dx, dw in (("dX", True, False), ("dW", False, True)):
+        for _ in range(2):
+            B.bitlinear_backward(dY, qa["q"], qa["scale"], B.BL_ACT_INT4_ABSMEAN, K, pk, ak, dx, dw, ws=ws)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            B.bitlinear_backward(dY, qa["q"], qa["scale"], B.BL_ACT_INT4_ABSMEAN, K, pk, ak, dx, dw, ws=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        res[label + "_ms"] = round(ms, 3)
+        res[label + "_tflops"] = round(2.0 * M * N * K / ms / 1e9, 1)
+        res[label + "_frac_of_bf16_peak"] = round(2.0 * M * N * K / ms / 1e9 / BF16_PEAK_TFLOPS, 3)
     return res
 
 

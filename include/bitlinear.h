@@ -345,6 +345,31 @@ int kv_cache_append(const void* X, bl_dtype x_dtype, int64_t T, int64_t H, int64
 int kv_cache_read(const void* cache, const float* scales, int64_t pos0, int64_t T, int64_t H, int64_t D,
                   void* out, bl_dtype out_dtype, void* stream);
 
+/* Backward pass of a quantized linear layer under the straight-through estimator (Section 2.2,
+ * "Gradient approximation": the quantization functions and the top-K function are passed over).  With
+ * the forward pass's dequantized operands Xq[m, k] = scale[m] * q[m, k] (zeros where Top_k masked) and
+ * Wq[n, k] = alpha * T[n, k]:
+ *     dX[m, k] = sum_n dY[m, n] * Wq[n, k]      (the gradient for X itself: independent of X and of the mask)
+ *     dW[n, k] = sum_m dY[m, n] * Xq[m, k]      (the gradient for the full-precision latent weight)
+ * Mixed precision: bfloat16 operands on the matrix units, float32 accumulation.  T and q are exact in
+ * bfloat16; the one operand rounding is bf16(dY[m, n] * scale[m]) in dW, so each dW[n, k] is within
+ * (2^-8 + M 2^-24) * sum_m |dY[m, n] Xq[m, k]| of the exact sum, and dX within N 2^-24 * alpha * sum_n
+ * |dY[m, n] T[n, k]| (plus one bfloat16 rounding if dx_dtype is BL_BF16).
+ *   dY         device, bfloat16 [M, N], 16-byte aligned; N % 8 == 0
+ *   q, scale   the codes and scales the forward pass's quantize_act wrote for X [M, K]: mode
+ *              BL_ACT_INT4_ABSMEAN (nibble form) or BL_ACT_TOPK_INT8_ABSMAX; K % 8 == 0
+ *   W_packed   the layer's weights in BL_W_KMAJOR (other layouts: BL_EUNSUPPORTED), alpha its scale
+ *   dX         device [M, K] of dx_dtype, or NULL;  dW  device float32 [N, K], or NULL (overwritten,
+ *              not accumulated into); at least one of the two
+ *   workspace  bitlinear_backward_workspace_bytes(M, N, K) bytes, 16-byte aligned (the transposed
+ *              bfloat16 operands: 2 * (K * Nc + N * Mc + K * Mc) bytes, Nc and Mc rounded up to 64)
+ * Errors: BL_EINVAL, BL_ESHAPE, BL_EALIGN, BL_EWORKSPACE, BL_EUNSUPPORTED (mode, layout, N % 8, K % 8). */
+size_t bitlinear_backward_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int bitlinear_backward(const void* dY, int64_t M, int64_t N, int64_t K, const void* q, const float* scale,
+                       bl_act_mode mode, const void* W_packed, bl_w_layout layout, const float* alpha,
+                       void* dX, bl_dtype dx_dtype, float* dW, void* workspace, size_t workspace_bytes,
+                       void* stream);
+
 /* ReLU^2 GLU combine (eq. 5): H = bf16(U * max(G, 0)^2), float32 steps in that order.
  * G, U device [M, N] of in_dtype; H device [M, N] bfloat16. */
 int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_t M, int64_t N,

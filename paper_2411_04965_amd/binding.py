@@ -56,6 +56,8 @@ _SIGNATURES = {
                                     _vp, _vp, _sz, _vp]),
     "bitlinear_gemm_glu": (_int, [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _int, _i64, _vp, _vp]),
     "bitlinear_a4_up_gated": (_int, [_vp, _i64, _i64, _vp, _vp, _i64, _f32, _vp, _int, _vp, _vp]),
+    "bitlinear_backward_workspace_bytes": (_sz, [_i64, _i64, _i64]),
+    "bitlinear_backward": (_int, [_vp, _i64, _i64, _i64, _vp, _vp, _int, _vp, _int, _vp, _vp, _int, _vp, _vp, _sz, _vp]),
     "unpack_ternary": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
     "unpack_act": (_int, [_vp, _int, _i64, _i64, _vp, _vp]),
     "bl_noop": (_int, [_vp]),
@@ -323,6 +325,22 @@ def kv_cache_read(cache, scales, pos0, T, H, D, out_dtype=torch.float32):
     out = torch.empty((T, H, D), dtype=out_dtype, device=cache.device)
     _check("kv_cache_read", lib().kv_cache_read(_ptr(cache), _ptr(scales), pos0, T, H, D, _ptr(out), _dt(out), _stream()))
     return out
+
+
+def bitlinear_backward(dY, q, scale, mode, K, W_kmajor, alpha, want_dx=True, want_dw=True,
+                       dx_dtype=torch.bfloat16, ws=None):
+    """Straight-through backward (Section 2.2): dY [M, N] bfloat16 and the forward's codes -> (dX, dW)."""
+    _dev(dY)
+    M, N = dY.shape
+    L = lib()
+    if ws is None:
+        ws = torch.empty(max(L.bitlinear_backward_workspace_bytes(M, N, K), 16), dtype=torch.uint8, device=dY.device)
+    dX = torch.empty((M, K), dtype=dx_dtype, device=dY.device) if want_dx else None
+    dW = torch.empty((N, K), dtype=torch.float32, device=dY.device) if want_dw else None
+    _check("bitlinear_backward", L.bitlinear_backward(
+        _ptr(dY), M, N, K, _ptr(q), _ptr(scale), mode, _ptr(W_kmajor), BL_W_KMAJOR, _ptr(alpha), _ptr(dX),
+        BL_F32 if dx_dtype == torch.float32 else BL_BF16, _ptr(dW), _ptr(ws), ws.numel(), _stream()))
+    return dX, dW
 
 
 def swish_glu(G, U):

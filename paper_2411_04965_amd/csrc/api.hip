@@ -617,3 +617,29 @@ extern "C" int relu2_glu(const void* G, const void* U, bl_dtype in_dtype, int64_
   BL_HIP_CHECK_LAUNCH();
   return BL_OK;
 }
+
+// ---------------------------------------------------------------- straight-through backward (Section 2.2)
+extern "C" size_t bitlinear_backward_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  if (M < 1 || N < 1 || K < 1 || M > ((int64_t)1 << 31) || N > ((int64_t)1 << 24) || K > BL_MAX_K) return 0;
+  return bl_ste_workspace_bytes(M, N, K);
+}
+
+extern "C" int bitlinear_backward(const void* dY, int64_t M, int64_t N, int64_t K, const void* q, const float* scale,
+                                  bl_act_mode mode, const void* W_packed, bl_w_layout layout, const float* alpha,
+                                  void* dX, bl_dtype dx_dtype, float* dW, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (!dY || !q || !scale || !W_packed || !alpha || !workspace || (!dX && !dW)) return BL_EINVAL;
+  if (!valid_dtype(dx_dtype)) return BL_EINVAL;
+  if (mode != BL_ACT_INT4_ABSMEAN && mode != BL_ACT_TOPK_INT8_ABSMAX) return BL_EUNSUPPORTED;
+  if (layout != BL_W_KMAJOR) return BL_EUNSUPPORTED;
+  if (M < 1 || N < 1 || K < 1) return BL_EINVAL;
+  if (M > ((int64_t)1 << 30) || N > ((int64_t)1 << 24) || K > BL_MAX_K) return BL_ESHAPE;
+  if (N % 8 != 0 || K % 8 != 0) return BL_EUNSUPPORTED;      // 16-byte pieces of the rows of dY, dX and the codes
+  if (!bl_aligned16(dY) || !bl_aligned16(q) || !bl_aligned16(W_packed) || !bl_aligned16(workspace) ||
+      (dX && !bl_aligned16(dX)) || (dW && !bl_aligned16(dW)) || (reinterpret_cast<uintptr_t>(scale) & 3))
+    return BL_EALIGN;
+  if (workspace_bytes < bl_ste_workspace_bytes(M, N, K)) return BL_EWORKSPACE;
+  return bl_launch_ste_backward(dY, M, N, K, q, scale, mode == BL_ACT_INT4_ABSMEAN, W_packed, alpha, dX, dx_dtype, dW,
+                                workspace, (hipStream_t)stream);
+}
+

@@ -174,3 +174,8 @@ int bl_launch_gemm_fp4_mx(const void* q, const uint8_t* xscale, int64_t M, int64
                           const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);
 int bl_launch_gemm_fp4(const void* q, const uint8_t* scale, int64_t M, int64_t K, const void* Wp,
                        const float* alpha, int64_t N, void* Y, bl_dtype ydt, hipStream_t s);
+size_t bl_ste_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int bl_launch_ste_backward(const void* dY, int64_t M, int64_t N, int64_t K, const void* q, const float* scale, bool a4,
+                           const void* Wk, const float* alpha, void* dX, bl_dtype dx_dtype, float* dW, void* ws,
+                           hipStream_t s);
+

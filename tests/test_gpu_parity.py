@@ -923,3 +923,94 @@ def test_config4_down_int8_sampled_rows():
     y_ref = O.rescale(acc_ref, d, alpha, "bf16")
     assert_close_rel(host(Y[idx]), y_ref)
     assert np.array_equal(host(Y[idx]), y_ref)
+
+
+# ------------------------------------------------------------------ straight-through backward (Section 2.2)
+def _ste_bounds(dYh, q, d, T, alpha, M, N):
+    """Per-element error bounds of the bfloat16 / float32-accumulate gradient GEMMs against the exact
+    sums: float32 accumulation of J terms in any order is within (J + 2) 2^-24 of the sum of the terms'
+    magnitudes; dW's left operand bf16(dY d_m) carries one more relative 2^-8 per term (bfloat16's unit roundoff)."""
+    absY = np.abs(dYh)
+    sx = np.float64(alpha) * (absY @ np.abs(T).astype(np.float64))
+    sw = absY.T @ (np.abs(q).astype(np.float64) * d.astype(np.float64)[:, None])
+    Mc = (M + 63) // 64 * 64
+    return (N + 2) * 2.0 ** -24 * sx, (2.0 ** -8 + (Mc + 3) * 2.0 ** -24) * sw
+
+
+@pytest.mark.parametrize("M,N,K,kind", [(200, 264, 392, "a4"), (130, 72, 520, "a8"), (64, 128, 256, "a4"),
+                                        (1, 8, 8, "a8"), (300, 1032, 136, "a8"), (257, 520, 1000, "a4")])
+def test_ste_backward(M, N, K, kind):
+    """dX = dY . Q_w(W) and dW = dY^T . Q(X) (the quantizers and Top_k passed over) against the oracle's
+    float64 sums, element by element, within the bounds the arithmetic gives; several tiles, ragged edges."""
+    say("ste backward M=%d N=%d K=%d %s" % (M, N, K, kind))
+    X = S.heavy(M, K, S.seed_for(5, 10 + M))
+    W = S.latent_weights(N, K, S.seed_for(5, 11 + N))
+    rng = np.random.default_rng(S.seed_for(5, 12 + K))
+    dYh = S.snap_bf16((rng.standard_normal((M, N)) * 0.01).astype(np.float32))
+    if kind == "a4":
+        lay = O.bitlinear_a4(X, W, EPS)
+        mode, topk = B.BL_ACT_INT4_ABSMEAN, 0
+    else:
+        lay = O.bitlinear_a8_sparse(X, W, max(1, K // 2), EPS)
+        mode, topk = B.BL_ACT_TOPK_INT8_ABSMAX, max(1, K // 2)
+    dX_ref, dW_ref = O.ste_backward(dYh, lay["q"], lay["d"], lay["T"], lay["alpha"])
+    bx, bw = _ste_bounds(dYh.astype(np.float64), lay["q"], lay["d"], lay["T"], lay["alpha"], M, N)
+    pk, ak = pack(W, B.BL_W_KMAJOR)
+    qa = B.quantize_act(dev(X, BF16), mode, topk, EPS)
+    dY = dev(dYh, BF16)
+    dX, dW = B.bitlinear_backward(dY, qa["q"], qa["scale"], mode, K, pk, ak, dx_dtype=F32)
+    ex = np.abs(host(dX).astype(np.float64) - dX_ref)
+    ew = np.abs(host(dW).astype(np.float64) - dW_ref)
+    assert np.all(ex <= bx + 1e-30), float((ex / (bx + 1e-30)).max())
+    assert np.all(ew <= bw + 1e-30), float((ew / (bw + 1e-30)).max())
+    # the sums are not trivially small against their bounds: the check would catch a dropped tile
+    assert np.abs(dX_ref).max() > 20 * bx.max() and np.abs(dW_ref).max() > 5 * bw.max()
+    # bfloat16 dX: one more rounding; dX alone and dW alone
+    dXb, none = B.bitlinear_backward(dY, qa["q"], qa["scale"], mode, K, pk, ak, want_dw=False, dx_dtype=BF16)
+    assert none is None
+    eb = np.abs(host(dXb).astype(np.float64) - dX_ref)
+    assert np.all(eb <= bx + 2.0 ** -8 * np.abs(dX_ref) + 1e-30)
+    none, dW2 = B.bitlinear_backward(dY, qa["q"], qa["scale"], mode, K, pk, ak, want_dx=False)
+    assert none is None and np.array_equal(host(dW2), host(dW))
+    # masked channels still receive a gradient (the estimator passes over Top_k)
+    if kind == "a8" and K >= 8:
+        assert np.abs(host(dX)[~lay["mask"]]).max() > 0
+
+
+def test_ste_backward_rejects():
+    """Shapes and layouts the backward entry point does not take are refused before any launch."""
+    L = B.lib()
+    z = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    p = z.data_ptr()
+    assert L.bitlinear_backward(p, 4, 12, 8, p, p, 0, p, B.BL_W_KMAJOR, p, p, 0, None, p, 1 << 16, None) == -6   # N % 8
+    assert L.bitlinear_backward(p, 4, 8, 8, p, p, 0, p, B.BL_W_GEMM, p, p, 0, None, p, 1 << 16, None) == -6      # layout
+    assert L.bitlinear_backward(p, 4, 8, 8, p, p, 2, p, B.BL_W_KMAJOR, p, p, 0, None, p, 1 << 16, None) == -6    # FP4 codes
+    assert L.bitlinear_backward(p, 4, 8, 8, p, p, 0, p, B.BL_W_KMAJOR, p, None, 0, None, p, 1 << 16, None) == -1  # no output
+    assert L.bitlinear_backward(p, 4, 8, 8, p, p, 0, p, B.BL_W_KMAJOR, p, p, 0, None, p, 16, None) == -4         # workspace
+
+
+def test_ste_backward_7b_sampled_rows():
+    """The qkv projection's backward at 7B width on 2048 tokens: sampled rows of dX and of dW against the
+    oracle's float64 sums (the oracle computes each sampled row on its own)."""
+    M, N, K = 2048, 12288, 4096
+    say("ste backward 7B qkv, M=%d" % M)
+    X = S.heavy(M, K, S.seed_for(5, 100))
+    W = S.latent_weights(N, K, S.seed_for(5, 101))
+    rng = np.random.default_rng(S.seed_for(5, 102))
+    dYh = S.snap_bf16((rng.standard_normal((M, N)) * 0.01).astype(np.float32))
+    T, alpha = O.ternarize(W, EPS)
+    q, d = O.quant_int4(X, EPS)
+    pk, ak = pack(W, B.BL_W_KMAJOR)
+    qa = B.quantize_act(dev(X, BF16), B.BL_ACT_INT4_ABSMEAN, 0, EPS)
+    dX, dW = B.bitlinear_backward(dev(dYh, BF16), qa["q"], qa["scale"], B.BL_ACT_INT4_ABSMEAN, K, pk, ak, dx_dtype=F32)
+    dXh, dWh = host(dX).astype(np.float64), host(dW).astype(np.float64)
+    dY64 = dYh.astype(np.float64)
+    rows_m = rng.choice(M, 24, replace=False)
+    ref, _ = O.ste_backward(dY64[rows_m], q[rows_m], d[rows_m], T, alpha)
+    bx = (N + 2) * 2.0 ** -24 * np.float64(alpha) * (np.abs(dY64[rows_m]) @ np.abs(T).astype(np.float64))
+    assert np.all(np.abs(dXh[rows_m] - ref) <= bx)
+    rows_n = rng.choice(N, 24, replace=False)
+    _, refw = O.ste_backward(dY64[:, rows_n], q, d, T[rows_n], alpha)
+    bw = (2.0 ** -8 + (M + 3) * 2.0 ** -24) * (np.abs(dY64[:, rows_n]).T @ (np.abs(q).astype(np.float64) * d.astype(np.float64)[:, None]))
+    assert np.all(np.abs(dWh[rows_n] - refw) <= bw)
+    assert np.abs(ref).max() > 20 * bx.max() and np.abs(refw).max() > 5 * bw.max()
