@@ -634,7 +634,6 @@ extern "C" int bitlinear_backward(const void* dY, int64_t M, int64_t N, int64_t 
   if (layout != BL_W_KMAJOR) return BL_EUNSUPPORTED;
   if (M < 1 || N < 1 || K < 1) return BL_EINVAL;
   if (M > ((int64_t)1 << 30) || N > ((int64_t)1 << 24) || K > BL_MAX_K) return BL_ESHAPE;
-  if (N % 8 != 0 || K % 8 != 0) return BL_EUNSUPPORTED;      // 16-byte pieces of the rows of dY, dX and the codes
   if (!bl_aligned16(dY) || !bl_aligned16(q) || !bl_aligned16(W_packed) || !bl_aligned16(workspace) ||
       (dX && !bl_aligned16(dX)) || (dW && !bl_aligned16(dW)) || (reinterpret_cast<uintptr_t>(scale) & 3))
     return BL_EALIGN;

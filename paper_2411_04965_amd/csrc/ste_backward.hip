@@ -46,6 +46,24 @@ __global__ __launch_bounds__(256) void ste_expand_weights_kernel(const u32* __re
   dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
+// Rows of dY whose length is no multiple of 8 do not start on 16-byte boundaries: they are copied once to
+// rows of Nc elements (zero padded), which the other kernels then read.  One thread per 16-byte piece.
+__global__ __launch_bounds__(256) void ste_pad_rows_kernel(const uint16_t* __restrict__ in, int64_t M, int64_t N, int64_t Nc,
+                                                           uint16_t* __restrict__ out) {
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t ppr = Nc >> 3;
+  if (id >= M * ppr) return;
+  const int64_t m = id / ppr, c = (id - m * ppr) * 8;
+  u32 o[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const u32 lo = c + 2 * e < N ? in[m * N + c + 2 * e] : 0u;
+    const u32 hi = c + 2 * e + 1 < N ? in[m * N + c + 2 * e + 1] : 0u;
+    o[e] = lo | (hi << 16);
+  }
+  *reinterpret_cast<uint4*>(out + m * Nc + c) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 // out[c][r] = bf16(f(in[r][c])) for a 64 x 64 tile per workgroup, through LDS.
 //   MODE 0: in = dY (bfloat16 [R][C]), f = value * scale[r]            (one float32 multiply, RNE)
 //   MODE 1: in = INT8 codes [R][ld_in] (one byte per channel), f = the integer
@@ -67,7 +85,7 @@ __global__ __launch_bounds__(256) void ste_transpose_kernel(const void* __restri
     uint16_t v[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = 0;
-    if (r < R && c < C) {                                   // (C % 8 == 0: a piece is inside or outside)
+    if (r < R && c < C) {                                   // (a piece that straddles C reads the row's zero padding)
       if (MODE == 0) {
         const uint4 x = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(in) + r * ld_in + c);
         const float s = scale[r];
@@ -223,7 +241,7 @@ __global__ __launch_bounds__(SB_THREADS) void ste_gemm_nt_kernel(const uint16_t*
 // ---------------------------------------------------------------- host
 size_t bl_ste_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   const int64_t Nc = bl_round_up(N, 64), Mc = bl_round_up(M, 64);
-  return (size_t)(K * Nc + N * Mc + K * Mc) * 2;
+  return (size_t)(K * Nc + N * Mc + K * Mc + (N % 8 ? M * Nc : 0)) * 2;
 }
 
 template <typename OutT>
@@ -245,6 +263,18 @@ int bl_launch_ste_backward(const void* dY, int64_t M, int64_t N, int64_t K, cons
   uint16_t* Tb = reinterpret_cast<uint16_t*>(ws);
   uint16_t* dYt = Tb + K * Nc;
   uint16_t* qt = dYt + N * Mc;
+  const uint16_t* dYa = reinterpret_cast<const uint16_t*>(dY);           // dY with 16-byte aligned rows
+  int64_t ldy = N;
+  if (N % 8) {
+    uint16_t* dYp = qt + K * Mc;
+    const int64_t pieces = M * (Nc >> 3);
+    if (!bl_grid_ok((pieces + 255) / 256)) return BL_ESHAPE;
+    ste_pad_rows_kernel<<<(unsigned)((pieces + 255) / 256), 256, 0, s>>>(dYa, M, N, Nc, dYp);
+    BL_HIP_CHECK_LAUNCH();
+    dYa = dYp;
+    ldy = Nc;
+  }
+  const int64_t Jx = bl_round_up(N, 8);                                  // contraction length of dX in whole pieces
   if (dX) {
     const int64_t words = K * (Nc >> 4);
     if (!bl_grid_ok((words + 255) / 256)) return BL_ESHAPE;
@@ -252,15 +282,15 @@ int bl_launch_ste_backward(const void* dY, int64_t M, int64_t N, int64_t K, cons
     BL_HIP_CHECK_LAUNCH();
     int rc;
     if (dx_dtype == BL_F32)
-      rc = sb_gemm<float>(reinterpret_cast<const uint16_t*>(dY), N, Tb, Nc, M, K, N, alpha, reinterpret_cast<float*>(dX), K, s);
+      rc = sb_gemm<float>(dYa, ldy, Tb, Nc, M, K, Jx, alpha, reinterpret_cast<float*>(dX), K, s);
     else
-      rc = sb_gemm<uint16_t>(reinterpret_cast<const uint16_t*>(dY), N, Tb, Nc, M, K, N, alpha, reinterpret_cast<uint16_t*>(dX), K, s);
+      rc = sb_gemm<uint16_t>(dYa, ldy, Tb, Nc, M, K, Jx, alpha, reinterpret_cast<uint16_t*>(dX), K, s);
     if (rc != BL_OK) return rc;
   }
   if (dW) {
     const dim3 g1((unsigned)(Mc / 64), (unsigned)((N + 63) / 64)), g2((unsigned)(Mc / 64), (unsigned)((K + 63) / 64));
     if (g1.y > 65535u || g2.y > 65535u) return BL_ESHAPE;
-    ste_transpose_kernel<0><<<g1, 256, 0, s>>>(dY, scale, M, N, N, Mc, dYt);
+    ste_transpose_kernel<0><<<g1, 256, 0, s>>>(dYa, scale, M, N, ldy, Mc, dYt);
     BL_HIP_CHECK_LAUNCH();
     if (a4) ste_transpose_kernel<2><<<g2, 256, 0, s>>>(q, nullptr, M, K, Kp / 2, Mc, qt);
     else ste_transpose_kernel<1><<<g2, 256, 0, s>>>(q, nullptr, M, K, Kp, Mc, qt);
