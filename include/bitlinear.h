@@ -355,7 +355,7 @@ int kv_cache_read(const void* cache, const float* scales, int64_t pos0, int64_t 
  * bfloat16; the one operand rounding is bf16(dY[m, n] * scale[m]) in dW, so each dW[n, k] is within
  * (2^-8 + M 2^-24) * sum_m |dY[m, n] Xq[m, k]| of the exact sum, and dX within N 2^-24 * alpha * sum_n
  * |dY[m, n] T[n, k]| (plus one bfloat16 rounding if dx_dtype is BL_BF16).
- *   dY         device, bfloat16 [M, N], 16-byte aligned (rows of a length that is no multiple of 8 are first
+ *   dY         device, bfloat16 [M, N], 16-byte aligned (rows of a length that is no multiple of 64 are first
  *              copied to padded rows in the workspace)
  *   q, scale   the codes and scales the forward pass's quantize_act wrote for X [M, K]: mode
  *              BL_ACT_INT4_ABSMEAN (nibble form) or BL_ACT_TOPK_INT8_ABSMAX
@@ -364,7 +364,7 @@ int kv_cache_read(const void* cache, const float* scales, int64_t pos0, int64_t 
  *              not accumulated into); at least one of the two
  *   workspace  bitlinear_backward_workspace_bytes(M, N, K) bytes, 16-byte aligned (the transposed
  *              bfloat16 operands: 2 * (K * Nc + N * Mc + K * Mc) bytes, Nc and Mc rounded up to 64, plus
- *              2 * M * Nc for the padded copy of dY when N % 8 != 0)
+ *              2 * M * Nc for the padded copy of dY when N % 64 != 0)
  * Errors: BL_EINVAL, BL_ESHAPE, BL_EALIGN, BL_EWORKSPACE, BL_EUNSUPPORTED (mode, layout). */
 size_t bitlinear_backward_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int bitlinear_backward(const void* dY, int64_t M, int64_t N, int64_t K, const void* q, const float* scale,

@@ -18,8 +18,6 @@
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-#define SB_BM 128
-#define SB_BN 128
 #define SB_BK 64
 #define SB_THREADS 256
 
@@ -46,8 +44,8 @@ __global__ __launch_bounds__(256) void ste_expand_weights_kernel(const u32* __re
   dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
-// Rows of dY whose length is no multiple of 8 do not start on 16-byte boundaries: they are copied once to
-// rows of Nc elements (zero padded), which the other kernels then read.  One thread per 16-byte piece.
+// Rows of dY whose length is no multiple of 64 are copied once to rows of Nc elements (zero padded), which the
+// other kernels then read: 16-byte aligned rows, and a contraction of whole 64-element steps.  One thread per 16-byte piece.
 __global__ __launch_bounds__(256) void ste_pad_rows_kernel(const uint16_t* __restrict__ in, int64_t M, int64_t N, int64_t Nc,
                                                            uint16_t* __restrict__ out) {
   const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -133,98 +131,122 @@ __global__ __launch_bounds__(256) void ste_transpose_kernel(const void* __restri
 }
 
 // ---------------------------------------------------------------- the contraction
-// C[r][c] = mul * sum_j A[r][j] B[c][j]; A [R][lda], B [Cn][ldb] bfloat16, J % 8 == 0, lda % 8 == 0, ldb % 8 == 0.
-// Pieces of A or B at j >= J read as zero (so the operands need no padding of their own); rows past the
-// end re-read the last row and their outputs are not stored.  Tile 128 x 128 per workgroup of four
-// waves (wave tile 64 x 64 = 2 x 2 MFMA tiles), 64 contraction indices per step, two LDS stages; a row
-// of a stage is 128 bytes whose 16-byte piece p sits at p ^ ((row / 2) % 8): the 16 rows that one
-// phase of a fragment read touches then cover the 16 slots of a 256-byte bank window.
-template <typename OutT>
+// C[r][c] = mul * sum_j A[r][j] B[c][j]; A [R][lda], B [Cn][ldb] bfloat16, J % 64 == 0 (the callers pad the
+// contraction with zeros), lda % 8 == 0, ldb % 8 == 0.  Rows past the end re-read the last row and their
+// outputs are not stored.  A workgroup of four waves (2 x 2) owns a tile
+// of 64 TM x 64 TN outputs, a wave TM x TN MFMA tiles of 32 x 32: 4 x 4 for large problems (256 x 256 per
+// workgroup, 256 accumulator registers, every fragment read from LDS feeds four MFMAs), 2 x 2 for small ones.
+// 64 contraction indices per step, two LDS stages, the next step's operands in registers while the current
+// one is multiplied.  A row of a stage is 128 bytes whose 16-byte piece p sits at p ^ ((row / 2) % 8): the
+// 16 rows that one phase of a fragment read touches then cover the 16 slots of a 256-byte bank window.
+template <typename OutT, int TM, int TN>
 __global__ __launch_bounds__(SB_THREADS) void ste_gemm_nt_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                                  const uint16_t* __restrict__ B, int64_t ldb, int R,
                                                                  int Cn, int J, const float* __restrict__ mul_p,
                                                                  OutT* __restrict__ Cout, int64_t ldc, int RT, int CT) {
-  __shared__ __align__(16) unsigned char lds[2][2][SB_BM * 128];          // [stage][A, B][row][128 bytes]
+  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr int STAGE = (BM + BN) * 128;                                    // bytes: A rows, then B rows
+  constexpr int PA = BM * 8 / SB_THREADS, PB = BN * 8 / SB_THREADS;        // 16-byte pieces per thread and step
+  extern __shared__ __align__(16) unsigned char sb_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int r0, c0;
-  bl_tile_origin(blockIdx.x, RT * CT, RT, CT, SB_BM, SB_BN, r0, c0);
-  const int wr = (wave >> 1) * 64, wc = (wave & 1) * 64;
+  bl_tile_origin(blockIdx.x, RT * CT, RT, CT, BM, BN, r0, c0);
+  const int wr = (wave >> 1) * (32 * TM), wc = (wave & 1) * (32 * TN);
 
-  // copy assignment: piece id = tid + 256 i, i < 4: row = id / 8, piece = id % 8
-  const uint16_t* a_src[4];
-  const uint16_t* b_src[4];
-  int lds_off[4], pj[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int id = tid + SB_THREADS * i, row = id >> 3, p = id & 7;
-    a_src[i] = A + (int64_t)min(r0 + row, R - 1) * lda + 8 * p;
-    b_src[i] = B + (int64_t)min(c0 + row, Cn - 1) * ldb + 8 * p;
-    lds_off[i] = row * 128 + ((p ^ ((row >> 1) & 7)) << 4);
-    pj[i] = 8 * p;
-  }
-  uint4 ra[4], rb[4];
+  // copy assignment: piece id = tid + 256 i: row = id / 8, piece = id % 8 (the same piece column for every i)
+  const int prow = tid >> 3, pp = tid & 7;
+  // rows prow + 32 i: (row / 2) % 8 does not depend on i, so one LDS offset serves all pieces of a thread
+  const int lds_off = prow * 128 + ((pp ^ ((prow >> 1) & 7)) << 4);
+  // (addresses are formed per load: 16 + 16 row pointers would take the registers the fragments need)
+  v4i ra[PA], rb[PB];                     // (a first-class vector type: the arrays then stay in registers)
   auto load = [&](int j0) {
+    const int64_t col = j0 + 8 * pp;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const bool in = j0 + pj[i] < J;
-      ra[i] = in ? *reinterpret_cast<const uint4*>(a_src[i] + j0) : make_uint4(0u, 0u, 0u, 0u);
-      rb[i] = in ? *reinterpret_cast<const uint4*>(b_src[i] + j0) : make_uint4(0u, 0u, 0u, 0u);
-    }
+    for (int i = 0; i < PA; ++i) ra[i] = *reinterpret_cast<const v4i*>(A + (int64_t)min(r0 + prow + 32 * i, R - 1) * lda + col);
+#pragma unroll
+    for (int i = 0; i < PB; ++i) rb[i] = *reinterpret_cast<const v4i*>(B + (int64_t)min(c0 + prow + 32 * i, Cn - 1) * ldb + col);
   };
   auto stage_store = [&](int st) {
+    unsigned char* sa = sb_lds + st * STAGE + lds_off;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<uint4*>(&lds[st][0][lds_off[i]]) = ra[i];
-      *reinterpret_cast<uint4*>(&lds[st][1][lds_off[i]]) = rb[i];
-    }
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<v4i*>(sa + i * 32 * 128) = ra[i];
+#pragma unroll
+    for (int i = 0; i < PB; ++i) *reinterpret_cast<v4i*>(sa + BM * 128 + i * 32 * 128) = rb[i];
   };
 
-  v16f acc[2][2];
+  v16f acc[TM][TN];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < TM; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < TN; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
   const int li = lane & 31, kg = lane >> 5;
+  // fragment addresses: row wr + 32 a + li (A) or wc + 32 b + li (B); (row / 2) % 8 is the same for every a, b
+  const int fsw = (li >> 1) & 7;
+  const int fa_off = (wr + li) * 128, fb_off = BM * 128 + (wc + li) * 128;
   const int steps = (J + SB_BK - 1) / SB_BK;
+  // Pipeline: the operands of step s + 2 are requested during step s and written to LDS during step s + 1,
+  // a quarter of the pieces in each of the four sub-steps (A pieces in sub-steps 0, 1, B pieces in 2, 3): every
+  // load has a whole step to arrive, and neither the requests nor the LDS writes come as a burst (a wave that
+  // issues many loads back to back stalls on them, and it is the only wave of its SIMD).  A piece's register
+  // is written to LDS and at once refilled by the next request, so one register set serves.  No branch in the
+  // loop (past the last step the requests re-read the last step's pieces and the LDS writes fill a stage that
+  // nobody reads any more), so that the compiler can count the loads in flight.
   load(0);
   stage_store(0);
+  load(min(1, steps - 1) * SB_BK);
   __syncthreads();
   for (int s = 0; s < steps; ++s) {
-    const int st = s & 1;
-    if (s + 1 < steps) load((s + 1) * SB_BK);                             // in flight during the MFMAs
+    const int cur = s & 1;
+    const unsigned char* st = sb_lds + cur * STAGE;
+    unsigned char* sn = sb_lds + (cur ^ 1) * STAGE + lds_off;               // stage of step s + 1
+    const int64_t coln = min(s + 2, steps - 1) * SB_BK + 8 * pp;           // column of step s + 2
+    v8bf fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a) fa[0][a] = *reinterpret_cast<const v8bf*>(st + fa_off + a * 32 * 128 + ((kg ^ fsw) << 4));
+#pragma unroll
+    for (int b = 0; b < TN; ++b) fb[0][b] = *reinterpret_cast<const v8bf*>(st + fb_off + b * 32 * 128 + ((kg ^ fsw) << 4));
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      v8bf fa[2], fb[2];
+      if (ks < 2) {
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        const int row = wr + 32 * a + li, p = 2 * ks + kg;
-        fa[a] = *reinterpret_cast<const v8bf*>(&lds[st][0][row * 128 + ((p ^ ((row >> 1) & 7)) << 4)]);
+        for (int i = ks * (PA / 2); i < (ks + 1) * (PA / 2); ++i) {
+          *reinterpret_cast<v4i*>(sn + i * 32 * 128) = ra[i];
+          ra[i] = *reinterpret_cast<const v4i*>(A + (int64_t)min(r0 + prow + 32 * i, R - 1) * lda + coln);
+        }
+      } else {
+#pragma unroll
+        for (int i = (ks - 2) * (PB / 2); i < (ks - 1) * (PB / 2); ++i) {
+          *reinterpret_cast<v4i*>(sn + BM * 128 + i * 32 * 128) = rb[i];
+          rb[i] = *reinterpret_cast<const v4i*>(B + (int64_t)min(c0 + prow + 32 * i, Cn - 1) * ldb + coln);
+        }
       }
+      if (ks + 1 < 4) {                                                     // fragments one sub-step ahead
+        const int poff = ((2 * (ks + 1) + kg) ^ fsw) << 4;
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const int row = wc + 32 * b + li, p = 2 * ks + kg;
-        fb[b] = *reinterpret_cast<const v8bf*>(&lds[st][1][row * 128 + ((p ^ ((row >> 1) & 7)) << 4)]);
+        for (int a = 0; a < TM; ++a) fa[(ks + 1) & 1][a] = *reinterpret_cast<const v8bf*>(st + fa_off + a * 32 * 128 + poff);
+#pragma unroll
+        for (int b = 0; b < TN; ++b) fb[(ks + 1) & 1][b] = *reinterpret_cast<const v8bf*>(st + fb_off + b * 32 * 128 + poff);
       }
+      __builtin_amdgcn_sched_barrier(0);                                   // (all of that stays ahead of the MFMAs)
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < TN; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][a], fb[ks & 1][b], acc[a][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (s + 1 < steps) {
-      stage_store(st ^ 1);              // the other stage: its last readers passed the barrier of step s - 1
-      __syncthreads();
-    }
+    __syncthreads();
   }
 
   // D of a 32 x 32 MFMA tile: lane (li, kg) holds column li, rows 8 (v / 4) + 4 kg + v % 4
   const float mul = mul_p ? mul_p[0] : 1.0f;
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < TM; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < TN; ++b) {
       const int c = c0 + wc + 32 * b + li;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -241,18 +263,30 @@ __global__ __launch_bounds__(SB_THREADS) void ste_gemm_nt_kernel(const uint16_t*
 // ---------------------------------------------------------------- host
 size_t bl_ste_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   const int64_t Nc = bl_round_up(N, 64), Mc = bl_round_up(M, 64);
-  return (size_t)(K * Nc + N * Mc + K * Mc + (N % 8 ? M * Nc : 0)) * 2;
+  return (size_t)(K * Nc + N * Mc + K * Mc + (N % 64 ? M * Nc : 0)) * 2;
 }
 
+template <typename OutT, int TM, int TN>
+static int sb_gemm_go(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int64_t R, int64_t Cn, int64_t J,
+                      const float* mul, OutT* C, int64_t ldc, hipStream_t s) {
+  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr size_t smem = 2 * (size_t)(BM + BN) * 128;
+  const int64_t RT = (R + BM - 1) / BM, CT = (Cn + BN - 1) / BN;
+  if (!bl_grid_ok(RT * CT)) return BL_ESHAPE;
+  BL_SET_MAX_LDS_ONCE((ste_gemm_nt_kernel<OutT, TM, TN>), smem);
+  ste_gemm_nt_kernel<OutT, TM, TN><<<(unsigned)(RT * CT), SB_THREADS, smem, s>>>(A, lda, B, ldb, (int)R, (int)Cn, (int)J,
+                                                                                mul, C, ldc, (int)RT, (int)CT);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}
+
+// 256 x 256 tiles where they fill the chip at least twice, else 128 x 128.
 template <typename OutT>
 static int sb_gemm(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int64_t R, int64_t Cn, int64_t J,
                    const float* mul, OutT* C, int64_t ldc, hipStream_t s) {
-  const int64_t RT = (R + SB_BM - 1) / SB_BM, CT = (Cn + SB_BN - 1) / SB_BN;
-  if (!bl_grid_ok(RT * CT)) return BL_ESHAPE;
-  ste_gemm_nt_kernel<OutT><<<(unsigned)(RT * CT), SB_THREADS, 0, s>>>(A, lda, B, ldb, (int)R, (int)Cn, (int)J, mul, C,
-                                                                     ldc, (int)RT, (int)CT);
-  BL_HIP_CHECK_LAUNCH();
-  return BL_OK;
+  if (((R + 255) / 256) * ((Cn + 255) / 256) >= 2 * (int64_t)bl_num_cus())
+    return sb_gemm_go<OutT, 4, 4>(A, lda, B, ldb, R, Cn, J, mul, C, ldc, s);
+  return sb_gemm_go<OutT, 2, 2>(A, lda, B, ldb, R, Cn, J, mul, C, ldc, s);
 }
 
 // q: INT4 nibble codes [M][Kp / 2] (a4 = true) or INT8 codes [M][Kp]; Wk: BL_W_KMAJOR.
@@ -265,7 +299,7 @@ int bl_launch_ste_backward(const void* dY, int64_t M, int64_t N, int64_t K, cons
   uint16_t* qt = dYt + N * Mc;
   const uint16_t* dYa = reinterpret_cast<const uint16_t*>(dY);           // dY with 16-byte aligned rows
   int64_t ldy = N;
-  if (N % 8) {
+  if (N % 64) {                                                          // (the contraction of dX runs to Nc)
     uint16_t* dYp = qt + K * Mc;
     const int64_t pieces = M * (Nc >> 3);
     if (!bl_grid_ok((pieces + 255) / 256)) return BL_ESHAPE;
@@ -274,7 +308,6 @@ int bl_launch_ste_backward(const void* dY, int64_t M, int64_t N, int64_t K, cons
     dYa = dYp;
     ldy = Nc;
   }
-  const int64_t Jx = bl_round_up(N, 8);                                  // contraction length of dX in whole pieces
   if (dX) {
     const int64_t words = K * (Nc >> 4);
     if (!bl_grid_ok((words + 255) / 256)) return BL_ESHAPE;
@@ -282,9 +315,9 @@ int bl_launch_ste_backward(const void* dY, int64_t M, int64_t N, int64_t K, cons
     BL_HIP_CHECK_LAUNCH();
     int rc;
     if (dx_dtype == BL_F32)
-      rc = sb_gemm<float>(dYa, ldy, Tb, Nc, M, K, Jx, alpha, reinterpret_cast<float*>(dX), K, s);
+      rc = sb_gemm<float>(dYa, ldy, Tb, Nc, M, K, Nc, alpha, reinterpret_cast<float*>(dX), K, s);
     else
-      rc = sb_gemm<uint16_t>(dYa, ldy, Tb, Nc, M, K, Jx, alpha, reinterpret_cast<uint16_t*>(dX), K, s);
+      rc = sb_gemm<uint16_t>(dYa, ldy, Tb, Nc, M, K, Nc, alpha, reinterpret_cast<uint16_t*>(dX), K, s);
     if (rc != BL_OK) return rc;
   }
   if (dW) {
