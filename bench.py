@@ -220,7 +220,13 @@ def main():
         rc = L.quantize_act(x_hidden.data_ptr(), B.BL_BF16, M, HIDDEN, b["mode"], 0, EPS, b["q"].data_ptr(),
                             b["scale"].data_ptr(), None, None, stream)
         assert rc == 0, rc
-        print(json.dumps({"operand_data_probe": operand_data_probe(B, L, torch, M, b, W["qkv"], A4L, stream)}))
+        bo = bufs["o"]
+        rc = L.quantize_act(x_attn.data_ptr(), B.BL_BF16, M, HIDDEN, bo["mode"], HIDDEN // 2, EPS, bo["q"].data_ptr(),
+                            bo["scale"].data_ptr(), None, None, stream)
+        assert rc == 0, rc
+        print(json.dumps({"operand_data_probe": {
+            "qkv_block_float_gemm": operand_data_probe(B, L, torch, M, 3 * HIDDEN, HIDDEN, b, W["qkv"], A4L, stream),
+            "o_int8_gemm": operand_data_probe(B, L, torch, M, HIDDEN, HIDDEN, bo, W["o"], B.BL_W_GEMM, stream)}}))
         return
 
     if args.no_prefill:
@@ -290,7 +296,9 @@ def main():
     }
     out["ffn_front"] = ffn_front_bench(B, L, torch, M, x_hidden, bufs["gate"], W, A4L, H_ffn, stream)
     if not args.no_probe:
-        out["operand_data_probe"] = operand_data_probe(B, L, torch, M, bufs["qkv"], W["qkv"], A4L, stream)
+        out["operand_data_probe"] = {
+            "qkv_block_float_gemm": operand_data_probe(B, L, torch, M, 3 * HIDDEN, HIDDEN, bufs["qkv"], W["qkv"], A4L, stream),
+            "o_int8_gemm": operand_data_probe(B, L, torch, M, HIDDEN, HIDDEN, bufs["o"], W["o"], B.BL_W_GEMM, stream)}
     if not args.no_decode:
         out["decode"] = decode_bench(B, S, torch, dev, tokens=tuple(args.decode_tokens))
         out["decode_ffn_1token"] = decode_ffn_bench(B, S, torch, dev)
@@ -351,18 +359,17 @@ def ffn_front_bench(B, L, torch, M, X, b, W, A4L, H, stream, iters=20):
     return res
 
 
-def operand_data_probe(B, L, torch, M, b, Wq, A4L, stream, iters=20):
-    """The qkv GEMM of the step timed on its real operands, then with the activation codes zeroed, then with
+def operand_data_probe(B, L, torch, M, N, K, b, Wq, layout, stream, iters=20):
+    """One GEMM of the step timed on its real operands, then with the activation codes zeroed, then with
     the weights zeroed too.  The kernel executes the same instructions on the same addresses in all three
     (no branch depends on a code or a weight), so a shorter time can only come from a higher clock: the
     matrix units draw less power when their operands do not toggle."""
-    N, K = 3 * HIDDEN, HIDDEN
     q0 = b["q"].clone()
     w0 = Wq[0].clone()
     Y = b["Y"]
 
     def run(q, w):
-        rc = L.bitlinear_gemm(q.data_ptr(), b["scale"].data_ptr(), b["mode"], M, K, w.data_ptr(), A4L,
+        rc = L.bitlinear_gemm(q.data_ptr(), b["scale"].data_ptr(), b["mode"], M, K, w.data_ptr(), layout,
                               Wq[1].data_ptr(), N, Y.data_ptr(), B.BL_BF16, None, b["ws"].data_ptr(),
                               b["ws"].numel(), stream)
         assert rc == 0, rc

@@ -647,7 +647,8 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
   for (int w = 0; w < NWD; ++w) eq_total += __popc(act[w]);
   eq_total = qa_wave_sum_dpp(eq_total);
   const int r = topk - above;
-  const bool eq_all = eq_total <= r;                      // wave-uniform
+  // (keys equal to a tau 8 binades below the row maximum have code 0 kept or not: no prefix search then)
+  const bool eq_all = eq_total <= r || tau + 1024u <= kmax;   // wave-uniform
   const u32 t1 = (tau + 1u) * 0x10001u, t0 = tau * 0x10001u;
   const u32 tk = eq_all ? t0 : t1;
   const uint64_t lt_mask = (1ull << lane) - 1ull;

@@ -88,11 +88,15 @@ __device__ __forceinline__ void qa_bit_transpose16(u32 (&w)[8]) {
 // wave that is all of them, none of them, or (for one wave of the token) a prefix found with
 // ballots.  raw / pg: the wave's chunks as loaded / with the guard bits set; out0: this lane's word
 // of the wave's first chunk (chunk i at out0[64 i]); sum: the sum of the lane's codes is added to it.
+// ties_matter = false: the keys equal to tau have code 0 whether they are kept or not (tau is at least 8
+// binades below the row maximum: |x| s <= 127 / 256), so the wave keeps all of them and the prefix
+// search is skipped -- the usual case for rows that are mostly zeros, where tau = 0.
 template <int CPW>
 __device__ __forceinline__ void qa_code_chunks(const u32 (&raw)[CPW][2], const u32 (&pg)[CPW][2], int nc, u32 tau,
-                                               int r, int eq_base, int eq_here, float s, u32* out0, int& sum) {
+                                               int r, int eq_base, int eq_here, float s, u32* out0, int& sum,
+                                               bool ties_matter = true) {
   const int lane = threadIdx.x & 63;
-  const bool eq_all = eq_base + eq_here <= r;
+  const bool eq_all = !ties_matter || eq_base + eq_here <= r;
   const bool eq_none = eq_base >= r;
   const u32 t1 = (tau + 1u) * 0x10001u, t0 = tau * 0x10001u;
   const u32 tk = eq_all ? t0 : t1;
@@ -258,7 +262,7 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
   eq_base = __builtin_amdgcn_readfirstlane(eq_base);
   const int eq_here = __builtin_amdgcn_readfirstlane((int)sh_c[wave]);
   int sum = 0;
-  qa_code_chunks<CPW>(raw, pg, nc, tau, r, eq_base, eq_here, s, out + c_begin * 64 + lane, sum);
+  qa_code_chunks<CPW>(raw, pg, nc, tau, r, eq_base, eq_here, s, out + c_begin * 64 + lane, sum, tau + 1024u > kmax);
   if (rowsum_out) {
     sum = qa_wave_sum_dpp(sum);
     __syncthreads();
