@@ -204,6 +204,37 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
   // a handful of instructions per lane instead of 1.5 per key.
   constexpr int NBK = CPW / 4;                            // blocks of 16 keys per lane
   static_assert(CPW % 4 == 0 && NBK >= 1 && NBK <= 3, "16 keys per block, at most 48 keys per lane");
+  // Mostly-zero rows (the FFN's intermediate state) need no search at all: a key at or below
+  // C = kmax - 8 binades has code 0 kept or not, so if no more than topk keys lie above C, keeping
+  // exactly those gives the codes of the exact selection.  One count and one barrier decide it.
+  if (kmax > 1024u) {                                     // workgroup-uniform
+    const u32 cc = (kmax - 1024u + 1u) * 0x10001u;        // key > C  <=>  guard bit of (key | guard) - (C + 1) stays set
+    int n_hi = 0;
+#pragma unroll
+    for (int i = 0; i < CPW; ++i)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) n_hi += __popc((pg[i][h] - cc) & QA_GUARD);
+    n_hi = qa_wave_sum_dpp(n_hi);
+    if (lane == 0) sh_c[wave] = (u32)n_hi;
+    __syncthreads();
+    const uint4 t = *reinterpret_cast<const uint4*>(sh_c);
+    const int total_hi = __builtin_amdgcn_readfirstlane((int)(t.x + t.y + t.z + t.w));
+    if (total_hi <= topk) {
+      int sum = 0;
+      qa_code_chunks<CPW>(raw, pg, nc, kmax - 1024u, 0, 0, 0, s, out + c_begin * 64 + lane, sum, false);
+      if (rowsum_out) {
+        sum = qa_wave_sum_dpp(sum);
+        if (lane == 0) sh_a[0][wave] = (u32)sum;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          const uint4 t2 = *reinterpret_cast<const uint4*>(sh_a[0]);
+          rowsum_out[0] = (int32_t)(t2.x + t2.y + t2.z + t2.w);
+        }
+      }
+      return;
+    }
+    // (sh_c is written again only after the barriers of the passes below)
+  }
   u32 pl[NBK][8];
 #pragma unroll
   for (int B = 0; B < NBK; ++B) {
@@ -295,7 +326,7 @@ __device__ __forceinline__ void qa_topk_row_regs(const void* __restrict__ x, con
 //     tie rule (lower channel first; waves own contiguous channel ranges) needs: no further exchange.
 //   raw     this wave's chunks of 256 channels as loaded by the caller (chunk i of the wave = chunk
 //           c_begin + i of the token; 4 consecutive channels per lane; zero beyond K and beyond nc)
-//   sh      80 words of LDS scratch (16-byte aligned)
+//   sh      80 words of LDS scratch (16-byte aligned): row maxima [8], early counts [8], class sizes [2][32]
 // Chunks are dealt to the waves in contiguous ranges of per_wave = ceil(n_chunks / 8), so channel
 // order is (wave, chunk, lane, j) order as in the 4-wave body.  Every thread of the workgroup must
 // call it (it has barriers); the caller adds the barrier that publishes the codes.
@@ -347,8 +378,30 @@ __device__ __forceinline__ void qa_topk_row_regs8(const u32 (&raw)[CPW][2], int 
   const float s = 127.0f / (gamma + eps);
   if (tid == 0) scale_out[0] = gamma / 127.0f;
 
-  // 11-bit keys and their bit planes: plane(bit) has key r of the lane in bit r
   const u32 C = kmax > 1024u ? kmax - 1024u : 0u;
+  // Wide rows are FFN states, mostly zeros: if no more than topk keys lie above C, keeping exactly those
+  // gives the codes of the exact selection (a key at or below C has code 0 kept or not), and neither bit
+  // planes nor passes are needed.  One count, one barrier (words 8..15 of `sh`).
+  if constexpr (CPW == 8) {
+    if (C > 0u) {                                         // workgroup-uniform
+      const u32 cc = (C + 1u) * 0x10001u;
+      int n_hi = 0;
+#pragma unroll
+      for (int i = 0; i < CPW; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) n_hi += __popc((pg[i][h] - cc) & QA_GUARD);
+      n_hi = qa_wave_sum_dpp(n_hi);
+      if (lane == 0) sh[8 + wave] = (u32)n_hi;
+      __syncthreads();
+      const int total_hi = __builtin_amdgcn_readfirstlane((int)qa_sum8_dpp(sh[8 + (lane & 7)]));
+      if (total_hi <= topk) {
+        int sum = 0;
+        qa_code_chunks<CPW>(raw, pg, nc, C, 0, 0, 0, s, out + c_begin * 64 + lane, sum, false);
+        return;
+      }
+    }
+  }
+  // 11-bit keys and their bit planes: plane(bit) has key r of the lane in bit r
   const us2 C2 = __builtin_bit_cast(us2, C * 0x10001u);
   u32 pl[NBK][8];
 #pragma unroll
