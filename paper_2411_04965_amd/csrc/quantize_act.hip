@@ -592,14 +592,18 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
   const float s = 127.0f / (gamma + eps);
   if (lane == 0) scale_out[m] = gamma / 127.0f;
 
-  // bit planes of the lane's keys; mask word w covers blocks 2w, 2w+1 = local chunks 8w .. 8w+7,
-  // chunk i in bits 4 (i % 8) .. +3, element j of the chunk in bit j of those
-  u32 pl[NB][8];
+  // Rows wider than 4096 channels are FFN states, mostly zeros: if no more than topk keys lie above
+  // C = kmax - 8 binades, keeping exactly those gives the codes of the exact selection (a key at or
+  // below C has code 0 kept or not) and the search is skipped.
+  bool early = false;
+  if (NB > 4 && kmax > 1024u) {                           // wave-uniform
+    const u32 cc = (kmax - 1024u + 1u) * 0x10001u;
+    int n_hi = 0;
 #pragma unroll
-  for (int B = 0; B < NB; ++B) {
+    for (int i = 0; i < NC; ++i)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) pl[B][i] = raw[4 * B + (i >> 1)][i & 1] & 0x7FFF7FFFu;
-    qa_bit_transpose16(pl[B]);
+      for (int h = 0; h < 2; ++h) n_hi += __popc(((raw[i][h] | QA_GUARD) - cc) & QA_GUARD);
+    early = qa_wave_sum_dpp(n_hi) <= topk;
   }
   u32 act[NWD];
 #pragma unroll
@@ -607,33 +611,44 @@ __global__ __launch_bounds__(QA_THREADS) void quant_topk_int8_wave_kernel(
     const int nreal = min(max(nc - 8 * w, 0), 8);         // chunks the token does not have stay out
     act[w] = nreal >= 8 ? 0xFFFFFFFFu : ((1u << (4 * nreal)) - 1u);
   }
-  u32 tau = 0;
+  u32 tau = early ? kmax - 1024u : 0u;
   int above = 0;
-  const int top_bit = 31 - __clz((int)(kmax | 1u));
+  if (!early) {
+    // bit planes of the lane's keys; mask word w covers blocks 2w, 2w+1 = local chunks 8w .. 8w+7,
+    // chunk i in bits 4 (i % 8) .. +3, element j of the chunk in bit j of those
+    u32 pl[NB][8];
 #pragma unroll
-  for (int bit = 14; bit >= 0; --bit) {
-    if (bit <= top_bit) {                                 // wave-uniform
-      u32 xw[NWD];
-      int cnt = 0;
+    for (int B = 0; B < NB; ++B) {
 #pragma unroll
-      for (int w = 0; w < NWD; ++w) {
-        u32 p;
-        if (2 * w + 1 < NB)
-          p = __builtin_amdgcn_perm(pl[2 * w + 1][bit >> 1], pl[2 * w][bit >> 1], (bit & 1) ? 0x07060302u : 0x05040100u);
-        else
-          p = (bit & 1) ? pl[2 * w][bit >> 1] >> 16 : pl[2 * w][bit >> 1] & 0xFFFFu;
-        xw[w] = act[w] & p;
-        cnt += __popc(xw[w]);
-      }
-      const int total = qa_wave_sum_dpp(cnt);
-      if (above + total >= topk) {
-        tau |= 1u << bit;
+      for (int i = 0; i < 8; ++i) pl[B][i] = raw[4 * B + (i >> 1)][i & 1] & 0x7FFF7FFFu;
+      qa_bit_transpose16(pl[B]);
+    }
+    const int top_bit = 31 - __clz((int)(kmax | 1u));
 #pragma unroll
-        for (int w = 0; w < NWD; ++w) act[w] = xw[w];
-      } else {
-        above += total;
+    for (int bit = 14; bit >= 0; --bit) {
+      if (bit <= top_bit) {                                 // wave-uniform
+        u32 xw[NWD];
+        int cnt = 0;
 #pragma unroll
-        for (int w = 0; w < NWD; ++w) act[w] ^= xw[w];
+        for (int w = 0; w < NWD; ++w) {
+          u32 p;
+          if (2 * w + 1 < NB)
+            p = __builtin_amdgcn_perm(pl[2 * w + 1][bit >> 1], pl[2 * w][bit >> 1], (bit & 1) ? 0x07060302u : 0x05040100u);
+          else
+            p = (bit & 1) ? pl[2 * w][bit >> 1] >> 16 : pl[2 * w][bit >> 1] & 0xFFFFu;
+          xw[w] = act[w] & p;
+          cnt += __popc(xw[w]);
+        }
+        const int total = qa_wave_sum_dpp(cnt);
+        if (above + total >= topk) {
+          tau |= 1u << bit;
+#pragma unroll
+          for (int w = 0; w < NWD; ++w) act[w] = xw[w];
+        } else {
+          above += total;
+#pragma unroll
+          for (int w = 0; w < NWD; ++w) act[w] ^= xw[w];
+        }
       }
     }
   }
