@@ -65,6 +65,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-fp4", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the operand-data probe of the qkv GEMM")
+    ap.add_argument("--step-only", action="store_true",
+                    help="time the prefill step and nothing else (for counter runs: every launch of the process is then "
+                         "one of the step's eight kernels)")
     ap.add_argument("--probe-only", action="store_true",
                     help="run only the operand-data probe (for a counter run: its launches are then the only "
                          "block-float GEMM launches of the process, 23 per operand setting, in order)")
@@ -294,6 +297,9 @@ def main():
         "roofline": roofline,
         "kernels": per_kernel,
     }
+    if args.step_only:
+        print(json.dumps(out))
+        return
     out["ffn_front"] = ffn_front_bench(B, L, torch, M, x_hidden, bufs["gate"], W, A4L, H_ffn, stream)
     if not args.no_probe:
         out["operand_data_probe"] = {
