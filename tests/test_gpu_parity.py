@@ -166,6 +166,47 @@ def test_quantize_topk_int8_seeded_sweep():
         assert np.array_equal(host(r["rowsum"])[rows], q_ref.sum(1, dtype=np.int32))
 
 
+def _rows_around_the_shortcut(M, K, n_big, seed):
+    """Rows with exactly n_big values within 8 binades of the row maximum; the rest are zeros or values
+    below gamma / 256 (their codes are 0 whether Top_k keeps them or not), some of them equal to each other."""
+    rng = np.random.default_rng(seed)
+    x = np.zeros((M, K), np.float32)
+    for m in range(M):
+        big = rng.choice(K, n_big, replace=False)
+        x[m, big] = (rng.standard_normal(n_big) * 3 + np.sign(rng.standard_normal(n_big)) * 0.5).astype(np.float32)
+        x[m, big[0]] = 40.0                                                    # the row maximum: gamma / 256 = 0.156
+        x[m, big] = np.where(np.abs(x[m, big]) < 0.2, 0.25, x[m, big])
+        small = np.setdiff1d(np.arange(K), big)
+        tiny = rng.choice(small, len(small) // 3, replace=False)
+        x[m, tiny] = (rng.integers(1, 5, len(tiny)) * 0.03125 * np.sign(rng.standard_normal(len(tiny)))).astype(np.float32)
+    return S.snap_bf16(x)
+
+
+@pytest.mark.parametrize("M,K", [(3, 11008), (2050, 5460), (2, 4096), (40, 9000)])
+def test_quantize_topk_shortcut_boundary(M, K):
+    """The Top-K kernels skip the threshold search when no more than topk keys lie within 8 binades of the
+    row maximum: topk one below, at and one above that count, and far above it, on rows whose remaining
+    values are zeros and tied small values; codes, scales and code sums bit for bit the oracle's.  Covers
+    the four-wave, the one-wave and (through the decode linear, one token) the eight-wave body."""
+    n_big = K // 5
+    x = _rows_around_the_shortcut(M, K, n_big, S.seed_for(0, 77 + K))
+    rows = np.arange(M) if M < 64 else np.array([0, 1, 7, M // 2, M - 1])
+    for topk in (n_big - 1, n_big, n_big + 1, K // 2, K):
+        say("shortcut boundary M=%d K=%d n_big=%d topk=%d" % (M, K, n_big, topk))
+        q_ref, d_ref, _ = O.quant_topk_int8(x[rows], topk, EPS)
+        r = B.quantize_act(dev(x, BF16), B.BL_ACT_TOPK_INT8_ABSMAX, topk, EPS, want_rowsum=True)
+        assert np.array_equal(host(r["scale"])[rows], d_ref)
+        assert np.array_equal(decode_int8(host(r["q"]), M, K)[rows], q_ref)
+        assert np.array_equal(host(r["rowsum"])[rows], q_ref.sum(1, dtype=np.int32))
+    # one token through the decode linear (the selection runs inside the GEMV launch)
+    N = 2064
+    W = S.latent_weights(N, K, S.seed_for(0, 78 + K))
+    p, a = pack(W)
+    for topk in (n_big - 1, n_big, n_big + 1, K // 2):
+        ref = O.bitlinear_a8_sparse(x[:1], W, topk, EPS, "f32")
+        _check_linear(B.bitlinear_a8_sparse(dev(x[:1], BF16), topk, p, a, N, EPS, B.BL_W_GEMM, F32, True), ref, F32)
+
+
 @pytest.mark.parametrize("M,K,topk,dtype", [(9, 5460, 2730, F32), (2051, 5460, 2730, F32), (33, 11008, 5504, BF16),
                                             (2050, 4096, 2048, BF16), (5, 1000, 1, BF16), (7, 12288, 12288, F32)])
 def test_quantize_glu_topk_int8(M, K, topk, dtype):
