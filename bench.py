@@ -437,8 +437,9 @@ def ste_backward_bench(B, S, torch, dev, M, iters=5):
 
 def decode_ffn_bench(B, S, torch, dev, layers=8, replays=20):
     """One token through the FFN's three linears and its glue at 7B width, from HIP-graph replays of
-    `layers` distinct weight sets: gate, up, ReLU^2 GLU, down as four calls against the gate-first
-    form (gate, then the up projection only where the gate is open with the GLU inside, then down)."""
+    `layers` distinct weight sets: gate, up, ReLU^2 GLU, down as four calls; the gate-first form (gate,
+    then the up projection only where the gate is open with the GLU inside, then down); and gate + up +
+    GLU as one launch followed by down."""
     bf16 = torch.bfloat16
     X = torch.from_numpy(S.heavy(1, HIDDEN, S.seed_for(2, 900))).to(dev).to(bf16)
     sets = []
@@ -470,9 +471,19 @@ def decode_ffn_bench(B, S, torch, dev, layers=8, replays=20):
         Hh = B.bitlinear_a4_up_gated(X, pr, ar, FFN, G, EPS)
         B.bitlinear_a8_sparse(Hh, FFN // 2, pd, ad, HIDDEN, EPS, ws=ws8, out=Y)
 
+    Hb = torch.empty((1, FFN), dtype=bf16, device=dev)
+    ws_gu = torch.empty(max(B.lib().bitlinear_gate_up_workspace_bytes(1, FFN, HIDDEN, B.BL_W_GEMM), 16), dtype=torch.uint8,
+                        device=dev)
+
+    def one_launch_front(l):
+        # gate, up and eq. 5 in one launch (H only), then down
+        (pg, ag), (pu, au), _, (pd, ad) = sets[l]
+        B.bitlinear_a4_gate_up(X, pg, ag, pu, au, FFN, EPS, B.BL_W_GEMM, want=("H",), ws=ws_gu, out={"H": Hb})
+        B.bitlinear_a8_sparse(Hb, FFN // 2, pd, ad, HIDDEN, EPS, ws=ws8, out=Y)
+
     res = {}
     side = torch.cuda.Stream()
-    for name, fn in (("four_calls", dense), ("gate_first", gate_first)):
+    for name, fn in (("four_calls", dense), ("gate_first", gate_first), ("gate_up_glu_then_down", one_launch_front)):
         for l in range(layers):
             fn(l)
         torch.cuda.synchronize()
