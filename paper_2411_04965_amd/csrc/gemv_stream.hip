@@ -224,7 +224,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_stream_kernel(
                "s"(m1.NT), "s"(H), "s"(y_bf16), "s"(upb), "s"(urem), "s"(topk));
   const int KT = Kp >> 8;
 
-  // ---- requests first.  Tokens (or their codes), then round 0 of the weights: loads come back in the
+  // ---- requests first.  Tokens (or their codes), then the first batch of weight tiles: loads come back in the
   // order they were issued, so the short token rows arrive at once and the quantizer (or the copy into
   // LDS) runs while the weights stream in.  Every weight load is unconditional (indices past the
   // workgroup's last tile re-read that tile, a cache hit) so that the compiler can count the loads in
