@@ -80,7 +80,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(sample_tokens=128):
+def cpu_baseline(sample_tokens=1024):
     """The oracle, as it stands, on a bounded sample: the qkv projection (INT4 quantize,
     integer matmul, rescale) for `sample_tokens` tokens at full N and K."""
     from oracle import bitnet_a48 as O
@@ -101,7 +101,7 @@ def cpu_baseline(sample_tokens=128):
         acc = O.matmul_int(q, T)
         O.rescale(acc, d, alpha, "bf16")
         reps += 1
-        if time.perf_counter() - t0 > 10.0 or reps >= 20:
+        if time.perf_counter() - t0 > 12.0 or reps >= 40:
             break
     dt = (time.perf_counter() - t0) / reps
     tops = 2.0 * sample_tokens * N * K / dt / 1e12
