@@ -530,6 +530,20 @@ extern "C" int bitlinear_a4_gate_up(const void* X, bl_dtype x_dtype, int64_t M, 
     return bl_launch_gemm_a4_mx_glu(codes, (const float*)scales, M, K, W_gate, alpha_gate, W_up, alpha_up,
                                     layout == BL_W_MX2, N, H, s);
   }
+  // 9 to 16 tokens (or tokens that are not bfloat16), 2-bit tile weights, only H wanted: the stand-alone
+  // quantizer, then both products and eq. 5 in one launch of the streaming kernel
+  if (layout == BL_W_GEMM && H && !G && !U && bl_gemv_stream_glu_codes_ok(M, N, K)) {
+    rc = bl_launch_quantize(X, x_dtype, M, K, mode, 0, eps, codes, scales, nullptr, nullptr, s);
+    if (rc) return rc;
+    return bl_launch_gemv_stream_glu_codes(codes, (const float*)scales, M, K, W_gate, alpha_gate, W_up, alpha_up, N, H, s);
+  }
+  // 17 to 64 tokens, 2-bit tile weights, only H wanted: both products and eq. 5 in one launch of the
+  // kernel that keeps the tokens' codes in LDS
+  if (layout == BL_W_GEMM && H && !G && !U && bl_gemm_decode_glu_ok(M, N, K)) {
+    rc = bl_launch_quantize(X, x_dtype, M, K, mode, 0, eps, codes, scales, nullptr, nullptr, s);
+    if (rc) return rc;
+    return bl_launch_gemm_decode_glu(codes, (const float*)scales, M, K, W_gate, alpha_gate, W_up, alpha_up, N, H, s);
+  }
   // when H is wanted the products are kept in float32 (eq. 5 combines them before any rounding)
   const bool need_f32 = H != nullptr && gu_dtype != BL_F32;
   void* Gt = G;

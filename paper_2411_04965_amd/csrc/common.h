@@ -178,4 +178,10 @@ size_t bl_ste_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int bl_launch_ste_backward(const void* dY, int64_t M, int64_t N, int64_t K, const void* q, const float* scale, bool a4,
                            const void* Wk, const float* alpha, void* dX, bl_dtype dx_dtype, float* dW, void* ws,
                            hipStream_t s);
+bool bl_gemm_decode_glu_ok(int64_t M, int64_t N, int64_t K);
+int bl_launch_gemm_decode_glu(const void* q, const float* scale, int64_t M, int64_t K, const void* Wg, const float* ag,
+                              const void* Wu, const float* au, int64_t N, void* H, hipStream_t s);
+bool bl_gemv_stream_glu_codes_ok(int64_t M, int64_t N, int64_t K);
+int bl_launch_gemv_stream_glu_codes(const void* q, const float* scale, int64_t M, int64_t K, const void* Wg,
+                                    const float* ag, const void* Wu, const float* au, int64_t N, void* H, hipStream_t s);
 

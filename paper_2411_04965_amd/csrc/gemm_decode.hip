@@ -639,12 +639,18 @@ __global__ __launch_bounds__(GD_THREADS) void gemm_decode_rows_kernel(
 #define GR_G 3
 #define GR_X_BYTES 131072                        // LDS for the codes (pitch = row bytes + 16)
 #define GR_LDS_MAX (160 * 1024)                  // the LDS of a compute unit
-template <int MT, bool A4>
+// GLU: two weight matrices of one shape (gate, up).  The block's NWT tiles are then tile PAIRS in the order
+// gate tile j, up tile j, a wave's group is one pair (G = 2), and the epilogue writes
+// H = bf16(u * max(g, 0)^2) of the two rescaled float32 values (eq. 5; `Y` is H, bfloat16) instead of
+// the products themselves.  No split of K across blocks in that form (S = 1).
+template <int MT, bool A4, bool GLU = false>
 __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
     const unsigned char* __restrict__ A, const float* __restrict__ scale, int M, int Kp,
     const unsigned char* __restrict__ Wp, const float* __restrict__ alpha_p, int N,
     void* __restrict__ Y, int y_bf16, int32_t* __restrict__ acc_out, int32_t* __restrict__ partial,
-    int NBn, int S, int NWT, int KS) {
+    int NBn, int S, int NWT, int KS, const unsigned char* __restrict__ Wp2 = nullptr,
+    const float* __restrict__ alpha2_p = nullptr) {
+  constexpr int G = GLU ? 2 : GR_G;              // output tiles per working wave
   extern __shared__ __align__(16) unsigned char gr_smem[];
   constexpr int TB = A4 ? 128 : 256;             // bytes of one token row per K tile
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -653,26 +659,30 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
   const int KT = Kp >> 8;
   const int t_begin = (int)((int64_t)split * KT / S), t_end = (int)((int64_t)(split + 1) * KT / S);
   const int L = t_end - t_begin;                 // tiles of this slice: L * TB * MT * 16 <= GR_X_BYTES
-  const int NT16 = (N + 15) >> 4;
+  const int NT16 = GLU ? 2 * ((N + 15) >> 4) : (N + 15) >> 4;   // tiles (GLU: gate and up tiles interleaved)
   const int a_row_bytes = A4 ? (Kp >> 1) : Kp;
   const int RB = L * TB, pitch = RB + 16, ppr = RB >> 4;
 
   // this wave's part of the work, and its first weight tiles (issued before the codes are staged)
-  const int NG = (NWT + GR_G - 1) / GR_G;
+  const int NG = (NWT + G - 1) / G;
   const int grp = wave / KS, ks = wave % KS;
-  const int g0 = grp * GR_G;                     // first output tile of the group, within the block
+  const int g0 = grp * G;                        // first output tile of the group, within the block
   const int nt0 = nbk * NWT + g0;
-  const int ng = grp < NG ? max(0, min(min(GR_G, NWT - g0), NT16 - nt0)) : 0;
+  const int ng = grp < NG ? max(0, min(min(G, NWT - g0), NT16 - nt0)) : 0;
   const int my_begin = t_begin + (int)((int64_t)ks * L / KS), my_end = t_begin + (int)((int64_t)(ks + 1) * L / KS);
-  const unsigned char* w_src[GR_G];
+  const unsigned char* w_src[G];
 #pragma unroll
-  for (int g = 0; g < GR_G; ++g) w_src[g] = Wp + (size_t)min(nt0 + g, NT16 - 1) * KT * 1024 + lane * 16;
-  uint4 wq[2][GR_G];
+  for (int g = 0; g < G; ++g) {
+    const int v = min(nt0 + g, NT16 - 1);
+    if (GLU) w_src[g] = ((v & 1) ? Wp2 : Wp) + (size_t)(v >> 1) * KT * 1024 + lane * 16;
+    else w_src[g] = Wp + (size_t)v * KT * 1024 + lane * 16;
+  }
+  uint4 wq[2][G];
   if (ng > 0 && my_begin < my_end) {
 #pragma unroll
     for (int d = 0; d < 2; ++d)
 #pragma unroll
-      for (int g = 0; g < GR_G; ++g)
+      for (int g = 0; g < G; ++g)
         wq[d][g] = *reinterpret_cast<const uint4*>(w_src[g] + (size_t)min(my_begin + d, my_end - 1) * 1024);
   }
 
@@ -699,9 +709,9 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
   }
   __syncthreads();
 
-  v4i acc[GR_G][MT];
+  v4i acc[G][MT];
 #pragma unroll
-  for (int g = 0; g < GR_G; ++g)
+  for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int b = 0; b < MT; ++b) acc[g][b] = (v4i){0, 0, 0, 0};
   if (ng > 0) {
@@ -711,12 +721,12 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
       for (int d = 0; d < 2; ++d) {
         const int t = t0 + d;
         if (t < my_end) {                        // wave-uniform
-          uint4 wc[GR_G];
+          uint4 wc[G];
 #pragma unroll
-          for (int g = 0; g < GR_G; ++g) wc[g] = wq[d][g];
+          for (int g = 0; g < G; ++g) wc[g] = wq[d][g];
           if (t + 2 < my_end) {
 #pragma unroll
-            for (int g = 0; g < GR_G; ++g)
+            for (int g = 0; g < G; ++g)
               wq[d][g] = *reinterpret_cast<const uint4*>(w_src[g] + (size_t)(t + 2) * 1024);
           }
           const unsigned char* xb = xrow + (t - t_begin) * TB;
@@ -735,7 +745,7 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
               }
             }
 #pragma unroll
-            for (int g = 0; g < GR_G; ++g) {
+            for (int g = 0; g < G; ++g) {
               if (g < ng) {                      // wave-uniform
                 const u32 w = t4 == 0 ? wc[g].x : t4 == 1 ? wc[g].y : t4 == 2 ? wc[g].z : wc[g].w;
                 const v4i wo = (v4i){(int)((w << 6) & 0xC0C0C0C0u), (int)((w << 4) & 0xC0C0C0C0u),
@@ -756,23 +766,23 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
   // and writes the totals as int32 [MT * 16 tokens][NWT * 16 outputs (+ 4)] behind them.
   const int OP = NWT * 16 + 4;                   // row pitch in words
   v4i* parts = reinterpret_cast<v4i*>(gr_smem);  // [working wave][g][b][lane]
-  int32_t* sums = reinterpret_cast<int32_t*>(gr_smem) + (size_t)NG * KS * GR_G * MT * 256;
+  int32_t* sums = reinterpret_cast<int32_t*>(gr_smem) + (size_t)NG * KS * G * MT * 256;
   __syncthreads();
   if (ks != 0 && ng > 0) {
 #pragma unroll
-    for (int g = 0; g < GR_G; ++g)
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int b = 0; b < MT; ++b) parts[((wave * GR_G + g) * MT + b) * 64 + lane] = acc[g][b];
+      for (int b = 0; b < MT; ++b) parts[((wave * G + g) * MT + b) * 64 + lane] = acc[g][b];
   }
   __syncthreads();
   if (ks == 0 && ng > 0) {
     for (int k = 1; k < KS; ++k)
 #pragma unroll
-      for (int g = 0; g < GR_G; ++g)
+      for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int b = 0; b < MT; ++b) acc[g][b] += parts[(((wave + k) * GR_G + g) * MT + b) * 64 + lane];
+        for (int b = 0; b < MT; ++b) acc[g][b] += parts[(((wave + k) * G + g) * MT + b) * 64 + lane];
 #pragma unroll
-    for (int g = 0; g < GR_G; ++g)
+    for (int g = 0; g < G; ++g)
       if (g < ng)
 #pragma unroll
         for (int b = 0; b < MT; ++b)
@@ -780,9 +790,42 @@ __global__ __launch_bounds__(GR_THREADS) void gemm_decode_resident_kernel(
   }
   __syncthreads();
 
-  // one thread per token and 4 consecutive outputs of the block's NWT * 16
   const float alpha = alpha_p[0];
   constexpr int SHIFT = A4 ? 10 : 6;
+  if constexpr (GLU) {
+    // one thread per token and 4 consecutive outputs of one of the block's NWT / 2 tile pairs
+    const float alpha2 = alpha2_p[0];
+    uint16_t* H = reinterpret_cast<uint16_t*>(Y);
+    const int qpr = (NWT >> 1) * 4;
+    for (int i = tid; i < M * qpr; i += GR_THREADS) {
+      const int m = i / qpr, c = (i % qpr) * 4;
+      const int n = nbk * (NWT >> 1) * 16 + c;
+      if (n >= N) continue;
+      const int col = ((c >> 4) << 5) + (c & 15);          // the gate tile's columns; the up tile's are 16 further
+      const v4i vg = *reinterpret_cast<const v4i*>(sums + m * OP + col);
+      const v4i vu = *reinterpret_cast<const v4i*>(sums + m * OP + col + 16);
+      const float d = scale[m];
+      uint16_t hv[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float g = ((float)(vg[r] >> SHIFT) * d) * alpha;
+        const float u = ((float)(vu[r] >> SHIFT) * d) * alpha2;
+        const float rl = fmaxf(g, 0.0f);
+        const float rr = rl * rl;
+        hv[r] = bl_f32_to_bf16_rne(u * rr);
+      }
+      const size_t o = (size_t)m * N + n;
+      if ((N & 3) == 0) {
+        *reinterpret_cast<uint2*>(H + o) = make_uint2((u32)hv[0] | ((u32)hv[1] << 16), (u32)hv[2] | ((u32)hv[3] << 16));
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (n + r < N) H[o + r] = hv[r];
+      }
+    }
+    return;
+  }
+  // one thread per token and 4 consecutive outputs of the block's NWT * 16
   const int qpr = NWT * 4;                       // groups of 4 outputs per row
   for (int i = tid; i < M * qpr; i += GR_THREADS) {
     const int m = i / qpr, c = (i % qpr) * 4;
@@ -922,9 +965,58 @@ static int gr_run(const void* q, const float* scale, int M, int Kp, const void* 
   const int ybf = ydt == BL_BF16 ? 1 : 0;
   kern<<<(unsigned)(NBn * S), GR_THREADS, smem, s>>>((const unsigned char*)q, scale, M, Kp,
                                                      (const unsigned char*)Wp, alpha, N, Y, ybf,
-                                                     acc_out, (int32_t*)ws, NBn, S, NWT, KS);
+                                                     acc_out, (int32_t*)ws, NBn, S, NWT, KS, nullptr, nullptr);
   BL_HIP_CHECK_LAUNCH();
   return S > 1 ? gd_reduce(S, M, N, A4 ? 10 : 6, scale, alpha, Y, ybf, acc_out, ws, s) : BL_OK;
+}
+
+// Gate and up projection of 17 to 64 tokens with eq. 5 in the same launch (INT4 codes, both matrices in
+// BL_W_GEMM): possible where all of K fits the LDS beside the tokens (no split across blocks).
+static bool gr_glu_plan(int M, int N, int Kp, int& MT, int& NWT, int& KS, int& NBn, size_t& smem) {
+  if (M <= 16 || M > 64) return false;
+  MT = M > 32 ? 4 : 2;
+  const int KT = Kp >> 8;
+  if (KT > gr_slice_tiles(MT, true)) return false;
+  const int NTv = 2 * ((N + 15) / 16);                   // gate and up tiles
+  NWT = 2;
+  while (NWT < 16 && (NTv + NWT - 1) / NWT > bl_num_cus()) NWT += 2;
+  NBn = (NTv + NWT - 1) / NWT;
+  const int NG = NWT / 2;                                // one tile pair per working wave
+  for (KS = max(1, min(GR_WAVES / NG, KT)); KS >= 1; --KS) {
+    smem = max((size_t)MT * 16 * ((size_t)KT * 128 + 16),
+               (size_t)NG * KS * 2 * MT * 1024 + (size_t)MT * 16 * (NWT * 16 + 4) * sizeof(int32_t));
+    if (smem <= GR_LDS_MAX) return bl_grid_ok(NBn);
+  }
+  return false;
+}
+
+bool bl_gemm_decode_glu_ok(int64_t M, int64_t N, int64_t K) {
+  int MT, NWT, KS, NBn;
+  size_t smem;
+  if (M > 64 || N > ((int64_t)1 << 27)) return false;
+  return gr_glu_plan((int)M, (int)N, (int)bl_round_up(K, BL_KPAD), MT, NWT, KS, NBn, smem);
+}
+
+template <int MT>
+static int gr_go_glu(const void* q, const float* scale, int M, int Kp, const void* Wg, const float* ag, const void* Wu,
+                     const float* au, int N, void* H, int NWT, int KS, int NBn, size_t smem, hipStream_t s) {
+  BL_SET_MAX_LDS_ONCE((gemm_decode_resident_kernel<MT, true, true>), GR_LDS_MAX);
+  gemm_decode_resident_kernel<MT, true, true><<<(unsigned)NBn, GR_THREADS, smem, s>>>(
+      (const unsigned char*)q, scale, M, Kp, (const unsigned char*)Wg, ag, N, H, 1, nullptr, nullptr, NBn, 1, NWT, KS,
+      (const unsigned char*)Wu, au);
+  BL_HIP_CHECK_LAUNCH();
+  return BL_OK;
+}
+
+// q: INT4 nibble codes [M][Kp / 2] with their scales; H [M, N] bfloat16.
+int bl_launch_gemm_decode_glu(const void* q, const float* scale, int64_t M, int64_t K, const void* Wg, const float* ag,
+                              const void* Wu, const float* au, int64_t N, void* H, hipStream_t s) {
+  int MT, NWT, KS, NBn;
+  size_t smem;
+  const int Kp = (int)bl_round_up(K, BL_KPAD);
+  if (!gr_glu_plan((int)M, (int)N, Kp, MT, NWT, KS, NBn, smem)) return BL_EUNSUPPORTED;
+  if (MT == 2) return gr_go_glu<2>(q, scale, (int)M, Kp, Wg, ag, Wu, au, (int)N, H, NWT, KS, NBn, smem, s);
+  return gr_go_glu<4>(q, scale, (int)M, Kp, Wg, ag, Wu, au, (int)N, H, NWT, KS, NBn, smem, s);
 }
 
 // The fused INT4 linear is used for one bfloat16 token when the one-tile-per-block kernel would be

@@ -606,6 +606,24 @@ int bl_launch_gemv_stream_gate_up(const void* X, int64_t M, int64_t K, float eps
   return gv_quant_dispatch<false>(X, (int)M, (int)K, Kp, eps, m0, m1, nullptr, ybf, grid, smem, s);
 }
 
+// INT4 codes from the stand-alone quantizer (up to 16 tokens), gate and up matrices, H = bf16(U * max(G, 0)^2) only.
+bool bl_gemv_stream_glu_codes_ok(int64_t M, int64_t N, int64_t K) {
+  int grid;
+  size_t smem;
+  return gv_plan(M, bl_round_up(K, BL_KPAD), (N + 15) / 16, 2, false, grid, smem);
+}
+
+int bl_launch_gemv_stream_glu_codes(const void* q, const float* scale, int64_t M, int64_t K, const void* Wg,
+                                    const float* ag, const void* Wu, const float* au, int64_t N, void* H, hipStream_t s) {
+  const int Kp = (int)bl_round_up(K, BL_KPAD), NT = (int)((N + 15) / 16);
+  int grid;
+  size_t smem;
+  if (!gv_plan(M, Kp, NT, 2, false, grid, smem)) return BL_EUNSUPPORTED;
+  const GvMat m0 = {(const unsigned char*)Wg, ag, nullptr, nullptr, (int)N, NT};
+  const GvMat m1 = {(const unsigned char*)Wu, au, nullptr, nullptr, (int)N, NT};
+  return gv_go<true, 0, true>(q, scale, (int)M, (int)K, Kp, 0.0f, m0, m1, (uint16_t*)H, 1, grid, smem, s);
+}
+
 // One bfloat16 token, Top_k + INT8 (eq. 1, eq. 3) inside, one matrix.
 bool bl_gemv_stream_topk_ok(int64_t M, int64_t N, int64_t K) {
   int grid;

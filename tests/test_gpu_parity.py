@@ -617,6 +617,10 @@ def test_decode_stream_codes_from_quantizer(M, N, K, kind):
                                           (8, 5460, 2048, B.BL_W_GEMM), (3, 37, 256, B.BL_W_GEMM),
                                           (2, 2050, 1000, B.BL_W_GEMM), (8, 16400, 512, B.BL_W_GEMM),
                                           (20, 1040, 2048, B.BL_W_GEMM), (130, 520, 1000, B.BL_W_MX2),
+                                          (32, 11008, 4096, B.BL_W_GEMM), (64, 11008, 4096, B.BL_W_GEMM),
+                                          (17, 37, 256, B.BL_W_GEMM), (33, 2050, 1000, B.BL_W_GEMM), (12, 11008, 4096, B.BL_W_GEMM),
+                                          (16, 2050, 1000, B.BL_W_GEMM), (9, 37, 256, B.BL_W_GEMM),
+                                          (50, 5460, 2048, B.BL_W_GEMM), (64, 1030, 8192, B.BL_W_GEMM),
                                           (70, 300, 512, B.BL_W_GEMM), (300, 5460, 2048, B.BL_W_MX2),
                                           (257, 330, 1504, B.BL_W_MX4), (513, 333, 256, B.BL_W_MX2),
                                           (2048, 5460, 2048, B.BL_W_MX2)])
