@@ -266,7 +266,9 @@ int bitlinear_gemm(const void* q, const void* scale, bl_act_mode mode, int64_t M
  *   workspace  device, >= bitlinear_gate_up_workspace_bytes(M, N, K, layout) bytes (packed activations,
  *              scales, decode partial sums, and float32 G and U where H is wanted without them)
  * Up to 8 bfloat16 tokens with BL_W_GEMM weights (K % 8 == 0, K <= 8192) run as one launch that
- * streams both matrices once and uses no workspace (it may then be NULL).  With block-float weights
+ * streams both matrices once and uses no workspace (it may then be NULL); up to 64 tokens with
+ * BL_W_GEMM weights and only H asked for run the quantizer and then one launch over both matrices
+ * (K up to 4096 beyond 32 tokens, 8192 beyond 16).  With block-float weights
  * (BL_W_MX4 / BL_W_MX2) and only H asked for, the quantizer is followed by one GEMM over both
  * matrices whose epilogue applies eq. 5 to its accumulators: G and U never reach memory.  Other
  * cases run the quantizer, the two products and the combine as separate kernels. */
