@@ -101,7 +101,7 @@ def cpu_baseline(sample_tokens=1024):
         acc = O.matmul_int(q, T)
         O.rescale(acc, d, alpha, "bf16")
         reps += 1
-        if time.perf_counter() - t0 > 12.0 or reps >= 40:
+        if time.perf_counter() - t0 > 12.0 or reps >= 200:
             break
     dt = (time.perf_counter() - t0) / reps
     tops = 2.0 * sample_tokens * N * K / dt / 1e12
